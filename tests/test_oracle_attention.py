@@ -1,0 +1,127 @@
+"""Pins of the oracle's operator / attention functions (CPU only).
+
+The random-feature result is an approximation of exact softmax attention; what
+is fixed is (i) the two evaluation orders of the same estimator agree to
+rounding, (ii) the estimator converges to the brute-force exact result at the
+Monte-Carlo rate as M grows, (iii) invariants that follow from positivity.
+"""
+import numpy as np
+import pytest
+
+from oracle import favorsharp_oracle as orc
+from paper_2302_00787_amd import synth
+
+
+def _qkv(seed, L, d, dv=None):
+    rng = np.random.default_rng(seed)
+    dv = d if dv is None else dv
+    return (rng.standard_normal((L, d)) + 0.2, rng.standard_normal((L, d)) - 0.1,
+            rng.standard_normal((L, dv)))
+
+
+def _theta(variant, Q, K, s):
+    return orc.fit(variant, s * Q, s * K)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant", ["posrf", "sderf", "aderf", "saderf"])
+def test_linear_order_equals_definition(causal, variant):
+    L, d, M = 37, 5, 24
+    Q, K, V = _qkv(0, L, d, dv=3)
+    s = d ** -0.25
+    th = _theta(variant, Q, K, s)
+    Om = np.random.default_rng(1).standard_normal((M, d))
+    a = orc.attention(th, Om, Q, K, V, s, causal)
+    b = orc.attention_khat_definition(th, Om, Q, K, V, s, causal)
+    np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-13)
+    rows = np.array([0, 5, 36])
+    np.testing.assert_allclose(orc.attention_khat_definition(th, Om, Q, K, V, s, causal, rows=rows), b[rows],
+                               rtol=1e-12)
+    # the definition itself, with unshifted features, spelled out once more
+    P, S = orc.features(th, Om, s * Q, 1), orc.features(th, Om, s * K, 2)
+    Kh = P @ S.T
+    if causal:
+        Kh = np.tril(Kh)
+    np.testing.assert_allclose(a, (Kh @ V) / Kh.sum(1, keepdims=True), rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_converges_to_exact_softmax_attention(causal):
+    L, d = 24, 4
+    Q, K, V = _qkv(2, L, d)
+    s = d ** -0.25
+    th = _theta("sderf", Q, K, s)
+    exact = orc.exact_attention(Q, K, V, s, causal)
+    errs = []
+    for M in (64, 1024, 16384):
+        e = []
+        for rep in range(6):
+            Om = np.random.default_rng(100 + rep).standard_normal((M, d))
+            e.append(np.linalg.norm(orc.attention(th, Om, Q, K, V, s, causal) - exact) / np.linalg.norm(exact))
+        errs.append(np.mean(e))
+    assert errs[2] < 0.02
+    # Monte-Carlo rate: 16x more features -> about 4x smaller error (allow 2.2x .. 8x)
+    assert 2.2 < errs[0] / errs[1] < 8.0 and 2.2 < errs[1] / errs[2] < 8.0
+
+
+def test_kernel_matvec_converges_to_exact_product_and_is_unbiased():
+    rng = np.random.default_rng(3)
+    N, d, n = 40, 4, 3
+    X = rng.random((N, d))
+    X *= 1.2 / np.linalg.norm(X, axis=1, keepdims=True)
+    C = rng.standard_normal((N, n))
+    th = orc.fit_sderf(X, X)
+    exact = orc.exact_kernel_matvec(X, X, C, alpha=-0.5)
+    # brute force by the Gaussian-kernel definition
+    brute = np.array([[sum(np.exp(-0.5 * np.sum((X[i] - X[j]) ** 2)) * C[j, c] for j in range(N))
+                       for c in range(n)] for i in range(N)])
+    np.testing.assert_allclose(exact, brute, rtol=1e-12)
+    est = np.mean([orc.kernel_matvec(th, np.random.default_rng(50 + r).standard_normal((2048, d)), X, X, C, -0.5)
+                   for r in range(8)], axis=0)
+    err_big = np.linalg.norm(est - exact) / np.linalg.norm(exact)          # 16384 features in total
+    err_small = np.mean([np.linalg.norm(orc.kernel_matvec(
+        th, np.random.default_rng(70 + r).standard_normal((64, d)), X, X, C, -0.5) - exact)
+        for r in range(8)]) / np.linalg.norm(exact)
+    assert err_big < 0.04 and 6.0 < err_small / err_big < 40.0                # 256x features -> ~16x
+    # P (S^T C) equals (P S^T) C
+    Om = rng.standard_normal((32, d))
+    P, S = orc.features(th, Om, X, 1, -0.5), orc.features(th, Om, X, 2, -0.5)
+    np.testing.assert_allclose(orc.kernel_matvec(th, Om, X, X, C, -0.5), (P @ S.T) @ C, rtol=1e-11)
+
+
+def test_attention_invariants():
+    L, d, M = 50, 6, 32
+    Q, K, V = _qkv(4, L, d)
+    s = d ** -0.25
+    th = _theta("sderf", Q, K, s)
+    Om = np.random.default_rng(5).standard_normal((M, d))
+    nc = orc.attention(th, Om, Q, K, V, s, False)
+    ca = orc.attention(th, Om, Q, K, V, s, True)
+    # positive features: every output row is a convex combination of rows of V
+    assert np.all(nc <= V.max(0) + 1e-12) and np.all(nc >= V.min(0) - 1e-12)
+    np.testing.assert_allclose(ca[0], V[0], rtol=1e-12)            # first causal row sees only key 0
+    np.testing.assert_allclose(ca[-1], nc[-1], rtol=1e-11)          # last causal row sees every key
+    # constant value column is reproduced exactly (weights sum to one)
+    Vc = np.concatenate([V, np.full((L, 1), 3.5)], axis=1)
+    np.testing.assert_allclose(orc.attention(th, Om, Q, K, Vc, s, True)[:, -1], 3.5, rtol=1e-12)
+    # a common factor on all key features (log D, M^-1/2) cannot change the result
+    th2 = orc.Theta(A=th.A, B1=th.B1, B2=th.B2, C1=th.C1, C2=th.C2, logD=th.logD + 1.7)
+    np.testing.assert_allclose(orc.attention(th2, Om, Q, K, V, s, True), ca, rtol=1e-11)
+    # permuting keys together with values leaves non-causal attention unchanged
+    perm = np.random.default_rng(6).permutation(L)
+    np.testing.assert_allclose(orc.attention(th, Om, Q, K[perm], V[perm], s, False), nc, rtol=1e-10)
+
+
+def test_c1_workload_is_finite_convex_and_improves_with_more_features():
+    w = synth.make("c1")
+    Q, K, V, Om = w["Q"][0, 0], w["K"][0, 0], w["V"][0, 0], w["Omega"][0]
+    s = w["qk_scale"]
+    th = orc.fit_sderf(s * Q.astype(np.float64), s * K.astype(np.float64))
+    rf = orc.attention(th, Om, Q, K, V, s, False)
+    ex = orc.exact_attention(Q, K, V, s, False)
+    # |x| is about 2 here and M is only 64, so the estimate is coarse (relative error of order one, reported
+    # by the benchmark, not asserted); what must hold is finiteness and the convex-combination property
+    assert np.isfinite(rf).all() and np.isfinite(ex).all()
+    assert np.all(rf <= V.max(0) + 1e-9) and np.all(rf >= V.min(0) - 1e-9)
+    big = orc.attention(th, np.random.default_rng(1).standard_normal((65536, 16)), Q, K, V, s, False)
+    assert np.linalg.norm(big - ex) < 0.35 * np.linalg.norm(rf - ex)

@@ -1,0 +1,269 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests touches the GPU or the HIP library.  Each one is chosen so
+that a plausible mistake in the oracle (dropped term, wrong sign, transposed
+operand, wrong index) makes it fail.
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy import optimize
+
+from oracle import favorsharp_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _sets(seed, L, d, kind="hetero", sigma=0.5):
+    rng = np.random.default_rng(seed)
+    if kind == "hetero":          # x ~ N(0, s^2 I), y ~ N(s 1, s^2 I): the paper's "heterogen" regime
+        X = sigma * rng.standard_normal((L, d))
+        Y = sigma * rng.standard_normal((L, d)) + sigma
+    elif kind == "aniso":
+        sc = np.linspace(0.2, 1.2, d)
+        Rx = np.linalg.qr(rng.standard_normal((d, d)))[0]
+        X = sigma * (rng.standard_normal((L, d)) * sc) @ Rx.T + 0.1
+        Y = sigma * (rng.standard_normal((L, d)) * sc[::-1]) @ Rx.T - 0.05
+    else:
+        X = sigma * rng.standard_normal((L, d))
+        Y = sigma * rng.standard_normal((L, d))
+    return X, Y
+
+
+ALL_FITS = ["posrf", "gerf", "saderf", "aderf", "sderf"]
+
+
+# ---- scalar lemma ---------------------------------------------------------
+def test_a_star_hand_values():
+    rows = np.loadtxt(os.path.join(GOLDEN, "a_star_hand_values.txt"))
+    for phi, a, gamma in rows:
+        assert orc.a_star(phi) == pytest.approx(a, abs=1e-15)
+        assert 1.0 / (1.0 - 8.0 * orc.a_star(phi)) == pytest.approx(gamma, abs=1e-14)
+
+
+@pytest.mark.parametrize("phi", [0.0, 0.03, 0.5, 2.0, 17.0])
+def test_a_star_minimises_scalar_function(phi):
+    f = lambda A: np.log(1 - 4 * A) - 0.5 * np.log(1 - 8 * A) + phi / (1 - 8 * A)
+    res = optimize.minimize_scalar(f, bounds=(-50.0, 0.125 - 1e-9), method="bounded",
+                                   options=dict(xatol=1e-12))
+    assert f(orc.a_star(phi)) <= res.fun + 1e-12
+    assert orc.a_star(phi) == pytest.approx(res.x, abs=2e-5)
+    g = 1.0 / (1.0 - 8.0 * orc.a_star(phi))           # positive root of 2 phi g^2 + (2 phi + 1) g - 1
+    assert 2 * phi * g * g + (2 * phi + 1) * g - 1 == pytest.approx(0.0, abs=1e-12)
+
+
+# ---- special cases of the DERF formula ------------------------------------
+def test_posrf_is_derf_with_A_zero():
+    rng = np.random.default_rng(1)
+    d, M = 7, 5
+    X, Om = 0.7 * rng.standard_normal((9, d)), rng.standard_normal((M, d))
+    th = orc.fit_posrf(d)
+    expect = np.exp(X @ Om.T - 0.5 * np.sum(X * X, 1)[:, None]) / np.sqrt(M)     # PosRF definition
+    for side in (1, 2):
+        np.testing.assert_allclose(orc.features(th, Om, X, side), expect, rtol=1e-13)
+
+
+def test_gerf_is_derf_with_scalar_matrices():
+    rng = np.random.default_rng(2)
+    d, M = 6, 4
+    X, Y = _sets(3, 40, d)
+    Om = rng.standard_normal((M, d))
+    th = orc.fit_gerf(X, Y)
+    A = th.A[0]
+    B, D = np.sqrt(1 - 4 * A), (1 - 4 * A) ** (d / 4)
+    expect = D * np.exp(A * np.sum(Om * Om, 1)[None, :] + B * X @ Om.T
+                        - 0.5 * np.sum(X * X, 1)[:, None]) / np.sqrt(M)          # GERF with C = -1/2
+    np.testing.assert_allclose(orc.features(th, Om, X, 1), expect, rtol=1e-13)
+    assert 1 - 8 * A > 0
+
+
+def test_saderf_with_unit_psi_is_gerf_and_sderf_isotropic_is_gerf():
+    d, L = 5, 64
+    rng = np.random.default_rng(4)
+    X = rng.standard_normal((L, d)) * 0.6
+    Y = X[rng.permutation(L)] * rng.choice([-1.0, 1.0], size=(L, 1))     # same per-coordinate second moments -> Psi = I
+    s, g = orc.fit_saderf(X, Y), orc.fit_gerf(X, Y)
+    np.testing.assert_allclose(s.B1, g.B1, atol=1e-13)
+    np.testing.assert_allclose(s.C2, g.C2, atol=1e-13)
+    # SDERF on data whose matrix N is lam*I has A_ll = A*(lam) for all l, i.e. the GERF with phi = lam
+    Xo = np.sqrt(d * 0.3) * np.eye(d)
+    Yo = -Xo                                     # means cancel in mu4 mu5^T + ...: N = M1 + M2 - 2 mu mu^T
+    th = orc.fit_sderf(np.vstack([Xo, -Xo]), np.vstack([Yo, -Yo]))       # zero means, M1 = M2 = 0.3 I
+    np.testing.assert_allclose(th.A, orc.a_star(0.6), atol=1e-14)
+    gg = orc.fit_gerf(np.vstack([Xo, -Xo]), np.vstack([Yo, -Yo]))
+    np.testing.assert_allclose(th.A, gg.A, atol=1e-14)
+    assert th.lbar == pytest.approx(gg.lbar, abs=1e-12)
+
+
+def test_alpha_factor_gives_gaussian_kernel_features():
+    rng = np.random.default_rng(5)
+    d = 4
+    X = rng.standard_normal((3, d))
+    Om = rng.standard_normal((6, d))
+    th = orc.fit_posrf(d)
+    ratio = orc.features(th, Om, X, 1, alpha=-0.5) / orc.features(th, Om, X, 1)
+    np.testing.assert_allclose(ratio, np.exp(-0.5 * np.sum(X * X, 1))[:, None] * np.ones((1, 6)), rtol=1e-13)
+    np.testing.assert_allclose(orc.exact_kernel(X, X, -0.5),
+                               np.exp(-0.5 * ((X[:, None] - X[None]) ** 2).sum(-1)), rtol=1e-12)
+
+
+# ---- validity conditions --------------------------------------------------
+@pytest.mark.parametrize("variant", ALL_FITS)
+@pytest.mark.parametrize("kind", ["hetero", "aniso"])
+def test_fitted_theta_satisfies_rf_conditions(variant, kind):
+    X, Y = _sets(6, 200, 8, kind)
+    th = orc.fit(variant, X, Y)
+    r = orc.validity_residuals(th)
+    assert r["max_8A"] < 1.0
+    assert r["cross"] < 1e-10 and r["C1"] < 1e-10 and r["C2"] < 1e-10 and r["logD"] < 1e-12
+
+
+# ---- unbiasedness and closed-form variance (Monte Carlo) ------------------
+@pytest.mark.parametrize("variant", ALL_FITS)
+def test_unbiased_and_variance_matches_closed_form(variant):
+    d, n_mc = 6, 400_000
+    X, Y = _sets(7, 50, d, "aniso", sigma=0.45)
+    th = orc.fit(variant, X, Y)
+    rng = np.random.default_rng(8)
+    Om = rng.standard_normal((n_mc, d))
+    xs, ys = X[:3], Y[:3]
+    f1 = orc.features(th, Om, xs, 1) * np.sqrt(n_mc)       # undo M^-1/2: plain f(omega, x)
+    f2 = orc.features(th, Om, ys, 2) * np.sqrt(n_mc)
+    var_cf = orc.variance(th, xs, ys)
+    K = orc.exact_kernel(xs, ys)
+    for i in range(3):
+        for j in range(3):
+            z = f1[i] * f2[j]
+            se = np.sqrt(var_cf[i, j] / n_mc)
+            assert abs(z.mean() - K[i, j]) < 5.0 * se, (variant, i, j)
+            # fourth moments are heavy: compare variances loosely but far tighter than a factor of 2
+            assert z.var() == pytest.approx(var_cf[i, j], rel=0.12), (variant, i, j)
+
+
+def test_variance_special_cases_posrf_and_gerf():
+    d = 5
+    X, Y = _sets(9, 30, d)
+    th = orc.fit_posrf(d)
+    K = orc.exact_kernel(X, Y)
+    sq = ((X[:, None] + Y[None]) ** 2).sum(-1)
+    np.testing.assert_allclose(orc.variance(th, X, Y), K ** 2 * (np.exp(sq) - 1.0), rtol=1e-10)
+    th = orc.fit_gerf(X, Y)
+    A = th.A[0]
+    L_ge = (d * np.log((1 - 4 * A) / np.sqrt(1 - 8 * A)) + 2 * (1 - 4 * A) / (1 - 8 * A) * sq
+            - (X * X).sum(1)[:, None] - (Y * Y).sum(1)[None])                    # GERF variance exponent
+    np.testing.assert_allclose(orc.variance(th, X, Y), np.exp(L_ge) - K ** 2, rtol=1e-9)
+
+
+# ---- objective: closed forms, lower bound, optimality ---------------------
+@pytest.mark.parametrize("variant", ["gerf", "saderf", "aderf", "sderf"])
+@pytest.mark.parametrize("kind", ["hetero", "aniso"])
+def test_closed_form_objective_equals_bruteforce(variant, kind):
+    X, Y = _sets(10, 60, 6, kind)
+    th = orc.fit(variant, X, Y)
+    assert th.lbar == pytest.approx(orc.lbar_bruteforce(th, X, Y), abs=1e-10)
+    # zero variance would give the mean of 2 x.y; nothing can go below it
+    assert th.lbar >= 2.0 * np.mean(X @ Y.T) - 1e-12
+
+
+@pytest.mark.parametrize("kind", ["hetero", "aniso", "iso"])
+def test_objective_ordering(kind):
+    X, Y = _sets(11, 80, 8, kind)
+    lb = {v: orc.lbar_bruteforce(orc.fit(v, X, Y), X, Y) for v in ALL_FITS}
+    assert lb["sderf"] <= lb["gerf"] + 1e-12 <= lb["posrf"] + 2e-12
+    assert lb["aderf"] <= lb["saderf"] + 1e-12 <= lb["gerf"] + 2e-12
+
+
+def _sderf_from(Avec, Qmat):
+    d = len(Avec)
+    B = np.diag(np.sqrt(1 - 4 * Avec)) @ Qmat
+    return orc.Theta(A=Avec, B1=B, B2=B.copy(), C1=-0.5 * np.eye(d), C2=-0.5 * np.eye(d),
+                     logD=0.25 * np.sum(np.log(1 - 4 * Avec)))
+
+
+def test_sderf_fit_is_not_improved_by_feasible_perturbations():
+    d = 6
+    X, Y = _sets(12, 70, d, "aniso")
+    th = orc.fit_sderf(X, Y)
+    base = orc.lbar_bruteforce(th, X, Y)
+    rng = np.random.default_rng(13)
+    Q0 = np.diag(1.0 / np.sqrt(1 - 4 * th.A)) @ th.B1
+    for eps in (1e-3, 3e-2, 0.3):
+        for _ in range(20):
+            W = rng.standard_normal((d, d))
+            R = np.linalg.qr(np.eye(d) + eps * (W - W.T))[0]
+            Av = np.minimum(th.A + eps * rng.standard_normal(d) * 0.2, 0.12)
+            cand = _sderf_from(Av, R @ Q0)
+            assert max(orc.validity_residuals(cand)[k] for k in ("cross", "C1", "C2", "logD")) < 1e-9
+            assert orc.lbar_bruteforce(cand, X, Y) >= base - 1e-11
+
+
+def test_aderf_fit_is_not_improved_by_feasible_perturbations():
+    d = 5
+    X, Y = _sets(14, 70, d, "aniso")
+    th = orc.fit_aderf(X, Y)
+    base = orc.lbar_bruteforce(th, X, Y)
+    rng = np.random.default_rng(15)
+    for eps in (1e-3, 3e-2, 0.3):
+        for _ in range(20):
+            A = min(th.A[0] + eps * 0.2 * rng.standard_normal(), 0.12)
+            B1 = (th.B1 / np.sqrt(1 - 4 * th.A[0]) + eps * rng.standard_normal((d, d))) * np.sqrt(1 - 4 * A)
+            B2 = (1 - 4 * A) * np.linalg.inv(B1).T
+            cand = orc.Theta(A=np.full(d, A), B1=B1, B2=B2, C1=-B1.T @ B1 / (2 * (1 - 4 * A)),
+                             C2=-B2.T @ B2 / (2 * (1 - 4 * A)), logD=0.25 * d * np.log(1 - 4 * A))
+            assert orc.validity_residuals(cand)["cross"] < 1e-8
+            assert orc.lbar_bruteforce(cand, X, Y) >= base - 1e-10
+
+
+def test_sderf_closed_form_matches_numerical_optimum_in_2d():
+    X, Y = _sets(16, 40, 2, "aniso", sigma=0.8)
+    th = orc.fit_sderf(X, Y)
+
+    def obj(p):
+        a = 0.125 - np.exp(p[:2])                 # any A < 1/8
+        c, s = np.cos(p[2]), np.sin(p[2])
+        return orc.lbar_bruteforce(_sderf_from(a, np.array([[c, -s], [s, c]])), X, Y)
+
+    best = min((optimize.minimize(obj, x0, method="Nelder-Mead",
+                                  options=dict(xatol=1e-9, fatol=1e-13, maxiter=4000))
+                for x0 in ([0.0, 0.0, 0.3], [-1.0, 0.5, 2.0], [0.5, -1.0, -1.0])), key=lambda r: r.fun)
+    assert th.lbar == pytest.approx(best.fun, abs=1e-8)
+    assert th.lbar <= best.fun + 1e-9
+
+
+def test_aderf_structure_identities():
+    d = 6
+    X, Y = _sets(17, 90, d, "aniso")
+    th = orc.fit_aderf(X, Y)
+    M1, M2, mu4, mu5 = orc.statistics(X, Y)
+    A = th.A[0]
+    F = th.B1.T @ th.B1 / (1 - 4 * A)
+    np.testing.assert_allclose(F @ M1 @ F, M2, atol=1e-10)
+    np.testing.assert_allclose(th.B1.T @ th.B2, (1 - 4 * A) * np.eye(d), atol=1e-10)
+    phi = float(np.trace(F @ M1)) * 2 / d + 2 * (mu4 @ mu5) / d
+    assert A == pytest.approx(orc.a_star(phi), abs=1e-12)
+
+
+def test_heterogen_regime_sderf_beats_gerf_by_a_wide_margin():
+    # Section 5.1 reports about e^5 lower variance for SDERF than GERF in the "heterogen" regime (d = 64).
+    X, Y = _sets(18, 256, 64, "hetero", sigma=0.5)
+    g = orc.second_moment_log(orc.fit_gerf(X, Y), X, Y).mean()
+    s = orc.second_moment_log(orc.fit_sderf(X, Y), X, Y).mean()
+    assert g - s > 3.0
+
+
+# ---- statistics -----------------------------------------------------------
+def test_statistics_by_loops():
+    X, Y = _sets(19, 11, 3, "aniso")
+    M1, M2, mu4, mu5 = orc.statistics(X, Y)
+    acc = np.zeros((3, 3))
+    for row in X:
+        acc += np.outer(row, row)
+    np.testing.assert_allclose(M1, acc / len(X), atol=1e-14)
+    np.testing.assert_allclose(mu5, sum(Y) / len(Y), atol=1e-14)
+    th = orc.fit_sderf(X, Y)
+    N = M1 + np.outer(mu4, mu5) + np.outer(mu5, mu4) + M2
+    brute = np.mean([[np.outer(x + y, x + y) for y in Y] for x in X], axis=(0, 1))
+    np.testing.assert_allclose(N, brute, atol=1e-13)
+    Q3t = np.diag(1 / np.sqrt(1 - 4 * th.A)) @ th.B1                 # = Q3^T, rows are eigenvectors of N
+    np.testing.assert_allclose(Q3t @ N @ Q3t.T, np.diag(np.sort(np.linalg.eigvalsh(N))[::-1]), atol=1e-12)
