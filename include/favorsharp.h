@@ -1,0 +1,150 @@
+/*
+ * favorsharp.h -- C ABI of the FAVOR# hot path for AMD MI355X (gfx950).
+ *
+ * FAVOR# approximates the softmax / Gaussian kernel operator with positive
+ * "dense-exponential" random features (DERFs):
+ *
+ *     f^(k)(omega, x) = D exp(omega^T A omega + omega^T B^(k) x + x^T C^(k) x),   k = 1 (queries), 2 (keys)
+ *
+ * (paper Section 4, DERF definition), with parameters theta = {A, B1, B2, C1, C2, D}
+ * fitted in closed form to statistics of the query / key sets (Theorems on
+ * ADERF and SDERF, Section 4.3 for SADERF, Section 2.3 for GERF / PosRF).
+ * With P[i,m] = M^-1/2 f1(omega_m, x_i), S[j,m] = M^-1/2 f2(omega_m, y_j)
+ * (Section 2.1) the kernel matrix is estimated by K_hat = P S^T and every
+ * product K_hat C costs O(L M n).
+ *
+ * Conventions for every entry point
+ *   - returns an fs_status; never throws, never aborts, never allocates device
+ *     memory: the caller owns every buffer, including the workspace, whose
+ *     size comes from the matching *_workspace_bytes query (same shapes);
+ *   - pointers are DEVICE pointers unless the name starts with host_;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  favorsharp_fit_params additionally waits for the
+ *     stream (its d x d closed form runs on the host in fp64); the others
+ *     return as soon as their kernels are enqueued;
+ *   - outputs are fully overwritten, inputs are never modified; the workspace
+ *     content is undefined afterwards; calls that share a workspace must be
+ *     ordered by the caller; there is no global mutable state;
+ *   - tensors are row-major; an fs_tensor carries element strides for the
+ *     batch, head and row axes, the innermost (feature) axis has stride 1 and
+ *     row starts must be 16-byte aligned (stride_l a multiple of 8 for bf16, of 4 for f32);
+ *   - x = qk_scale * Q_i and y = qk_scale * K_j are the vectors the paper's
+ *     formulas see (attention: qk_scale = d^-1/4, Section 2.2).
+ */
+#ifndef FAVORSHARP_H
+#define FAVORSHARP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FS_OK = 0,
+  FS_ERR_INVALID_ARG = 1,        /* null pointer, bad shape / stride / dtype / enum */
+  FS_ERR_UNSUPPORTED = 2,        /* valid but outside what the kernels cover (d > 128, causal with Lq != Lk, ...) */
+  FS_ERR_NOT_PD = 3,             /* fit: statistics are singular where the theorem needs them nonsingular */
+  FS_ERR_WORKSPACE_TOO_SMALL = 4,
+  FS_ERR_DEVICE = 5              /* a HIP call failed */
+} fs_status;
+
+typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype;
+
+/* Which closed-form family favorsharp_fit_params fits. */
+typedef enum {
+  FS_POSRF = 0,   /* A = 0: exp(omega.x - |x|^2/2)                         (Section 2.3) */
+  FS_GERF = 1,    /* scalar A, homogeneity heuristic                        (Sections 2.3, 3.1) */
+  FS_SADERF = 2,  /* GERF on (Psi x, Psi^-1 y), diagonal Psi                (Section 4.3) */
+  FS_ADERF = 3,   /* A = a I, B1 != B2, via eig(M1), eig(M2) and one SVD    (Theorem on ADERF) */
+  FS_SDERF = 4    /* B1 = B2, diagonal A, via one eigendecomposition        (Theorem on SDERF) */
+} fs_variant;
+
+/* A [B, H, L, d] tensor (or [L, d] with B = H = 1): element strides, innermost stride 1. */
+typedef struct {
+  const void* ptr;     /* device */
+  int32_t dtype;       /* fs_dtype */
+  int64_t stride_b;
+  int64_t stride_h;
+  int64_t stride_l;
+} fs_tensor;
+
+/*
+ * Layout of one parameter set theta (float32, `favorsharp_theta_floats(d)` values):
+ *   [0] log D   [1] fitted value of the shifted log-variance objective (Section 3.1; NaN if none)
+ *   [2] flags (as a float; bit 0 set: C1 = C2 = -I/2 exactly, bit 1 set: B1 = B2)   [3] fs_variant   [4..7] reserved
+ *   then diag(A)[d], B1[d*d], B2[d*d], C1[d*d], C2[d*d], all row-major.
+ * A parameter buffer holds `groups` such sets back to back; the set used for
+ * batch b, head h is 0 (groups = 1), h (groups = H) or b*H + h (groups = B*H).
+ */
+#define FS_THETA_HEADER 8
+size_t favorsharp_theta_floats(int d);
+
+const char* favorsharp_status_string(int status);
+const char* favorsharp_version(void);
+
+/*
+ * Fit theta from data statistics (Theorems on ADERF / SDERF, Sections 2.3, 3.1, 4.3).
+ * Per group: mu4 = mean x, mu5 = mean y, M1 = mean x x^T, M2 = mean y y^T over all rows of
+ * all (b, h) that map to the group (one scan of X and Y on the GPU), then the variant's closed form
+ * (eigendecompositions / SVD of d x d matrices in fp64 on the host), written to `theta`.
+ *   X: [B, H, Lx, d], Y: [B, H, Ly, d] (f32 or bf16, same dtype); d <= 128; groups in {1, H, B*H}.
+ *   eig_ridge >= 0 is added to the diagonals of M1 and M2 before the ADERF decompositions (0 = exact theorem).
+ *   theta: device, groups * favorsharp_theta_floats(d) floats, overwritten.
+ * Synchronous with respect to `stream`.  FS_ERR_NOT_PD when ADERF / SADERF meet a singular statistic.
+ */
+size_t favorsharp_fit_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups);
+int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y,
+                          int B, int H, int Lx, int Ly, int d, float qk_scale, int groups,
+                          float eig_ridge, float* theta, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/*
+ * Materialise one side of the feature matrix (Section 2.1: rows of P for side = 1, of S for side = 2):
+ *   out[i, m] = M^-1/2 exp(alpha |x_i|^2) f^(side)(omega_m, x_i),  x_i = qk_scale * X[i, :]
+ * (Section 2.3 for the exp(alpha |x|^2) factor that turns softmax-kernel features into K^(alpha) features).
+ *   X: [n, d] (stride_l used; B = H = 1), theta: one parameter set, Omega: [M, d] float32 rows omega_m,
+ *   out: [n, M] float32.  If row_logscale != NULL (n floats) the row is stabilised:
+ *   row_logscale[i] = max_m log out[i, m] and out[i, m] is divided by exp(row_logscale[i]).
+ */
+size_t favorsharp_features_workspace_bytes(int n, int d, int M);
+int favorsharp_features(const float* theta, int side, const fs_tensor* X, int n, int d,
+                        float qk_scale, float alpha, const float* Omega, int M,
+                        float* out, float* row_logscale,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Attention with K_hat in place of the softmax kernel matrix (Section 2.2, the attention equation):
+ *   Y[b,h,i,:] = sum_j K_hat[i,j] V[b,h,j,:] / sum_j K_hat[i,j],   K_hat = P S^T,
+ * over all j (causal = 0) or over j <= i (causal = 1, requires Lq == Lk).  P and S are never written to memory.
+ *   Q: [B,H,Lq,d], K: [B,H,Lk,d], V: [B,H,Lk,dv], Y: [B,H,Lq,dv] (Y->ptr is written; dtypes f32 or bf16,
+ *   Q, K, V share one dtype, Y may differ); d <= 128, dv <= 128.
+ *   theta: `groups` parameter sets, Omega: [omega_groups, M, d] float32, groups and omega_groups in {1, H, B*H}.
+ *   chunk: rows per step of the causal prefix-state recurrence; it changes the schedule, not the result
+ *   (0 = library default; supported: 32 or 64).
+ */
+size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M,
+                                            int causal, int groups, int omega_groups);
+int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                         const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv,
+                         float qk_scale, const float* Omega, int omega_groups, int M,
+                         int causal, int chunk, const fs_tensor* Y,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Unbiased estimate of the kernel operator K^(alpha)(X, Y) C (Section 2.1, the problem statement):
+ *   out = P (S^T C),  P, S built from x_i = qk_scale * X[i,:], y_j = qk_scale * Y[j,:] with the
+ *   exp(alpha |.|^2) factors of Section 2.3, D and M^-1/2 all kept (alpha = -1/2: Gaussian kernel).
+ *   X: [Nx, d], Y: [Ny, d] (same dtype), C: [Ny, n] float32 contiguous, out: [Nx, n] float32, n <= 128.
+ */
+size_t favorsharp_kernel_matvec_workspace_bytes(int Nx, int Ny, int d, int M, int n);
+int favorsharp_kernel_matvec(const float* theta, const fs_tensor* X, const fs_tensor* Y,
+                             int Nx, int Ny, int d, float qk_scale, float alpha,
+                             const float* Omega, int M, const float* C, int n, float* out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAVORSHARP_H */

@@ -1,0 +1,288 @@
+// C ABI of the FAVOR# library: argument validation, workspace planning and kernel dispatch.
+// Nothing here allocates device memory; everything runs on the caller's stream.
+#include "../../include/favorsharp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "host_fit.h"
+#include "kernels.h"
+
+using namespace fs;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+bool tensor_ok(const fs_tensor* t, int d, bool need_ptr = true) {
+  if (t == nullptr) return false;
+  if (need_ptr && t->ptr == nullptr) return false;
+  if (t->dtype != FS_F32 && t->dtype != FS_BF16) return false;
+  if (t->stride_l < d) return false;
+  const int q = t->dtype == FS_BF16 ? 8 : 4;
+  if (t->stride_l % q || t->stride_b % q || t->stride_h % q) return false;
+  if (((uintptr_t)t->ptr) % 16) return false;
+  return true;
+}
+
+TensorDev dev(const fs_tensor* t) { return TensorDev{t->ptr, t->dtype, t->stride_b, t->stride_h, t->stride_l}; }
+
+bool groups_ok(int g, int B, int H) { return g == 1 || g == H || g == B * H; }
+
+struct AttnPlan {
+  int pgroups, ldt, nseg, rows_per_seg;
+  size_t off_W, off_Wbf, off_bias, off_kmax, off_state, total;
+};
+
+// Shared by the workspace query and the call so that both agree.
+void plan_contraction(int BH, int pgroups, int Lk, int d, int M, int nv1, int causal, AttnPlan* p) {
+  p->pgroups = pgroups;
+  p->ldt = ceil_div(nv1, 16) * 16;
+  const int nmb = ceil_div(M, 32);
+  int want;
+  if (causal) want = std::max(1, std::min(ceil_div(1024, BH), ceil_div(Lk, 128)));
+  else want = std::max(1, std::min(ceil_div(2048, BH * nmb), ceil_div(Lk, 32)));
+  p->rows_per_seg = ceil_div(ceil_div(Lk, want), 32) * 32;
+  p->nseg = ceil_div(Lk, p->rows_per_seg);
+  size_t off = 0;
+  p->off_W = off;    off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(float));
+  p->off_Wbf = off;  off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(uint16_t));
+  p->off_bias = off; off = align_up(off + (size_t)pgroups * 2 * M * sizeof(float));
+  p->off_kmax = off; off = align_up(off + (size_t)BH * sizeof(uint32_t));
+  p->off_state = off; off = align_up(off + (size_t)BH * p->nseg * M * p->ldt * sizeof(float));
+  p->total = off;
+}
+
+struct FitPlan {
+  int nchunks, rows_per_chunk;
+  size_t off_part, off_stats, total;
+};
+
+void plan_fit(int B, int H, int Lx, int Ly, int d, int groups, FitPlan* p) {
+  const int L = std::max(Lx, Ly);
+  const int want = std::max(1, std::min(ceil_div(1024, B * H), ceil_div(L, 32)));
+  p->rows_per_chunk = ceil_div(ceil_div(L, want), 32) * 32;
+  p->nchunks = ceil_div(L, p->rows_per_chunk);
+  const size_t per = (size_t)d * d + d;
+  size_t off = 0;
+  p->off_part = off;  off = align_up(off + (size_t)2 * B * H * p->nchunks * per * sizeof(float));
+  p->off_stats = off; off = align_up(off + (size_t)groups * 2 * per * sizeof(double));
+  p->total = off;
+}
+
+int device_lds_limit() {
+  int dev_id = 0, v = 0;
+  if (hipGetDevice(&dev_id) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev_id) != hipSuccess) return 0;
+  return v;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t favorsharp_theta_floats(int d) { return d > 0 ? (size_t)FS_THETA_HEADER + (size_t)d + 4 * (size_t)d * d : 0; }
+
+const char* favorsharp_status_string(int status) {
+  switch (status) {
+    case FS_OK: return "ok";
+    case FS_ERR_INVALID_ARG: return "invalid argument";
+    case FS_ERR_UNSUPPORTED: return "unsupported shape or option";
+    case FS_ERR_NOT_PD: return "statistics are singular";
+    case FS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case FS_ERR_DEVICE: return "device error";
+    default: return "unknown status";
+  }
+}
+
+const char* favorsharp_version(void) { return "favorsharp 0.1 (gfx950)"; }
+
+// ------------------------------------------------------------------------------------------ fit
+size_t favorsharp_fit_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups) {
+  if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || d > 128 || !groups_ok(groups, B, H)) return 0;
+  FitPlan p;
+  plan_fit(B, H, Lx, Ly, d, groups, &p);
+  return p.total;
+}
+
+int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y, int B, int H, int Lx, int Ly, int d,
+                          float qk_scale, int groups, float eig_ridge, float* theta, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  if (variant < FS_POSRF || variant > FS_SDERF) return FS_ERR_INVALID_ARG;
+  if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || !groups_ok(groups, B, H)) return FS_ERR_INVALID_ARG;
+  if (d > 128) return FS_ERR_UNSUPPORTED;
+  if (!tensor_ok(X, d) || !tensor_ok(Y, d) || X->dtype != Y->dtype) return FS_ERR_INVALID_ARG;
+  if (theta == nullptr || workspace == nullptr || !(eig_ridge >= 0.f) || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
+  FitPlan p;
+  plan_fit(B, H, Lx, Ly, d, groups, &p);
+  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if ((int)gen_lds_stats(d) > device_lds_limit()) return FS_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* part = (float*)(ws + p.off_part);
+  double* stats = (double*)(ws + p.off_stats);
+  if (int rc = launch_stats(dev(X), dev(Y), B, H, Lx, Ly, d, qk_scale, groups, p.rows_per_chunk, p.nchunks, part,
+                            stats, st))
+    return rc;
+  const size_t per = (size_t)d * d + d;
+  std::vector<double> host_stats((size_t)groups * 2 * per);
+  if (hipMemcpyAsync(host_stats.data(), stats, host_stats.size() * sizeof(double), hipMemcpyDeviceToHost, st) != hipSuccess)
+    return FS_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;
+  const size_t tf = favorsharp_theta_floats(d);
+  std::vector<float> host_theta((size_t)groups * tf);
+  int status = FS_OK;
+  for (int g = 0; g < groups && status == FS_OK; ++g) {
+    const double* sx = host_stats.data() + ((size_t)g * 2) * per;
+    const double* sy = sx + per;
+    status = fit_group(variant, d, sx, sy, sx + (size_t)d * d, sy + (size_t)d * d, (double)eig_ridge,
+                       host_theta.data() + (size_t)g * tf);
+  }
+  if (status != FS_OK) return status;
+  if (hipMemcpyAsync(theta, host_theta.data(), host_theta.size() * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess)
+    return FS_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;
+  return FS_OK;
+}
+
+// ------------------------------------------------------------------------------------------ features
+size_t favorsharp_features_workspace_bytes(int n, int d, int M) {
+  if (n < 0 || d < 1 || d > 128 || M < 1) return 0;
+  AttnPlan p;
+  plan_contraction(1, 1, 32, d, M, 1, 0, &p);
+  return p.off_kmax;       // projection constants only
+}
+
+int favorsharp_features(const float* theta, int side, const fs_tensor* X, int n, int d, float qk_scale, float alpha,
+                        const float* Omega, int M, float* out, float* row_logscale, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (n < 0 || d < 1 || M < 1 || (side != 1 && side != 2)) return FS_ERR_INVALID_ARG;
+  if (d > 128) return FS_ERR_UNSUPPORTED;
+  if (theta == nullptr || Omega == nullptr || workspace == nullptr || !tensor_ok(X, d, n > 0)) return FS_ERR_INVALID_ARG;
+  if (n > 0 && out == nullptr) return FS_ERR_INVALID_ARG;
+  if (workspace_bytes < favorsharp_features_workspace_bytes(n, d, M)) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if (n == 0) return FS_OK;
+  if ((int)gen_lds_features(d) > device_lds_limit()) return FS_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  AttnPlan p;
+  plan_contraction(1, 1, 32, d, M, 1, 0, &p);
+  char* ws = (char*)workspace;
+  float* W = (float*)(ws + p.off_W);
+  uint16_t* Wbf = (uint16_t*)(ws + p.off_Wbf);
+  float* bias = (float*)(ws + p.off_bias);
+  if (int rc = launch_prep(theta, 1, Omega, 1, 1, 1, 1, M, d, W, Wbf, bias, st)) return rc;
+  const size_t dd = (size_t)d * d;
+  const long long c_off = FS_THETA_HEADER + d + 2 * dd + (side == 2 ? dd : 0);
+  return launch_gen_features(dev(X), n, d, qk_scale, alpha, W + (side == 2 ? (size_t)M * d : 0),
+                             bias + (side == 2 ? M : 0), theta, c_off, M, out, row_logscale, st);
+}
+
+// ------------------------------------------------------------------------------------------ attention
+size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M, int causal,
+                                            int groups, int omega_groups) {
+  if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1) return 0;
+  if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
+  AttnPlan p;
+  plan_contraction(B * H, std::max(groups, omega_groups), Lk, d, M, dv + 1, causal, &p);
+  return p.total;
+}
+
+int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V,
+                         int B, int H, int Lq, int Lk, int d, int dv, float qk_scale, const float* Omega,
+                         int omega_groups, int M, int causal, int chunk, const fs_tensor* Y, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
+  if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
+  if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
+  if (chunk != 0 && chunk != 32 && chunk != 64) return chunk < 0 ? FS_ERR_INVALID_ARG : FS_ERR_UNSUPPORTED;
+  if (d > 128 || dv > 128) return FS_ERR_UNSUPPORTED;
+  if (causal && Lq != Lk) return FS_ERR_UNSUPPORTED;
+  if (theta == nullptr || Omega == nullptr || workspace == nullptr || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
+  if (!tensor_ok(Q, d, Lq > 0) || !tensor_ok(K, d) || !tensor_ok(V, dv) || !tensor_ok(Y, dv, Lq > 0))
+    return FS_ERR_INVALID_ARG;
+  if (Q->dtype != K->dtype || Q->dtype != V->dtype) return FS_ERR_INVALID_ARG;
+  const int BH = B * H, pgroups = std::max(groups, omega_groups);
+  AttnPlan p;
+  plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p);
+  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if (Lq == 0) return FS_OK;
+  const int lds_limit = device_lds_limit();
+  const size_t lds_need = causal ? gen_lds_causal(d, p.ldt) : std::max(gen_lds_state(d, p.ldt), gen_lds_apply(d, p.ldt));
+  if ((int)lds_need > lds_limit) return FS_ERR_UNSUPPORTED;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* W = (float*)(ws + p.off_W);
+  uint16_t* Wbf = (uint16_t*)(ws + p.off_Wbf);
+  float* bias = (float*)(ws + p.off_bias);
+  uint32_t* kmax = (uint32_t*)(ws + p.off_kmax);
+  float* state = (float*)(ws + p.off_state);
+  const size_t dd = (size_t)d * d;
+  const long long tf = (long long)favorsharp_theta_floats(d);
+
+  if (int rc = launch_prep(theta, groups, Omega, omega_groups, pgroups, B, H, M, d, W, Wbf, bias, st)) return rc;
+  if (int rc = launch_fill_u32(kmax, 0u, BH, st)) return rc;
+  GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
+  GenSide ks{dev(K), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
+  if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
+  if (int rc = launch_gen_state(ks, dev(V), Lk, BH, H, M, d, dv, 1, p.ldt, p.rows_per_seg, p.nseg, kmax, state, st))
+    return rc;
+  const size_t per_state = (size_t)M * p.ldt;
+  if (int rc = launch_gen_reduce(state, BH, p.nseg, per_state, causal, st)) return rc;
+  if (causal)
+    return launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), st);
+  return launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), st);
+}
+
+// ------------------------------------------------------------------------------------------ operator
+size_t favorsharp_kernel_matvec_workspace_bytes(int Nx, int Ny, int d, int M, int n) {
+  if (Nx < 0 || Ny < 1 || d < 1 || d > 128 || M < 1 || n < 1 || n > 128) return 0;
+  AttnPlan p;
+  plan_contraction(1, 1, Ny, d, M, n, 0, &p);
+  return p.total;
+}
+
+int favorsharp_kernel_matvec(const float* theta, const fs_tensor* X, const fs_tensor* Y, int Nx, int Ny, int d,
+                             float qk_scale, float alpha, const float* Omega, int M, const float* C, int n, float* out,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  if (Nx < 0 || Ny < 1 || d < 1 || M < 1 || n < 1) return FS_ERR_INVALID_ARG;
+  if (d > 128 || n > 128) return FS_ERR_UNSUPPORTED;
+  if (theta == nullptr || Omega == nullptr || C == nullptr || workspace == nullptr || !(qk_scale > 0.f))
+    return FS_ERR_INVALID_ARG;
+  if (!tensor_ok(X, d, Nx > 0) || !tensor_ok(Y, d) || X->dtype != Y->dtype) return FS_ERR_INVALID_ARG;
+  if (Nx > 0 && out == nullptr) return FS_ERR_INVALID_ARG;
+  AttnPlan p;
+  plan_contraction(1, 1, Ny, d, M, n, 0, &p);
+  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if (Nx == 0) return FS_OK;
+  if ((int)std::max(gen_lds_state(d, p.ldt), gen_lds_apply(d, p.ldt)) > device_lds_limit()) return FS_ERR_UNSUPPORTED;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* W = (float*)(ws + p.off_W);
+  uint16_t* Wbf = (uint16_t*)(ws + p.off_Wbf);
+  float* bias = (float*)(ws + p.off_bias);
+  uint32_t* kmax = (uint32_t*)(ws + p.off_kmax);
+  float* state = (float*)(ws + p.off_state);
+  const size_t dd = (size_t)d * d;
+  const long long tf = (long long)favorsharp_theta_floats(d);
+  if (int rc = launch_prep(theta, 1, Omega, 1, 1, 1, 1, M, d, W, Wbf, bias, st)) return rc;
+  if (int rc = launch_fill_u32(kmax, 0u, 1, st)) return rc;
+  GenSide qs{dev(X), qk_scale, alpha, W, bias, theta, 1, 1, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
+  GenSide ks{dev(Y), qk_scale, alpha, W, bias, theta, 1, 1, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
+  qs.X.sb = qs.X.sh = ks.X.sb = ks.X.sh = 0;
+  TensorDev Cv{C, FS_F32, 0, 0, n};
+  TensorDev Ov{out, FS_F32, 0, 0, n};
+  if (int rc = launch_gen_kmax(ks, Ny, 1, 1, M, d, kmax, st)) return rc;
+  if (int rc = launch_gen_state(ks, Cv, Ny, 1, 1, M, d, n, 0, p.ldt, p.rows_per_seg, p.nseg, kmax, state, st)) return rc;
+  const size_t per_state = (size_t)M * p.ldt;
+  if (int rc = launch_gen_reduce(state, 1, p.nseg, per_state, 0, st)) return rc;
+  return launch_gen_apply(qs, Nx, 1, 1, M, d, n, p.ldt, state, (size_t)p.nseg * per_state, kmax, 1, Ov, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+// Host-callable launchers of the FAVOR# kernels.  Every launcher enqueues on `st`, returns an fs_status
+// value (0 ok, 2 unsupported, 5 HIP error) and allocates nothing.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fs_common.h"
+
+namespace fs {
+
+constexpr int FS_THETA_HEADER_ = 8;
+
+// One side (queries or keys) of a feature map as the general-shape kernels see it.
+struct GenSide {
+  TensorDev X;          // rows to map
+  float scale;          // qk_scale
+  float alpha;          // coefficient of |x|^2 added to the exponent (Section 2.3), 0 for attention
+  const float* W;       // [pgroups][2][M][d] projection matrices times log2(e)
+  const float* bias;    // [pgroups][2][M]    biases times log2(e)
+  const float* theta;   // parameter sets
+  int groups;           // number of parameter sets
+  int pgroups;          // number of projection-constant sets
+  long long theta_stride;
+  long long c_offset;   // offset of this side's C matrix inside a parameter set
+};
+
+size_t gen_lds_features(int d);
+size_t gen_lds_state(int d, int ldt);
+size_t gen_lds_apply(int d, int ldt);
+size_t gen_lds_causal(int d, int ldt);
+size_t gen_lds_stats(int d);
+
+int launch_prep(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                int M, int d, float* W, uint16_t* Wbf, float* bias, hipStream_t st);
+int launch_fill_u32(uint32_t* p, uint32_t v, size_t n, hipStream_t st);
+int launch_gen_features(const TensorDev& X, int n, int d, float scale, float alpha, const float* W, const float* bias,
+                        const float* theta, long long c_offset, int M, float* out, float* row_logscale,
+                        hipStream_t st);
+int launch_gen_kmax(const GenSide& ks, int Lk, int BH, int H, int M, int d, uint32_t* kmax_u, hipStream_t st);
+int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int H, int M, int d, int nv,
+                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tpart,
+                     hipStream_t st);
+int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int prefix, hipStream_t st);
+int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
+                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, hipStream_t st);
+int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
+                      int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
+                      const TensorDev& Y, hipStream_t st);
+int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, int Ly, int d, float scale, int groups,
+                 int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st);
+
+}  // namespace fs

@@ -1,0 +1,753 @@
+// General-shape FAVOR# kernels: fp32 arithmetic on fp32 MFMA tiles (v_mfma_f32_16x16x4_f32), any d <= 128,
+// any M, any sequence length, f32 or bf16 storage.  They serve the fp32 workloads and every shape the
+// bf16 fast path does not cover.  All exponents are kept in the log2 domain: the projection matrices and
+// biases arrive pre-multiplied by log2(e), so a feature is exp2(E2 - shift).
+//
+// Tile shape everywhere: 32 rows (tokens) x 32 features per step, 256 threads = 4 waves.
+// MFMA 16x16x4 f32 operand layout used below: lane l supplies A[l%16][l/16] and B[l/16][l%16];
+// accumulator register r of lane l is D[4*(l/16) + r][l%16].
+#include "fs_common.h"
+#include "kernels.h"
+
+namespace fs {
+
+constexpr int TR = 32;     // rows per tile
+constexpr int MB = 32;     // features per block
+constexpr int NT = 256;    // threads per workgroup
+
+constexpr int ACC_PER_WAVE = 5;   // ceil(2 * MAXVT / 4)
+
+// This side's C matrix, or nullptr when the parameter set says C = -I/2 (flag bit 0 of the theta header).
+__device__ __forceinline__ const float* side_cmat(const GenSide& s, int b, int h, int H) {
+  const float* th = s.theta + (size_t)group_of(s.groups, b, h, H) * s.theta_stride;
+  return (((int)th[2]) & 1) ? nullptr : th + s.c_offset;
+}
+
+__device__ __forceinline__ f32x4 mfma4(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// dst[r][c] = scale * T[row0 + r][c] for r < 32; zero outside [0, nrows) x [0, ncols); columns up to ncols_pad written.
+__device__ void load_rows(float* dst, int ld, const TensorDev& t, long long base, int row0, int nrows,
+                          int ncols, int ncols_pad, float scale) {
+  for (int idx = threadIdx.x; idx < TR * ncols_pad; idx += NT) {
+    const int r = idx / ncols_pad, c = idx - r * ncols_pad;
+    float v = 0.f;
+    if (row0 + r < nrows && c < ncols) v = scale * load_elem(t, base + (long long)(row0 + r) * t.sl + c);
+    dst[r * ld + c] = v;
+  }
+}
+
+// Value tile with an optional column of ones at index ncols (the normaliser column of attention).
+__device__ void load_values(float* dst, int ld, const TensorDev& t, long long base, int row0, int nrows,
+                            int ncols, int ncols_pad, int append_ones) {
+  for (int idx = threadIdx.x; idx < TR * ncols_pad; idx += NT) {
+    const int r = idx / ncols_pad, c = idx - r * ncols_pad;
+    float v = 0.f;
+    if (row0 + r < nrows) {
+      if (c < ncols) v = load_elem(t, base + (long long)(row0 + r) * t.sl + c);
+      else if (c == ncols && append_ones) v = 1.f;
+    }
+    dst[r * ld + c] = v;
+  }
+}
+
+// Ws[f][c] = W[m0 + f][c] (zero rows past M), bias_s[f] = bias[m0 + f].
+__device__ void load_wblock(float* Ws, float* bias_s, int ld, const float* W, const float* bias, int m0, int M,
+                            int d, int dpad) {
+  for (int idx = threadIdx.x; idx < MB * dpad; idx += NT) {
+    const int f = idx / dpad, c = idx - f * dpad;
+    Ws[f * ld + c] = (m0 + f < M && c < d) ? W[(long long)(m0 + f) * d + c] : 0.f;
+  }
+  if (threadIdx.x < MB) bias_s[threadIdx.x] = (m0 + threadIdx.x < M) ? bias[m0 + threadIdx.x] : 0.f;
+}
+
+// rterm[r] = log2e * (x_r^T C x_r + alpha |x_r|^2); Cmat == nullptr means C = -I/2.
+__device__ void row_terms(float* rterm, const float* Xs, int ld, int d, const float* Cmat, float alpha) {
+  const int r = threadIdx.x >> 3, part = threadIdx.x & 7;
+  const float* x = Xs + r * ld;
+  float acc = 0.f;
+  if (Cmat == nullptr) {
+    for (int a = part; a < d; a += 8) acc += x[a] * x[a];
+    acc *= (alpha - 0.5f);
+  } else {
+    for (int a = part; a < d; a += 8) {
+      float t = 0.f;
+      for (int b = 0; b < d; ++b) t += Cmat[a * d + b] * x[b];
+      acc += x[a] * (t + alpha * x[a]);
+    }
+  }
+  acc += __shfl_xor(acc, 1);
+  acc += __shfl_xor(acc, 2);
+  acc += __shfl_xor(acc, 4);
+  if (part == 0) rterm[r] = kLog2e * acc;
+}
+
+// Wave w computes the 16x16 tile (row tile w>>1, feature tile w&1) of Xs * Ws^T.
+__device__ __forceinline__ f32x4 proj_tile(const float* Xs, const float* Ws, int ld, int dpad) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* ap = Xs + ((w >> 1) * 16 + (lane & 15)) * ld + (lane >> 4);
+  const float* bp = Ws + ((w & 1) * 16 + (lane & 15)) * ld + (lane >> 4);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < dpad; k += 4) acc = mfma4(ap[k], bp[k], acc);
+  return acc;
+}
+
+// Max of e[0..3] over the 16 lanes that share lane>>4, combined into LDS (ordered-uint image) per row.
+__device__ __forceinline__ void rowmax_update(uint32_t* rowmax_u, const float e[4]) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float v = e[r];
+    v = fmaxf(v, __shfl_xor(v, 1));
+    v = fmaxf(v, __shfl_xor(v, 2));
+    v = fmaxf(v, __shfl_xor(v, 4));
+    v = fmaxf(v, __shfl_xor(v, 8));
+    if ((lane & 15) == 0) atomicMax(&rowmax_u[(w >> 1) * 16 + 4 * (lane >> 4) + r], float_to_ordered(v));
+  }
+}
+
+// One pass over all feature blocks computing, per row, max_m (W_m . x + bias_m) (+ rterm is added by the caller).
+__device__ void rowmax_pass(uint32_t* rowmax_u, const float* Xs, float* Ws, float* bias_s, int ld, const float* W,
+                            const float* bias, int M, int d, int dpad) {
+  if (threadIdx.x < TR) rowmax_u[threadIdx.x] = 0u;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int m0 = 0; m0 < M; m0 += MB) {
+    __syncthreads();
+    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+    __syncthreads();
+    const f32x4 acc = proj_tile(Xs, Ws, ld, dpad);
+    const int f = (w & 1) * 16 + (lane & 15);
+    float e[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) e[r] = (m0 + f < M) ? acc[r] + bias_s[f] : -INFINITY;
+    rowmax_update(rowmax_u, e);
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Projection constants (Section 4, evaluation recipe): W~[m,:] = log2e * omega_m^T B, bias_m = log2e *
+// (omega_m^T A omega_m + log D - 1/2 log M).  grid (M, 2 sides, pgroups), block 128.
+// ---------------------------------------------------------------------------------------------------
+__global__ void k_prep(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups,
+                       int B, int H, int M, int d, float* W, uint16_t* Wbf, float* bias) {
+  const int m = blockIdx.x, side = blockIdx.y, pg = blockIdx.z;
+  int b = 0, h = 0;
+  if (pgroups == H && pgroups != 1) h = pg;
+  else if (pgroups != 1) { b = pg / H; h = pg % H; }
+  const size_t tf = FS_THETA_HEADER_ + (size_t)d + 4 * (size_t)d * d;
+  const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
+  const float* om = Omega + ((size_t)group_of(omega_groups, b, h, H) * M + m) * d;
+  const float* Bm = th + FS_THETA_HEADER_ + d + (side ? (size_t)d * d : 0);
+  const size_t o = (((size_t)pg * 2 + side) * M + m);
+  const int c = threadIdx.x;
+  if (c < d) {
+    float acc = 0.f;
+    for (int l = 0; l < d; ++l) acc += om[l] * Bm[l * d + c];
+    acc *= kLog2e;
+    W[o * d + c] = acc;
+    Wbf[o * d + c] = f32_to_bf16_bits(acc);
+  }
+  if (c == 0) {
+    const float* A = th + FS_THETA_HEADER_;
+    float q = 0.f;
+    for (int l = 0; l < d; ++l) q += A[l] * om[l] * om[l];
+    bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)M));
+  }
+}
+
+__global__ void k_fill_u32(uint32_t* p, uint32_t v, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Materialised features (Section 2.1, rows of P or S).  grid (ceil(n/32)), dynamic LDS.
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_gen_features(TensorDev X, int n, int d, float scale, float alpha,
+                                                     const float* W, const float* bias, const float* theta,
+                                                     long long c_offset, int M, float* out, float* row_logscale) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1;
+  float* Xs = smem;
+  float* Ws = Xs + TR * ld;
+  float* bias_s = Ws + MB * ld;
+  float* rterm = bias_s + MB;
+  uint32_t* rowmax_u = (uint32_t*)(rterm + TR);
+  const int row0 = blockIdx.x * TR;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* Cmat = (((int)theta[2]) & 1) ? nullptr : theta + c_offset;
+
+  load_rows(Xs, ld, X, 0, row0, n, d, dpad, scale);
+  __syncthreads();
+  row_terms(rterm, Xs, ld, d, Cmat, alpha);
+  __syncthreads();
+  if (row_logscale != nullptr) {
+    rowmax_pass(rowmax_u, Xs, Ws, bias_s, ld, W, bias, M, d, dpad);
+    if (threadIdx.x < TR && row0 + threadIdx.x < n)
+      row_logscale[row0 + threadIdx.x] = (ordered_to_float(rowmax_u[threadIdx.x]) + rterm[threadIdx.x]) * kLn2;
+  }
+  for (int m0 = 0; m0 < M; m0 += MB) {
+    __syncthreads();
+    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+    __syncthreads();
+    const f32x4 acc = proj_tile(Xs, Ws, ld, dpad);
+    const int f = (w & 1) * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+      float e = acc[r] + bias_s[f];
+      e = (row_logscale != nullptr) ? e - ordered_to_float(rowmax_u[row]) : e + rterm[row];
+      if (row0 + row < n && m0 + f < M) out[(size_t)(row0 + row) * M + m0 + f] = fast_exp2(e);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Key-side maximum of the exponent per (b, h): kmax[bh] = max_{j,m} E2[j,m] (ordered-uint image, atomicMax).
+// grid (ceil(Lk/32), B*H).
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_gen_kmax(GenSide ks, int Lk, int H, int M, int d, uint32_t* kmax_u) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1;
+  float* Xs = smem;
+  float* Ws = Xs + TR * ld;
+  float* bias_s = Ws + MB * ld;
+  float* rterm = bias_s + MB;
+  uint32_t* rowmax_u = (uint32_t*)(rterm + TR);
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int row0 = blockIdx.x * TR;
+  const int pg = group_of(ks.pgroups, b, h, H);
+  const float* W = ks.W + ((size_t)pg * 2 + 1) * M * d;
+  const float* bias = ks.bias + ((size_t)pg * 2 + 1) * M;
+  const float* Cmat = side_cmat(ks, b, h, H);
+
+  load_rows(Xs, ld, ks.X, b * ks.X.sb + h * ks.X.sh, row0, Lk, d, dpad, ks.scale);
+  __syncthreads();
+  row_terms(rterm, Xs, ld, d, Cmat, ks.alpha);
+  rowmax_pass(rowmax_u, Xs, Ws, bias_s, ld, W, bias, M, d, dpad);
+  if (threadIdx.x < 64) {
+    float v = (threadIdx.x < TR && row0 + threadIdx.x < Lk)
+                  ? ordered_to_float(rowmax_u[threadIdx.x]) + rterm[threadIdx.x] : -INFINITY;
+    for (int s = 1; s < 64; s <<= 1) v = fmaxf(v, __shfl_xor(v, s));
+    if (threadIdx.x == 0) atomicMax(&kmax_u[bh], float_to_ordered(v));
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Key-side partial states (Section 2.1, S^T C): Tpart[bh][seg][m][v] = sum_{j in seg} exp2(E2[j,m] - kmax) * V1[j,v].
+// grid (nseg, ceil(M/32), B*H).
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int Lk, int H, int M, int d, int nv,
+                                                  int append_ones, int ldt, int rows_per_seg, int nseg,
+                                                  const uint32_t* kmax_u, float* Tpart) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
+  float* Xs = smem;
+  float* Ws = Xs + TR * ld;
+  float* Vs = Ws + MB * ld;
+  float* Ss = Vs + TR * ldv;
+  float* bias_s = Ss + TR * lds;
+  float* rterm = bias_s + MB;
+  const int seg = blockIdx.x, m0 = blockIdx.y * MB, bh = blockIdx.z, b = bh / H, h = bh % H;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pg = group_of(ks.pgroups, b, h, H);
+  const float* W = ks.W + ((size_t)pg * 2 + 1) * M * d;
+  const float* bias = ks.bias + ((size_t)pg * 2 + 1) * M;
+  const float* Cmat = side_cmat(ks, b, h, H);
+  const float c = ordered_to_float(kmax_u[bh]);
+  const int nvt = ldt / 16, ntiles = 2 * nvt;
+
+  load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+  f32x4 acc[ACC_PER_WAVE];
+#pragma unroll
+  for (int t = 0; t < ACC_PER_WAVE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int row_end = min(Lk, (seg + 1) * rows_per_seg);
+  for (int row0 = seg * rows_per_seg; row0 < row_end; row0 += TR) {
+    __syncthreads();
+    load_rows(Xs, ld, ks.X, b * ks.X.sb + h * ks.X.sh, row0, row_end, d, dpad, ks.scale);
+    load_values(Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, append_ones);
+    __syncthreads();
+    row_terms(rterm, Xs, ld, d, Cmat, ks.alpha);
+    __syncthreads();
+    const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
+    const int f = (w & 1) * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+      Ss[row * lds + f] = (m0 + f < M) ? fast_exp2(e[r] + bias_s[f] + rterm[row] - c) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int mt = t & 1, vt = t >> 1;
+        const float* ap = Ss + (lane >> 4) * lds + mt * 16 + (lane & 15);      // A[i=m][k=j] = Ss[j][m]
+        const float* bp = Vs + (lane >> 4) * ldv + vt * 16 + (lane & 15);      // B[k=j][n=v] = Vs[j][v]
+        for (int k = 0; k < TR; k += 4) acc[tl] = mfma4(ap[k * lds], bp[k * ldv], acc[tl]);
+      }
+    }
+  }
+  float* out = Tpart + (((size_t)bh * nseg + seg) * M) * ldt;
+#pragma unroll
+  for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+    const int t = w + 4 * tl;
+    if (t < ntiles) {
+      const int mt = t & 1, vt = t >> 1;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + mt * 16 + 4 * (lane >> 4) + r;
+        if (m < M) out[(size_t)m * ldt + vt * 16 + (lane & 15)] = acc[tl][r];
+      }
+    }
+  }
+}
+
+// Sum (prefix = 0: result in segment 0's slot) or exclusive prefix (prefix = 1, in place) over the segments.
+__global__ void k_gen_reduce(float* Tpart, int nseg, size_t per_state, size_t total, int prefix) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const size_t bh = i / per_state, e = i - bh * per_state;
+  float* p = Tpart + bh * nseg * per_state + e;
+  float run = 0.f;
+  for (int s = 0; s < nseg; ++s) {
+    const float v = p[(size_t)s * per_state];
+    if (prefix) p[(size_t)s * per_state] = run;
+    run += v;
+  }
+  if (!prefix) p[0] = run;
+}
+
+// Normalise (attention) or rescale (operator) an accumulated 32 x ldt tile held in LDS and store it.
+__device__ void store_result(const float* Os, int ldo, const TensorDev& Y, long long ybase, int row0, int nrows,
+                             int nv, int matvec, const float* row_log2scale) {
+  for (int idx = threadIdx.x; idx < TR * nv; idx += NT) {
+    const int r = idx / nv, c = idx - r * nv;
+    if (row0 + r >= nrows) continue;
+    float v = Os[r * ldo + c];
+    if (matvec) v *= fast_exp2(row_log2scale[r]);
+    else {
+      const float den = Os[r * ldo + nv];
+      v = den > 0.f ? v / den : 0.f;
+    }
+    store_elem(Y, ybase + (long long)(row0 + r) * Y.sl + c, v);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Query side of the non-causal contraction (Section 2.1, P (S^T C); Section 2.2 for the row normalisation).
+// grid (ceil(Lq/32), B*H).  T: [bh][M][ldt] with stride state_stride between (b,h).
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int M, int d, int nv, int ldt,
+                                                  const float* T, size_t state_stride, const uint32_t* kmax_u,
+                                                  int matvec, TensorDev Y) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldts = ldt + 1, lds = MB + 1;
+  float* Xs = smem;
+  float* Ws = Xs + TR * ld;
+  float* Ts = Ws + MB * ld;          // also reused as the output tile (32 x ldts)
+  float* Ps = Ts + MB * ldts;
+  float* bias_s = Ps + TR * lds;
+  float* rterm = bias_s + MB;
+  float* rscale = rterm + TR;
+  uint32_t* rowmax_u = (uint32_t*)(rscale + TR);
+  const int bh = blockIdx.y, b = bh / H, h = bh % H, row0 = blockIdx.x * TR;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pg = group_of(qs.pgroups, b, h, H);
+  const float* W = qs.W + ((size_t)pg * 2) * M * d;
+  const float* bias = qs.bias + ((size_t)pg * 2) * M;
+  const float* Cmat = side_cmat(qs, b, h, H);
+  const float* Tb = T + (size_t)bh * state_stride;
+  const int nvt = ldt / 16, ntiles = 2 * nvt;
+
+  load_rows(Xs, ld, qs.X, b * qs.X.sb + h * qs.X.sh, row0, Lq, d, dpad, qs.scale);
+  __syncthreads();
+  row_terms(rterm, Xs, ld, d, Cmat, qs.alpha);
+  rowmax_pass(rowmax_u, Xs, Ws, bias_s, ld, W, bias, M, d, dpad);
+  // operator mode multiplies the shifts back: exp2(rowmax + rterm + kmax)
+  if (threadIdx.x < TR)
+    rscale[threadIdx.x] = ordered_to_float(rowmax_u[threadIdx.x]) + rterm[threadIdx.x] + ordered_to_float(kmax_u[bh]);
+
+  f32x4 acc[ACC_PER_WAVE];
+#pragma unroll
+  for (int t = 0; t < ACC_PER_WAVE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int m0 = 0; m0 < M; m0 += MB) {
+    __syncthreads();
+    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+    for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
+      const int f = idx / ldt, c = idx - f * ldt;
+      Ts[f * ldts + c] = (m0 + f < M) ? Tb[(size_t)(m0 + f) * ldt + c] : 0.f;
+    }
+    __syncthreads();
+    const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
+    const int f = (w & 1) * 16 + (lane & 15);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+      Ps[row * lds + f] = (m0 + f < M) ? fast_exp2(e[r] + bias_s[f] - ordered_to_float(rowmax_u[row])) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+        const float* ap = Ps + (rt * 16 + (lane & 15)) * lds + (lane >> 4);    // A[i][k=m] = Ps[i][m]
+        const float* bp = Ts + (lane >> 4) * ldts + vt * 16 + (lane & 15);     // B[k=m][n=v] = Ts[m][v]
+        for (int k = 0; k < MB; k += 4) acc[tl] = mfma4(ap[k], bp[k * ldts], acc[tl]);
+      }
+    }
+  }
+  __syncthreads();
+  float* Os = Ts;
+#pragma unroll
+  for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+    const int t = w + 4 * tl;
+    if (t < ntiles) {
+      const int rt = t & 1, vt = t >> 1;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Os[(rt * 16 + 4 * (lane >> 4) + r) * ldts + vt * 16 + (lane & 15)] = acc[tl][r];
+    }
+  }
+  __syncthreads();
+  store_result(Os, ldts, Y, b * Y.sb + h * Y.sh, row0, Lq, nv, matvec, rscale);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Causal contraction over one segment of one sequence, 32 rows per step, running state in global memory
+// (initialised with the exclusive prefix of the segment states).  For each step:
+//   Y_c = (tril(P_c S_c^T) [V_c 1] + P_c T_prev) normalised by its last column;  T += S_c^T [V_c 1].
+// grid (nseg, B*H).
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, TensorDev V, int L, int H, int M, int d,
+                                                   int nv, int ldt, int rows_per_seg, int nseg,
+                                                   const uint32_t* kmax_u, float* Tstate, TensorDev Y) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
+  float* Qs = smem;
+  float* Ks = Qs + TR * ld;
+  float* Ws = Ks + TR * ld;
+  float* Vs = Ws + MB * ld;
+  float* Ts = Vs + TR * ldv;          // state block, later the output tile
+  float* Ps = Ts + MB * ldv;
+  float* Ss = Ps + TR * lds;
+  float* As = Ss + TR * lds;
+  float* bias_s = As + TR * lds;
+  float* rterm = bias_s + MB;
+  uint32_t* rowmax_u = (uint32_t*)(rterm + TR);
+  const int seg = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pgq = group_of(qs.pgroups, b, h, H);
+  const float* W1 = qs.W + ((size_t)pgq * 2) * M * d;
+  const float* bias1 = qs.bias + ((size_t)pgq * 2) * M;
+  const float* W2 = ks.W + ((size_t)pgq * 2 + 1) * M * d;
+  const float* bias2 = ks.bias + ((size_t)pgq * 2 + 1) * M;
+  const float* Cmat2 = side_cmat(ks, b, h, H);
+  const float c = ordered_to_float(kmax_u[bh]);
+  float* Tg = Tstate + ((size_t)bh * nseg + seg) * M * ldt;
+  const int nvt = ldt / 16, ntiles = 2 * nvt;
+  const long long qbase = b * qs.X.sb + h * qs.X.sh, kbase = b * ks.X.sb + h * ks.X.sh;
+
+  const int row_end = min(L, (seg + 1) * rows_per_seg);
+  for (int row0 = seg * rows_per_seg; row0 < row_end; row0 += TR) {
+    __syncthreads();
+    load_rows(Qs, ld, qs.X, qbase, row0, row_end, d, dpad, qs.scale);
+    load_rows(Ks, ld, ks.X, kbase, row0, row_end, d, dpad, ks.scale);
+    load_values(Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, 1);
+    __syncthreads();
+    row_terms(rterm, Ks, ld, d, Cmat2, 0.f);
+    rowmax_pass(rowmax_u, Qs, Ws, bias_s, ld, W1, bias1, M, d, dpad);
+
+    f32x4 acc[ACC_PER_WAVE];
+#pragma unroll
+    for (int t = 0; t < ACC_PER_WAVE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 sc = {0.f, 0.f, 0.f, 0.f};          // scores tile (query tile w>>1, key tile w&1)
+    for (int m0 = 0; m0 < M; m0 += MB) {
+      const int f = (w & 1) * 16 + (lane & 15);
+      __syncthreads();
+      load_wblock(Ws, bias_s, ld, W1, bias1, m0, M, d, dpad);
+      for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
+        const int ff = idx / ldt, cc = idx - ff * ldt;
+        Ts[ff * ldv + cc] = (m0 + ff < M) ? Tg[(size_t)(m0 + ff) * ldt + cc] : 0.f;
+      }
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(Qs, Ws, ld, dpad);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          Ps[row * lds + f] = (m0 + f < M) ? fast_exp2(e[r] + bias_s[f] - ordered_to_float(rowmax_u[row])) : 0.f;
+        }
+      }
+      __syncthreads();
+      load_wblock(Ws, bias_s, ld, W2, bias2, m0, M, d, dpad);
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(Ks, Ws, ld, dpad);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          Ss[row * lds + f] = (m0 + f < M) ? fast_exp2(e[r] + bias_s[f] + rterm[row] - c) : 0.f;
+        }
+      }
+      __syncthreads();
+      {   // scores: A[i][k=m] = Ps[i][m], B[k=m][n=j] = Ss[j][m]
+        const float* ap = Ps + ((w >> 1) * 16 + (lane & 15)) * lds + (lane >> 4);
+        const float* bp = Ss + ((w & 1) * 16 + (lane & 15)) * lds + (lane >> 4);
+        for (int k = 0; k < MB; k += 4) sc = mfma4(ap[k], bp[k], sc);
+      }
+#pragma unroll
+      for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ntiles) {
+          const int rt = t & 1, vt = t >> 1;
+          {   // inter-chunk term with the state before this step
+            const float* ap = Ps + (rt * 16 + (lane & 15)) * lds + (lane >> 4);
+            const float* bp = Ts + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+            for (int k = 0; k < MB; k += 4) acc[tl] = mfma4(ap[k], bp[k * ldv], acc[tl]);
+          }
+          {   // state update for feature tile rt: T[m][v] += sum_j Ss[j][m] Vs[j][v]
+            f32x4 up = {0.f, 0.f, 0.f, 0.f};
+            const float* ap = Ss + (lane >> 4) * lds + rt * 16 + (lane & 15);
+            const float* bp = Vs + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+            for (int k = 0; k < TR; k += 4) up = mfma4(ap[k * lds], bp[k * ldv], up);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int m = m0 + rt * 16 + 4 * (lane >> 4) + r;
+              if (m < M) Tg[(size_t)m * ldt + vt * 16 + (lane & 15)] += up[r];
+            }
+          }
+        }
+      }
+    }
+    // causal mask inside the step (key j <= query i), then the intra-chunk product
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = (w >> 1) * 16 + 4 * (lane >> 4) + r, j = (w & 1) * 16 + (lane & 15);
+      As[i * lds + j] = (j <= i) ? sc[r] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+        const float* ap = As + (rt * 16 + (lane & 15)) * lds + (lane >> 4);
+        const float* bp = Vs + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+        for (int k = 0; k < TR; k += 4) acc[tl] = mfma4(ap[k], bp[k * ldv], acc[tl]);
+      }
+    }
+    __syncthreads();
+    float* Os = Ts;
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Os[(rt * 16 + 4 * (lane >> 4) + r) * ldv + vt * 16 + (lane & 15)] = acc[tl][r];
+      }
+    }
+    __syncthreads();
+    store_result(Os, ldv, Y, b * Y.sb + h * Y.sh, row0, row_end, nv, 0, nullptr);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Statistics scan for the fits: per (b,h) and row chunk, sum x and sum x x^T of the scaled rows (fp32 MFMA,
+// fp32 partials), then a second kernel adds the partials of all (b,h) of a group in fp64.
+// grid (nchunks, B*H, 2 tensors).  part: [2][B*H][nchunks][d*d + d].
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(NT) k_stats_partial(TensorDev X, TensorDev Yt, int Lx, int Ly, int H, int d,
+                                                      float scale, int rows_per_chunk, int nchunks, float* part) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 15) & ~15, ld = dpad + 1;
+  float* Xs = smem;
+  const int which = blockIdx.z, bh = blockIdx.y, b = bh / H, h = bh % H, chunk = blockIdx.x;
+  const TensorDev& T = which ? Yt : X;
+  const int L = which ? Ly : Lx;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int nt = dpad / 16, ntiles = nt * nt;      // <= 64 tiles, 16 per wave
+  f32x4 acc[16];
+#pragma unroll
+  for (int t = 0; t < 16; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float colsum = 0.f;
+  const int row_end = min(L, (chunk + 1) * rows_per_chunk);
+  for (int row0 = chunk * rows_per_chunk; row0 < row_end; row0 += TR) {
+    __syncthreads();
+    load_rows(Xs, ld, T, b * T.sb + h * T.sh, row0, row_end, d, dpad, scale);
+    __syncthreads();
+    if (threadIdx.x < d)
+      for (int r = 0; r < TR; ++r) colsum += Xs[r * ld + threadIdx.x];
+#pragma unroll
+    for (int tl = 0; tl < 16; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int at = t / nt, bt = t - at * nt;
+        const float* ap = Xs + (lane >> 4) * ld + at * 16 + (lane & 15);      // A[i=a][k=row] = Xs[row][a]
+        const float* bp = Xs + (lane >> 4) * ld + bt * 16 + (lane & 15);
+        for (int k = 0; k < TR; k += 4) acc[tl] = mfma4(ap[k * ld], bp[k * ld], acc[tl]);
+      }
+    }
+  }
+  float* out = part + (((size_t)which * gridDim.y + bh) * nchunks + chunk) * ((size_t)d * d + d);
+#pragma unroll
+  for (int tl = 0; tl < 16; ++tl) {
+    const int t = w + 4 * tl;
+    if (t < ntiles) {
+      const int at = t / nt, bt = t - at * nt;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int a = at * 16 + 4 * (lane >> 4) + r, bb = bt * 16 + (lane & 15);
+        if (a < d && bb < d) out[(size_t)a * d + bb] = acc[tl][r];
+      }
+    }
+  }
+  if (threadIdx.x < d) out[(size_t)d * d + threadIdx.x] = colsum;
+}
+
+// stats: [groups][2][d*d + d] doubles: mean x x^T then mean x, for X (0) and Y (1).
+__global__ void k_stats_final(const float* part, int B, int H, int nchunks, int d, int groups, int Lx, int Ly,
+                              double* stats) {
+  const size_t per = (size_t)d * d + d;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)groups * 2 * per) return;
+  const int g = (int)(i / (2 * per));
+  const int which = (int)((i / per) & 1);
+  const size_t e = i % per;
+  double s = 0.0;
+  long long rows = 0;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h) {
+      if (group_of(groups, b, h, H) != g) continue;
+      rows += which ? Ly : Lx;
+      const float* p = part + (((size_t)which * B * H + (size_t)b * H + h) * nchunks) * per + e;
+      for (int c = 0; c < nchunks; ++c) s += (double)p[(size_t)c * per];
+    }
+  stats[i] = s / (double)rows;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// host launchers
+// ---------------------------------------------------------------------------------------------------
+static size_t lds_floats_basic(int d) { const int ld = ((d + 3) & ~3) + 1; return (size_t)(TR + MB) * ld + MB + 2 * TR + TR; }
+
+size_t gen_lds_features(int d) { return lds_floats_basic(d) * 4; }
+size_t gen_lds_state(int d, int ldt) {
+  const int ld = ((d + 3) & ~3) + 1;
+  return ((size_t)(TR + MB) * ld + (size_t)TR * (ldt + 1) + (size_t)TR * (MB + 1) + MB + TR) * 4;
+}
+size_t gen_lds_apply(int d, int ldt) {
+  const int ld = ((d + 3) & ~3) + 1;
+  return ((size_t)(TR + MB) * ld + (size_t)MB * (ldt + 1) + (size_t)TR * (MB + 1) + MB + 3 * TR) * 4;
+}
+size_t gen_lds_causal(int d, int ldt) {
+  const int ld = ((d + 3) & ~3) + 1;
+  return ((size_t)(2 * TR + MB) * ld + (size_t)(TR + MB) * (ldt + 1) + (size_t)3 * TR * (MB + 1) + MB + 2 * TR) * 4;
+}
+size_t gen_lds_stats(int d) { return (size_t)TR * (((d + 15) & ~15) + 1) * 4; }
+
+#define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
+
+static int set_lds(const void* fn, size_t bytes) {
+  if (bytes > 48 * 1024) {
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+      (void)hipGetLastError();
+      return 2;
+    }
+  }
+  return 0;
+}
+
+int launch_prep(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                int M, int d, float* W, uint16_t* Wbf, float* bias, hipStream_t st) {
+  hipLaunchKernelGGL(k_prep, dim3(M, 2, pgroups), dim3(128), 0, st, theta, groups, Omega, omega_groups, pgroups, B, H,
+                     M, d, W, Wbf, bias);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_fill_u32(uint32_t* p, uint32_t v, size_t n, hipStream_t st) {
+  if (n == 0) return 0;
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, v, n);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_features(const TensorDev& X, int n, int d, float scale, float alpha, const float* W, const float* bias,
+                        const float* theta, long long c_offset, int M, float* out, float* row_logscale,
+                        hipStream_t st) {
+  const size_t lds = gen_lds_features(d);
+  if (int rc = set_lds((const void*)k_gen_features, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_features, dim3((n + TR - 1) / TR), dim3(NT), lds, st, X, n, d, scale, alpha, W, bias, theta,
+                     c_offset, M, out, row_logscale);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_kmax(const GenSide& ks, int Lk, int BH, int H, int M, int d, uint32_t* kmax_u, hipStream_t st) {
+  const size_t lds = gen_lds_features(d);
+  if (int rc = set_lds((const void*)k_gen_kmax, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_kmax, dim3((Lk + TR - 1) / TR, BH), dim3(NT), lds, st, ks, Lk, H, M, d, kmax_u);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int H, int M, int d, int nv,
+                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tpart,
+                     hipStream_t st) {
+  const size_t lds = gen_lds_state(d, ldt);
+  if (int rc = set_lds((const void*)k_gen_state, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_state, dim3(nseg, (M + MB - 1) / MB, BH), dim3(NT), lds, st, ks, V, Lk, H, M, d, nv,
+                     append_ones, ldt, rows_per_seg, nseg, kmax_u, Tpart);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int prefix, hipStream_t st) {
+  const size_t total = (size_t)BH * per_state;
+  hipLaunchKernelGGL(k_gen_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Tpart, nseg, per_state,
+                     total, prefix);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
+                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, hipStream_t st) {
+  const size_t lds = gen_lds_apply(d, ldt);
+  if (int rc = set_lds((const void*)k_gen_apply, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_apply, dim3((Lq + TR - 1) / TR, BH), dim3(NT), lds, st, qs, Lq, H, M, d, nv, ldt, T,
+                     state_stride, kmax_u, matvec, Y);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
+                      int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
+                      const TensorDev& Y, hipStream_t st) {
+  const size_t lds = gen_lds_causal(d, ldt);
+  if (int rc = set_lds((const void*)k_gen_causal, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_causal, dim3(nseg, BH), dim3(NT), lds, st, qs, ks, V, L, H, M, d, nv, ldt, rows_per_seg,
+                     nseg, kmax_u, Tstate, Y);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, int Ly, int d, float scale, int groups,
+                 int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st) {
+  const size_t lds = gen_lds_stats(d);
+  if (int rc = set_lds((const void*)k_stats_partial, lds)) return rc;
+  hipLaunchKernelGGL(k_stats_partial, dim3(nchunks, B * H, 2), dim3(NT), lds, st, X, Y, Lx, Ly, H, d, scale,
+                     rows_per_chunk, nchunks, part);
+  FS_LAUNCH_CHECK();
+  const size_t total = (size_t)groups * 2 * ((size_t)d * d + d);
+  hipLaunchKernelGGL(k_stats_final, dim3((unsigned)((total + 127) / 128)), dim3(128), 0, st, part, B, H, nchunks, d,
+                     groups, Lx, Ly, stats);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+}  // namespace fs

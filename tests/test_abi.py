@@ -1,0 +1,78 @@
+"""The C-ABI library loads, exports every symbol the header declares, and its pure-host entry points answer.
+No kernel is launched here (there is no GPU on the build machine)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "favorsharp.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2302_00787_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2302_00787_amd import build
+        build.build(verbose=False)
+    return binding.lib()
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(favorsharp_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"favorsharp_fit_params", "favorsharp_features", "favorsharp_attention",
+            "favorsharp_kernel_matvec"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_host_only_queries(lib):
+    assert lib.favorsharp_theta_floats(64) == 8 + 64 + 4 * 64 * 64
+    assert lib.favorsharp_theta_floats(0) == 0
+    assert lib.favorsharp_status_string(0) == b"ok"
+    assert b"workspace" in lib.favorsharp_status_string(4)
+    assert b"gfx950" in lib.favorsharp_version()
+    assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 64, 64, 256, 1, 8, 8) > 0
+    assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 129, 64, 256, 1, 8, 8) == 0     # d > 128
+    assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 64, 64, 256, 1, 3, 8) == 0      # bad groups
+    assert lib.favorsharp_kernel_matvec_workspace_bytes(16384, 16384, 32, 512, 8) > 0
+    assert lib.favorsharp_features_workspace_bytes(100, 16, 64) > 0
+    assert lib.favorsharp_fit_workspace_bytes(4, 8, 16384, 16384, 64, 8) > 0
+
+
+def test_argument_errors_are_reported_before_any_device_work(lib):
+    from paper_2302_00787_amd.binding import FsTensor
+    t = FsTensor(None, 0, 0, 0, 64)
+    P = ctypes.byref
+    # null tensors / parameters -> invalid argument
+    assert lib.favorsharp_attention(None, 1, P(t), P(t), P(t), 1, 1, 64, 64, 64, 64, 1.0, None, 1, 64, 0, 0, P(t),
+                                    None, 0, None) == 1
+    # causal with different query / key lengths, d too large -> unsupported
+    assert lib.favorsharp_attention(None, 1, P(t), P(t), P(t), 1, 1, 32, 64, 64, 64, 1.0, None, 1, 64, 1, 0, P(t),
+                                    None, 0, None) == 2
+    assert lib.favorsharp_attention(None, 1, P(t), P(t), P(t), 1, 1, 64, 64, 256, 64, 1.0, None, 1, 64, 0, 0, P(t),
+                                    None, 0, None) == 2
+    assert lib.favorsharp_fit_params(9, P(t), P(t), 1, 1, 8, 8, 8, 1.0, 1, 0.0, None, None, 0, None) == 1
+    assert lib.favorsharp_features(None, 3, P(t), 8, 8, 1.0, 0.0, None, 8, None, None, None, 0, None) == 1
+    assert lib.favorsharp_kernel_matvec(None, P(t), P(t), 8, 8, 8, 1.0, 0.0, None, 8, None, 200, None, None, 0,
+                                        None) == 2
+
+
+def test_pack_and_unpack_theta_roundtrip():
+    import numpy as np
+    from paper_2302_00787_amd import binding
+    d = 5
+    rng = np.random.default_rng(0)
+    B = rng.standard_normal((d, d))
+    vec = binding.pack_theta(-rng.random(d), B, B, -0.5 * np.eye(d), -0.5 * np.eye(d), 0.3, 1.5, 4)
+    u = binding.unpack_theta(vec, d)
+    assert u["flags"] == 3 and u["variant"] == 4 and abs(u["logD"] - 0.3) < 1e-6
+    np.testing.assert_allclose(u["B2"], B.astype(np.float32))
+    assert len(vec) == 8 + d + 4 * d * d

@@ -1,0 +1,279 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element, on the same seeded
+inputs, the same omega and the same parameter block.
+
+Tolerances (relative): 1e-4 for f32 inputs, 2e-2 for bf16 inputs with f32 accumulation.  For attention the
+relative error is the Frobenius one per (b, h), plus a per-row bound |dY_i| <= 4 tol max_j |V_j| (rows of Y
+can be close to zero, so an element-wise relative error would be ill-posed).
+"""
+import numpy as np
+import pytest
+
+from oracle import favorsharp_oracle as orc
+from paper_2302_00787_amd import synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2302_00787_amd import binding
+    binding.lib()                      # raises if the HIP library was not built: there is no fallback
+    return binding
+
+
+def _fit_theta_block(variant, Q, K, scale, groups_shape):
+    """Oracle fit per group (here: per head, rows pooled over the batch) -> float32 parameter blocks."""
+    B, H, L, d = Q.shape
+    vecs = []
+    for h in range(H):
+        X = scale * Q[:, h].reshape(-1, d).astype(np.float64)
+        Y = scale * K[:, h].reshape(-1, d).astype(np.float64)
+        vecs.append(util.theta_vec_from_oracle(orc.fit(variant, X, Y)))
+    return np.stack(vecs)
+
+
+def _check_attention(fs, Q, K, V, Omega, scale, causal, variant, dtype, chunk=0, heads_to_check=None):
+    import torch
+    B, H, Lq, d = Q.shape
+    theta = _fit_theta_block(variant, Q, K, scale, None)
+    Y = fs.attention(torch.from_numpy(theta).cuda(), util.to_device(Q, dtype), util.to_device(K, dtype),
+                     util.to_device(V, dtype), scale, torch.from_numpy(Omega).cuda(), causal=causal, chunk=chunk)
+    torch.cuda.synchronize()
+    Yh = util.to_host(Y)
+    assert np.isfinite(Yh).all()
+    tol = TOL[dtype]
+    worst = (0.0, 0.0)
+    for b in range(B):
+        for h in (range(H) if heads_to_check is None else heads_to_check):
+            th = util.oracle_theta_from_vec(theta[h], d)
+            ref = orc.attention(th, Omega[h], Q[b, h], K[b, h], V[b, h], scale, causal)
+            fro, row = util.attention_errors(Yh[b, h], ref, V[b, h].astype(np.float64))
+            worst = (max(worst[0], fro), max(worst[1], row))
+            assert fro <= tol, (b, h, fro)
+            assert row <= 4 * tol, (b, h, row)
+    return worst
+
+
+# ----------------------------------------------------------------------------- features
+@pytest.mark.parametrize("variant", ["posrf", "gerf", "saderf", "aderf", "sderf"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_features_match_oracle(fs, variant, dtype):
+    import torch
+    rng = np.random.default_rng(11)
+    n, d, M = 77, 24, 45                      # ragged in rows and in features
+    X = (0.8 * rng.standard_normal((n, d)) + 0.1).astype(np.float32)
+    Yk = (0.7 * rng.standard_normal((n, d)) - 0.1).astype(np.float32)
+    if dtype == "bf16":
+        X, Yk = synth.round_to_bf16(X), synth.round_to_bf16(Yk)
+    Om = rng.standard_normal((M, d)).astype(np.float32)
+    scale = 0.9
+    vec = util.theta_vec_from_oracle(orc.fit(variant, scale * X.astype(np.float64), scale * Yk.astype(np.float64)))
+    th = util.oracle_theta_from_vec(vec, d)
+    tdev, odev = torch.from_numpy(vec).cuda(), torch.from_numpy(Om).cuda()
+    for side, data, alpha in ((1, X, 0.0), (2, Yk, -0.5)):
+        ref = orc.features(th, Om, scale * data.astype(np.float64), side, alpha)
+        out = util.to_host(fs.features(tdev, side, util.to_device(data, dtype), scale, alpha, odev))
+        np.testing.assert_allclose(out, ref, rtol=1e-4)
+        out_s, rls = fs.features(tdev, side, util.to_device(data, dtype), scale, alpha, odev, stabilise=True)
+        E = orc.log_features(th, Om, scale * data.astype(np.float64), side, alpha)
+        np.testing.assert_allclose(util.to_host(rls), E.max(axis=1), rtol=0, atol=2e-5 * max(1.0, np.abs(E).max()))
+        np.testing.assert_allclose(util.to_host(out_s), np.exp(E - E.max(axis=1, keepdims=True)), rtol=1e-4, atol=1e-30)
+
+
+# ----------------------------------------------------------------------------- attention, small general shapes
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant", ["sderf", "aderf", "saderf", "gerf"])
+def test_attention_f32_small_ragged(fs, causal, variant):
+    rng = np.random.default_rng(21)
+    B, H, L, d, dv, M = 2, 3, 203, 24, 20, 72          # several 32-row tiles plus a ragged tail; M not a tile multiple
+    Q = (rng.standard_normal((B, H, L, d)) + 0.2).astype(np.float32)
+    K = (rng.standard_normal((B, H, L, d)) - 0.1).astype(np.float32)
+    V = rng.standard_normal((B, H, L, dv)).astype(np.float32)
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    _check_attention(fs, Q, K, V, Om, d ** -0.25, causal, variant, "f32")
+
+
+def test_attention_noncausal_different_lengths_and_strides(fs):
+    import torch
+    rng = np.random.default_rng(22)
+    B, H, Lq, Lk, d, M = 1, 2, 50, 131, 16, 64
+    Q = rng.standard_normal((B, H, Lq, d)).astype(np.float32)
+    K = rng.standard_normal((B, H, Lk, d)).astype(np.float32)
+    V = rng.standard_normal((B, H, Lk, d)).astype(np.float32)
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    s = d ** -0.25
+    theta = np.stack([util.theta_vec_from_oracle(orc.fit_sderf(s * Q[0, h].astype(np.float64), s * K[0, h].astype(np.float64)))
+                      for h in range(H)])
+    # keys and values interleaved in one buffer: [B, Lk, H, 2, d] viewed as two strided [B,H,Lk,d] tensors
+    kv = torch.empty((B, Lk, H, 2, d), dtype=torch.float32, device="cuda")
+    kv[:, :, :, 0] = torch.from_numpy(K).cuda().permute(0, 2, 1, 3)
+    kv[:, :, :, 1] = torch.from_numpy(V).cuda().permute(0, 2, 1, 3)
+    Kd, Vd = kv[:, :, :, 0].permute(0, 2, 1, 3), kv[:, :, :, 1].permute(0, 2, 1, 3)
+    Y = fs.attention(torch.from_numpy(theta).cuda(), torch.from_numpy(Q).cuda(), Kd, Vd, s, torch.from_numpy(Om).cuda())
+    Yh = util.to_host(Y)
+    for h in range(H):
+        ref = orc.attention(util.oracle_theta_from_vec(theta[h], d), Om[h], Q[0, h], K[0, h], V[0, h], s, False)
+        fro, row = util.attention_errors(Yh[0, h], ref, V[0, h].astype(np.float64))
+        assert fro <= 1e-4 and row <= 4e-4
+
+
+def test_attention_group_modes(fs):
+    """One parameter set / omega for everything, per head, and per (batch, head) all address the right block."""
+    import torch
+    rng = np.random.default_rng(23)
+    B, H, L, d, M = 2, 2, 64, 16, 32
+    Q = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    K = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    V = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    s = d ** -0.25
+    for groups in (1, H, B * H):
+        Om = rng.standard_normal((groups, M, d)).astype(np.float32)
+        vecs = []
+        for g in range(groups):
+            sel = [(b, h) for b in range(B) for h in range(H) if (0 if groups == 1 else h if groups == H else b * H + h) == g]
+            X = np.concatenate([s * Q[b, h] for b, h in sel]).astype(np.float64)
+            Yk = np.concatenate([s * K[b, h] for b, h in sel]).astype(np.float64)
+            vecs.append(util.theta_vec_from_oracle(orc.fit_sderf(X, Yk)))
+        theta = np.stack(vecs)
+        Y = util.to_host(fs.attention(torch.from_numpy(theta).cuda(), torch.from_numpy(Q).cuda(), torch.from_numpy(K).cuda(),
+                                      torch.from_numpy(V).cuda(), s, torch.from_numpy(Om).cuda(), causal=True))
+        for b in range(B):
+            for h in range(H):
+                g = 0 if groups == 1 else h if groups == H else b * H + h
+                ref = orc.attention(util.oracle_theta_from_vec(theta[g], d), Om[g], Q[b, h], K[b, h], V[b, h], s, True)
+                fro, row = util.attention_errors(Y[b, h], ref, V[b, h].astype(np.float64))
+                assert fro <= 1e-4 and row <= 4e-4, (groups, b, h)
+
+
+@pytest.mark.parametrize("L,M,d", [(1, 1, 4), (33, 16, 8), (64, 200, 128)])
+def test_attention_degenerate_sizes(fs, L, M, d):
+    rng = np.random.default_rng(24)
+    Q = rng.standard_normal((1, 1, L, d)).astype(np.float32)
+    K = rng.standard_normal((1, 1, L, d)).astype(np.float32)
+    V = rng.standard_normal((1, 1, L, d)).astype(np.float32)
+    Om = rng.standard_normal((1, M, d)).astype(np.float32)
+    for causal in (False, True):
+        _check_attention(fs, Q, K, V, Om, d ** -0.25, causal, "sderf", "f32")
+
+
+def test_attention_empty_query_set_and_error_paths(fs):
+    import torch
+    d, M = 16, 32
+    th = torch.from_numpy(util.theta_vec_from_oracle(orc.fit_posrf(d))[None]).cuda()
+    Om = torch.randn(1, M, d, device="cuda")
+    K = torch.randn(1, 1, 40, d, device="cuda")
+    Y = fs.attention(th, torch.empty(1, 1, 0, d, device="cuda"), K, K, 0.5, Om)
+    assert Y.shape == (1, 1, 0, d)
+    with pytest.raises(fs.FavorSharpError) as e:
+        fs.attention(th, K[:, :, :20], K, K, 0.5, Om, causal=True)            # causal needs Lq == Lk
+    assert e.value.status == 2
+    with pytest.raises(fs.FavorSharpError) as e:
+        fs.attention(th, K, K, K, 0.5, Om, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 4
+
+
+# ----------------------------------------------------------------------------- kernel operator
+@pytest.mark.parametrize("variant", ["sderf", "aderf"])
+def test_kernel_matvec_small(fs, variant):
+    import torch
+    rng = np.random.default_rng(31)
+    Nx, Ny, d, M, n = 70, 121, 12, 56, 5
+    X = rng.random((Nx, d)).astype(np.float32)
+    Yp = rng.random((Ny, d)).astype(np.float32)
+    C = rng.standard_normal((Ny, n)).astype(np.float32)
+    Om = rng.standard_normal((M, d)).astype(np.float32)
+    vec = util.theta_vec_from_oracle(orc.fit(variant, X.astype(np.float64), Yp.astype(np.float64)))
+    th = util.oracle_theta_from_vec(vec, d)
+    for alpha in (0.0, -0.5):
+        ref = orc.kernel_matvec(th, Om, X, Yp, C, alpha)
+        out = util.to_host(fs.kernel_matvec(torch.from_numpy(vec).cuda(), torch.from_numpy(X).cuda(),
+                                            torch.from_numpy(Yp).cuda(), 1.0, alpha, torch.from_numpy(Om).cuda(),
+                                            torch.from_numpy(C).cuda()))
+        assert np.linalg.norm(out - ref) / np.linalg.norm(ref) <= 1e-4
+        np.testing.assert_allclose(out, ref, rtol=1e-3, atol=1e-4 * np.abs(ref).max())
+
+
+# ----------------------------------------------------------------------------- fit
+@pytest.mark.parametrize("variant", ["posrf", "gerf", "saderf", "aderf", "sderf"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fit_params_invariants(fs, variant, dtype):
+    """Eigenvectors are unique only up to sign / rotation inside equal eigenvalues, so the fit is compared on what
+    is unique: A, log D, the objective value, B^T B and B1^T B2, and the validity conditions of the DERF theorem."""
+    rng = np.random.default_rng(41)
+    B, H, L, d = 2, 3, 300, 16
+    sc = np.linspace(0.4, 1.3, d)
+    Q = (rng.standard_normal((B, H, L, d)) * sc + 0.15).astype(np.float32)
+    K = (rng.standard_normal((B, H, L, d)) * sc[::-1] - 0.1).astype(np.float32)
+    if dtype == "bf16":
+        Q, K = synth.round_to_bf16(Q), synth.round_to_bf16(K)
+    s = d ** -0.25
+    theta = util.to_host(fs.fit_params(variant, util.to_device(Q, dtype), util.to_device(K, dtype), s, groups=H))
+    for h in range(H):
+        X = s * Q[:, h].reshape(-1, d).astype(np.float64)
+        Yk = s * K[:, h].reshape(-1, d).astype(np.float64)
+        ref = orc.fit(variant, X, Yk)
+        got = util.oracle_theta_from_vec(theta[h], d)
+        np.testing.assert_allclose(np.sort(got.A), np.sort(ref.A), atol=2e-5)
+        assert got.logD == pytest.approx(ref.logD, abs=1e-4)
+        if ref.lbar is not None:
+            assert float(theta[h][1]) == pytest.approx(ref.lbar, abs=2e-4 * max(1.0, abs(ref.lbar)))
+        np.testing.assert_allclose(got.B1.T @ got.B1, ref.B1.T @ ref.B1, atol=3e-4)
+        np.testing.assert_allclose(got.B1.T @ got.B2, ref.B1.T @ ref.B2, atol=3e-4)
+        np.testing.assert_allclose(got.C1, ref.C1, atol=3e-4)
+        np.testing.assert_allclose(got.C2, ref.C2, atol=3e-4)
+        r = orc.validity_residuals(got)
+        assert r["max_8A"] < 1 and r["cross"] < 1e-4 and r["C1"] < 1e-4 and r["C2"] < 1e-4 and r["logD"] < 1e-4
+        # the fitted parameters reach the oracle's optimum of the objective on the same data
+        assert orc.lbar_bruteforce(got, X[:200], Yk[:200]) == pytest.approx(orc.lbar_bruteforce(ref, X[:200], Yk[:200]), abs=2e-4)
+
+
+def test_fit_then_attention_end_to_end(fs):
+    """theta fitted by the library, downloaded and handed to the oracle: the whole path on one parameter block."""
+    import torch
+    w = synth.make("c1")
+    Q, K, V, Om, s = w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"]
+    Qd, Kd, Vd = (torch.from_numpy(a).cuda() for a in (Q, K, V))
+    theta = fs.fit_params("sderf", Qd, Kd, s, groups=1)
+    Y = util.to_host(fs.attention(theta, Qd, Kd, Vd, s, torch.from_numpy(Om).cuda()))
+    th = util.oracle_theta_from_vec(util.to_host(theta)[0].astype(np.float32), w["d"])
+    ref = orc.attention(th, Om[0], Q[0, 0], K[0, 0], V[0, 0], s, False)
+    fro, row = util.attention_errors(Y[0, 0], ref, V[0, 0].astype(np.float64))
+    assert fro <= 1e-4 and row <= 4e-4
+
+
+# ----------------------------------------------------------------------------- the five workloads
+def test_c1_full(fs):
+    w = synth.make("c1")
+    _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], False, "sderf", "f32")
+
+
+def test_c2_full(fs):
+    import torch
+    w = synth.make("c2")
+    X, C, Om = w["X"], w["C"], w["Omega"][0]
+    vec = util.theta_vec_from_oracle(orc.fit_sderf(X.astype(np.float64), X.astype(np.float64)))
+    th = util.oracle_theta_from_vec(vec, w["d"])
+    Xd = torch.from_numpy(X).cuda()
+    out = util.to_host(fs.kernel_matvec(torch.from_numpy(vec).cuda(), Xd, Xd, 1.0, w["alpha"], torch.from_numpy(Om).cuda(),
+                                        torch.from_numpy(C).cuda()))
+    ref = orc.kernel_matvec(th, Om, X, X, C, w["alpha"])
+    assert np.linalg.norm(out - ref) / np.linalg.norm(ref) <= 1e-4
+    assert np.abs(out - ref).max() <= 1e-4 * np.abs(ref).max() * 4
+
+
+@pytest.mark.parametrize("name,over", [
+    ("c3", dict(B=2, H=2, L=704)),
+    ("c4", dict(B=1, H=2, L=1216)),
+    ("c5", dict(B=1, H=2, L=832)),
+])
+def test_bf16_workloads_reduced(fs, name, over):
+    """The bf16 workloads at their real d, M and statistics, shortened so the oracle finishes in seconds; the
+    lengths are not multiples of 128 so several tiles and a ragged tail are covered."""
+    w = synth.make(name, **over)
+    _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], w["causal"], "sderf", "bf16",
+                     chunk=w.get("chunk", 0))
