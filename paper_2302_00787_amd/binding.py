@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.favorsharp_attention.restype = c_int
         L.favorsharp_attention.argtypes = [c_void_p, c_int, P, P, P, c_int, c_int, c_int, c_int, c_int, c_int, c_float,
                                            c_void_p, c_int, c_int, c_int, c_int, P, c_void_p, c_size_t, c_void_p]
+        L.favorsharp_attention_timed.restype = c_int
+        L.favorsharp_attention_timed.argtypes = L.favorsharp_attention.argtypes + [c_void_p, c_void_p]
         L.favorsharp_kernel_matvec_workspace_bytes.restype = c_size_t
         L.favorsharp_kernel_matvec_workspace_bytes.argtypes = [c_int] * 5
         L.favorsharp_kernel_matvec.restype = c_int
@@ -197,7 +199,7 @@ def attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_grou
 
 def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, qk_scale: float,
               Omega: torch.Tensor, causal: bool = False, chunk: int = 0, out: torch.Tensor | None = None,
-              out_dtype=None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+              out_dtype=None, workspace: torch.Tensor | None = None, events=None) -> torch.Tensor:
     """favorsharp_attention: Q [B,H,Lq,d], K [B,H,Lk,d], V [B,H,Lk,dv], theta [groups,*], Omega [og,M,d] -> Y."""
     B, H, Lq, d = Q.shape
     Lk, dv = K.shape[2], V.shape[3]
@@ -208,9 +210,13 @@ def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
     nbytes = attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, og)
     ws = _workspace(nbytes, Q.device, workspace)
     dq, dk, dvv, dy = _desc4(Q), _desc4(K), _desc4(V), _desc4(out)
-    st = lib().favorsharp_attention(theta.data_ptr(), groups, ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dvv),
-                                    B, H, Lq, Lk, d, dv, qk_scale, Omega.data_ptr(), og, M, int(causal), chunk,
-                                    ctypes.byref(dy), ws.data_ptr(), ws.numel(), _stream())
+    args = (theta.data_ptr(), groups, ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dvv),
+            B, H, Lq, Lk, d, dv, qk_scale, Omega.data_ptr(), og, M, int(causal), chunk,
+            ctypes.byref(dy), ws.data_ptr(), ws.numel(), _stream())
+    if events is None:
+        st = lib().favorsharp_attention(*args)
+    else:       # (hipEvent_t begin, hipEvent_t end) as integers: favorsharp_attention_timed
+        st = lib().favorsharp_attention_timed(*args, events[0], events[1])
     _check(st, "favorsharp_attention")
     return out
 

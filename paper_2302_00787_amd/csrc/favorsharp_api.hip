@@ -196,6 +196,15 @@ int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, con
                          int B, int H, int Lq, int Lk, int d, int dv, float qk_scale, const float* Omega,
                          int omega_groups, int M, int causal, int chunk, const fs_tensor* Y, void* workspace,
                          size_t workspace_bytes, void* stream) {
+  return favorsharp_attention_timed(theta, groups, Q, K, V, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M,
+                                    causal, chunk, Y, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                               const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv, float qk_scale,
+                               const float* Omega, int omega_groups, int M, int causal, int chunk,
+                               const fs_tensor* Y, void* workspace, size_t workspace_bytes, void* stream,
+                               void* event_main_begin, void* event_main_end) {
   if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
@@ -234,9 +243,15 @@ int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, con
     return rc;
   const size_t per_state = (size_t)M * p.ldt;
   if (int rc = launch_gen_reduce(state, BH, p.nseg, per_state, causal, st)) return rc;
+  if (event_main_begin && hipEventRecord((hipEvent_t)event_main_begin, st) != hipSuccess) return FS_ERR_DEVICE;
+  int rc;
   if (causal)
-    return launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), st);
-  return launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), st);
+    rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), st);
+  else
+    rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), st);
+  if (rc) return rc;
+  if (event_main_end && hipEventRecord((hipEvent_t)event_main_end, st) != hipSuccess) return FS_ERR_DEVICE;
+  return FS_OK;
 }
 
 // ------------------------------------------------------------------------------------------ operator
