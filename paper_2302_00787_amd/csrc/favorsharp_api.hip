@@ -75,6 +75,25 @@ void plan_fit(int B, int H, int Lx, int Ly, int d, int groups, FitPlan* p) {
   p->total = off;
 }
 
+struct FastPlan {
+  int pgroups, nseg, rows_per_seg;
+  size_t off_Wbf, off_bias, off_bounds, off_rk, off_state, off_cpart, off_cstar, total;
+};
+
+void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
+  p->pgroups = pgroups;
+  fast_plan(BH, Lk, &p->nseg, &p->rows_per_seg);
+  size_t off = 0;
+  p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 256 * 64 * sizeof(uint16_t));
+  p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 256 * sizeof(float));
+  p->off_bounds = off; off = align_up(off + (size_t)pgroups * 4 * sizeof(float));
+  p->off_rk = off;     off = align_up(off + (size_t)BH * Lk * sizeof(float));
+  p->off_state = off;  off = align_up(off + (size_t)BH * p->nseg * 256 * 80 * sizeof(float));
+  p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nseg * sizeof(float));
+  p->off_cstar = off;  off = align_up(off + (size_t)BH * sizeof(float));
+  p->total = off;
+}
+
 int device_lds_limit() {
   int dev_id = 0, v = 0;
   if (hipGetDevice(&dev_id) != hipSuccess) return 0;
@@ -189,7 +208,13 @@ size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d,
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
   AttnPlan p;
   plan_contraction(B * H, std::max(groups, omega_groups), Lk, d, M, dv + 1, causal, &p);
-  return p.total;
+  size_t total = p.total;
+  if (fast_supported(FS_BF16, d, dv, M)) {      // the query does not know the dtype: cover both paths
+    FastPlan fp;
+    plan_fast(B * H, std::max(groups, omega_groups), Lk, &fp);
+    total = std::max(total, fp.total);
+  }
+  return total;
 }
 
 int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V,
@@ -216,11 +241,27 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     return FS_ERR_INVALID_ARG;
   if (Q->dtype != K->dtype || Q->dtype != V->dtype) return FS_ERR_INVALID_ARG;
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
-  AttnPlan p;
-  plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p);
-  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < favorsharp_attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups))
+    return FS_ERR_WORKSPACE_TOO_SMALL;
   if (Lq == 0) return FS_OK;
   const int lds_limit = device_lds_limit();
+  if (fast_supported(Q->dtype, d, dv, M) && (int)fast_lds_bytes() <= lds_limit) {
+    FastPlan fp;
+    plan_fast(BH, pgroups, Lk, &fp);
+    char* w8 = (char*)workspace;
+    FastLaunch f;
+    f.Q = dev(Q); f.K = dev(K); f.V = dev(V); f.Y = dev(Y);
+    f.theta = theta; f.Omega = Omega;
+    f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
+    f.B = B; f.H = H; f.Lq = Lq; f.Lk = Lk; f.causal = causal;
+    f.nseg = fp.nseg; f.rows_per_seg = fp.rows_per_seg; f.scale = qk_scale;
+    f.Wbf = (uint16_t*)(w8 + fp.off_Wbf); f.bias = (float*)(w8 + fp.off_bias); f.bounds = (float*)(w8 + fp.off_bounds);
+    f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
+    f.cstar = (float*)(w8 + fp.off_cstar);
+    return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
+  }
+  AttnPlan p;
+  plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p);
   const size_t lds_need = causal ? gen_lds_causal(d, p.ldt) : std::max(gen_lds_state(d, p.ldt), gen_lds_apply(d, p.ldt));
   if ((int)lds_need > lds_limit) return FS_ERR_UNSUPPORTED;
 

@@ -51,3 +51,30 @@ int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, i
                  int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st);
 
 }  // namespace fs
+
+namespace fs {
+
+// bf16 fast path (d = dv = 64, M = 256): everything one attention call needs.
+struct FastLaunch {
+  TensorDev Q, K, V, Y;
+  const float* theta;
+  const float* Omega;
+  int groups, omega_groups, pgroups;
+  int B, H, Lq, Lk, causal;
+  int nseg, rows_per_seg;
+  float scale;
+  uint16_t* Wbf;    // [pgroups][2][256][64]
+  float* bias;      // [pgroups][2][256]
+  float* bounds;    // [pgroups][2][2]
+  float* rk;        // [B*H][Lk]
+  float* Tpart;     // [B*H][nseg][256][80]
+  float* cpart;     // [B*H][nseg]
+  float* cstar;     // [B*H]
+};
+
+size_t fast_lds_bytes();
+bool fast_supported(int dtype, int d, int dv, int M);
+void fast_plan(int BH, int L, int* nseg, int* rows_per_seg);
+int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
+
+}  // namespace fs

@@ -277,3 +277,77 @@ def test_bf16_workloads_reduced(fs, name, over):
     w = synth.make(name, **over)
     _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], w["causal"], "sderf", "bf16",
                      chunk=w.get("chunk", 0))
+
+
+# ----------------------------------------------------------------------------- bf16 MFMA path (d = 64, M = 256)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("L", [64, 100, 1000])
+@pytest.mark.parametrize("variant", ["sderf", "aderf"])
+def test_bf16_path_lengths_and_variants(fs, causal, L, variant):
+    """Chunk-exact, ragged and multi-segment lengths; ADERF exercises the dense key-side quadratic form."""
+    w = synth.make("c4", B=2, H=2, L=L, seed=77 + L)
+    worst = _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], causal, variant, "bf16", chunk=64)
+    print(f"bf16 path causal={causal} L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
+def test_bf16_path_f32_output_strided_inputs_and_shared_parameters(fs):
+    import torch
+    w = synth.make("c3", B=2, H=2, L=320)
+    Q, K, V, Om, s, d = w["Q"], w["K"], w["V"], w["Omega"][:1], w["qk_scale"], w["d"]
+    X = np.concatenate([s * Q[b, h] for b in range(2) for h in range(2)]).astype(np.float64)
+    Yk = np.concatenate([s * K[b, h] for b in range(2) for h in range(2)]).astype(np.float64)
+    vec = util.theta_vec_from_oracle(orc.fit_sderf(X, Yk))
+    th = util.oracle_theta_from_vec(vec, d)
+    qkv = torch.empty((2, 320, 2, 3, d), dtype=torch.bfloat16, device="cuda")          # packed [B, L, H, 3, d]
+    for i, a in enumerate((Q, K, V)):
+        qkv[:, :, :, i] = util.to_device(a, "bf16").permute(0, 2, 1, 3)
+    Qd, Kd, Vd = (qkv[:, :, :, i].permute(0, 2, 1, 3) for i in range(3))
+    for causal in (False, True):
+        Y = fs.attention(torch.from_numpy(vec[None]).cuda(), Qd, Kd, Vd, s, torch.from_numpy(Om).cuda(), causal=causal,
+                         out_dtype=torch.float32)
+        assert Y.dtype == torch.float32
+        Yh = util.to_host(Y)
+        for b in range(2):
+            for h in range(2):
+                ref = orc.attention(th, Om[0], Q[b, h], K[b, h], V[b, h], s, causal)
+                fro, row = util.attention_errors(Yh[b, h], ref, V[b, h].astype(np.float64))
+                assert fro <= 2e-2 and row <= 8e-2, (causal, b, h, fro, row)
+
+
+def test_bf16_path_extreme_scales_stay_finite(fs):
+    """Key rows 30x larger than the rest (late in the sequence: their features vanish, the running shift must not
+    follow them) and query rows 3x larger (their own shift grows) leave the result finite and within tolerance."""
+    w = synth.make("c4", B=1, H=1, L=512, seed=5)
+    Q, K = w["Q"].copy(), w["K"].copy()
+    K[0, 0, 300:304] *= 30.0
+    Q[0, 0, 100:102] *= 3.0
+    Q, K = synth.round_to_bf16(Q), synth.round_to_bf16(K)
+    _check_attention(fs, Q, K, w["V"], w["Omega"], w["qk_scale"], True, "posrf", "bf16")
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_bf16_workloads_full_size_sampled_rows(fs, name):
+    """The full workload in the launch configuration the benchmark times; the oracle evaluates sampled output rows
+    one by one from the definition (rows of K_hat, masked when causal): sequence start, segment and chunk
+    boundaries, the end, and random rows, for three (b, h) pairs."""
+    import torch
+    w = synth.make(name)
+    B, H, L, d = w["B"], w["H"], w["L"], w["d"]
+    s, causal = w["qk_scale"], w["causal"]
+    Qd, Kd, Vd = (util.to_device(w[k], "bf16") for k in ("Q", "K", "V"))
+    theta = fs.fit_params("sderf", Qd, Kd, s, groups=H)
+    Y = fs.attention(theta, Qd, Kd, Vd, s, torch.from_numpy(w["Omega"]).cuda(), causal=causal, chunk=w.get("chunk", 0))
+    torch.cuda.synchronize()
+    th_host = util.to_host(theta).astype(np.float32)
+    rng = np.random.default_rng(9)
+    fixed = [0, 1, 63, 64, 65, 2047, 2048, 2049, L // 2 - 1, L // 2, L - 2, L - 1]
+    for b, h in [(0, 0), (B - 1, H - 1), (B // 2, H // 2)]:
+        rows = np.unique(np.concatenate([fixed, rng.integers(0, L, 52)]))
+        th = util.oracle_theta_from_vec(th_host[h], d)
+        ref = orc.attention_khat_definition(th, w["Omega"][h], w["Q"][b, h], w["K"][b, h], w["V"][b, h], s, causal, rows=rows)
+        got = util.to_host(Y[b, h][torch.from_numpy(rows).cuda()])
+        assert np.isfinite(got).all()
+        fro, row = util.attention_errors(got, ref, w["V"][b, h].astype(np.float64))
+        print(f"{name} full size (b={b}, h={h}): {len(rows)} sampled rows, frobenius {fro:.2e}, worst row {row:.2e}")
+        assert fro <= 2e-2 and row <= 8e-2
+    assert torch.isfinite(Y.float()).all().item()
