@@ -8,15 +8,21 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfavorsharp.so")
-SOURCES = ["favorsharp_api.hip", "kernels_generic.hip", "kernels_bf16.hip", "host_fit.cpp"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
+OBJ = os.path.join(HERE, "_build")
+COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-source extra flags.  Kernels that fit in 256 registers keep their MFMA results in ordinary vector registers
+# (no accumulator-register copies before the exp2 / convert steps).
+SOURCES = {
+    "favorsharp_api.hip": [],
+    "kernels_generic.hip": [],
+    "kernels_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "kernels_bf16_causal.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "host_fit.cpp": [],
+}
 
 
-def build(verbose: bool = True) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
-    cmd = [hipcc, *FLAGS, "-x", "hip", *srcs, "-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -26,6 +32,17 @@ def build(verbose: bool = True) -> str:
         print(err, file=sys.stderr)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
+
+
+def build(verbose: bool = True) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(OBJ, exist_ok=True)
+    objs = []
+    for src, extra in SOURCES.items():
+        obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
+        _run([hipcc, *COMMON, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj], verbose)
+        objs.append(obj)
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB], verbose)
     return LIB
 
 

@@ -1,0 +1,372 @@
+// Device-side building blocks of the bf16 attention kernels (d = dv = 64, M = 256) for gfx950.
+//
+// One workgroup = 4 waves = one CU.  Wave w owns the 64 random features [64w, 64w+64): its slice of the
+// projection matrix W~ (bf16) and of the M x (d+1) state T (fp32 MFMA accumulators) stay in registers for the
+// whole kernel, so the feature matrices P, S are produced, used and discarded in registers:
+//
+//   E^T tile   = W~ (A operand) x tokens (B operand)      -> accumulator: lane <-> token, registers <-> feature
+//   S, P       = exp2(E^T)  (bias preloaded in the accumulator, per-token shift added before the exp2)
+//   scores^T   = S (A operand, straight from the accumulator layout) x P^T (B operand, ditto)
+//   Y^T        = T^T (A operand = converted accumulators) x P^T  +  V'^T (A operand) x scores^T (B operand)
+//   T         += S^T x V'   where S^T (lane <-> feature) is obtained from S by an MFMA against a selection matrix
+//
+// All MFMAs are v_mfma_f32_16x16x32_bf16: lane l supplies A[l%16][8(l/16)..+7], B[8(l/16)..+7][l%16] and owns
+// D[4(l/16)..+3][l%16].  Stacking two 16-row accumulator tiles gives, per lane, the 8 values of one operand row;
+// the induced order of the contraction index is k = 8g+e  <->  16(e/4) + 4g + e%4, the same for every operand
+// built that way, so products stay consistent.
+//
+// Exponents live in the log2 domain; W~ carries log2(e) and qk_scale.  Shifts: every query row has its own (it
+// cancels in the normalisation, Section 2.2); the key side needs a common one, kept as a running maximum of a
+// per-token bound with the state rescaled whenever it grows.  Both come from the Cauchy-Schwarz bound on the
+// projection (see row_shift), so nothing can overflow; rows whose bound exceeds about 2^250 may flush to zero.
+#pragma once
+#include "fs_common.h"
+#include "kernels.h"
+
+namespace fs {
+namespace fast {
+
+constexpr int D = 64;            // head dimension (= value dimension)
+constexpr int M = 256;           // random features
+constexpr int NW = 4;            // waves per workgroup, 64 features each
+constexpr int NT = NW * 64;
+constexpr int TC = 64;           // tokens per chunk
+constexpr int KS = D / 32;       // MFMA k-steps of a projection
+constexpr int NVT = 5;           // value tiles of 16 columns: 64 values + normaliser column + padding
+constexpr int DVP = NVT * 16;    // 80
+constexpr int LDR = D + 8;       // row stride (bf16 elements) of a token tile in LDS: 36 dwords, conflict-free b128 reads
+constexpr int LDJ = TC + 4;      // row stride of the transposed value tile in LDS: 34 dwords, conflict-free b64 reads
+constexpr int LDX = DVP + 4;     // row stride (floats) of the exchange buffer
+constexpr float kBeta = 0.5f;
+
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x8 pack8(f32x4 a, f32x4 b) {
+  f32x8 t = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_convertvector(t, bf16x8);
+}
+__device__ __forceinline__ f32x4 exp2v(f32x4 x) {
+  return f32x4{fast_exp2(x[0]), fast_exp2(x[1]), fast_exp2(x[2]), fast_exp2(x[3])};
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int s = 1; s < 64; s <<= 1) v = fmaxf(v, __shfl_xor(v, s));
+  return v;
+}
+
+// Data-parallel-primitive moves inside a row of 16 lanes (no LDS round trip).  CTRL: 0xB1 = swap lanes within pairs,
+// 0x4E = swap pairs within quads, 0x141 = mirror within 8 lanes, 0x124 / 0x128 = rotate the row by 4 / 8 lanes.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+// Sum over the aligned group of 8 lanes the lane belongs to; every lane of the group gets the total.
+__device__ __forceinline__ float sum8(float v) {
+  v += dpp_f<0xB1>(v);
+  v += dpp_f<0x4E>(v);
+  v += dpp_f<0x141>(v);
+  return v;
+}
+// Maximum over the row of 16 lanes the lane belongs to; every lane of the row gets it.
+__device__ __forceinline__ float max16(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));
+  v = fmaxf(v, dpp_f<0x4E>(v));
+  v = fmaxf(v, dpp_f<0x124>(v));
+  v = fmaxf(v, dpp_f<0x128>(v));
+  return v;
+}
+
+// Per-token shift of the projection part W~_m . x of the exponent.  With cs = max_m |W~_m| |x| (Cauchy-Schwarz)
+// the projection never exceeds cs; random directions reach about 0.4 cs.  max(cs/2, cs - 120) keeps the largest
+// shifted exponent below 2^120 for every input and near zero for ordinary ones.
+__device__ __forceinline__ float row_shift(float n2, float wmax) {
+  const float cs = wmax * sqrtf(n2);
+  return fmaxf(kBeta * cs, cs - 120.f);
+}
+
+// The key-side kernel only touches the members up to `q`, and asks for that much LDS (so that two of its
+// workgroups fit on a CU).
+struct Smem {
+  uint16_t k[2][TC][LDR];       // key rows, bf16 bits
+  uint16_t vt[2][DVP][LDJ];     // values transposed: [column][token]; row 64 = ones, rows 65.. = 0
+  float kadd[2][TC];            // per key token: row term log2e y^T C2 y
+  __attribute__((aligned(16))) float kbnd[2][TC];   // per key token: row_shift + row term (-inf past the end)
+  __attribute__((aligned(16))) uint16_t q[2][TC][LDR];       // query rows
+  float qadd[2][TC];            // per query token: - row_shift
+  __attribute__((aligned(16))) float xch[NW][NW][16][LDX];   // partial outputs: [token tile][source wave][token][column]
+};
+
+// Everything the kernels of one attention call share.
+struct FastArgs {
+  TensorDev Q, K, V, Y;
+  const uint16_t* Wbf;     // [pg][2][M][D]
+  const float* bias;       // [pg][2][M]
+  const float* bounds;     // [pg][2][2]: max_m |Wbf_m|, max_m bias
+  const float* theta;
+  const float* rk;         // [BH][L] key row terms for parameter sets with a dense C2, else unused
+  float* Tpart;            // [BH][nslot][M][DVP], nslot = nseg * sub: one state per sub-segment
+  float* cpart;            // [BH][nslot]
+  float* cstar;            // [BH]
+  int groups, pgroups, H, L, rows_per_seg, nseg;
+  int sub, nslot;          // sub-segments per segment (key-side kernel granularity) and total state slots
+  float scale;
+};
+
+// ---- staging: global -> registers (one chunk ahead) -> LDS -------------------------------------------------------
+// Rows: each thread carries two 16-byte pieces of a 64 x 64 bf16 tile: piece q = tid + 256 i -> row q/8, bytes 16 (q%8).
+struct RowRegs { u32x4 p[2]; };
+
+__device__ __forceinline__ void load_rows_g(RowRegs& r, const uint16_t* base, long long sl, int row0, int row_end) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = threadIdx.x + NT * i, row = q >> 3, pc = q & 7;
+    r.p[i] = u32x4{0u, 0u, 0u, 0u};
+    if (row0 + row < row_end) r.p[i] = *(const u32x4*)(base + (long long)(row0 + row) * sl + pc * 8);
+  }
+}
+
+// Writes the pieces and returns, in every lane of the 8 that share a row, the squared norm of that row.
+__device__ __forceinline__ void store_rows_s(const RowRegs& r, uint16_t (*tile)[LDR], float (&n2)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = threadIdx.x + NT * i, row = q >> 3, pc = q & 7;
+    *(u32x4*)(&tile[row][pc * 8]) = r.p[i];
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __uint_as_float(r.p[i][e] << 16), hi = __uint_as_float(r.p[i][e] & 0xffff0000u);
+      s += lo * lo + hi * hi;
+    }
+    n2[i] = sum8(s);
+  }
+}
+
+__device__ __forceinline__ void store_query_rows(const RowRegs& r, Smem& sm, int buf, float wmax) {
+  float n2[2];
+  store_rows_s(r, sm.q[buf], n2);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = threadIdx.x + NT * i;
+    if ((q & 7) == 0) sm.qadd[buf][q >> 3] = -row_shift(n2[i], wmax);
+  }
+}
+
+__device__ __forceinline__ void store_key_rows(const RowRegs& r, Smem& sm, int buf, const FastArgs& a, bool isoC, int bh,
+                                               int row0, int row_end, float wmax) {
+  float n2[2];
+  store_rows_s(r, sm.k[buf], n2);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int q = threadIdx.x + NT * i, row = q >> 3;
+    if ((q & 7) == 0) {
+      const bool valid = row0 + row < row_end;
+      float rt = -0.5f * kLog2e * a.scale * a.scale * n2[i];
+      if (!isoC) rt = valid ? a.rk[(size_t)bh * a.L + row0 + row] : 0.f;
+      sm.kadd[buf][row] = rt;
+      sm.kbnd[buf][row] = valid ? row_shift(n2[i], wmax) + rt : -INFINITY;
+    }
+  }
+}
+
+// Values: lane pairs (2t, 2t+1) exchange halves so that each lane writes whole dwords {token 2t, token 2t+1} of one
+// column: thread -> token tid%64, 16-byte pieces tid/64 and tid/64 + 4 of that token's row.
+__device__ __forceinline__ void load_vals_g(RowRegs& r, const uint16_t* base, long long sl, int row0, int row_end) {
+  const int j = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int pc = (threadIdx.x >> 6) + 4 * i;
+    r.p[i] = u32x4{0u, 0u, 0u, 0u};
+    if (row0 + j < row_end) r.p[i] = *(const u32x4*)(base + (long long)(row0 + j) * sl + pc * 8);
+  }
+}
+
+__device__ __forceinline__ void store_vals_s(const RowRegs& r, uint16_t (*vt)[LDJ], int row0, int row_end) {
+  const int j = threadIdx.x & 63, odd = j & 1;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int pc = (threadIdx.x >> 6) + 4 * i;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t mine = r.p[i][e], other = dpp_u<0xB1>(mine);
+      // even lane: column 2e of tokens (j, j+1); odd lane: column 2e+1 of tokens (j-1, j)
+      const uint32_t w = odd ? ((other >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (other << 16));
+      *(uint32_t*)(&vt[pc * 8 + 2 * e + odd][j & ~1]) = w;
+    }
+  }
+  if (threadIdx.x < 32) {
+    const int t0 = 2 * threadIdx.x;
+    const uint32_t one = 0x3f80u;     // bf16(1)
+    *(uint32_t*)(&vt[D][t0]) = (row0 + t0 < row_end ? one : 0u) | (row0 + t0 + 1 < row_end ? one << 16 : 0u);
+  }
+}
+
+__device__ __forceinline__ void zero_pad_rows(Smem& sm) {
+  for (int idx = threadIdx.x; idx < 2 * (DVP - D - 1) * LDJ; idx += NT) {
+    const int b = idx / ((DVP - D - 1) * LDJ), rem = idx - b * (DVP - D - 1) * LDJ;
+    sm.vt[b][D + 1 + rem / LDJ][rem % LDJ] = 0;
+  }
+}
+
+// ---- per-wave constants ----------------------------------------------------------------------------------------
+// The bias_m = log2e (w_m^T A w_m + log D - 1/2 log M) is the same for both sides (A and D are shared by f1 and f2,
+// Section 4).  It is applied once, doubled, on the query side; key features and the state carry none:
+//   S'[j,m] = exp2(W~2_m . k_j + rowterm_j - shift),   P'[i,m] = exp2(W~1_m . q_i - rowshift_i + 2 (bias_m - amax)),
+// so that sum_m P' S' equals sum_m P S up to factors that cancel in the normalisation.
+struct WSlice {
+  bf16x8 w[4][KS];     // W~ slice as A operand: row = feature 64w + 16mt + c, k = 32ks + 8g + e
+};
+struct QBias {
+  f32x4 b[4];          // 2 (bias - largest bias) of features 64w + 16mt + 4g + r
+};
+
+__device__ __forceinline__ void load_wslice(WSlice& ws, const uint16_t* Wbf) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      ws.w[mt][ks] = *(const bf16x8*)(Wbf + (size_t)(64 * w + 16 * mt + c) * D + 32 * ks + 8 * g);
+}
+
+__device__ __forceinline__ void load_qbias(QBias& qb, const float* bias, float amax) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (bias[64 * w + 16 * mt + 4 * g + r] - amax);
+}
+
+// Selection matrices (B operands) that turn an A operand (lane <-> token, k <-> feature) into an accumulator with
+// lane <-> feature: sel[hh] has a one at (k, n) iff k addresses feature 16 hh + n of the 32-feature block.
+__device__ __forceinline__ void make_sel(bf16x8 sel[2]) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    f32x8 t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = ((e >> 2) == hh && 4 * g + (e & 3) == c) ? 1.f : 0.f;
+    sel[hh] = __builtin_convertvector(t, bf16x8);
+  }
+}
+
+// Feature tile of 16 tokens: for each 32-feature block mb the packed exp2 values (A / B operand layout:
+// lane <-> token 16 jt + c, k <-> feature).  `add` is the per-token part of the exponent (lane c's token).
+template <bool WITH_BIAS>
+__device__ __forceinline__ void feature_tile(const WSlice& ws, const QBias* qb, const uint16_t (*tile)[LDR], int jt,
+                                             float add, bf16x8 out[2]) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  bf16x8 b[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+  f32x4 acc[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], b[ks], acc[mt]);
+  }
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) acc[mt] = exp2v(acc[mt] + add);
+  out[0] = pack8(acc[0], acc[1]);
+  out[1] = pack8(acc[2], acc[3]);
+}
+
+// Key-side features of one pair of token tiles (tokens 32 jp .. 32 jp + 31) in both operand layouts: s[jj][mb]
+// (lane <-> token 16 (2 jp + jj) + c) for the scores and st[mt] (lane <-> feature 16 mt + c, k <-> tokens
+// {32 jp + 4g + r, 32 jp + 16 + 4g + r}) for the state update.
+__device__ __forceinline__ void key_pair(const WSlice& wk, const Smem& sm, int buf, int jp, float dk,
+                                         const bf16x8 sel[2], bf16x8 (&s)[2][2], bf16x8 (&st)[4]) {
+  const int c = threadIdx.x & 15;
+  f32x4 tr[2][4];      // [token tile within the pair][feature tile]
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int jt = 2 * jp + jj;
+    feature_tile<false>(wk, nullptr, sm.k[buf], jt, sm.kadd[buf][16 * jt + c] - dk, s[jj]);
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+        tr[jj][2 * mb + hh] = mfma(s[jj][mb], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
+  }
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) st[mt] = pack8(tr[0][mt], tr[1][mt]);
+}
+
+// B operand / A operand of the value tile: lane <-> column 16 vt + c, k <-> tokens {32 jp + 4g + r, 32 jp + 16 + 4g + r}.
+__device__ __forceinline__ bf16x8 load_vop(const uint16_t (*vt)[LDJ], int jp, int vtile) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  const u32x2 lo = *(const u32x2*)(&vt[16 * vtile + c][32 * jp + 4 * g]);
+  const u32x2 hi = *(const u32x2*)(&vt[16 * vtile + c][32 * jp + 16 + 4 * g]);
+  const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Running key shift: largest bound of this chunk's tokens; when it exceeds the current one the state is rebased.
+// Every wave computes the same numbers (same inputs, same operations).  Returns the new shift (relative to amax).
+__device__ __forceinline__ float key_shift_update(const Smem& sm, int buf, float dk, f32x4 (&T)[4][NVT]) {
+  const f32x4 b4 = *(const f32x4*)(&sm.kbnd[buf][4 * (threadIdx.x & 15)]);      // each row of 16 lanes sees all 64 tokens
+  const float dnew = max16(fmaxf(fmaxf(b4[0], b4[1]), fmaxf(b4[2], b4[3])));
+  if (dnew > dk) {
+    const float f = fast_exp2(dk - dnew);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) T[mt][vt] *= f;
+    return dnew;
+  }
+  return dk;
+}
+
+// ---- exchange of the partial outputs between the four waves ------------------------------------------------------
+// Every wave hands over its partial result for token tile `it` (its own tile included: no branch in the chunk body).
+__device__ __forceinline__ void exchange_put(Smem& sm, const f32x4 (&y)[NVT], int it) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) *(f32x4*)(&sm.xch[it][w][c][16 * vt + 4 * g]) = y[vt];
+}
+
+// After every tile has been put: wave w adds the four parts of token tile w, normalises by row v = 64 and stores.
+__device__ __forceinline__ void exchange_finish(Smem& sm, const TensorDev& Y, long long ybase, int row0, int row_end) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  __syncthreads();
+  f32x4 own[NVT];
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) {
+    own[vt] = *(const f32x4*)(&sm.xch[w][0][c][16 * vt + 4 * g]);
+#pragma unroll
+    for (int src = 1; src < NW; ++src) own[vt] += *(const f32x4*)(&sm.xch[w][src][c][16 * vt + 4 * g]);
+  }
+  const float den = __shfl(own[NVT - 1][0], c);          // row v = 64 lives in lane (g = 0, c), register 0
+  const float inv = den > 0.f ? 1.f / den : 0.f;
+  const int token = row0 + 16 * w + c;
+  if (token < row_end) {
+    if (Y.dtype == 1) {
+      uint16_t* yp = (uint16_t*)Y.ptr + ybase + (long long)token * Y.sl + 4 * g;
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) {
+        const f32x4 v = own[vt] * inv;
+        *(bf16x4*)(yp + 16 * vt) = __builtin_convertvector(v, bf16x4);
+      }
+    } else {
+      float* yp = (float*)Y.ptr + ybase + (long long)token * Y.sl + 4 * g;
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = own[vt] * inv;
+    }
+  }
+}
+
+}  // namespace fast
+
+// Launcher of the causal segment kernel (its own translation unit: it is compiled with different code-generation
+// options than the other kernels of the path).
+int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st);
+
+}  // namespace fs

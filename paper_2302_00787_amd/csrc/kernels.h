@@ -61,20 +61,21 @@ struct FastLaunch {
   const float* Omega;
   int groups, omega_groups, pgroups;
   int B, H, Lq, Lk, causal;
-  int nseg, rows_per_seg;
+  int nseg, rows_per_seg, sub;
   float scale;
   uint16_t* Wbf;    // [pgroups][2][256][64]
   float* bias;      // [pgroups][2][256]
+  float* wnorm;     // [pgroups][2][256]
   float* bounds;    // [pgroups][2][2]
   float* rk;        // [B*H][Lk]
-  float* Tpart;     // [B*H][nseg][256][80]
-  float* cpart;     // [B*H][nseg]
+  float* Tpart;     // [B*H][nseg*sub][256][80]
+  float* cpart;     // [B*H][nseg*sub]
   float* cstar;     // [B*H]
 };
 
 size_t fast_lds_bytes();
 bool fast_supported(int dtype, int d, int dv, int M);
-void fast_plan(int BH, int L, int* nseg, int* rows_per_seg);
+void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub);
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
 
 }  // namespace fs
