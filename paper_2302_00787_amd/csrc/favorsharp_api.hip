@@ -246,7 +246,10 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     return FS_ERR_WORKSPACE_TOO_SMALL;
   if (Lq == 0) return FS_OK;
   const int lds_limit = device_lds_limit();
-  if (fast_supported(Q->dtype, d, dv, M) && (int)fast_lds_bytes() <= lds_limit) {
+  // the bf16 kernels address the rows of a chunk with 32-bit offsets
+  const long long max_sl = 1ll << 23;
+  const bool small_strides = Q->stride_l < max_sl && K->stride_l < max_sl && V->stride_l < max_sl && Y->stride_l < max_sl;
+  if (fast_supported(Q->dtype, d, dv, M) && small_strides && (int)fast_lds_bytes() <= lds_limit) {
     FastPlan fp;
     plan_fast(BH, pgroups, Lk, &fp);
     char* w8 = (char*)workspace;

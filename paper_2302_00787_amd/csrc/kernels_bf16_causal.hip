@@ -7,12 +7,17 @@
 // Wave w owns the 32 random features [32w, 32w+32): its slices of the projection matrix W~ (bf16) and of the state T
 // (fp32, 32 x 80) stay in registers, so every wave needs at most 256 registers, two waves share a SIMD and one wave's
 // exp2 / convert work overlaps the other's MFMAs and LDS waits.  Register-level dataflow, operand layouts and shifts
-// are those described in fast_common.h (with one 32-feature block per wave instead of two).  The partial outputs
-// of the eight waves are exchanged through LDS as bf16; wave w finishes token tile w/2, value columns 32 (w%2) .. +31.
+// are those described in fast_common.h (with one 32-feature block per wave instead of two).
+//
+// The partial outputs of the eight waves (each a sum over that wave's features) are exchanged through LDS as bf16 and
+// summed on the MFMA pipe.  The exchange is pipelined by half chunks so that no wave ever sits in a phase of its own:
+//   barrier X | key side of chunk c, and the finish of token tiles 2, 3 of chunk c-1 | query tiles 0, 1 of chunk c,
+//   and the next chunk's rows go to LDS | barrier Y | query tiles 2, 3, and the finish of token tiles 0, 1 of chunk c.
+// A wave finishes one 16 x 16 piece per half chunk: token tile 2 half + w/4, value columns 16 (w%4) .. +15.
 //
 // Two instantiations: SYM (B1 = B2, the query and key projections share one W~ slice: PosRF, GERF, SDERF; fewer live
-// registers, measurably faster) and the general one; each workgroup looks at the flag of its own parameter set and the
-// instantiation that does not match returns at once.
+// registers) and the general one; each workgroup looks at the flag of its own parameter set and the instantiation
+// that does not match returns at once.
 #include "fast_common.h"
 
 namespace fs {
@@ -29,9 +34,9 @@ struct Smem8 {
   uint16_t k[2][TC][LDR];          // key rows, bf16 bits
   uint16_t q[2][TC][LDR];          // query rows
   uint16_t vt[2][DVP][LDJ];        // values transposed: [column][token]; row 64 = ones, rows 65.. = 0
-  float kadd[2][TC];               // per key token: row term log2e y^T C2 y
+  __attribute__((aligned(16))) float kadd[2][TC];   // per key token t, at index 4 (t%16) + t/16: row term log2e y^T C2 y
   __attribute__((aligned(16))) float kbnd[2][TC];   // per key token: row_shift + row term (-inf past the end)
-  float qadd[2][TC];               // per query token: - row_shift
+  __attribute__((aligned(16))) float qadd[2][TC];   // per query token t, at index 4 (t%16) + t/16: - row_shift
   __attribute__((aligned(16))) uint16_t xch[4][NW8][16][LDXB];   // partial outputs (bf16): [token tile][source wave][token][column]
 };
 
@@ -47,13 +52,34 @@ __device__ __forceinline__ void load_w32(W32& ws, const uint16_t* Wbf) {
       ws.w[mt][ks] = *(const bf16x8*)(Wbf + (size_t)(32 * w + 16 * mt + c) * D + 32 * ks + 8 * g);
 }
 
-// One 16-byte piece per thread of a 64 x 64 bf16 tile: row tid/8, bytes 16 (tid%8).
-__device__ __forceinline__ u32x4 load_row_piece(const uint16_t* base, long long sl, int row0, int row_end) {
-  const int row = threadIdx.x >> 3, pc = threadIdx.x & 7;
-  u32x4 p = {0u, 0u, 0u, 0u};
-  if (row0 + row < row_end) p = *(const u32x4*)(base + (long long)(row0 + row) * sl + pc * 8);
-  return p;
+// Staging, one chunk ahead: every thread carries one 16-byte piece of the query tile, of the key tile (row tid/8,
+// bytes 16 (tid%8)) and of the value tile (token tid%64, bytes 16 (tid/64)).  Addresses are a uniform chunk base plus
+// a 32-bit byte offset per thread that does not change from chunk to chunk.
+struct Stage { u32x4 q, k, v; float rk; };
+
+// Global memory of a chunk is addressed through buffer descriptors: a uniform base (the chunk's first row), a 32-bit
+// byte offset per thread, and a byte count that ends with the last valid row, so that reads past the end of the
+// segment return zero and writes there are dropped, without branches or 64-bit address registers.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void* base, long long sl_bytes, int rows_valid, int row_bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0,
+                                           rows_valid > 0 ? (int)((rows_valid - 1) * sl_bytes + row_bytes) : 0, 0x00020000);
 }
+
+__device__ __forceinline__ void stage_load(Stage& s, const uint16_t* Qb, const uint16_t* Kb, const uint16_t* Vb,
+                                           const FastArgs& a, bool isoC, int bh, int row0, int nv) {
+  const int row = threadIdx.x >> 3, pc = threadIdx.x & 7, j = threadIdx.x & 63, pv = threadIdx.x >> 6;
+  const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(Qb + (long long)row0 * a.Q.sl, 2 * a.Q.sl, nv, 2 * D);
+  const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(Kb + (long long)row0 * a.K.sl, 2 * a.K.sl, nv, 2 * D);
+  const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(Vb + (long long)row0 * a.V.sl, 2 * a.V.sl, nv, 2 * D);
+  s.q = __builtin_amdgcn_raw_buffer_load_b128(rq, 2 * (row * (int)a.Q.sl + pc * 8), 0, 0);
+  s.k = __builtin_amdgcn_raw_buffer_load_b128(rk, 2 * (row * (int)a.K.sl + pc * 8), 0, 0);
+  s.v = __builtin_amdgcn_raw_buffer_load_b128(rv, 2 * (j * (int)a.V.sl + pv * 8), 0, 0);
+  // key row terms of a dense C2 (an empty range, hence zeros, when the closed form -|k|^2/2 applies)
+  const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.rk + (size_t)bh * a.L + row0), 0,
+                                                                      isoC ? 0 : 4 * max(nv, 0), 0x00020000);
+  s.rk = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, 4 * row, 0, 0));
+}
+
 __device__ __forceinline__ float store_row_piece(u32x4 p, uint16_t (*tile)[LDR]) {
   const int row = threadIdx.x >> 3, pc = threadIdx.x & 7;
   *(u32x4*)(&tile[row][pc * 8]) = p;
@@ -65,13 +91,7 @@ __device__ __forceinline__ float store_row_piece(u32x4 p, uint16_t (*tile)[LDR])
   }
   return sum8(s);
 }
-// Values: token tid%64, piece tid/64; lane pairs swap halves so that every lane writes whole dwords.
-__device__ __forceinline__ u32x4 load_val_piece(const uint16_t* base, long long sl, int row0, int row_end) {
-  const int j = threadIdx.x & 63, pc = threadIdx.x >> 6;
-  u32x4 p = {0u, 0u, 0u, 0u};
-  if (row0 + j < row_end) p = *(const u32x4*)(base + (long long)(row0 + j) * sl + pc * 8);
-  return p;
-}
+// Values: lane pairs swap halves so that every lane writes whole dwords {token 2t, token 2t+1} of one column.
 __device__ __forceinline__ void store_val_piece(u32x4 p, uint16_t (*vt)[LDJ], int row0, int row_end) {
   const int j = threadIdx.x & 63, pc = threadIdx.x >> 6, odd = j & 1;
 #pragma unroll
@@ -80,59 +100,128 @@ __device__ __forceinline__ void store_val_piece(u32x4 p, uint16_t (*vt)[LDJ], in
     const uint32_t w = odd ? ((other >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (other << 16));
     *(uint32_t*)(&vt[pc * 8 + 2 * e + odd][j & ~1]) = w;
   }
-  if (threadIdx.x < 32) {
+  if (threadIdx.x < 32) {          // the row of ones (zero past the end of the sequence)
     const int t0 = 2 * threadIdx.x;
-    const uint32_t one = 0x3f80u;     // bf16(1)
+    const uint32_t one = 0x3f80u;  // bf16(1)
     *(uint32_t*)(&vt[D][t0]) = (row0 + t0 < row_end ? one : 0u) | (row0 + t0 + 1 < row_end ? one << 16 : 0u);
   }
 }
 
-struct Stage { u32x4 q, k, v; };
-
-__device__ __forceinline__ void stage_load(Stage& s, const uint16_t* Qb, const uint16_t* Kb, const uint16_t* Vb,
-                                           const FastArgs& a, int row0, int row_end) {
-  s.q = load_row_piece(Qb, a.Q.sl, row0, row_end);
-  s.k = load_row_piece(Kb, a.K.sl, row0, row_end);
-  s.v = load_val_piece(Vb, a.V.sl, row0, row_end);
-}
-
-__device__ __forceinline__ void stage_store(const Stage& s, Smem8& sm, int buf, const FastArgs& a, bool isoC, int bh,
+__device__ __forceinline__ void stage_store(const Stage& s, Smem8& sm, int buf, const FastArgs& a, bool isoC,
                                             int row0, int row_end, float wmax1, float wmax2) {
   const int row = threadIdx.x >> 3;
   const float nq2 = store_row_piece(s.q, sm.q[buf]);
   const float nk2 = store_row_piece(s.k, sm.k[buf]);
   if ((threadIdx.x & 7) == 0) {
     const bool valid = row0 + row < row_end;
-    float rt = -0.5f * kLog2e * a.scale * a.scale * nk2;
-    if (!isoC) rt = valid ? a.rk[(size_t)bh * a.L + row0 + row] : 0.f;
-    sm.qadd[buf][row] = -row_shift(nq2, wmax1);
-    sm.kadd[buf][row] = rt;
+    const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * nk2 : s.rk;
+    const int pos = 4 * (row & 15) + (row >> 4);
+    sm.qadd[buf][pos] = -row_shift(nq2, wmax1);
+    sm.kadd[buf][pos] = rt;
     sm.kbnd[buf][row] = valid ? row_shift(nk2, wmax2) + rt : -INFINITY;
   }
   store_val_piece(s.v, sm.vt[buf], row0, row_end);
 }
 
+// Selection matrices (B operands) that turn an A operand (lane <-> token, k <-> feature) into an accumulator with
+// lane <-> feature: sel[hh] has a one at (k, n) iff k addresses feature 16 hh + n of the 32-feature block.
+__device__ __forceinline__ void make_sel32(bf16x8 sel[2], int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  // the only one of lane (g, c) sits in sel[(c >> 2) == g ? .. ]: element e with e/4 = hh and 4g + e%4 = c
+  const uint32_t one = (c & 1) ? 0x3f800000u : 0x3f80u;
+  const bool mine = (c >> 2) == g;
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    v[2 * hh] = (mine && (c & 2) == 0) ? one : 0u;
+    v[2 * hh + 1] = (mine && (c & 2) != 0) ? one : 0u;
+    sel[hh] = __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+// 16 token rows as MFMA operand: lane <-> token 16 jt + c, k = 32 ks + 8g + e
+struct XOp { bf16x8 b[KS]; };
+__device__ __forceinline__ void load_xop(XOp& x, const uint16_t (*tile)[LDR], int jt) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) x.b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+}
+
 // Feature tile of 16 tokens and this wave's 32 features, packed as an MFMA operand (lane <-> token 16 jt + c,
 // k = 8g + e <-> feature 16 (e/4) + 4g + e%4 of the wave's block).
 template <bool WITH_BIAS>
-__device__ __forceinline__ bf16x8 feature_tile32(const W32& ws, const B32* qb, const uint16_t (*tile)[LDR], int jt, float add) {
-  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
-  bf16x8 b[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+__device__ __forceinline__ bf16x8 feature_tile32(const W32& ws, const B32* qb, const XOp& x, float add) {
   f32x4 acc[2];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
     acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], b[ks], acc[mt]);
+    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], x.b[ks], acc[mt]);
   }
   return pack8(exp2v(acc[0] + add), exp2v(acc[1] + add));
+}
+
+// Finish of one 16 x 16 piece of the output: token tile `it` of a chunk, value columns 16 vt .. +15.  The sum over
+// the eight source waves is itself a contraction, done on the MFMA pipe: B[k = (source, row-in-group)][n = token]
+// straight from the exchange buffer (lanes of group g read sources g and g + 4: their blocks lie 32 banks apart),
+// A = a 0/1 matrix that routes column group q's four rows to accumulator rows 4q .. 4q+3 (four MFMAs fill the
+// tile), and for the normaliser (column 64) a matrix that copies its row everywhere.  Split in two so that the LDS
+// reads can be issued well before their use.
+struct Fin { u32x2 lo[4], hi[4], dlo, dhi; };
+
+__device__ __forceinline__ void finish_issue(Fin& f, const Smem8& sm, int it, int vt) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    f.lo[q] = *(const u32x2*)(&sm.xch[it][g][c][16 * vt + 4 * q]);
+    f.hi[q] = *(const u32x2*)(&sm.xch[it][g + 4][c][16 * vt + 4 * q]);
+  }
+  f.dlo = *(const u32x2*)(&sm.xch[it][g][c][D]);
+  f.dhi = *(const u32x2*)(&sm.xch[it][g + 4][c][D]);
+}
+
+// `chunk_y`: first output row of the chunk (already offset to batch and head); `nv`: its number of valid rows
+// (0: nothing is stored).
+__device__ __forceinline__ void finish_complete(const Fin& f, const TensorDev& Y, long long chunk_row, long long ybase,
+                                                int nv, int it, int vt) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  const uint32_t base0 = (c & 3) == 0 ? 0x3f80u : ((c & 3) == 1 ? 0x3f800000u : 0u);
+  const uint32_t base1 = (c & 3) == 2 ? 0x3f80u : ((c & 3) == 3 ? 0x3f800000u : 0u);
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const u32x4 bq = {f.lo[q][0], f.lo[q][1], f.hi[q][0], f.hi[q][1]};
+    const uint32_t a0 = (c >> 2) == q ? base0 : 0u, a1 = (c >> 2) == q ? base1 : 0u;
+    const u32x4 aq = {a0, a1, a0, a1};
+    sum = mfma(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq), sum);
+  }
+  const u32x4 bd = {f.dlo[0], f.dlo[1], f.dhi[0], f.dhi[1]};
+  const u32x4 ad = {0x3f80u, 0u, 0x3f80u, 0u};
+  const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), __builtin_bit_cast(bf16x8, bd), f32x4{0.f, 0.f, 0.f, 0.f});
+  const float den = dn[0];
+  const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+  const f32x4 v = sum * inv;
+  if (Y.dtype == 1) {
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const uint16_t*)Y.ptr + ybase + chunk_row * Y.sl, 2 * Y.sl, nv, 2 * D);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4)), ry,
+                                          2 * ((16 * it + c) * (int)Y.sl + 16 * vt + 4 * g), 0, 0);
+  } else {
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const float*)Y.ptr + ybase + chunk_row * Y.sl, 4 * Y.sl, nv, 4 * D);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ry,
+                                           4 * ((16 * it + c) * (int)Y.sl + 16 * vt + 4 * g), 0, 0);
+  }
 }
 
 }  // namespace c8
 
 using namespace c8;
+
+#ifdef FS_PROFILE
+__device__ unsigned long long fs_prof[8 * 64 * 16];
+#define FS_TICK(slot) do { if (prof_on && lane == 0) { __builtin_amdgcn_sched_barrier(0); fs_prof[(w * 64 + ci) * 16 + (slot)] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0);} } while (0)
+#else
+#define FS_TICK(slot)
+#endif
 
 // grid (nseg, B*H), block 512.
 template <bool SYM>
@@ -162,8 +251,7 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
     for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (a.bias[((size_t)pg * 2) * M + 32 * w + 16 * mt + 4 * g + r] - amax1);
-  bf16x8 sel[2];
-  make_sel(sel);
+  // padding rows of the transposed value tiles (the staging writes rows 0 .. 64 only)
   for (int idx = threadIdx.x; idx < 2 * (DVP - D - 1) * LDJ; idx += NT8) {
     const int bb = idx / ((DVP - D - 1) * LDJ), rem = idx - bb * (DVP - D - 1) * LDJ;
     sm.vt[bb][D + 1 + rem / LDJ][rem % LDJ] = 0;
@@ -182,17 +270,26 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
 
   const int row_beg = seg * a.rows_per_seg, row_end = min(a.L, row_beg + a.rows_per_seg);
   Stage stg;
-  stage_load(stg, Qb, Kb, Vb, a, row_beg, row_end);
-  stage_store(stg, sm, 0, a, isoC, bh, row_beg, row_end, wmax1, wmax2);
-  __syncthreads();
+  stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row_beg, min(TC, row_end - row_beg));
+  stage_store(stg, sm, 0, a, isoC, row_beg, row_end, wmax1, wmax2);
 
-  // this wave finishes token tile w/2, value tiles 2 (w%2) and 2 (w%2) + 1
-  const int oit = w >> 1, ovt = 2 * (w & 1);
+  // the pieces this wave finishes: token tile 2 half + fit, value tile fvt
+  const int fit = w >> 2, fvt = w & 3;
 
   int buf = 0;
+#ifdef FS_PROFILE
+  const bool prof_on = seg == 3 && bh == 5;
+  int ci = -1;
+#endif
   for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
-    const bool more = row0 + TC < row_end;
-    if (more) stage_load(stg, Qb, Kb, Vb, a, row0 + TC, row_end);
+    __syncthreads();               // barrier X: staged rows of this chunk and query tiles 2, 3 of the previous one are complete
+#ifdef FS_PROFILE
+    ++ci;
+    if (prof_on && lane == 0) fs_prof[(w * 64 + ci) * 16 + 15] = wall_clock64();
+#endif
+    FS_TICK(0);
+    // next chunk's rows (an empty range, hence zeros that nobody reads, after the last chunk)
+    stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row0 + TC, min(TC, row_end - row0 - TC));
 
     // running key shift (every wave computes the same numbers); the state is rebased when it grows
     {
@@ -208,6 +305,23 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
       }
     }
 
+    // Operands are fetched from LDS one tile ahead of their use; the fences keep that order in the schedule.
+    const f32x4 kadd4 = *(const f32x4*)(&sm.kadd[buf][4 * c]);
+    const f32x4 qadd4 = *(const f32x4*)(&sm.qadd[buf][4 * c]);
+    XOp xo[2];
+    load_xop(xo[0], sm.k[buf], 0);
+    Fin fin;
+    finish_issue(fin, sm, 2 + fit, fvt);       // previous chunk, second half
+
+    // The selection matrices of the key side are rebuilt every chunk (a dozen instructions) instead of occupying
+    // eight registers through the query side; the opaque copy of the lane number keeps them from being hoisted.
+    bf16x8 sel[2];
+    {
+      int lane_here = lane;
+      asm volatile("" : "+v"(lane_here));
+      make_sel32(sel, lane_here);
+    }
+
     // state before this chunk as A operand (T^T: row v = 16 vt + c, k <-> feature)
     bf16x8 tb[NVT];
 #pragma unroll
@@ -215,28 +329,47 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
 
     // key side: S (lane <-> token) for the scores, S^T (lane <-> feature) for the state update, pair by pair
     bf16x8 s[4];
+    bf16x8 vop[2][NVT];
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
       f32x4 tr[2][2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int jt = 2 * jp + jj;
-        s[jt] = feature_tile32<false>(wk, nullptr, sm.k[buf], jt, sm.kadd[buf][16 * jt + c] - dk);
+        if (jt < 3) load_xop(xo[(jt + 1) & 1], sm.k[buf], jt + 1);
+        else load_xop(xo[(jt + 1) & 1], sm.q[buf], 0);
+        if (jj == 0) {
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) vop[jp][vt] = load_vop(sm.vt[buf], jp, vt);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        s[jt] = feature_tile32<false>(wk, nullptr, xo[jt & 1], kadd4[jt] - dk);
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) tr[jj][hh] = mfma(s[jt], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
+        // the previous chunk's second half leaves (nothing is stored on the first pass: there is no previous chunk)
+        if (jt == 0) finish_complete(fin, a.Y, row0 - TC, ybase, row0 > row_beg ? TC : 0, 2 + fit, fvt);
       }
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
         const bf16x8 st = pack8(tr[0][mt], tr[1][mt]);
 #pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(st, load_vop(sm.vt[buf], jp, vt), T[mt][vt]);
+        for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(st, vop[jp][vt], T[mt][vt]);
       }
     }
+    FS_TICK(1);
 
     // query side, one token tile at a time
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      const bf16x8 p = feature_tile32<true>(wq, &qb, sm.q[buf], it, sm.qadd[buf][16 * it + c]);
+      if (it == 2) {
+        FS_TICK(2);
+        __syncthreads();           // barrier Y: query tiles 0, 1 and the next chunk's staged rows are complete
+        FS_TICK(3);
+        finish_issue(fin, sm, fit, fvt);
+      }
+      if (it < 3) load_xop(xo[(it + 1) & 1], sm.q[buf], it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      const bf16x8 p = feature_tile32<true>(wq, &qb, xo[it & 1], qadd4[it]);
       f32x4 y[NVT];
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(tb[vt], p, f32x4{0.f, 0.f, 0.f, 0.f});
@@ -259,60 +392,26 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
           }
           const bf16x8 sb = pack8(sc[0], sc[1]);
 #pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(load_vop(sm.vt[buf], jp, vt), sb, y[vt]);
+          for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(jp == 0 ? vop[0][vt] : load_vop(sm.vt[buf], 1, vt), sb, y[vt]);
         }
       }
       // hand the partial tile over (bf16): rows v = 16 vt + 4g + r of token column c
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt)
         *(bf16x4*)(&sm.xch[it][w][c][16 * vt + 4 * g]) = __builtin_convertvector(y[vt], bf16x4);
+      // the staged rows of the next chunk go to LDS between the two barriers
+      if (it == 1) stage_store(stg, sm, buf ^ 1, a, isoC, row0 + TC, row_end, wmax1, wmax2);
+      if (it == 2) finish_complete(fin, a.Y, row0, ybase, min(TC, row_end - row0), fit, fvt);
     }
-    __syncthreads();
-
-    // finish: sum the eight parts of (token tile oit, value tiles ovt, ovt + 1) and of the normaliser row v = 64.
-    // The sum over the source waves is itself a contraction, done on the MFMA pipe: B[k = (source, row-in-group)][n =
-    // token] straight from the exchange buffer, A = a 0/1 matrix that routes group q's four rows to accumulator rows
-    // 4q .. 4q+3 (so four MFMAs fill one 16 x 16 tile), and for the normaliser a matrix that copies its row everywhere.
-    {
-      const uint32_t base0 = (c & 3) == 0 ? 0x3f80u : ((c & 3) == 1 ? 0x3f800000u : 0u);
-      const uint32_t base1 = (c & 3) == 2 ? 0x3f80u : ((c & 3) == 3 ? 0x3f800000u : 0u);
-      f32x4 sum[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const u32x2 lo = *(const u32x2*)(&sm.xch[oit][2 * g][c][16 * (ovt + u) + 4 * q]);
-          const u32x2 hi = *(const u32x2*)(&sm.xch[oit][2 * g + 1][c][16 * (ovt + u) + 4 * q]);
-          const u32x4 bq = {lo[0], lo[1], hi[0], hi[1]};
-          const uint32_t a0 = (c >> 2) == q ? base0 : 0u, a1 = (c >> 2) == q ? base1 : 0u;
-          const u32x4 aq = {a0, a1, a0, a1};
-          sum[u] = mfma(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq), sum[u]);
-        }
-      const u32x2 dlo = *(const u32x2*)(&sm.xch[oit][2 * g][c][D]);
-      const u32x2 dhi = *(const u32x2*)(&sm.xch[oit][2 * g + 1][c][D]);
-      const u32x4 bd = {dlo[0], dlo[1], dhi[0], dhi[1]};
-      const u32x4 ad = {0x3f80u, 0u, 0x3f80u, 0u};
-      const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), __builtin_bit_cast(bf16x8, bd), f32x4{0.f, 0.f, 0.f, 0.f});
-      const float den = dn[0];
-      const float inv = den > 0.f ? 1.f / den : 0.f;
-      const int token = row0 + 16 * oit + c;
-      if (token < row_end) {
-        if (a.Y.dtype == 1) {
-          uint16_t* yp = (uint16_t*)a.Y.ptr + ybase + (long long)token * a.Y.sl + 16 * ovt + 4 * g;
-#pragma unroll
-          for (int u = 0; u < 2; ++u) {
-            const f32x4 v = sum[u] * inv;
-            *(bf16x4*)(yp + 16 * u) = __builtin_convertvector(v, bf16x4);
-          }
-        } else {
-          float* yp = (float*)a.Y.ptr + ybase + (long long)token * a.Y.sl + 16 * ovt + 4 * g;
-#pragma unroll
-          for (int u = 0; u < 2; ++u) *(f32x4*)(yp + 16 * u) = sum[u] * inv;
-        }
-      }
-    }
-    if (more) stage_store(stg, sm, buf ^ 1, a, isoC, bh, row0 + TC, row_end, wmax1, wmax2);
-    __syncthreads();
+    FS_TICK(4);
+  }
+  // second half of the last chunk
+  __syncthreads();
+  {
+    const int last0 = row_beg + ((row_end - row_beg - 1) / TC) * TC;
+    Fin fin;
+    finish_issue(fin, sm, 2 + fit, fvt);
+    if (row_end > row_beg) finish_complete(fin, a.Y, last0, ybase, row_end - last0, 2 + fit, fvt);
   }
 }
 
@@ -331,3 +430,9 @@ int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st) {
 }
 
 }  // namespace fs
+
+#ifdef FS_PROFILE
+extern "C" int favorsharp_prof_read(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(fs::fs_prof), sizeof(unsigned long long) * 8 * 64 * 16);
+}
+#endif
