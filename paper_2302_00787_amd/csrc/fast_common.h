@@ -84,6 +84,13 @@ __device__ __forceinline__ float max16(float v) {
   return v;
 }
 
+// Largest of 256 floats (16-byte aligned), as a wave-uniform value.
+__device__ __forceinline__ float max256(const float* p) {
+  const f32x4 v = *(const f32x4*)(p + 4 * (threadIdx.x & 63));
+  const float m = wave_max(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, m)));
+}
+
 // Per-token shift of the projection part W~_m . x of the exponent.  With cs = max_m |W~_m| |x| (Cauchy-Schwarz)
 // the projection never exceeds cs; random directions reach about 0.4 cs.  max(cs/2, cs - 120) keeps the largest
 // shifted exponent below 2^120 for every input and near zero for ordinary ones.
@@ -109,7 +116,7 @@ struct FastArgs {
   TensorDev Q, K, V, Y;
   const uint16_t* Wbf;     // [pg][2][M][D]
   const float* bias;       // [pg][2][M]
-  const float* bounds;     // [pg][2][2]: max_m |Wbf_m|, max_m bias
+  const float* wnorm;      // [pg][2][M]: |Wbf_m|
   const float* theta;
   const float* rk;         // [BH][L] key row terms for parameter sets with a dense C2, else unused
   float* Tpart;            // [BH][nslot][M][DVP], nslot = nseg * sub: one state per sub-segment

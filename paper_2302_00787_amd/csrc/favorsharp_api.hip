@@ -77,7 +77,7 @@ void plan_fit(int B, int H, int Lx, int Ly, int d, int groups, FitPlan* p) {
 
 struct FastPlan {
   int pgroups, nseg, rows_per_seg, sub;
-  size_t off_Wbf, off_bias, off_wnorm, off_bounds, off_rk, off_state, off_cpart, off_cstar, total;
+  size_t off_Wbf, off_bias, off_wnorm, off_rk, off_state, off_cpart, off_cstar, total;
 };
 
 void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
@@ -87,7 +87,6 @@ void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
   p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 256 * 64 * sizeof(uint16_t));
   p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 256 * sizeof(float));
   p->off_wnorm = off;  off = align_up(off + (size_t)pgroups * 2 * 256 * sizeof(float));
-  p->off_bounds = off; off = align_up(off + (size_t)pgroups * 4 * sizeof(float));
   p->off_rk = off;     off = align_up(off + (size_t)BH * Lk * sizeof(float));
   p->off_state = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * 256 * 80 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * sizeof(float));
@@ -260,7 +259,6 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     f.B = B; f.H = H; f.Lq = Lq; f.Lk = Lk; f.causal = causal;
     f.nseg = fp.nseg; f.rows_per_seg = fp.rows_per_seg; f.sub = fp.sub; f.scale = qk_scale;
     f.Wbf = (uint16_t*)(w8 + fp.off_Wbf); f.bias = (float*)(w8 + fp.off_bias); f.wnorm = (float*)(w8 + fp.off_wnorm);
-    f.bounds = (float*)(w8 + fp.off_bounds);
     f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
     f.cstar = (float*)(w8 + fp.off_cstar);
     return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);

@@ -66,7 +66,6 @@ struct FastLaunch {
   uint16_t* Wbf;    // [pgroups][2][256][64]
   float* bias;      // [pgroups][2][256]
   float* wnorm;     // [pgroups][2][256]
-  float* bounds;    // [pgroups][2][2]
   float* rk;        // [B*H][Lk]
   float* Tpart;     // [B*H][nseg*sub][256][80]
   float* cpart;     // [B*H][nseg*sub]

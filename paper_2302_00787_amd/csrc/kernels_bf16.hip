@@ -11,64 +11,53 @@ namespace fs {
 using namespace fast;
 
 // ---------------------------------------------------------------------------------------------------
-// Projection constants (Section 4, evaluation recipe): Wbf[pg][side][m][:] = bf16(qk_scale log2e omega_m^T B),
-// bias[pg][side][m] = log2e (omega_m^T A omega_m + log D - 1/2 log M), wnorm[pg][side][m] = |Wbf_m|.
-// grid (M/4, 2, pgroups), block 256: one wave per feature, one lane per column.
+// Per-call constants, one launch.  grid 128 * pgroups + rowblocks * B*H workgroups of 256 threads:
+//
+// workgroups [0, 128 pgroups): projection constants (Section 4, evaluation recipe), one wave per feature, one lane
+// per column: Wbf[pg][side][m][:] = bf16(qk_scale log2e omega_m^T B), bias[pg][side][m] = log2e (omega_m^T A omega_m
+// + log D - 1/2 log M), wnorm[pg][side][m] = |Wbf_m|.
+//
+// the other workgroups: key-side row term log2e * y^T C2 y for parameter sets whose C2 is not -I/2 (ADERF, SADERF);
+// workgroups of sets with the -I/2 flag return at once (the kernels then use -|y|^2/2).  One wave per token
+// (grid-stride over the tokens of a sequence), lane a handles row a of C2.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_fast_prep(const float* theta, int groups, const float* Omega,
-                                                   int omega_groups, int pgroups, int B, int H, float scale,
-                                                   uint16_t* Wbf, float* bias, float* wnorm) {
-  const int m = blockIdx.x * 4 + (threadIdx.x >> 6), c = threadIdx.x & 63, side = blockIdx.y, pg = blockIdx.z;
-  int b = 0, h = 0;
-  if (pgroups == H && pgroups != 1) h = pg;
-  else if (pgroups != 1) { b = pg / H; h = pg % H; }
+__global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups, const float* Omega, int omega_groups,
+                                                  int pgroups, int B, int H, float scale, uint16_t* Wbf, float* bias,
+                                                  float* wnorm, TensorDev K, int L, int rowblocks, float* rk) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D;
-  const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
-  const float* om = Omega + ((size_t)group_of(omega_groups, b, h, H) * M + m) * D;
-  const float* Bm = th + FS_THETA_HEADER_ + D + (side ? (size_t)D * D : 0);
-  const float* A = th + FS_THETA_HEADER_;
-  const size_t o = ((size_t)pg * 2 + side) * M + m;
-  float acc = 0.f;
+  const int nprep = (M / 4) * 2 * pgroups;
+  if ((int)blockIdx.x < nprep) {
+    const int pg = blockIdx.x / ((M / 4) * 2), rem = blockIdx.x % ((M / 4) * 2), side = rem / (M / 4);
+    const int m = (rem % (M / 4)) * 4 + (threadIdx.x >> 6), c = threadIdx.x & 63;
+    int b = 0, h = 0;
+    if (pgroups == H && pgroups != 1) h = pg;
+    else if (pgroups != 1) { b = pg / H; h = pg % H; }
+    const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
+    const float* om = Omega + ((size_t)group_of(omega_groups, b, h, H) * M + m) * D;
+    const float* Bm = th + FS_THETA_HEADER_ + D + (side ? (size_t)D * D : 0);
+    const float* A = th + FS_THETA_HEADER_;
+    const size_t o = ((size_t)pg * 2 + side) * M + m;
+    float acc = 0.f;
 #pragma unroll 8
-  for (int l = 0; l < D; ++l) acc += om[l] * Bm[l * D + c];
-  const uint16_t bits = f32_to_bf16_bits(acc * kLog2e * scale);
-  Wbf[o * D + c] = bits;
-  const float r = bf16_bits_to_f32(bits);
-  float n2 = r * r, q = A[c] * om[c] * om[c];
+    for (int l = 0; l < D; ++l) acc += om[l] * Bm[l * D + c];
+    const uint16_t bits = f32_to_bf16_bits(acc * kLog2e * scale);
+    Wbf[o * D + c] = bits;
+    const float r = bf16_bits_to_f32(bits);
+    float n2 = r * r, q = A[c] * om[c] * om[c];
 #pragma unroll
-  for (int s = 1; s < 64; s <<= 1) { n2 += __shfl_xor(n2, s); q += __shfl_xor(q, s); }
-  if (c == 0) {
-    bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)M));
-    wnorm[o] = sqrtf(n2);
+    for (int s = 1; s < 64; s <<= 1) { n2 += __shfl_xor(n2, s); q += __shfl_xor(q, s); }
+    if (c == 0) {
+      bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)M));
+      wnorm[o] = sqrtf(n2);
+    }
+    return;
   }
-}
-
-// bounds[pg][side] = {max_m wnorm, max_m bias}.  grid (2, pgroups), block 256 (= M).
-__global__ void __launch_bounds__(256) k_fast_bounds(const float* bias, const float* wnorm, float* bounds) {
-  __shared__ float red[2][4];
-  const size_t o = ((size_t)blockIdx.y * 2 + blockIdx.x) * M + threadIdx.x;
-  const float wn = wave_max(wnorm[o]), bm = wave_max(bias[o]);
-  if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = wn; red[1][threadIdx.x >> 6] = bm; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    float* out = bounds + ((size_t)blockIdx.y * 2 + blockIdx.x) * 2;
-    out[0] = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
-    out[1] = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
-  }
-}
-
-// Key-side row term log2e * y^T C2 y for parameter sets whose C2 is not -I/2 (ADERF, SADERF); workgroups of sets
-// with the -I/2 flag return at once (the kernels then use -|y|^2/2).  grid (<= 64, B*H), block 256: one wave
-// per token (grid-stride over the tokens), lane a handles row a of C2.
-__global__ void __launch_bounds__(256) k_fast_rowterm(TensorDev K, int L, int H, const float* theta, int groups,
-                                                      float scale, float* rk) {
-  const int bh = blockIdx.y, b = bh / H, h = bh % H;
-  const size_t tf = FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D;
+  const int rb = blockIdx.x - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
   const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
   if (((int)th[2]) & 1) return;
   const float* C2 = th + FS_THETA_HEADER_ + D + 3 * (size_t)D * D;
   const int a = threadIdx.x & 63;
-  for (int j = blockIdx.x * 4 + (threadIdx.x >> 6); j < L; j += 4 * gridDim.x) {
+  for (int j = blk * 4 + (threadIdx.x >> 6); j < L; j += 4 * rowblocks) {
     const uint16_t* row = (const uint16_t*)K.ptr + b * K.sb + h * K.sh + (long long)j * K.sl;
     const float ya = scale * bf16_bits_to_f32(row[a]);
     float t = 0.f;
@@ -93,7 +82,7 @@ __global__ void __launch_bounds__(NT) k_fast_state(FastArgs a) {
   const int pg = group_of(a.pgroups, b, h, a.H);
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
   const bool isoC = ((int)th[2]) & 1;
-  const float wmax = a.bounds[((size_t)pg * 2 + 1) * 2];
+  const float wmax = max256(a.wnorm + ((size_t)pg * 2 + 1) * M);
   const int rows_per_slot = a.rows_per_seg / a.sub;
   const uint16_t* Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
   const uint16_t* Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
@@ -184,7 +173,7 @@ __global__ void __launch_bounds__(NT) k_fast_apply(FastArgs a, int Lq, int rows_
   const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
-  const float wmax = a.bounds[((size_t)pg * 2) * 2], amax = a.bounds[((size_t)pg * 2) * 2 + 1];
+  const float wmax = max256(a.wnorm + ((size_t)pg * 2) * M), amax = max256(a.bias + ((size_t)pg * 2) * M);
   const uint16_t* Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   const long long ybase = b * a.Y.sb + h * a.Y.sh;
 
@@ -259,19 +248,15 @@ static int set_fast_lds(const void* fn) {
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   FastArgs a;
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
-  a.Wbf = f.Wbf; a.bias = f.bias; a.bounds = f.bounds; a.theta = f.theta; a.rk = f.rk;
+  a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.theta = f.theta; a.rk = f.rk;
   a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
   a.groups = f.groups; a.pgroups = f.pgroups; a.H = f.H; a.L = f.Lk; a.rows_per_seg = f.rows_per_seg; a.nseg = f.nseg;
   a.sub = f.sub; a.nslot = f.nseg * f.sub;
   a.scale = f.scale;
   const int BH = f.B * f.H;
-  hipLaunchKernelGGL(k_fast_prep, dim3(M / 4, 2, f.pgroups), dim3(256), 0, st, f.theta, f.groups, f.Omega,
-                     f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm);
-  FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_fast_bounds, dim3(2, f.pgroups), dim3(256), 0, st, f.bias, f.wnorm, f.bounds);
-  FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_fast_rowterm, dim3(std::min(64, (f.Lk + 3) / 4), BH), dim3(256), 0, st, f.K, f.Lk, f.H, f.theta, f.groups,
-                     f.scale, f.rk);
+  const int rowblocks = std::min(64, (f.Lk + 3) / 4);
+  hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * f.pgroups + rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
+                     f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk);
   FS_LAUNCH_CHECK();
   if (int rc = set_fast_lds((const void*)k_fast_apply)) return rc;
   // the last segment's states are never needed by the causal pass

@@ -17,7 +17,7 @@
 //
 // Two instantiations: SYM (B1 = B2, the query and key projections share one W~ slice: PosRF, GERF, SDERF; fewer live
 // registers) and the general one; each workgroup looks at the flag of its own parameter set and the instantiation
-// that does not match returns at once.
+// that does not match returns at once.  (One kernel holding both loops allocates registers worse for both.)
 #include "fast_common.h"
 
 namespace fs {
@@ -147,18 +147,22 @@ __device__ __forceinline__ void load_xop(XOp& x, const uint16_t (*tile)[LDR], in
   for (int ks = 0; ks < KS; ++ks) x.b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
 }
 
-// Feature tile of 16 tokens and this wave's 32 features, packed as an MFMA operand (lane <-> token 16 jt + c,
-// k = 8g + e <-> feature 16 (e/4) + 4g + e%4 of the wave's block).
+// Feature tile of 16 tokens and this wave's 32 features in two steps, so that the exp2 / convert work of one tile can
+// be interleaved with the MFMAs that consume the previous one: the projection (accumulators: rows = features
+// 16 mt + 4g + r, column = token c), then the packed MFMA operand (lane <-> token 16 jt + c, k = 8g + e <-> feature
+// 16 (e/4) + 4g + e%4 of the wave's block).
+struct Proj { f32x4 acc[2]; };
 template <bool WITH_BIAS>
-__device__ __forceinline__ bf16x8 feature_tile32(const W32& ws, const B32* qb, const XOp& x, float add) {
-  f32x4 acc[2];
+__device__ __forceinline__ void project(Proj& pr, const W32& ws, const B32* qb, const XOp& x) {
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
-    acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
+    pr.acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], x.b[ks], acc[mt]);
+    for (int ks = 0; ks < KS; ++ks) pr.acc[mt] = mfma(ws.w[mt][ks], x.b[ks], pr.acc[mt]);
   }
-  return pack8(exp2v(acc[0] + add), exp2v(acc[1] + add));
+}
+__device__ __forceinline__ bf16x8 expack(const Proj& pr, float add) {
+  return pack8(exp2v(pr.acc[0] + add), exp2v(pr.acc[1] + add));
 }
 
 // Finish of one 16 x 16 piece of the output: token tile `it` of a chunk, value columns 16 vt .. +15.  The sum over
@@ -235,8 +239,8 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
   const bool isoC = flags & 1;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
-  const float wmax1 = a.bounds[((size_t)pg * 2) * 2], amax1 = a.bounds[((size_t)pg * 2) * 2 + 1];
-  const float wmax2 = a.bounds[((size_t)pg * 2 + 1) * 2];
+  const float wmax1 = max256(a.wnorm + ((size_t)pg * 2) * M), amax1 = max256(a.bias + ((size_t)pg * 2) * M);
+  const float wmax2 = max256(a.wnorm + ((size_t)pg * 2 + 1) * M);
   const uint16_t* Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   const uint16_t* Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
   const uint16_t* Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
@@ -327,33 +331,47 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
 #pragma unroll
     for (int vt = 0; vt < NVT; ++vt) tb[vt] = pack8(T[0][vt], T[1][vt]);
 
-    // key side: S (lane <-> token) for the scores, S^T (lane <-> feature) for the state update, pair by pair
+    // Software pipeline over the eight feature tiles of the chunk (keys 0..3, queries 0..3): the projection of tile
+    // n+1 is issued ahead of the MFMAs that consume tile n, and its exp2 / convert work follows them in program order,
+    // so that the two kinds of work are independent neighbours which the hardware can run side by side.
     bf16x8 s[4];
-    bf16x8 vop[2][NVT];
+    bf16x8 vop0[NVT];
+    Proj pr;
+    project<false>(pr, wk, nullptr, xo[0]);
+    load_xop(xo[1], sm.k[buf], 1);
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt) vop0[vt] = load_vop(sm.vt[buf], 0, vt);
+    s[0] = expack(pr, kadd4[0] - dk);
+    bf16x8 p;
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
       f32x4 tr[2][2];
 #pragma unroll
       for (int jj = 0; jj < 2; ++jj) {
         const int jt = 2 * jp + jj;
-        if (jt < 3) load_xop(xo[(jt + 1) & 1], sm.k[buf], jt + 1);
-        else load_xop(xo[(jt + 1) & 1], sm.q[buf], 0);
-        if (jj == 0) {
-#pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) vop[jp][vt] = load_vop(sm.vt[buf], jp, vt);
-        }
+        // operands two tiles ahead
+        if (jt < 2) load_xop(xo[jt & 1], sm.k[buf], jt + 2);
+        else load_xop(xo[jt & 1], sm.q[buf], jt - 2);
         __builtin_amdgcn_sched_barrier(0);
-        s[jt] = feature_tile32<false>(wk, nullptr, xo[jt & 1], kadd4[jt] - dk);
+        // projection of the next tile
+        if (jt < 3) project<false>(pr, wk, nullptr, xo[(jt + 1) & 1]);
+        else project<true>(pr, wq, &qb, xo[(jt + 1) & 1]);
+        // consumers of this tile
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) tr[jj][hh] = mfma(s[jt], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-        // the previous chunk's second half leaves (nothing is stored on the first pass: there is no previous chunk)
         if (jt == 0) finish_complete(fin, a.Y, row0 - TC, ybase, row0 > row_beg ? TC : 0, 2 + fit, fvt);
-      }
+        if (jj == 1) {
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const bf16x8 st = pack8(tr[0][mt], tr[1][mt]);
+          for (int mt = 0; mt < 2; ++mt) {
+            const bf16x8 st = pack8(tr[0][mt], tr[1][mt]);
 #pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(st, vop[jp][vt], T[mt][vt]);
+            for (int vt = 0; vt < NVT; ++vt)
+              T[mt][vt] = mfma(st, jp == 0 ? vop0[vt] : load_vop(sm.vt[buf], 1, vt), T[mt][vt]);
+          }
+        }
+        // exp2 / convert of the next tile
+        if (jt < 3) s[jt + 1] = expack(pr, kadd4[jt + 1] - dk);
+        else p = expack(pr, qadd4[0]);
       }
     }
     FS_TICK(1);
@@ -367,9 +385,9 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
         FS_TICK(3);
         finish_issue(fin, sm, fit, fvt);
       }
-      if (it < 3) load_xop(xo[(it + 1) & 1], sm.q[buf], it + 1);
+      if (it < 2) load_xop(xo[it & 1], sm.q[buf], it + 2);
       __builtin_amdgcn_sched_barrier(0);
-      const bf16x8 p = feature_tile32<true>(wq, &qb, xo[it & 1], qadd4[it]);
+      if (it < 3) project<true>(pr, wq, &qb, xo[(it + 1) & 1]);
       f32x4 y[NVT];
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(tb[vt], p, f32x4{0.f, 0.f, 0.f, 0.f});
@@ -392,9 +410,10 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
           }
           const bf16x8 sb = pack8(sc[0], sc[1]);
 #pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(jp == 0 ? vop[0][vt] : load_vop(sm.vt[buf], 1, vt), sb, y[vt]);
+          for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(jp == 0 ? vop0[vt] : load_vop(sm.vt[buf], 1, vt), sb, y[vt]);
         }
       }
+      if (it < 3) p = expack(pr, qadd4[it + 1]);
       // hand the partial tile over (bf16): rows v = 16 vt + 4g + r of token column c
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt)
