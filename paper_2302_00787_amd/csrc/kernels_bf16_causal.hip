@@ -28,7 +28,7 @@ namespace c8 {
 
 constexpr int NW8 = 8;             // waves per workgroup, 32 features each
 constexpr int NT8 = NW8 * 64;
-constexpr int LDXB = DVP + 4;      // row stride (bf16 elements) of the exchange buffer: 42 dwords, conflict-free b64 access
+constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the exchange buffer: 176 bytes, so that the paired reads of the finish are 16-byte aligned; 44 dwords, conflict-free b64 writes and b128 reads
 
 struct Smem8 {
   uint16_t k[2][TC][LDR];          // key rows, bf16 bits
