@@ -10,10 +10,9 @@
 // are those described in fast_common.h (with one 32-feature block per wave instead of two).
 //
 // The partial outputs of the eight waves (each a sum over that wave's features) are exchanged through LDS as bf16 and
-// summed on the MFMA pipe.  The exchange is pipelined by half chunks so that no wave ever sits in a phase of its own:
-//   barrier X | key side of chunk c, and the finish of token tiles 2, 3 of chunk c-1 | query tiles 0, 1 of chunk c,
-//   and the next chunk's rows go to LDS | barrier Y | query tiles 2, 3, and the finish of token tiles 0, 1 of chunk c.
-// A wave finishes one 16 x 16 piece per half chunk: token tile 2 half + w/4, value columns 16 (w%4) .. +15.
+// summed on the MFMA pipe, one chunk behind: barrier X | key side of chunk c, and the finish of chunk c-1 (wave w:
+// token tile w/2, value columns 32 (w%2) .. +31) | barrier Y | query side of chunk c (writes the exchange buffer),
+// and the next chunk's rows go to LDS.  So no wave ever sits in a phase of its own.
 //
 // Two instantiations: SYM (B1 = B2, the query and key projections share one W~ slice: PosRF, GERF, SDERF; fewer live
 // registers) and the general one; each workgroup looks at the flag of its own parameter set and the instantiation
@@ -28,7 +27,7 @@ namespace c8 {
 
 constexpr int NW8 = 8;             // waves per workgroup, 32 features each
 constexpr int NT8 = NW8 * 64;
-constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the exchange buffer: 176 bytes, so that the paired reads of the finish are 16-byte aligned; 44 dwords, conflict-free b64 writes and b128 reads
+constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the exchange buffer: 176 bytes = 44 dwords: 16-byte accesses of 8 consecutive rows hit 32 different banks
 
 struct Smem8 {
   uint16_t k[2][TC][LDR];          // key rows, bf16 bits
@@ -37,7 +36,10 @@ struct Smem8 {
   __attribute__((aligned(16))) float kadd[2][TC];   // per key token t, at index 4 (t%16) + t/16: row term log2e y^T C2 y
   __attribute__((aligned(16))) float kbnd[2][TC];   // per key token: row_shift + row term (-inf past the end)
   __attribute__((aligned(16))) float qadd[2][TC];   // per query token t, at index 4 (t%16) + t/16: - row_shift
-  __attribute__((aligned(16))) uint16_t xch[4][NW8][16][LDXB];   // partial outputs (bf16): [token tile][source wave][token][column]
+  // partial outputs (bf16): [token tile][source wave][token][position]; value column 16 vt + 4 g + r sits at position
+  // 32 (vt/2) + 8 g + 4 (vt%2) + r (a lane writes two value tiles with one 16-byte store), the normaliser tile
+  // (vt = 4) at 64 + 4 g + r
+  __attribute__((aligned(16))) uint16_t xch[4][NW8][16][LDXB];
 };
 
 struct W32 { bf16x8 w[2][KS]; };   // rows = features 32w + 16mt + c, k = 32ks + 8g + e
@@ -66,8 +68,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void* base, l
 }
 
 __device__ __forceinline__ void stage_load(Stage& s, const uint16_t* Qb, const uint16_t* Kb, const uint16_t* Vb,
-                                           const FastArgs& a, bool isoC, int bh, int row0, int nv) {
-  const int row = threadIdx.x >> 3, pc = threadIdx.x & 7, j = threadIdx.x & 63, pv = threadIdx.x >> 6;
+                                           const FastArgs& a, bool isoC, int bh, int row0, int nv, int tid) {
+  const int row = tid >> 3, pc = tid & 7, j = tid & 63, pv = tid >> 6;
   const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(Qb + (long long)row0 * a.Q.sl, 2 * a.Q.sl, nv, 2 * D);
   const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(Kb + (long long)row0 * a.K.sl, 2 * a.K.sl, nv, 2 * D);
   const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(Vb + (long long)row0 * a.V.sl, 2 * a.V.sl, nv, 2 * D);
@@ -80,8 +82,8 @@ __device__ __forceinline__ void stage_load(Stage& s, const uint16_t* Qb, const u
   s.rk = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, 4 * row, 0, 0));
 }
 
-__device__ __forceinline__ float store_row_piece(u32x4 p, uint16_t (*tile)[LDR]) {
-  const int row = threadIdx.x >> 3, pc = threadIdx.x & 7;
+__device__ __forceinline__ float store_row_piece(u32x4 p, uint16_t (*tile)[LDR], int tid) {
+  const int row = tid >> 3, pc = tid & 7;
   *(u32x4*)(&tile[row][pc * 8]) = p;
   float s = 0.f;
 #pragma unroll
@@ -92,27 +94,27 @@ __device__ __forceinline__ float store_row_piece(u32x4 p, uint16_t (*tile)[LDR])
   return sum8(s);
 }
 // Values: lane pairs swap halves so that every lane writes whole dwords {token 2t, token 2t+1} of one column.
-__device__ __forceinline__ void store_val_piece(u32x4 p, uint16_t (*vt)[LDJ], int row0, int row_end) {
-  const int j = threadIdx.x & 63, pc = threadIdx.x >> 6, odd = j & 1;
+__device__ __forceinline__ void store_val_piece(u32x4 p, uint16_t (*vt)[LDJ], int row0, int row_end, int tid) {
+  const int j = tid & 63, pc = tid >> 6, odd = j & 1;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const uint32_t mine = p[e], other = dpp_u<0xB1>(mine);
     const uint32_t w = odd ? ((other >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (other << 16));
     *(uint32_t*)(&vt[pc * 8 + 2 * e + odd][j & ~1]) = w;
   }
-  if (threadIdx.x < 32) {          // the row of ones (zero past the end of the sequence)
-    const int t0 = 2 * threadIdx.x;
+  if (tid < 32) {                  // the row of ones (zero past the end of the sequence)
+    const int t0 = 2 * tid;
     const uint32_t one = 0x3f80u;  // bf16(1)
     *(uint32_t*)(&vt[D][t0]) = (row0 + t0 < row_end ? one : 0u) | (row0 + t0 + 1 < row_end ? one << 16 : 0u);
   }
 }
 
 __device__ __forceinline__ void stage_store(const Stage& s, Smem8& sm, int buf, const FastArgs& a, bool isoC,
-                                            int row0, int row_end, float wmax1, float wmax2) {
-  const int row = threadIdx.x >> 3;
-  const float nq2 = store_row_piece(s.q, sm.q[buf]);
-  const float nk2 = store_row_piece(s.k, sm.k[buf]);
-  if ((threadIdx.x & 7) == 0) {
+                                            int row0, int row_end, float wmax1, float wmax2, int tid) {
+  const int row = tid >> 3;
+  const float nq2 = store_row_piece(s.q, sm.q[buf], tid);
+  const float nk2 = store_row_piece(s.k, sm.k[buf], tid);
+  if ((tid & 7) == 0) {
     const bool valid = row0 + row < row_end;
     const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * nk2 : s.rk;
     const int pos = 4 * (row & 15) + (row >> 4);
@@ -120,7 +122,7 @@ __device__ __forceinline__ void stage_store(const Stage& s, Smem8& sm, int buf, 
     sm.kadd[buf][pos] = rt;
     sm.kbnd[buf][row] = valid ? row_shift(nk2, wmax2) + rt : -INFINITY;
   }
-  store_val_piece(s.v, sm.vt[buf], row0, row_end);
+  store_val_piece(s.v, sm.vt[buf], row0, row_end, tid);
 }
 
 // Selection matrices (B operands) that turn an A operand (lane <-> token, k <-> feature) into an accumulator with
@@ -165,54 +167,60 @@ __device__ __forceinline__ bf16x8 expack(const Proj& pr, float add) {
   return pack8(exp2v(pr.acc[0] + add), exp2v(pr.acc[1] + add));
 }
 
-// Finish of one 16 x 16 piece of the output: token tile `it` of a chunk, value columns 16 vt .. +15.  The sum over
-// the eight source waves is itself a contraction, done on the MFMA pipe: B[k = (source, row-in-group)][n = token]
-// straight from the exchange buffer (lanes of group g read sources g and g + 4: their blocks lie 32 banks apart),
-// A = a 0/1 matrix that routes column group q's four rows to accumulator rows 4q .. 4q+3 (four MFMAs fill the
-// tile), and for the normaliser (column 64) a matrix that copies its row everywhere.  Split in two so that the LDS
-// reads can be issued well before their use.
-struct Fin { u32x2 lo[4], hi[4], dlo, dhi; };
+// Finish of one 16 x 32 piece of the output: token tile `it` of a chunk, value tiles 2 cp and 2 cp + 1.  The sum
+// over the eight source waves is itself a contraction, done on the MFMA pipe: B[k = (source, row-in-group)][n = token]
+// straight from the exchange buffer (lanes of group g read sources g and g + 4; one 16-byte read holds four rows of
+// each of the two value tiles), A = a 0/1 matrix that routes column group q's four rows to accumulator rows 4q .. 4q+3
+// (four MFMAs fill a tile), and for the normaliser (column 64) a matrix that copies its row everywhere.  Done in
+// steps (two column groups at a time) so that the LDS reads can be issued well before their use.
+struct FinPart { u32x4 lo[2], hi[2]; };
+struct FinSum { f32x4 even, odd; };
 
-__device__ __forceinline__ void finish_issue(Fin& f, const Smem8& sm, int it, int vt) {
-  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+__device__ __forceinline__ void finish_read(FinPart& f, const Smem8& sm, int it, int cp, int qh, int lane) {
+  const int g = lane >> 4, c = lane & 15;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    f.lo[q] = *(const u32x2*)(&sm.xch[it][g][c][16 * vt + 4 * q]);
-    f.hi[q] = *(const u32x2*)(&sm.xch[it][g + 4][c][16 * vt + 4 * q]);
+  for (int i = 0; i < 2; ++i) {
+    f.lo[i] = *(const u32x4*)(&sm.xch[it][g][c][32 * cp + 8 * (2 * qh + i)]);
+    f.hi[i] = *(const u32x4*)(&sm.xch[it][g + 4][c][32 * cp + 8 * (2 * qh + i)]);
   }
-  f.dlo = *(const u32x2*)(&sm.xch[it][g][c][D]);
-  f.dhi = *(const u32x2*)(&sm.xch[it][g + 4][c][D]);
 }
-
-// `chunk_y`: first output row of the chunk (already offset to batch and head); `nv`: its number of valid rows
-// (0: nothing is stored).
-__device__ __forceinline__ void finish_complete(const Fin& f, const TensorDev& Y, long long chunk_row, long long ybase,
-                                                int nv, int it, int vt) {
-  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+__device__ __forceinline__ void finish_add(FinSum& acc, const FinPart& f, int qh, int lane) {
+  const int c = lane & 15;
   const uint32_t base0 = (c & 3) == 0 ? 0x3f80u : ((c & 3) == 1 ? 0x3f800000u : 0u);
   const uint32_t base1 = (c & 3) == 2 ? 0x3f80u : ((c & 3) == 3 ? 0x3f800000u : 0u);
-  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const u32x4 bq = {f.lo[q][0], f.lo[q][1], f.hi[q][0], f.hi[q][1]};
+  for (int i = 0; i < 2; ++i) {
+    const int q = 2 * qh + i;
     const uint32_t a0 = (c >> 2) == q ? base0 : 0u, a1 = (c >> 2) == q ? base1 : 0u;
     const u32x4 aq = {a0, a1, a0, a1};
-    sum = mfma(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bq), sum);
+    const u32x4 be = {f.lo[i][0], f.lo[i][1], f.hi[i][0], f.hi[i][1]};
+    const u32x4 bo = {f.lo[i][2], f.lo[i][3], f.hi[i][2], f.hi[i][3]};
+    acc.even = mfma(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, be), acc.even);
+    acc.odd = mfma(__builtin_bit_cast(bf16x8, aq), __builtin_bit_cast(bf16x8, bo), acc.odd);
   }
-  const u32x4 bd = {f.dlo[0], f.dlo[1], f.dhi[0], f.dhi[1]};
+}
+// `chunk_row`: first row of the chunk; `nv`: its number of valid rows (0: nothing is stored).
+__device__ __forceinline__ void finish_store(const FinSum& acc, const Smem8& sm, const TensorDev& Y, long long chunk_row,
+                                             long long ybase, int nv, int it, int cp, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  const u32x2 dlo = *(const u32x2*)(&sm.xch[it][g][c][D]);
+  const u32x2 dhi = *(const u32x2*)(&sm.xch[it][g + 4][c][D]);
+  const u32x4 bd = {dlo[0], dlo[1], dhi[0], dhi[1]};
   const u32x4 ad = {0x3f80u, 0u, 0x3f80u, 0u};
   const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), __builtin_bit_cast(bf16x8, bd), f32x4{0.f, 0.f, 0.f, 0.f});
   const float den = dn[0];
   const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
-  const f32x4 v = sum * inv;
+  const f32x4 ve = acc.even * inv, vo = acc.odd * inv;
   if (Y.dtype == 1) {
     const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const uint16_t*)Y.ptr + ybase + chunk_row * Y.sl, 2 * Y.sl, nv, 2 * D);
-    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4)), ry,
-                                          2 * ((16 * it + c) * (int)Y.sl + 16 * vt + 4 * g), 0, 0);
+    const int off = 2 * ((16 * it + c) * (int)Y.sl + 32 * cp + 4 * g);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(ve, bf16x4)), ry, off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(vo, bf16x4)), ry, off + 32, 0, 0);
   } else {
     const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const float*)Y.ptr + ybase + chunk_row * Y.sl, 4 * Y.sl, nv, 4 * D);
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), ry,
-                                           4 * ((16 * it + c) * (int)Y.sl + 16 * vt + 4 * g), 0, 0);
+    const int off = 4 * ((16 * it + c) * (int)Y.sl + 32 * cp + 4 * g);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ve), ry, off, 0, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, vo), ry, off + 64, 0, 0);
   }
 }
 
@@ -274,11 +282,11 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
 
   const int row_beg = seg * a.rows_per_seg, row_end = min(a.L, row_beg + a.rows_per_seg);
   Stage stg;
-  stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row_beg, min(TC, row_end - row_beg));
-  stage_store(stg, sm, 0, a, isoC, row_beg, row_end, wmax1, wmax2);
+  stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row_beg, min(TC, row_end - row_beg), threadIdx.x);
+  stage_store(stg, sm, 0, a, isoC, row_beg, row_end, wmax1, wmax2, threadIdx.x);
 
-  // the pieces this wave finishes: token tile 2 half + fit, value tile fvt
-  const int fit = w >> 2, fvt = w & 3;
+  // the piece of every chunk this wave finishes: token tile fit, value tiles 2 fcp and 2 fcp + 1
+  const int fit = w >> 1, fcp = w & 1;
 
   int buf = 0;
 #ifdef FS_PROFILE
@@ -286,14 +294,19 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
   int ci = -1;
 #endif
   for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
-    __syncthreads();               // barrier X: staged rows of this chunk and query tiles 2, 3 of the previous one are complete
+    __syncthreads();               // barrier X: the staged rows of this chunk and the partial outputs of the previous one are complete
 #ifdef FS_PROFILE
     ++ci;
     if (prof_on && lane == 0) fs_prof[(w * 64 + ci) * 16 + 15] = wall_clock64();
 #endif
     FS_TICK(0);
+    // Addresses that are used once per chunk are rebuilt from an opaque copy of the thread number instead of living
+    // in registers through the whole loop.
+    int tid_here = threadIdx.x;
+    asm volatile("" : "+v"(tid_here));
+    const int lane_here = tid_here & 63, fit_here = tid_here >> 7, fcp_here = (tid_here >> 6) & 1;
     // next chunk's rows (an empty range, hence zeros that nobody reads, after the last chunk)
-    stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row0 + TC, min(TC, row_end - row0 - TC));
+    stage_load(stg, Qb, Kb, Vb, a, isoC, bh, row0 + TC, min(TC, row_end - row0 - TC), tid_here);
 
     // running key shift (every wave computes the same numbers); the state is rebased when it grows
     {
@@ -314,8 +327,10 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
     const f32x4 qadd4 = *(const f32x4*)(&sm.qadd[buf][4 * c]);
     XOp xo[2];
     load_xop(xo[0], sm.k[buf], 0);
-    Fin fin;
-    finish_issue(fin, sm, 2 + fit, fvt);       // previous chunk, second half
+    // the previous chunk leaves during the key side (on the first pass there is none: nothing is stored)
+    FinPart fp0;
+    FinSum fsum = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    finish_read(fp0, sm, fit_here, fcp_here, 0, lane_here);
 
     // The selection matrices of the key side are rebuilt every chunk (a dozen instructions) instead of occupying
     // eight registers through the query side; the opaque copy of the lane number keeps them from being hoisted.
@@ -359,7 +374,9 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
         // consumers of this tile
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) tr[jj][hh] = mfma(s[jt], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-        if (jt == 0) finish_complete(fin, a.Y, row0 - TC, ybase, row0 > row_beg ? TC : 0, 2 + fit, fvt);
+        if (jt == 0) { finish_add(fsum, fp0, 0, lane_here); finish_read(fp0, sm, fit_here, fcp_here, 1, lane_here); }
+        if (jt == 1) finish_add(fsum, fp0, 1, lane_here);
+        if (jt == 2) finish_store(fsum, sm, a.Y, row0 - TC, ybase, row0 > row_beg ? TC : 0, fit_here, fcp_here, lane_here);
         if (jj == 1) {
 #pragma unroll
           for (int mt = 0; mt < 2; ++mt) {
@@ -375,16 +392,12 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
       }
     }
     FS_TICK(1);
+    __syncthreads();               // barrier Y: every wave has read what it needs of the previous chunk's partial outputs
+    FS_TICK(3);
 
     // query side, one token tile at a time
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-      if (it == 2) {
-        FS_TICK(2);
-        __syncthreads();           // barrier Y: query tiles 0, 1 and the next chunk's staged rows are complete
-        FS_TICK(3);
-        finish_issue(fin, sm, fit, fvt);
-      }
       if (it < 2) load_xop(xo[it & 1], sm.q[buf], it + 2);
       __builtin_amdgcn_sched_barrier(0);
       if (it < 3) project<true>(pr, wq, &qb, xo[(it + 1) & 1]);
@@ -414,23 +427,28 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
         }
       }
       if (it < 3) p = expack(pr, qadd4[it + 1]);
-      // hand the partial tile over (bf16): rows v = 16 vt + 4g + r of token column c
+      // hand the partial tile over (bf16): rows v = 16 vt + 4g + r of token column c, two value tiles per store
 #pragma unroll
-      for (int vt = 0; vt < NVT; ++vt)
-        *(bf16x4*)(&sm.xch[it][w][c][16 * vt + 4 * g]) = __builtin_convertvector(y[vt], bf16x4);
-      // the staged rows of the next chunk go to LDS between the two barriers
-      if (it == 1) stage_store(stg, sm, buf ^ 1, a, isoC, row0 + TC, row_end, wmax1, wmax2);
-      if (it == 2) finish_complete(fin, a.Y, row0, ybase, min(TC, row_end - row0), fit, fvt);
+      for (int vp = 0; vp < 2; ++vp)
+        *(bf16x8*)(&sm.xch[it][w][c][32 * vp + 8 * g]) = pack8(y[2 * vp], y[2 * vp + 1]);
+      *(bf16x4*)(&sm.xch[it][w][c][D + 4 * g]) = __builtin_convertvector(y[NVT - 1], bf16x4);
+      // the staged rows of the next chunk go to LDS while nobody reads that buffer
+      if (it == 1) stage_store(stg, sm, buf ^ 1, a, isoC, row0 + TC, row_end, wmax1, wmax2, tid_here);
     }
     FS_TICK(4);
   }
-  // second half of the last chunk
+  // the last chunk
   __syncthreads();
-  {
+  if (row_end > row_beg) {
     const int last0 = row_beg + ((row_end - row_beg - 1) / TC) * TC;
-    Fin fin;
-    finish_issue(fin, sm, 2 + fit, fvt);
-    if (row_end > row_beg) finish_complete(fin, a.Y, last0, ybase, row_end - last0, 2 + fit, fvt);
+    FinPart fp0;
+    FinSum fsum = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int qh = 0; qh < 2; ++qh) {
+      finish_read(fp0, sm, fit, fcp, qh, lane);
+      finish_add(fsum, fp0, qh, lane);
+    }
+    finish_store(fsum, sm, a.Y, last0, ybase, row_end - last0, fit, fcp, lane);
   }
 }
 
