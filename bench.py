@@ -28,6 +28,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this
+# script with --calibrate-copy, each counter scaled by what it reads for the 256 MiB copy (FETCH_SIZE x 2.0,
+# WRITE_SIZE x 1.0); figures and commands in profiles/c4_hbm_traffic.md.  The kernel reads Q, K, V and the prefix
+# states once and writes Y once, so the figure does not depend on how its instructions are scheduled.
+MEASURED_TRAFFIC_BYTES = {"c4": 291.9e6}
 
 
 class HipEvents:
@@ -105,6 +110,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4", choices=["c1", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1",
@@ -150,6 +158,13 @@ def main():
         fs.attention(st_["theta"], st_["Q"], st_["K"], st_["V"], s, st_["Omega"], causal=causal, chunk=chunk,
                      out=outs[i % nsets], workspace=ws, events=events)
 
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -181,9 +196,14 @@ def main():
         "fit_ms": fit_ms,
         "main_kernel_ms": main_ms,
         "algorithmic_tflops": counts["flops"] / (ms_per_step * 1e-3) / 1e12,
+        # dominant kernel (k_fast_causal / k_fast_apply / the generic equivalents); the HBM bound is the tighter of
+        # the two rooflines on the algorithmic counts (c4: 33.6 us against 32.1 us on the MFMA side)
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "mfma_frac_of_step": counts["flops"] / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "kernel_mfma_tflops": counts["flops"] / (main_ms * 1e-3) / 1e12,
+                     "kernel_mfma_frac": counts["flops"] / (main_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "step_hbm_frac": counts["bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "step_mfma_frac": counts["flops"] / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w0)
