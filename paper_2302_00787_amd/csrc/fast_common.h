@@ -95,7 +95,7 @@ __device__ __forceinline__ float max256(const float* p) {
 // the projection never exceeds cs; random directions reach about 0.4 cs.  max(cs/2, cs - 120) keeps the largest
 // shifted exponent below 2^120 for every input and near zero for ordinary ones.
 __device__ __forceinline__ float row_shift(float n2, float wmax) {
-  const float cs = wmax * sqrtf(n2);
+  const float cs = wmax * __builtin_amdgcn_sqrtf(n2);     // the hardware square root: any bound of this size will do
   return fmaxf(kBeta * cs, cs - 120.f);
 }
 

@@ -9,19 +9,20 @@
 //   producer j  stages the next chunk's Q, K, V rows (global -> registers -> LDS, V transposed, row norms and
 //               shifts), computes the feature tiles of its 64 features (projection MFMA, shift, exp2, convert) and
 //               hands them to its consumer through LDS as register images (lane-linear 16-byte pieces that the
-//               consumer reads back as ready MFMA operands).
+//               consumer reads back as ready MFMA operands); one chunk later it sums the four consumers' partial
+//               tiles of token tile j (an MFMA against a 0/1 routing matrix), normalises and stores them.
 //   consumer j  holds the state slice T (64 features x 80 columns, fp32) in registers and does the contractions:
 //               state update S^T [V 1] (S^T from an MFMA against a 0/1 selection matrix), inter-chunk term P T,
 //               scores S P^T (masked on the diagonal tiles) and scores x [V 1]; it writes its partial output tiles
-//               (a sum over its 64 features) to LDS as bf16, and, one chunk later, sums the four consumers' partial
-//               tiles of token tile j (an MFMA against a 0/1 routing matrix), normalises and stores them.
+//               (a sum over its 64 features) to LDS as bf16.
 // One wave's exp2 / convert stream thus runs beside the other's MFMA stream on every SIMD by construction.
 //
 // The chunk is four steps of two token tiles (key tiles 0-1, 2-3, query tiles 0-1, 2-3), one workgroup barrier after
 // each; the producer works one step ahead of the consumer.  Both roles execute exactly the same number of barriers
-// (1 + 4 per chunk + 2).  With t = 4 (chunk index) + step: the feature tiles of step t are written in interval t and
+// (2 + 4 per chunk).  With t = 4 (chunk index) + step: the feature tiles of step t are written in interval t and
 // read in interval t+1 (two slots); the partial outputs of chunk c are written in intervals 4c+3 and 4c+4 and summed
-// by the consumers in interval 4c+5 (their first key step); the rows of chunk c+1 go to the other LDS buffer part by
+// by the producers in interval 4c+6 (their third step of the next chunk, before the consumers overwrite them in
+// 4c+7); the rows of chunk c+1 go to the other LDS buffer part by
 // part in the four steps of chunk c (after every reader of chunk c-1: the producers' tile reads end in interval
 // 4c-1, the consumers' value reads in 4c-2) and are first read in interval 4c+3 (the prefetch of the next chunk's
 // first key tiles, whose rows were stored in step 1); each part's registers are refilled at once with the same part
@@ -192,29 +193,33 @@ __device__ __forceinline__ void finish_tiles(f32x4 (&fs)[4], const SmemPC& sm, i
     }
   }
 }
-// `chunk_row`: first row of the chunk; `nv`: its number of valid rows (0: nothing is stored).
-__device__ __forceinline__ void finish_store(const f32x4 (&fs)[4], const SmemPC& sm, const TensorDev& Y, long long chunk_row,
-                                             long long ybase, int nv, int it, int lane) {
+// Normaliser of token tile `it`: column 64 of the four partial tiles, summed and copied to every row by an MFMA; the
+// sums are scaled in place.
+__device__ __forceinline__ void finish_norm(f32x4 (&fs)[4], const SmemPC& sm, int it, int lane) {
   const int g = lane >> 4, c = lane & 15;
   const bf16x8 bd = *(const bf16x8*)(&sm.xch[it][g][c][D]);
   const u32x4 ad = {0x3f80u, 0u, 0u, 0u};
   const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), bd, f32x4{0.f, 0.f, 0.f, 0.f});
   const float den = dn[0];
   const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+#pragma unroll
+  for (int vt = 0; vt < 4; ++vt) fs[vt] *= inv;
+}
+// `ychunk`: first output row of the chunk (bytes); `nv`: its number of valid rows (0: nothing is stored).
+__device__ __forceinline__ void finish_store(const f32x4 (&fs)[4], const TensorDev& Y, const char* ychunk, int nv, int it, int lane) {
+  const int g = lane >> 4, c = lane & 15;
   if (Y.dtype == 1) {
-    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const uint16_t*)Y.ptr + ybase + chunk_row * Y.sl, 2 * Y.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 2 * Y.sl, nv, 2 * D);
     const int off = 2 * ((16 * it + c) * (int)Y.sl + 4 * g);
 #pragma unroll
-    for (int vt = 0; vt < 4; ++vt) {
-      const f32x4 v = fs[vt] * inv;
-      __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(v, bf16x4)), ry, off + 32 * vt, 0, 0);
-    }
+    for (int vt = 0; vt < 4; ++vt)
+      __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(fs[vt], bf16x4)), ry, off + 32 * vt, 0, 0);
   } else {
-    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc((const float*)Y.ptr + ybase + chunk_row * Y.sl, 4 * Y.sl, nv, 4 * D);
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 4 * Y.sl, nv, 4 * D);
     const int off = 4 * ((16 * it + c) * (int)Y.sl + 4 * g);
 #pragma unroll
     for (int vt = 0; vt < 4; ++vt)
-      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fs[vt] * inv), ry, off + 64 * vt, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fs[vt]), ry, off + 64 * vt, 0, 0);
   }
 }
 
@@ -248,16 +253,18 @@ __device__ unsigned long long fs_prof[8 * 64 * 32];
 // Per-part staging: the rows of a chunk travel in four parts (0: query rows, 1: key rows, 2 and 3: value pieces);
 // part p of chunk c+1 goes to LDS in step p of chunk c and its registers are refilled at once with part p of
 // chunk c+2, so every load has a whole chunk time to arrive.
-__device__ __forceinline__ void stage_load_part(Stage& s, const SegCtx& cx, const FastArgs& a, int row0, int nv, int tid, int part) {
+struct ChunkPtr { const uint16_t *q, *k, *v; const float* rk; };   // first row of a chunk in each tensor (uniform)
+
+__device__ __forceinline__ void stage_load_part(Stage& s, const ChunkPtr& cp, const SegCtx& cx, const FastArgs& a, int nv, int tid, int part) {
   const int row = tid >> 3, pc = tid & 7, j = tid & 63, pv = tid >> 6;
   if (part == 0) {
-    const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(cx.Qb + (long long)row0 * a.Q.sl, 2 * a.Q.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(cp.q, 2 * a.Q.sl, nv, 2 * D);
 #pragma unroll
     for (int i = 0; i < 2; ++i) s.q[i] = __builtin_amdgcn_raw_buffer_load_b128(rq, 2 * ((row + 32 * i) * (int)a.Q.sl + pc * 8), 0, 0);
   } else if (part == 1) {
-    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(cx.Kb + (long long)row0 * a.K.sl, 2 * a.K.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(cp.k, 2 * a.K.sl, nv, 2 * D);
     // key row terms of a dense C2 (an empty range, hence zeros, when the closed form -|k|^2/2 applies)
-    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.rk + (size_t)cx.bh * a.L + row0), 0,
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(cp.rk), 0,
                                                                         cx.isoC ? 0 : 4 * max(nv, 0), 0x00020000);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -266,7 +273,7 @@ __device__ __forceinline__ void stage_load_part(Stage& s, const SegCtx& cx, cons
     }
   } else {
     const int i = part - 2;
-    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(cx.Vb + (long long)row0 * a.V.sl, 2 * a.V.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(cp.v, 2 * a.V.sl, nv, 2 * D);
     s.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, 2 * (j * (int)a.V.sl + (pv + 4 * i) * 8), 0, 0);
   }
 }
@@ -292,13 +299,20 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
 
   // first chunk to LDS, second chunk into the staging registers
   Stage stg;
+  ChunkPtr cp = {cx.Qb + (long long)cx.row_beg * a.Q.sl, cx.Kb + (long long)cx.row_beg * a.K.sl,
+                 cx.Vb + (long long)cx.row_beg * a.V.sl, a.rk + (size_t)cx.bh * a.L + cx.row_beg};
+  const long long qstep = TC * a.Q.sl, kstep = TC * a.K.sl, vstep = TC * a.V.sl;
 #pragma unroll
-  for (int part = 0; part < 4; ++part) stage_load_part(stg, cx, a, cx.row_beg, min(TC, cx.row_end - cx.row_beg), tid, part);
+  for (int part = 0; part < 4; ++part) stage_load_part(stg, cp, cx, a, min(TC, cx.row_end - cx.row_beg), tid, part);
+  cp.q += qstep; cp.k += kstep; cp.v += vstep; cp.rk += TC;
 #pragma unroll
   for (int part = 0; part < 4; ++part) {
     stage_store(stg, sm, 0, a, cx.isoC, cx.row_beg, cx.row_end, wmax1, wmax2, tid, part);
-    stage_load_part(stg, cx, a, cx.row_beg + TC, min(TC, cx.row_end - cx.row_beg - TC), tid, part);
+    stage_load_part(stg, cp, cx, a, min(TC, cx.row_end - cx.row_beg - TC), tid, part);
   }
+  // output rows of the previous chunk (finished by the producers one chunk later)
+  const long long ystep = (long long)TC * a.Y.sl * (a.Y.dtype == 1 ? 2 : 4);
+  const char* yprev = (const char*)a.Y.ptr + (cx.ybase + (long long)cx.row_beg * a.Y.sl) * (a.Y.dtype == 1 ? 2 : 4) - ystep;
   FS_STEP_BARRIER();               // barrier 0: the first chunk's rows are in LDS
 
   XOp xo[2][2];                    // [step parity][tile of the step]
@@ -326,6 +340,9 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
     }
     const f32x4 kadd4 = *(const f32x4*)(&sm.kadd[buf][4 * c_here]);
     const f32x4 qadd4 = *(const f32x4*)(&sm.qadd[buf][4 * c_here]);
+    cp.q += qstep; cp.k += kstep; cp.v += vstep; cp.rk += TC;     // now the chunk after the next
+    const int nv2 = min(TC, cx.row_end - row0 - 2 * TC);
+    f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
@@ -354,13 +371,29 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
 
       // staging: part S of the next chunk goes to LDS, part S of the chunk after it is requested
       stage_store(stg, sm, buf ^ 1, a, cx.isoC, row0 + TC, cx.row_end, wmax1, wmax2, tid_here, S);
-      stage_load_part(stg, cx, a, row0 + 2 * TC, min(TC, cx.row_end - row0 - 2 * TC), tid_here, S);
+      stage_load_part(stg, cp, cx, a, nv2, tid_here, S);
+      // the previous chunk leaves: its partial tiles are summed in step 2 (before the consumers start to overwrite
+      // them in interval 4c+3) and stored in step 3 (nothing is stored on the first pass: there is no previous chunk)
+      if (S == 2) {
+        finish_tiles(fsum, sm, j, 0, lane_here);
+        finish_tiles(fsum, sm, j, 2, lane_here);
+        finish_norm(fsum, sm, j, lane_here);
+      }
+      if (S == 3) finish_store(fsum, a.Y, yprev, row0 > cx.row_beg ? TC : 0, j, lane_here);
       FS_TICK(j, 2 * S + 1);
       FS_STEP_BARRIER();
     }
+    yprev += ystep;
   }
-  FS_STEP_BARRIER();               // the consumers' last step
-  FS_STEP_BARRIER();               // the consumers' finish of the last chunk needs every partial tile
+  FS_STEP_BARRIER();               // the consumers' last step: every partial tile of the last chunk is written
+  if (cx.row_end > cx.row_beg) {
+    const int last0 = cx.row_beg + ((cx.row_end - cx.row_beg - 1) / TC) * TC;
+    f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    finish_tiles(fsum, sm, j, 0, lane);
+    finish_tiles(fsum, sm, j, 2, lane);
+    finish_norm(fsum, sm, j, lane);
+    finish_store(fsum, a.Y, yprev, cx.row_end - last0, j, lane);
+  }
 }
 
 __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const SegCtx& cx, int seg, int j) {
@@ -421,13 +454,6 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
           for (int blk = 0; blk < 2; ++blk) sk[2 * S + u][blk] = *(const bf16x8*)(&sm.feat[S & 1][u][j][blk][lane][0]);
 #pragma unroll
         for (int vt = 0; vt < NVT; ++vt) vop[S][vt] = load_vop_l(sm.vt[buf], S, vt, lane);
-        if (S == 0) {
-          // the previous chunk leaves (nothing is stored on the first pass: there is none)
-          f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-          finish_tiles(fsum, sm, j, 0, lane);
-          finish_tiles(fsum, sm, j, 2, lane);
-          finish_store(fsum, sm, a.Y, row0 - TC, cx.ybase, row0 > cx.row_beg ? TC : 0, j, lane);
-        }
         // state update: S^T (lane <-> feature) from an MFMA against the selection matrices
         bf16x8 sel[2];
         {
@@ -488,14 +514,6 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
       FS_TICK(4 + j, 2 * S + 1);
       FS_STEP_BARRIER();
     }
-  }
-  FS_STEP_BARRIER();               // matches the producers' count
-  if (cx.row_end > cx.row_beg) {
-    const int last0 = cx.row_beg + ((cx.row_end - cx.row_beg - 1) / TC) * TC;
-    f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-    finish_tiles(fsum, sm, j, 0, lane);
-    finish_tiles(fsum, sm, j, 2, lane);
-    finish_store(fsum, sm, a.Y, last0, cx.ybase, cx.row_end - last0, j, lane);
   }
 }
 
