@@ -278,15 +278,14 @@ __device__ __forceinline__ void stage_load_part(Stage& s, const ChunkPtr& cp, co
   }
 }
 
-template <bool SYM>
 __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const SegCtx& cx, int j) {
   const int tid = threadIdx.x, lane = tid & 63;
   const float wmax1 = max256(a.wnorm + ((size_t)cx.pg * 2) * M), amax1 = max256(a.bias + ((size_t)cx.pg * 2) * M);
   const float wmax2 = max256(a.wnorm + ((size_t)cx.pg * 2 + 1) * M);
-  W64 wq, wk2;
+  // both projection slices stay in registers (they are the same numbers when B1 = B2; the producers have room)
+  W64 wq, wk;
   load_w64(wq, a.Wbf + ((size_t)cx.pg * 2) * M * D, j, lane);
-  if (!SYM) load_w64(wk2, a.Wbf + ((size_t)cx.pg * 2 + 1) * M * D, j, lane);
-  const W64& wk = SYM ? wq : wk2;
+  load_w64(wk, a.Wbf + ((size_t)cx.pg * 2 + 1) * M * D, j, lane);
   B64 qb;
   {
     const int g = lane >> 4;
@@ -521,17 +520,13 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
 
 using namespace pc;
 
-// grid (nseg, B*H), block 512.  Two instantiations: SYM (B1 = B2: the query and key projections share one W~ slice:
-// PosRF, GERF, SDERF) and the general one; each workgroup looks at the flag of its own parameter set and the
-// instantiation that does not match returns at once.
-template <bool SYM>
+// grid (nseg, B*H), block 512.
 __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   SmemPC& sm = *reinterpret_cast<SmemPC*>(smem_raw);
   const int seg = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
   const int flags = (int)th[2];
-  if (((flags >> 1) & 1) != (SYM ? 1 : 0)) return;
   SegCtx cx;
   cx.isoC = flags & 1;
   cx.bh = bh;
@@ -548,20 +543,17 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
     sm.vt[bb][D + 1 + rem / LDJ][rem % LDJ] = 0;
   }
   const int w = threadIdx.x >> 6;
-  if (w < 4) producer<SYM>(a, sm, cx, w);
+  if (w < 4) producer(a, sm, cx, w);
   else consumer(a, sm, cx, seg, w - 4);
 }
 
 int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st) {
-  const void* fns[2] = {(const void*)k_fast_causal<true>, (const void*)k_fast_causal<false>};
-  for (const void* fn : fns)
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPC)) != hipSuccess) {
-      (void)hipGetLastError();
-      return 2;
-    }
-  hipLaunchKernelGGL(k_fast_causal<true>, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, a);
-  if (hipGetLastError() != hipSuccess) return 5;
-  hipLaunchKernelGGL(k_fast_causal<false>, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, a);
+  if (hipFuncSetAttribute((const void*)k_fast_causal, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPC)) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return 2;
+  }
+  hipLaunchKernelGGL(k_fast_causal, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, a);
   if (hipGetLastError() != hipSuccess) return 5;
   return 0;
 }
