@@ -144,7 +144,8 @@ __global__ void __launch_bounds__(NT) k_fast_state(FastArgs a) {
 
 // Brings the segment states of one (b,h) to the common shift c* = max_seg cpart and sums them (prefix = 0: total
 // in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  grid (ceil(M*DVP/256), B*H).
-__global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, int nseg, int nseg_valid, int prefix) {
+__global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, int nseg, int nseg_valid, int prefix,
+                              int sub) {
   const int bh = blockIdx.y;
   const size_t per = (size_t)M * DVP;
   const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -157,7 +158,7 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
   for (int s = 0; s < nseg; ++s) {
     float v = 0.f;
     if (s < nseg_valid) v = p[(size_t)s * per] * fast_exp2(cpart[(size_t)bh * nseg + s] - cs);
-    if (prefix) p[(size_t)s * per] = run;
+    if (prefix && s % sub == 0) p[(size_t)s * per] = run;    // only the slots that open a segment are read back
     run += v;
   }
   if (!prefix) p[0] = run;
@@ -266,7 +267,7 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
     FS_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
-                     a.nslot, nstate, f.causal);
+                     a.nslot, nstate, f.causal, f.sub);
   FS_LAUNCH_CHECK();
   if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
   if (f.causal) {

@@ -469,12 +469,16 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
           for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(stv, vop[S][vt], T[mt][vt]);
         }
       } else {
+        // both tiles' query images are requested before the first one is used
+        bf16x8 pq[2][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk) pq[u][blk] = *(const bf16x8*)(&sm.feat[S & 1][u][j][blk][lane][0]);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
           const int it = 2 * (S - 2) + u;
-          bf16x8 p[2];
-#pragma unroll
-          for (int blk = 0; blk < 2; ++blk) p[blk] = *(const bf16x8*)(&sm.feat[S & 1][u][j][blk][lane][0]);
+          const bf16x8* p = pq[u];
           f32x4 y[NVT];
 #pragma unroll
           for (int vt = 0; vt < NVT; ++vt) {
