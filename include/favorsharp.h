@@ -157,6 +157,20 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
                                void* workspace, size_t workspace_bytes, void* stream,
                                void* event_main_begin, void* event_main_end);
 
+/*
+ * Block-orthogonal random features (the appendix on the classification experiments says the omegas there are
+ * orthogonal; the construction is not printed in the paper: this is the textbook one).  HOST function, host pointers:
+ *   host_gauss_dir, host_gauss_len: [groups][M][d] float32, independent N(0,1) draws supplied by the caller;
+ *   host_omega (out):               [groups][M][d] float32.
+ * The M rows of a group are taken in blocks of d (the last block may be shorter); inside a block the rows of
+ * host_gauss_dir are orthonormalised in order (Gram-Schmidt, double precision), and row i is then given the length
+ * |host_gauss_len[i,:]|, so that every omega_i is marginally N(0, I_d) while the directions of a block are exactly
+ * orthogonal.  FS_ERR_NOT_PD if a block is numerically rank deficient, FS_ERR_INVALID_ARG on null pointers or
+ * non-positive sizes.  No device work, no stream.
+ */
+int favorsharp_orthogonal_omega(const float* host_gauss_dir, const float* host_gauss_len, int groups, int M, int d,
+                                float* host_omega);
+
 #ifdef __cplusplus
 }
 #endif

@@ -341,3 +341,24 @@ def exact_attention(Q, K, V, qk_scale: float, causal: bool = False) -> np.ndarra
         Z = np.where(np.arange(Y.shape[0])[None, :] <= np.arange(X.shape[0])[:, None], Z, -np.inf)
     W = np.exp(Z - Z.max(axis=1, keepdims=True))
     return (W @ np.asarray(V, dtype=np.float64)) / W.sum(axis=1, keepdims=True)
+
+
+def orthogonal_omega(gauss_dir, gauss_len):
+    """Block-orthogonal random features: the appendix on the classification experiments uses orthogonal omegas and
+    refers to the literature for the construction; this is the textbook one.  Rows are taken in blocks of d; the rows
+    of `gauss_dir` in a block are orthonormalised in order (Gram-Schmidt = the QR factorisation of the transposed
+    block with a positive diagonal of R), and row i is given the length |gauss_len[i]| (a chi_d variable), so that
+    every omega_i is marginally N(0, I_d).  Shapes [M, d] -> [M, d], float64."""
+    G = np.asarray(gauss_dir, dtype=np.float64)
+    N = np.asarray(gauss_len, dtype=np.float64)
+    M, d = G.shape
+    out = np.empty_like(G)
+    for r0 in range(0, M, d):
+        blk = G[r0:r0 + d]
+        Qm, R = np.linalg.qr(blk.T)                 # blk^T = Q R: column i of Q spans rows 0..i of blk
+        sgn = np.sign(np.diag(R))
+        sgn[sgn == 0] = 1.0
+        dirs = (Qm * sgn).T[: blk.shape[0]]         # Gram-Schmidt directions (positive diagonal of R)
+        out[r0:r0 + d] = np.linalg.norm(N[r0:r0 + d], axis=1)[:, None] * dirs
+    return out
+

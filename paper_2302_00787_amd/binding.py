@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.favorsharp_status_string.argtypes = [c_int]
         L.favorsharp_version.restype = c_char_p
         L.favorsharp_version.argtypes = []
+        L.favorsharp_orthogonal_omega.restype = c_int
+        L.favorsharp_orthogonal_omega.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p]
         L.favorsharp_fit_workspace_bytes.restype = c_size_t
         L.favorsharp_fit_workspace_bytes.argtypes = [c_int] * 6
         L.favorsharp_fit_params.restype = c_int
@@ -218,6 +220,20 @@ def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
     else:       # (hipEvent_t begin, hipEvent_t end) as integers: favorsharp_attention_timed
         st = lib().favorsharp_attention_timed(*args, events[0], events[1])
     _check(st, "favorsharp_attention")
+    return out
+
+
+def orthogonal_omega(gauss_dir: np.ndarray, gauss_len: np.ndarray) -> np.ndarray:
+    """favorsharp_orthogonal_omega (host): [groups, M, d] or [M, d] Gaussian draws -> block-orthogonal omega, float32."""
+    g = np.ascontiguousarray(gauss_dir, dtype=np.float32)
+    n = np.ascontiguousarray(gauss_len, dtype=np.float32)
+    if g.shape != n.shape or g.ndim not in (2, 3):
+        raise ValueError("gauss_dir and gauss_len must have the same shape [groups, M, d] or [M, d]")
+    groups = 1 if g.ndim == 2 else g.shape[0]
+    M, d = g.shape[-2], g.shape[-1]
+    out = np.empty_like(g)
+    _check(lib().favorsharp_orthogonal_omega(g.ctypes.data_as(c_void_p), n.ctypes.data_as(c_void_p), groups, M, d,
+                                             out.ctypes.data_as(c_void_p)), "favorsharp_orthogonal_omega")
     return out
 
 

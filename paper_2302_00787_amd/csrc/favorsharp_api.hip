@@ -121,6 +121,31 @@ const char* favorsharp_status_string(int status) {
 
 const char* favorsharp_version(void) { return "favorsharp 0.1 (gfx950)"; }
 
+// ------------------------------------------------------------------------------------------ orthogonal omega (host)
+int favorsharp_orthogonal_omega(const float* host_gauss_dir, const float* host_gauss_len, int groups, int M, int d,
+                                float* host_omega) {
+  if (host_gauss_dir == nullptr || host_gauss_len == nullptr || host_omega == nullptr) return FS_ERR_INVALID_ARG;
+  if (groups < 1 || M < 1 || d < 1) return FS_ERR_INVALID_ARG;
+  std::vector<double> g((size_t)d * d), len(d), out((size_t)d * d);
+  for (int grp = 0; grp < groups; ++grp)
+    for (int r0 = 0; r0 < M; r0 += d) {
+      const int n = std::min(d, M - r0);
+      const size_t base = ((size_t)grp * M + r0) * d;
+      for (int i = 0; i < n; ++i) {
+        double l2 = 0.0;
+        for (int c = 0; c < d; ++c) {
+          g[(size_t)i * d + c] = host_gauss_dir[base + (size_t)i * d + c];
+          const double v = host_gauss_len[base + (size_t)i * d + c];
+          l2 += v * v;
+        }
+        len[i] = std::sqrt(l2);
+      }
+      if (!orthogonal_rows(n, d, g.data(), len.data(), out.data())) return FS_ERR_NOT_PD;
+      for (size_t e = 0; e < (size_t)n * d; ++e) host_omega[base + e] = (float)out[e];
+    }
+  return FS_OK;
+}
+
 // ------------------------------------------------------------------------------------------ fit
 size_t favorsharp_fit_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups) {
   if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || d > 128 || !groups_ok(groups, B, H)) return 0;

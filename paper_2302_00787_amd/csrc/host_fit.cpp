@@ -267,4 +267,27 @@ int fit_group(int variant, int d, const double* M1, const double* M2, const doub
   return 1;
 }
 
+bool orthogonal_rows(int n, int d, const double* g, const double* len, double* out) {
+  std::vector<double> q((size_t)n * d);
+  for (int i = 0; i < n; ++i) {
+    double* qi = &q[(size_t)i * d];
+    double n0 = 0.0;
+    for (int c = 0; c < d; ++c) { qi[c] = g[(size_t)i * d + c]; n0 += qi[c] * qi[c]; }
+    for (int pass = 0; pass < 2; ++pass)
+      for (int j = 0; j < i; ++j) {
+        const double* qj = &q[(size_t)j * d];
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += qi[c] * qj[c];
+        for (int c = 0; c < d; ++c) qi[c] -= dot * qj[c];
+      }
+    double n1 = 0.0;
+    for (int c = 0; c < d; ++c) n1 += qi[c] * qi[c];
+    if (!(n1 > 1e-24 * n0) || !(n0 > 0.0)) return false;
+    const double inv = 1.0 / std::sqrt(n1);
+    for (int c = 0; c < d; ++c) qi[c] *= inv;
+    for (int c = 0; c < d; ++c) out[(size_t)i * d + c] = len[i] * qi[c];
+  }
+  return true;
+}
+
 }  // namespace fs

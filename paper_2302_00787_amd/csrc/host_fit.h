@@ -12,4 +12,8 @@ void jacobi_eigh(int n, std::vector<double>& a, std::vector<double>& w, std::vec
 int fit_group(int variant, int d, const double* M1, const double* M2, const double* mu4, const double* mu5,
               double ridge, float* theta);
 
+// Orthonormalises the rows of g (n x d, n <= d, row-major) in order (modified Gram-Schmidt, two passes) and scales
+// row i to length len[i].  Returns false if a row has (numerically) no component outside the span of the earlier ones.
+bool orthogonal_rows(int n, int d, const double* g, const double* len, double* out);
+
 }  // namespace fs

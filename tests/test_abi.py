@@ -76,3 +76,30 @@ def test_pack_and_unpack_theta_roundtrip():
     assert u["flags"] == 3 and u["variant"] == 4 and abs(u["logD"] - 0.3) < 1e-6
     np.testing.assert_allclose(u["B2"], B.astype(np.float32))
     assert len(vec) == 8 + d + 4 * d * d
+
+
+def test_orthogonal_omega_matches_the_oracle_and_reports_rank_deficiency():
+    """Host-only entry point: runs without a GPU.  Compared element by element with the oracle's QR-based routine."""
+    import numpy as np
+    from oracle import favorsharp_oracle as orc
+    from paper_2302_00787_amd import binding as fs
+    rng = np.random.default_rng(21)
+    groups, M, d = 3, 150, 64                   # two full blocks and a ragged one per group
+    G = rng.standard_normal((groups, M, d)).astype(np.float32)
+    N = rng.standard_normal((groups, M, d)).astype(np.float32)
+    out = fs.orthogonal_omega(G, N)
+    assert out.shape == (groups, M, d) and out.dtype == np.float32
+    for g in range(groups):
+        ref = orc.orthogonal_omega(G[g].astype(np.float64), N[g].astype(np.float64))
+        assert np.max(np.abs(out[g] - ref)) <= 2e-6 * np.max(np.abs(ref))
+    # 2-D input = one group; M < d = one short block
+    small = fs.orthogonal_omega(G[0, :5], N[0, :5])
+    assert np.allclose(small, orc.orthogonal_omega(G[0, :5].astype(np.float64), N[0, :5].astype(np.float64)), atol=1e-5)
+    # a repeated row has no direction of its own left
+    bad = G[0, :8].copy()
+    bad[3] = bad[1]
+    try:
+        fs.orthogonal_omega(bad, N[0, :8])
+        raise AssertionError("rank deficiency not reported")
+    except fs.FavorSharpError as e:
+        assert "NOT_PD" in str(e).upper() or "singular" in str(e).lower(), str(e)

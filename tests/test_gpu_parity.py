@@ -290,6 +290,20 @@ def test_bf16_path_lengths_and_variants(fs, causal, L, variant):
     print(f"bf16 path causal={causal} L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_with_block_orthogonal_omega(fs, causal):
+    """Orthogonal random features only change omega: the library's host-side generator and the oracle's build the same
+    omega from the same Gaussian draws, and the attention kernels run on it unchanged."""
+    w = synth.make("c4", B=1, H=2, L=384, seed=91)
+    rng = np.random.default_rng(92)
+    G = rng.standard_normal(w["Omega"].shape).astype(np.float32)
+    N = rng.standard_normal(w["Omega"].shape).astype(np.float32)
+    Om_lib = fs.orthogonal_omega(G, N)
+    Om_ref = np.stack([orc.orthogonal_omega(G[h].astype(np.float64), N[h].astype(np.float64)) for h in range(G.shape[0])])
+    assert np.max(np.abs(Om_lib - Om_ref)) <= 2e-6 * np.max(np.abs(Om_ref))
+    _check_attention(fs, w["Q"], w["K"], w["V"], Om_lib, w["qk_scale"], causal, "sderf", "bf16", chunk=64)
+
+
 def test_bf16_path_f32_output_strided_inputs_and_shared_parameters(fs):
     import torch
     w = synth.make("c3", B=2, H=2, L=320)
