@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <thread>
 #include <vector>
 
 #include "host_fit.h"
@@ -180,14 +181,26 @@ int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y, i
   if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;
   const size_t tf = favorsharp_theta_floats(d);
   std::vector<float> host_theta((size_t)groups * tf);
-  int status = FS_OK;
-  for (int g = 0; g < groups && status == FS_OK; ++g) {
-    const double* sx = host_stats.data() + ((size_t)g * 2) * per;
-    const double* sy = sx + per;
-    status = fit_group(variant, d, sx, sy, sx + (size_t)d * d, sy + (size_t)d * d, (double)eig_ridge,
-                       host_theta.data() + (size_t)g * tf);
+  // the groups are independent d x d problems: one host thread each (at most 16)
+  std::vector<int> status_of(groups, FS_OK);
+  auto fit_range = [&](int g0, int g1) {
+    for (int g = g0; g < g1; ++g) {
+      const double* sx = host_stats.data() + ((size_t)g * 2) * per;
+      const double* sy = sx + per;
+      status_of[g] = fit_group(variant, d, sx, sy, sx + (size_t)d * d, sy + (size_t)d * d, (double)eig_ridge,
+                               host_theta.data() + (size_t)g * tf);
+    }
+  };
+  const int nthreads = std::max(1, std::min({groups, 16, (int)std::thread::hardware_concurrency()}));
+  if (nthreads == 1) {
+    fit_range(0, groups);
+  } else {
+    std::vector<std::thread> pool;
+    for (int t = 0; t < nthreads; ++t) pool.emplace_back(fit_range, groups * t / nthreads, groups * (t + 1) / nthreads);
+    for (auto& th : pool) th.join();
   }
-  if (status != FS_OK) return status;
+  for (int g = 0; g < groups; ++g)
+    if (status_of[g] != FS_OK) return status_of[g];
   if (hipMemcpyAsync(theta, host_theta.data(), host_theta.size() * sizeof(float), hipMemcpyHostToDevice, st) != hipSuccess)
     return FS_ERR_DEVICE;
   if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;

@@ -47,6 +47,9 @@ int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
                       const TensorDev& Y, hipStream_t st);
+bool stats_bf16_supported(const TensorDev& X, const TensorDev& Y, int d);
+int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
+                      int rows_per_chunk, int nchunks, float* part, hipStream_t st);
 int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, int Ly, int d, float scale, int groups,
                  int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st);
 

@@ -246,6 +246,72 @@ static int set_fast_lds(const void* fn) {
   return 0;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Statistics scan of the fits for bf16 rows of 64 numbers (Section 4: mu4, mu5, M1, M2 are means of x, y, x x^T,
+// y y^T): per (b,h), tensor and row chunk, sum x and sum x x^T on bf16 MFMA tiles.  The rows of a 64-token tile are
+// staged transposed ([number][token], a row of ones appended), so that one operand layout (lane <-> number, k <->
+// tokens) serves both sides of X^T X and the ones row yields the column sums.  Wave w owns the Gram tiles (w, 0..3)
+// and the 16 column sums of block w.  Output layout as the general kernel's: part[which][bh][chunk][d*d + d], with
+// qk_scale applied (squared on the Gram part).  grid (nchunks, B*H, 2), block 256.
+// ---------------------------------------------------------------------------------------------------
+struct SmemStats { uint16_t vt[2][DVP][LDJ]; };
+
+__global__ void __launch_bounds__(NT) k_stats_bf16(TensorDev X, TensorDev Yt, int Lx, int Ly, int H, float scale,
+                                                   int rows_per_chunk, int nchunks, float* part) {
+  __shared__ SmemStats sm;
+  const int which = blockIdx.z, bh = blockIdx.y, b = bh / H, h = bh % H, chunk = blockIdx.x;
+  const TensorDev& T = which ? Yt : X;
+  const int L = which ? Ly : Lx;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const uint16_t* base = (const uint16_t*)T.ptr + b * T.sb + h * T.sh;
+  for (int idx = threadIdx.x; idx < 2 * (DVP - D - 1) * LDJ; idx += NT) {
+    const int bb = idx / ((DVP - D - 1) * LDJ), rem = idx - bb * (DVP - D - 1) * LDJ;
+    sm.vt[bb][D + 1 + rem / LDJ][rem % LDJ] = 0;
+  }
+  f32x4 acc[4], sums = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int bt = 0; bt < 4; ++bt) acc[bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int row_beg = chunk * rows_per_chunk, row_end = min(L, row_beg + rows_per_chunk);
+  RowRegs r;
+  load_vals_g(r, base, T.sl, row_beg, row_end);
+  store_vals_s(r, sm.vt[0], row_beg, row_end);
+  __syncthreads();
+  int buf = 0;
+  for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
+    const bool more = row0 + TC < row_end;
+    if (more) load_vals_g(r, base, T.sl, row0 + TC, row_end);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8 mine = load_vop(sm.vt[buf], ks, w);
+      const bf16x8 ones = load_vop(sm.vt[buf], ks, 4);
+#pragma unroll
+      for (int bt = 0; bt < 4; ++bt) acc[bt] = mfma(mine, load_vop(sm.vt[buf], ks, bt), acc[bt]);
+      sums = mfma(ones, mine, sums);
+    }
+    if (more) store_vals_s(r, sm.vt[buf ^ 1], row0 + TC, row_end);
+    __syncthreads();
+  }
+  float* out = part + (((size_t)which * gridDim.y + bh) * nchunks + chunk) * ((size_t)D * D + D);
+  const float s2 = scale * scale;
+#pragma unroll
+  for (int bt = 0; bt < 4; ++bt)
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) out[(size_t)(16 * w + 4 * g + rr) * D + 16 * bt + c] = s2 * acc[bt][rr];
+  if (g == 0) out[(size_t)D * D + 16 * w + c] = scale * sums[0];
+}
+
+bool stats_bf16_supported(const TensorDev& X, const TensorDev& Y, int d) {
+  return X.dtype == 1 && Y.dtype == 1 && d == D;
+}
+
+int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
+                      int rows_per_chunk, int nchunks, float* part, hipStream_t st) {
+  hipLaunchKernelGGL(k_stats_bf16, dim3(nchunks, BH, 2), dim3(NT), 0, st, X, Y, Lx, Ly, H, scale, rows_per_chunk, nchunks,
+                     part);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   FastArgs a;
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;

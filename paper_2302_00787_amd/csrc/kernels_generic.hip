@@ -738,11 +738,15 @@ int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, 
 
 int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, int Ly, int d, float scale, int groups,
                  int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st) {
-  const size_t lds = gen_lds_stats(d);
-  if (int rc = set_lds((const void*)k_stats_partial, lds)) return rc;
-  hipLaunchKernelGGL(k_stats_partial, dim3(nchunks, B * H, 2), dim3(NT), lds, st, X, Y, Lx, Ly, H, d, scale,
-                     rows_per_chunk, nchunks, part);
-  FS_LAUNCH_CHECK();
+  if (stats_bf16_supported(X, Y, d)) {
+    if (int rc = launch_stats_bf16(X, Y, B * H, H, Lx, Ly, scale, rows_per_chunk, nchunks, part, st)) return rc;
+  } else {
+    const size_t lds = gen_lds_stats(d);
+    if (int rc = set_lds((const void*)k_stats_partial, lds)) return rc;
+    hipLaunchKernelGGL(k_stats_partial, dim3(nchunks, B * H, 2), dim3(NT), lds, st, X, Y, Lx, Ly, H, d, scale,
+                       rows_per_chunk, nchunks, part);
+    FS_LAUNCH_CHECK();
+  }
   const size_t total = (size_t)groups * 2 * ((size_t)d * d + d);
   hipLaunchKernelGGL(k_stats_final, dim3((unsigned)((total + 127) / 128)), dim3(128), 0, st, part, B, H, nchunks, d,
                      groups, Lx, Ly, stats);
