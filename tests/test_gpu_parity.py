@@ -339,7 +339,7 @@ def test_bf16_path_extreme_scales_stay_finite(fs):
     _check_attention(fs, Q, K, w["V"], w["Omega"], w["qk_scale"], True, "posrf", "bf16")
 
 
-@pytest.mark.parametrize("name", ["c3", "c4"])
+@pytest.mark.parametrize("name", ["c3", "c4", "c5"])
 def test_bf16_workloads_full_size_sampled_rows(fs, name):
     """The full workload in the launch configuration the benchmark times; the oracle evaluates sampled output rows
     one by one from the definition (rows of K_hat, masked when causal): sequence start, segment and chunk
@@ -354,7 +354,7 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name):
     torch.cuda.synchronize()
     th_host = util.to_host(theta).astype(np.float32)
     rng = np.random.default_rng(9)
-    fixed = [0, 1, 63, 64, 65, 2047, 2048, 2049, L // 2 - 1, L // 2, L - 2, L - 1]
+    fixed = [0, 1, 31, 32, 33, 63, 64, 65, 2047, 2048, 2049, L // 2 - 1, L // 2, L - 2, L - 1]
     for b, h in [(0, 0), (B - 1, H - 1), (B // 2, H // 2)]:
         rows = np.unique(np.concatenate([fixed, rng.integers(0, L, 52)]))
         th = util.oracle_theta_from_vec(th_host[h], d)
