@@ -103,12 +103,50 @@ def cpu_baseline(w: dict, budget_s: float = 20.0) -> dict:
                        f"{dt:.1f} s; head-tokens/s divided by H={w['H']}")
 
 
+def bench_matvec(args, cfg, fs, synth, util, torch):
+    """The kernel-operator workload (K^(alpha)(X, Y) C, Section 2.1): one step = one favorsharp_kernel_matvec call
+    with theta and omega resident; fp32 in and out, so the bound is the fp32 MFMA peak."""
+    N, d, M, n, alpha = cfg["N"], cfg["d"], cfg["M"], cfg["n"], cfg["alpha"]
+    sets = []
+    for i in range(3):
+        w = synth.make(args.workload, seed=cfg["seed"] + i)
+        X = torch.from_numpy(w["X"].astype(np.float32)).cuda()
+        C = torch.from_numpy(w["C"].astype(np.float32)).cuda()
+        Om = torch.from_numpy(w["Omega"].astype(np.float32)).cuda()
+        theta = fs.fit_params("sderf", X, X, w["qk_scale"], groups=1)
+        sets.append((theta, X, C, Om, w["qk_scale"]))
+    ws = torch.empty(fs.kernel_matvec_workspace_bytes(N, N, d, M, n), dtype=torch.uint8, device="cuda")
+
+    def step(i):
+        theta, X, C, Om, s = sets[i % 3]
+        return fs.kernel_matvec(theta, X, X, s, alpha, Om, C, workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        out = step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    assert torch.isfinite(out).all().item()
+    flops = N * (2 * 2 * d * M + 2 * 2 * M * n)          # two projections, state update and state read
+    tf = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "FAVOR# kernel operator points/s (c2: N=16384 d=32 M=512 n=8, alpha=-1/2)", "value": N / (ms * 1e-3),
+        "unit": "points/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "c2: kernel operator, fp32, X = Y, SDERF, theta and omega resident"},
+        "roofline": {"bound": "mfma", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
+                     "traffic": None}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
@@ -126,6 +164,9 @@ def main():
 
     fs.lib()
     cfg = dict(synth.WORKLOADS[args.workload])
+    if cfg.get("kind") == "matvec":
+        bench_matvec(args, cfg, fs, synth, util, torch)
+        return
     dtype = cfg["dtype"]
     nsets = 3
     sets, w0 = [], None

@@ -1,8 +1,10 @@
 // Device-side building blocks of the bf16 attention kernels (d = dv = 64, M = 256) for gfx950.
 //
-// One workgroup = 4 waves = one CU.  Wave w owns the 64 random features [64w, 64w+64): its slice of the
-// projection matrix W~ (bf16) and of the M x (d+1) state T (fp32 MFMA accumulators) stay in registers for the
-// whole kernel, so the feature matrices P, S are produced, used and discarded in registers:
+// Key-side state kernel and non-causal query-side kernel: one workgroup = 4 waves; wave w owns the 64 random
+// features [64w, 64w+64): its slice of the projection matrix W~ (bf16) and of the M x (d+1) state T (fp32 MFMA
+// accumulators) stay in registers for the whole kernel, so the feature matrices P, S are produced, used and
+// discarded in registers.  (The causal kernel splits the same dataflow over producer and consumer waves, see
+// kernels_bf16_causal.hip; operand layouts, exponents and shifts are the ones described here.)
 //
 //   E^T tile   = W~ (A operand) x tokens (B operand)      -> accumulator: lane <-> token, registers <-> feature
 //   S, P       = exp2(E^T)  (bias preloaded in the accumulator, per-token shift added before the exp2)
