@@ -275,15 +275,17 @@ __device__ __forceinline__ void feature_tile(const WSlice& ws, const QBias* qb, 
   bf16x8 b[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+  // without a bias the token's part of the exponent is the accumulator's initial value: nothing is left to add
+  const f32x4 add4 = {add, add, add, add};
   f32x4 acc[4];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt) {
-    acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[mt] = mfma(ws.w[mt][0], b[0], WITH_BIAS ? qb->b[mt] : add4);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], b[ks], acc[mt]);
+    for (int ks = 1; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], b[ks], acc[mt]);
   }
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt) acc[mt] = exp2v(acc[mt] + add);
+  for (int mt = 0; mt < 4; ++mt) acc[mt] = exp2v(WITH_BIAS ? acc[mt] + add : acc[mt]);
   out[0] = pack8(acc[0], acc[1]);
   out[1] = pack8(acc[2], acc[3]);
 }

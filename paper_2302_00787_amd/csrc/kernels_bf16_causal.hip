@@ -162,15 +162,18 @@ __device__ __forceinline__ void load_xop(XOp& x, const uint16_t (*tile)[LDR], in
 // blk (lane <-> token 16 jt + c, k = 8g + e <-> feature 32 blk + 16 (e/4) + 4g + e%4).
 template <bool WITH_BIAS>
 __device__ __forceinline__ void feature_tile64(const W64& ws, const B64* qb, const XOp& x, float add, bf16x8 img[2]) {
+  // without a bias the token's shift is the accumulator's initial value: nothing is left to add afterwards
+  const f32x4 add4 = {add, add, add, add};
   f32x4 acc[4];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt) {
-    acc[mt] = WITH_BIAS ? qb->b[mt] : f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[mt] = mfma(ws.w[mt][0], x.b[0], WITH_BIAS ? qb->b[mt] : add4);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], x.b[ks], acc[mt]);
+    for (int ks = 1; ks < KS; ++ks) acc[mt] = mfma(ws.w[mt][ks], x.b[ks], acc[mt]);
   }
 #pragma unroll
-  for (int blk = 0; blk < 2; ++blk) img[blk] = pack8(exp2v(acc[2 * blk] + add), exp2v(acc[2 * blk + 1] + add));
+  for (int blk = 0; blk < 2; ++blk)
+    img[blk] = WITH_BIAS ? pack8(exp2v(acc[2 * blk] + add), exp2v(acc[2 * blk + 1] + add)) : pack8(exp2v(acc[2 * blk]), exp2v(acc[2 * blk + 1]));
 }
 
 // Finish of token tile `it` of a chunk (all 64 value columns): the sum over the four consumers' partial tiles is a
