@@ -6,7 +6,8 @@
 One "step" is one call of favorsharp_attention on the metric workload (causal, bf16, B=4 H=8 L=16384 d=64
 M=256, chunk 64): projection constants, both feature maps (fused, never stored) and the causal prefix-state
 contraction, with Q, K, V, omega and the fitted parameters already resident in HBM.  The closed-form fit
-(statistics scan on the GPU + d x d algebra on the host) is timed separately and reported as `fit_ms`.
+(statistics scan on the GPU + d x d algebra on the host) is timed separately and reported as `fit_ms`, the
+device-resident variant of the same fit as `fit_device_ms`.
 Inputs rotate over three distinct sets so the 256 MB last-level cache cannot hold a set across steps.
 
 Prints ONE JSON line: throughput in tokens/s (B*L per step), the roofline of the dominant kernel measured
@@ -187,6 +188,15 @@ def main():
     fs.fit_params("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H)
     torch.cuda.synchronize()
     fit_ms = (time.perf_counter() - t0) * 1e3
+    # the same fit with the closed form on the device (asynchronous entry point; the timing includes the final sync)
+    fit_ws = torch.empty(fs.fit_device_workspace_bytes(B, H, L, L, d, H), dtype=torch.uint8, device="cuda")
+    fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    _, fit_status = fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
+    torch.cuda.synchronize()
+    fit_device_ms = (time.perf_counter() - t0) * 1e3
+    assert int(fit_status.abs().sum().item()) == 0
 
     nbytes = fs.attention_workspace_bytes(B, H, L, L, d, d, M, causal, H, H)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
@@ -235,6 +245,7 @@ def main():
                                + (f" chunk={chunk}" if causal else "") + ", SDERF per head, theta and omega resident"},
         "head_tokens_per_s": B * H * L / (ms_per_step * 1e-3),
         "fit_ms": fit_ms,
+        "fit_device_ms": fit_device_ms,
         "main_kernel_ms": main_ms,
         "algorithmic_tflops": counts["flops"] / (ms_per_step * 1e-3) / 1e12,
         # dominant kernel (k_fast_causal / k_fast_apply / the generic equivalents); the HBM bound is the tighter of

@@ -101,6 +101,26 @@ int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y,
                           void* stream);
 
 /*
+ * The same fit without a host round trip (the paper names the eigendecomposition on accelerators as the
+ * practical obstacle of the dense families, Section 4.3 and the discussion of limitations): the statistics scan and
+ * the closed forms of the Theorems on ADERF / SDERF and of Sections 2.3, 3.1, 4.3 all run on the device, the
+ * d x d decompositions as one-sided Jacobi iterations in fp64, one workgroup per group.
+ * Arguments as favorsharp_fit_params, plus
+ *   status: device, `groups` int32 values, overwritten: FS_OK, or FS_ERR_NOT_PD for a group whose statistics are
+ *           singular where ADERF / SADERF need them nonsingular (that group's theta is then left unwritten).
+ * Asynchronous: returns once the kernels are enqueued on `stream`; theta and status are valid after the stream
+ * reaches that point.  The returned value covers argument and launch errors only.
+ * Eigenvectors are unique only up to sign and up to rotations inside equal-eigenvalue blocks, so theta may differ
+ * from favorsharp_fit_params' in exactly those freedoms; log D, diag(A), the objective value, B^T B and the kernel
+ * estimate's distribution are the same.
+ */
+size_t favorsharp_fit_device_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups);
+int favorsharp_fit_params_device(int variant, const fs_tensor* X, const fs_tensor* Y,
+                                 int B, int H, int Lx, int Ly, int d, float qk_scale, int groups,
+                                 float eig_ridge, float* theta, int32_t* status,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Materialise one side of the feature matrix (Section 2.1: rows of P for side = 1, of S for side = 2):
  *   out[i, m] = M^-1/2 exp(alpha |x_i|^2) f^(side)(omega_m, x_i),  x_i = qk_scale * X[i, :]
  * (Section 2.3 for the exp(alpha |x|^2) factor that turns softmax-kernel features into K^(alpha) features).

@@ -58,6 +58,11 @@ def lib() -> ctypes.CDLL:
         L.favorsharp_fit_params.restype = c_int
         L.favorsharp_fit_params.argtypes = [c_int, P, P, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_float,
                                             c_void_p, c_void_p, c_size_t, c_void_p]
+        L.favorsharp_fit_device_workspace_bytes.restype = c_size_t
+        L.favorsharp_fit_device_workspace_bytes.argtypes = [c_int] * 6
+        L.favorsharp_fit_params_device.restype = c_int
+        L.favorsharp_fit_params_device.argtypes = [c_int, P, P, c_int, c_int, c_int, c_int, c_int, c_float, c_int, c_float,
+                                                   c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
         L.favorsharp_features_workspace_bytes.restype = c_size_t
         L.favorsharp_features_workspace_bytes.argtypes = [c_int] * 3
         L.favorsharp_features.restype = c_int
@@ -173,6 +178,31 @@ def fit_params(variant, X: torch.Tensor, Y: torch.Tensor, qk_scale: float, group
                                      eig_ridge, theta.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(st, "favorsharp_fit_params")
     return theta
+
+
+def fit_device_workspace_bytes(B, H, Lx, Ly, d, groups) -> int:
+    return int(lib().favorsharp_fit_device_workspace_bytes(B, H, Lx, Ly, d, groups))
+
+
+def fit_params_device(variant, X: torch.Tensor, Y: torch.Tensor, qk_scale: float, groups: int = 1,
+                      eig_ridge: float = 0.0, workspace: torch.Tensor | None = None):
+    """favorsharp_fit_params_device: as fit_params, without a host round trip.  Returns (theta, status), both on the
+    device; status [groups] int32 is valid once the stream has run the call (no synchronisation happens here)."""
+    v = VARIANTS[variant] if isinstance(variant, str) else int(variant)
+    if X.dim() == 2:
+        X, Y = X[None, None], Y[None, None]
+    B, H, Lx, d = X.shape
+    Ly = Y.shape[2]
+    theta = torch.empty((groups, theta_floats(d)), dtype=torch.float32, device=X.device)
+    status = torch.empty((groups,), dtype=torch.int32, device=X.device)
+    nbytes = fit_device_workspace_bytes(B, H, Lx, Ly, d, groups)
+    ws = _workspace(nbytes, X.device, workspace)
+    dx, dy = _desc4(X), _desc4(Y)
+    st = lib().favorsharp_fit_params_device(v, ctypes.byref(dx), ctypes.byref(dy), B, H, Lx, Ly, d, qk_scale, groups,
+                                            eig_ridge, theta.data_ptr(), status.data_ptr(), ws.data_ptr(), ws.numel(),
+                                            _stream())
+    _check(st, "favorsharp_fit_params_device")
+    return theta, status
 
 
 def features_workspace_bytes(n, d, M) -> int:

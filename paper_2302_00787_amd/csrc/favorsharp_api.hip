@@ -207,6 +207,37 @@ int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y, i
   return FS_OK;
 }
 
+size_t favorsharp_fit_device_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups) {
+  const size_t base = favorsharp_fit_workspace_bytes(B, H, Lx, Ly, d, groups);
+  if (base == 0) return 0;
+  return base + align_up(fit_device_workspace_doubles(d, groups) * sizeof(double));
+}
+
+int favorsharp_fit_params_device(int variant, const fs_tensor* X, const fs_tensor* Y, int B, int H, int Lx, int Ly, int d,
+                                 float qk_scale, int groups, float eig_ridge, float* theta, int32_t* status,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (variant < FS_POSRF || variant > FS_SDERF) return FS_ERR_INVALID_ARG;
+  if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || !groups_ok(groups, B, H)) return FS_ERR_INVALID_ARG;
+  if (d > 128) return FS_ERR_UNSUPPORTED;
+  if (!tensor_ok(X, d) || !tensor_ok(Y, d) || X->dtype != Y->dtype) return FS_ERR_INVALID_ARG;
+  if (theta == nullptr || status == nullptr || workspace == nullptr || !(eig_ridge >= 0.f) || !(qk_scale > 0.f))
+    return FS_ERR_INVALID_ARG;
+  FitPlan p;
+  plan_fit(B, H, Lx, Ly, d, groups, &p);
+  if (workspace_bytes < favorsharp_fit_device_workspace_bytes(B, H, Lx, Ly, d, groups)) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if ((int)gen_lds_stats(d) > device_lds_limit()) return FS_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* part = (float*)(ws + p.off_part);
+  double* stats = (double*)(ws + p.off_stats);
+  double* fitws = (double*)(ws + p.total);
+  if (int rc = launch_stats(dev(X), dev(Y), B, H, Lx, Ly, d, qk_scale, groups, p.rows_per_chunk, p.nchunks, part,
+                            stats, st))
+    return rc;
+  return launch_fit_device(variant, d, groups, stats, (double)eig_ridge, fitws, theta, status,
+                           favorsharp_theta_floats(d), st);
+}
+
 // ------------------------------------------------------------------------------------------ features
 size_t favorsharp_features_workspace_bytes(int n, int d, int M) {
   if (n < 0 || d < 1 || d > 128 || M < 1) return 0;

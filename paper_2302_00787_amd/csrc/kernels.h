@@ -50,6 +50,11 @@ int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, 
 bool stats_bf16_supported(const TensorDev& X, const TensorDev& Y, int d);
 int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
                       int rows_per_chunk, int nchunks, float* part, hipStream_t st);
+// Device-resident closed-form fit (kernels_fit.hip): one workgroup per group; ws holds fit_device_workspace_doubles
+// doubles; status[g] receives an fs_status value.
+size_t fit_device_workspace_doubles(int d, int groups);
+int launch_fit_device(int variant, int d, int groups, const double* stats, double ridge, double* ws, float* theta,
+                      int* status, size_t theta_floats, hipStream_t st);
 int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, int Ly, int d, float scale, int groups,
                  int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st);
 

@@ -199,11 +199,22 @@ def test_kernel_matvec_small(fs, variant):
 
 
 # ----------------------------------------------------------------------------- fit
+def _fit(fs, entry, variant, Qd, Kd, s, groups):
+    """theta [groups, floats] on the host from either fit entry point."""
+    if entry == "host":
+        return util.to_host(fs.fit_params(variant, Qd, Kd, s, groups=groups))
+    theta, status = fs.fit_params_device(variant, Qd, Kd, s, groups=groups)
+    assert util.to_host(status).tolist() == [0] * groups
+    return util.to_host(theta)
+
+
+@pytest.mark.parametrize("entry", ["host", "device"])
 @pytest.mark.parametrize("variant", ["posrf", "gerf", "saderf", "aderf", "sderf"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_fit_params_invariants(fs, variant, dtype):
+def test_fit_params_invariants(fs, variant, dtype, entry):
     """Eigenvectors are unique only up to sign / rotation inside equal eigenvalues, so the fit is compared on what
-    is unique: A, log D, the objective value, B^T B and B1^T B2, and the validity conditions of the DERF theorem."""
+    is unique: A, log D, the objective value, B^T B and B1^T B2, and the validity conditions of the DERF theorem.
+    Both entry points (closed forms on the host, closed forms on the device) are held to the same oracle."""
     rng = np.random.default_rng(41)
     B, H, L, d = 2, 3, 300, 16
     sc = np.linspace(0.4, 1.3, d)
@@ -212,7 +223,7 @@ def test_fit_params_invariants(fs, variant, dtype):
     if dtype == "bf16":
         Q, K = synth.round_to_bf16(Q), synth.round_to_bf16(K)
     s = d ** -0.25
-    theta = util.to_host(fs.fit_params(variant, util.to_device(Q, dtype), util.to_device(K, dtype), s, groups=H))
+    theta = _fit(fs, entry, variant, util.to_device(Q, dtype), util.to_device(K, dtype), s, H)
     for h in range(H):
         X = s * Q[:, h].reshape(-1, d).astype(np.float64)
         Yk = s * K[:, h].reshape(-1, d).astype(np.float64)
@@ -230,6 +241,81 @@ def test_fit_params_invariants(fs, variant, dtype):
         assert r["max_8A"] < 1 and r["cross"] < 1e-4 and r["C1"] < 1e-4 and r["C2"] < 1e-4 and r["logD"] < 1e-4
         # the fitted parameters reach the oracle's optimum of the objective on the same data
         assert orc.lbar_bruteforce(got, X[:200], Yk[:200]) == pytest.approx(orc.lbar_bruteforce(ref, X[:200], Yk[:200]), abs=2e-4)
+
+
+@pytest.mark.parametrize("variant", ["sderf", "aderf"])
+@pytest.mark.parametrize("d", [9, 64, 128])
+def test_device_fit_dense_families_at_other_sizes(fs, variant, d):
+    """The device-resident fit at an odd d (strided rows; the round-robin ordering gets a bye), at d = 64 (matrices in
+    LDS) and at d = 128 (matrices in global memory), on anisotropic data with a mean, against the oracle's fit."""
+    import torch
+    rng = np.random.default_rng(300 + d)
+    L, dpad = 700, (d + 3) // 4 * 4
+    U, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    spec = np.linspace(1.2, 0.3, d)
+    Q = np.zeros((1, 1, L, dpad), np.float32)
+    K = np.zeros((1, 1, L, dpad), np.float32)
+    Q[..., :d] = (rng.standard_normal((L, d)) * spec) @ U.T + 0.1
+    K[..., :d] = (rng.standard_normal((L, d)) * spec[::-1]) @ U.T - 0.05
+    s = d ** -0.25
+    Qd, Kd = torch.from_numpy(Q).cuda()[..., :d], torch.from_numpy(K).cuda()[..., :d]
+    theta = _fit(fs, "device", variant, Qd, Kd, s, 1)
+    X = s * Q[0, 0, :, :d].astype(np.float64)
+    Yk = s * K[0, 0, :, :d].astype(np.float64)
+    ref = orc.fit(variant, X, Yk)
+    got = util.oracle_theta_from_vec(theta[0], d)
+    np.testing.assert_allclose(np.sort(got.A), np.sort(ref.A), atol=2e-5)
+    assert got.logD == pytest.approx(ref.logD, abs=1e-4 * max(1.0, abs(ref.logD)))
+    assert float(theta[0][1]) == pytest.approx(ref.lbar, abs=2e-4 * max(1.0, abs(ref.lbar)))
+    np.testing.assert_allclose(got.B1.T @ got.B1, ref.B1.T @ ref.B1, atol=3e-4)
+    np.testing.assert_allclose(got.B1.T @ got.B2, ref.B1.T @ ref.B2, atol=3e-4)
+    np.testing.assert_allclose(got.C1, ref.C1, atol=3e-4)
+    np.testing.assert_allclose(got.C2, ref.C2, atol=3e-4)
+    r = orc.validity_residuals(got)
+    assert r["max_8A"] < 1 and r["cross"] < 1e-4 and r["C1"] < 1e-4 and r["C2"] < 1e-4 and r["logD"] < 1e-4
+    # and the host entry point agrees on the same invariants
+    host = util.oracle_theta_from_vec(_fit(fs, "host", variant, Qd, Kd, s, 1)[0], d)
+    np.testing.assert_allclose(np.sort(got.A), np.sort(host.A), atol=2e-5)
+    np.testing.assert_allclose(got.B1.T @ got.B2, host.B1.T @ host.B2, atol=3e-4)
+
+
+def test_device_fit_reports_singular_statistics_per_group(fs):
+    """ADERF needs nonsingular second moments: a head whose queries miss one coordinate gets FS_ERR_NOT_PD in its own
+    status word, the other head is fitted; the host entry point returns the same code for the call."""
+    import torch
+    rng = np.random.default_rng(77)
+    B, H, L, d = 1, 2, 200, 8
+    Q = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    K = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    Q[:, 1, :, 3] = 0.0
+    Qd, Kd = torch.from_numpy(Q).cuda(), torch.from_numpy(K).cuda()
+    s = d ** -0.25
+    theta, status = fs.fit_params_device("aderf", Qd, Kd, s, groups=H)
+    assert util.to_host(status).tolist() == [0, 3]
+    ref = orc.fit("aderf", s * Q[0, 0].astype(np.float64), s * K[0, 0].astype(np.float64))
+    got = util.oracle_theta_from_vec(util.to_host(theta)[0], d)
+    np.testing.assert_allclose(got.B1.T @ got.B2, ref.B1.T @ ref.B2, atol=3e-4)
+    with pytest.raises(fs.FavorSharpError) as err:
+        fs.fit_params("aderf", Qd, Kd, s, groups=H)
+    assert err.value.status == 3
+
+
+def test_device_fit_then_attention_without_host_round_trip(fs):
+    """Fit on the device and attention enqueued right behind it on the same stream; the parameter block is
+    downloaded afterwards and handed to the oracle, so the whole path is checked on one theta."""
+    import torch
+    w = synth.make("c4", B=1, H=2, L=640)
+    Q, K, V, Om, s = w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"]
+    Qd, Kd, Vd = (util.to_device(a, "bf16") for a in (Q, K, V))
+    theta, status = fs.fit_params_device("sderf", Qd, Kd, s, groups=2)
+    Y = util.to_host(fs.attention(theta, Qd, Kd, Vd, s, torch.from_numpy(Om).cuda(), causal=True, chunk=64))
+    assert util.to_host(status).tolist() == [0, 0]
+    th_host = util.to_host(theta)
+    for h in range(2):
+        th = util.oracle_theta_from_vec(th_host[h].astype(np.float32), w["d"])
+        ref = orc.attention(th, Om[h], Q[0, h], K[0, h], V[0, h], s, True)
+        fro, row = util.attention_errors(Y[0, h], ref, V[0, h].astype(np.float64))
+        assert fro <= 2e-2 and row <= 8e-2
 
 
 def test_fit_then_attention_end_to_end(fs):
