@@ -318,6 +318,67 @@ def attention_khat_definition(th: Theta, Omega, Q, K, V, qk_scale: float, causal
     return (Khat @ V) / Khat.sum(axis=1, keepdims=True)
 
 
+def attention_backward(th: Theta, Omega, Q, K, V, dY, qk_scale: float, causal: bool = False):
+    """Gradients of the scalar  sum(Y * dY)  with respect to Q, K and V, where Y is `attention(...)` above
+    (Section 2.2 with K_hat = P S^T) and theta, omega are held fixed (the paper fits theta from the data's statistics
+    and then treats it as a set of constants of the feature map, Sections 3.1 and 4.3).
+
+    Chain rule written out on the same quantities as the forward pass.  With V1 = [V 1], Yhat = P T (numerators and
+    denominator) and T = S^T V1 (causal: T_i = sum_{j<=i} S_j V1_j^T):
+      G1_i  = [dY_i / den_i, -(dY_i . Y_i) / den_i]                      (gradient of the row of Yhat)
+      dP_im = G1_i . T_(i),m        dE1 = P * dP                          (P = exp(E1))
+      R_j   = sum_{i (>= j when causal)} P_i^T G1_i                       (gradient of S_j V1_j^T)
+      dV1_j = S_j R_j               dS_jm = V1_j . R_(j),m    dE2 = S * dS
+      E1_im = omega_m^T B1 x_i + x_i^T C1 x_i + const_m   =>   dx_i = dE1_i (Omega B1) + sum_m dE1_im (C1 + C1^T) x_i
+    and the same on the key side; x = qk_scale Q, so dQ = qk_scale dx.  Returns (dQ, dK, dV), float64."""
+    Omega = np.asarray(Omega, dtype=np.float64)
+    X = qk_scale * np.asarray(Q, dtype=np.float64)
+    Y = qk_scale * np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    G = np.asarray(dY, dtype=np.float64)
+    E1 = log_features(th, Omega, X, 1)
+    E2 = log_features(th, Omega, Y, 2)
+    P = np.exp(E1 - E1.max(axis=1, keepdims=True))    # inert shifts: they cancel in Y and hence in its gradient
+    S = np.exp(E2 - E2.max())
+    V1 = np.concatenate([V, np.ones((V.shape[0], 1))], axis=1)
+    Lq, Lk = X.shape[0], Y.shape[0]
+    if not causal:
+        T = S.T @ V1
+        R = P @ T
+        den = R[:, -1]
+        out = R[:, :-1] / den[:, None]
+        G1 = np.concatenate([G / den[:, None], -(np.sum(G * out, axis=1) / den)[:, None]], axis=1)
+        dP = G1 @ T.T
+        Rk = P.T @ G1                                  # one R for every key
+        dV1 = S @ Rk
+        dS = V1 @ Rk.T
+    else:
+        if Lq != Lk:
+            raise ValueError("causal attention needs as many queries as keys")
+        Mf, n1 = S.shape[1], V1.shape[1]
+        dP = np.empty_like(P)
+        G1 = np.empty((Lq, n1))
+        T = np.zeros((Mf, n1))
+        for i in range(Lq):                            # forward sweep: prefix states
+            T += np.outer(S[i], V1[i])
+            r = P[i] @ T
+            yi = r[:-1] / r[-1]
+            G1[i] = np.concatenate([G[i] / r[-1], [-(G[i] @ yi) / r[-1]]])
+            dP[i] = T @ G1[i]
+        dV1 = np.empty_like(V1)
+        dS = np.empty_like(S)
+        Rk = np.zeros((Mf, n1))
+        for j in range(Lk - 1, -1, -1):                # backward sweep: suffix sums
+            Rk += np.outer(P[j], G1[j])
+            dV1[j] = S[j] @ Rk
+            dS[j] = Rk @ V1[j]
+    dE1 = P * dP
+    dE2 = S * dS
+    dX = dE1 @ (Omega @ th.B1) + dE1.sum(axis=1, keepdims=True) * (X @ (th.C1 + th.C1.T))
+    dYk = dE2 @ (Omega @ th.B2) + dE2.sum(axis=1, keepdims=True) * (Y @ (th.C2 + th.C2.T))
+    return qk_scale * dX, qk_scale * dYk, dV1[:, :-1]
+
+
 # --------------------------------------------------------------------------
 # exact references (never compared with the GPU; they validate the above)
 # --------------------------------------------------------------------------

@@ -125,3 +125,90 @@ def test_c1_workload_is_finite_convex_and_improves_with_more_features():
     assert np.all(rf <= V.max(0) + 1e-9) and np.all(rf >= V.min(0) - 1e-9)
     big = orc.attention(th, np.random.default_rng(1).standard_normal((65536, 16)), Q, K, V, s, False)
     assert np.linalg.norm(big - ex) < 0.35 * np.linalg.norm(rf - ex)
+
+
+# ----------------------------------------------------------------------------- gradients
+def _grad_case(variant, causal, seed, L=14, d=6, M=10, dv=5):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((L, d)) * np.linspace(0.5, 1.2, d) + 0.1
+    K = rng.standard_normal((L, d)) * np.linspace(1.1, 0.6, d) - 0.05
+    V = rng.standard_normal((L, dv))
+    dY = rng.standard_normal((L, dv))
+    Om = rng.standard_normal((M, d))
+    s = d ** -0.25
+    th = orc.fit(variant, s * Q, s * K)
+    return th, Om, Q, K, V, dY, s
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("variant", ["sderf", "aderf", "saderf", "gerf"])
+def test_attention_backward_matches_central_differences_of_the_forward_pass(variant, causal):
+    """The gradient is pinned to the forward oracle (itself pinned to the K_hat definition): directional derivatives
+    of sum(Y * dY) by central differences along random directions of Q, K and V, theta and omega held fixed."""
+    th, Om, Q, K, V, dY, s = _grad_case(variant, causal, 11)
+    dQ, dK, dV = orc.attention_backward(th, Om, Q, K, V, dY, s, causal)
+    rng = np.random.default_rng(12)
+    f = lambda q, k, v: float(np.sum(orc.attention(th, Om, q, k, v, s, causal) * dY))
+    eps = 1e-6
+    for _ in range(4):
+        uq, uk, uv = rng.standard_normal(Q.shape), rng.standard_normal(K.shape), rng.standard_normal(V.shape)
+        fd_q = (f(Q + eps * uq, K, V) - f(Q - eps * uq, K, V)) / (2 * eps)
+        fd_k = (f(Q, K + eps * uk, V) - f(Q, K - eps * uk, V)) / (2 * eps)
+        fd_v = (f(Q, K, V + eps * uv) - f(Q, K, V - eps * uv)) / (2 * eps)
+        assert fd_q == pytest.approx(float(np.sum(dQ * uq)), rel=2e-6, abs=1e-8)
+        assert fd_k == pytest.approx(float(np.sum(dK * uk)), rel=2e-6, abs=1e-8)
+        assert fd_v == pytest.approx(float(np.sum(dV * uv)), rel=2e-6, abs=1e-8)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_attention_backward_structure(causal):
+    """What the mathematics fixes without any differencing: the attention weights of a row sum to one, so the
+    value gradients add up to the output gradients and equal W^T dY for the row-stochastic weight matrix W of the
+    K_hat definition; when causal, row 0 of Y equals V_0 whatever Q_0 is, and row i never sees keys j > i."""
+    th, Om, Q, K, V, dY, s = _grad_case("sderf", causal, 21)
+    dQ, dK, dV = orc.attention_backward(th, Om, Q, K, V, dY, s, causal)
+    np.testing.assert_allclose(dV.sum(axis=0), dY.sum(axis=0), rtol=1e-10, atol=1e-12)
+    # dV = W^T dY with W the row-stochastic weight matrix of the K_hat definition
+    X, Yk = s * Q, s * K
+    Khat = orc.features(th, Om, X, 1) @ orc.features(th, Om, Yk, 2).T
+    if causal:
+        Khat = np.tril(Khat)
+    W = Khat / Khat.sum(axis=1, keepdims=True)
+    np.testing.assert_allclose(dV, W.T @ dY, rtol=1e-9, atol=1e-12)
+    if causal:
+        np.testing.assert_allclose(dQ[0], 0.0, atol=1e-12)
+        only_last = np.zeros_like(dY)
+        only_last[-1] = dY[-1]
+        g = orc.attention_backward(th, Om, Q, K, V, only_last, s, True)
+        np.testing.assert_allclose(g[0][:-1], 0.0, atol=1e-14)        # other queries do not matter to the last row
+        only_first = np.zeros_like(dY)
+        only_first[0] = dY[0]
+        g = orc.attention_backward(th, Om, Q, K, V, only_first, s, True)
+        np.testing.assert_allclose(g[1][1:], 0.0, atol=1e-14)         # later keys do not matter to the first row
+        np.testing.assert_allclose(g[2][1:], 0.0, atol=1e-14)
+
+
+def test_attention_backward_of_posrf_matches_the_closed_form_of_softmax_like_weights():
+    """With the weights W_ij = K_hat_ij / sum_j K_hat_ij the gradient with respect to the scores has the softmax
+    form; written out through d K_hat / d x for the positive random features (Section 2.3: exp(w.x - |x|^2/2)) this
+    gives dX_i = sum_j W_ij (dY_i . (V_j - Y_i)) * (sum_m P_im S_jm w_m / K_hat_ij - x_i), checked element by element
+    with explicit loops."""
+    rng = np.random.default_rng(5)
+    L, d, M, dv = 7, 4, 6, 3
+    Q, K, V, dY = (rng.standard_normal(sh) for sh in ((L, d), (L, d), (L, dv), (L, dv)))
+    Om = rng.standard_normal((M, d))
+    s = 0.7
+    th = orc.fit_posrf(d)
+    dQ, _, _ = orc.attention_backward(th, Om, Q, K, V, dY, s, False)
+    X, Yk = s * Q, s * K
+    P, S = orc.features(th, Om, X, 1), orc.features(th, Om, Yk, 2)
+    Khat = P @ S.T
+    W = Khat / Khat.sum(axis=1, keepdims=True)
+    Yo = W @ V
+    want = np.zeros_like(Q)
+    for i in range(L):
+        for j in range(L):
+            coef = W[i, j] * float(dY[i] @ (V[j] - Yo[i]))
+            dlogk = sum(P[i, m] * S[j, m] * Om[m] for m in range(M)) / Khat[i, j] - X[i]
+            want[i] += coef * dlogk
+    np.testing.assert_allclose(dQ, s * want, rtol=1e-9, atol=1e-12)
