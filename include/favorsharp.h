@@ -153,6 +153,24 @@ int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, con
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Backward pass of favorsharp_attention: gradients of  sum(Y * dY)  with respect to Q, K and V (the chain rule on
+ * the attention equation of Section 2.2 with K_hat = P S^T; theta and omega are constants of the feature map, as
+ * in the paper's training experiments where theta is fitted from the data's statistics, Sections 3.1 and 4.3).
+ * Nothing from the forward call is needed: the state, the outputs and the denominators are recomputed.
+ *   Q, K, V as in favorsharp_attention; dY: [B,H,Lq,dv] (f32 or bf16); dQ: [B,H,Lq,d], dK: [B,H,Lk,d],
+ *   dV: [B,H,Lk,dv] are written (->ptr; f32 or bf16 each).
+ *   causal must be 0 (the paper's attention is bidirectional; the causal variant's backward pass is not built:
+ *   FS_ERR_UNSUPPORTED).  Asynchronous on `stream`.
+ */
+size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M,
+                                                     int causal, int groups, int omega_groups);
+int favorsharp_attention_backward(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                  const fs_tensor* V, const fs_tensor* dY, int B, int H, int Lq, int Lk, int d, int dv,
+                                  float qk_scale, const float* Omega, int omega_groups, int M, int causal,
+                                  const fs_tensor* dQ, const fs_tensor* dK, const fs_tensor* dV,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Unbiased estimate of the kernel operator K^(alpha)(X, Y) C (Section 2.1, the problem statement):
  *   out = P (S^T C),  P, S built from x_i = qk_scale * X[i,:], y_j = qk_scale * Y[j,:] with the
  *   exp(alpha |.|^2) factors of Section 2.3, D and M^-1/2 all kept (alpha = -1/2: Gaussian kernel).

@@ -75,6 +75,12 @@ def lib() -> ctypes.CDLL:
                                            c_void_p, c_int, c_int, c_int, c_int, P, c_void_p, c_size_t, c_void_p]
         L.favorsharp_attention_timed.restype = c_int
         L.favorsharp_attention_timed.argtypes = L.favorsharp_attention.argtypes + [c_void_p, c_void_p]
+        L.favorsharp_attention_backward_workspace_bytes.restype = c_size_t
+        L.favorsharp_attention_backward_workspace_bytes.argtypes = [c_int] * 10
+        L.favorsharp_attention_backward.restype = c_int
+        L.favorsharp_attention_backward.argtypes = [c_void_p, c_int, P, P, P, P, c_int, c_int, c_int, c_int, c_int, c_int,
+                                                    c_float, c_void_p, c_int, c_int, c_int, P, P, P, c_void_p, c_size_t,
+                                                    c_void_p]
         L.favorsharp_kernel_matvec_workspace_bytes.restype = c_size_t
         L.favorsharp_kernel_matvec_workspace_bytes.argtypes = [c_int] * 5
         L.favorsharp_kernel_matvec.restype = c_int
@@ -251,6 +257,35 @@ def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
         st = lib().favorsharp_attention_timed(*args, events[0], events[1])
     _check(st, "favorsharp_attention")
     return out
+
+
+def attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups) -> int:
+    return int(lib().favorsharp_attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, int(causal), groups,
+                                                                    omega_groups))
+
+
+def attention_backward(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, dY: torch.Tensor,
+                       qk_scale: float, Omega: torch.Tensor, causal: bool = False, grad_dtype=None,
+                       workspace: torch.Tensor | None = None):
+    """favorsharp_attention_backward: gradients of sum(Y * dY) -> (dQ, dK, dV), shaped like Q, K, V."""
+    B, H, Lq, d = Q.shape
+    Lk, dv = K.shape[2], V.shape[3]
+    groups = theta.shape[0] if theta.dim() == 2 else 1
+    og, M = (Omega.shape[0], Omega.shape[1]) if Omega.dim() == 3 else (1, Omega.shape[0])
+    gd = grad_dtype or Q.dtype
+    gQ = torch.empty((B, H, Lq, d), dtype=gd, device=Q.device)
+    gK = torch.empty((B, H, Lk, d), dtype=gd, device=Q.device)
+    gV = torch.empty((B, H, Lk, dv), dtype=gd, device=Q.device)
+    nbytes = attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, og)
+    ws = _workspace(nbytes, Q.device, workspace)
+    descs = [_desc4(t) for t in (Q, K, V, dY, gQ, gK, gV)]
+    st = lib().favorsharp_attention_backward(theta.data_ptr(), groups, ctypes.byref(descs[0]), ctypes.byref(descs[1]),
+                                             ctypes.byref(descs[2]), ctypes.byref(descs[3]), B, H, Lq, Lk, d, dv,
+                                             qk_scale, Omega.data_ptr(), og, M, int(causal), ctypes.byref(descs[4]),
+                                             ctypes.byref(descs[5]), ctypes.byref(descs[6]), ws.data_ptr(), ws.numel(),
+                                             _stream())
+    _check(st, "favorsharp_attention_backward")
+    return gQ, gK, gV
 
 
 def orthogonal_omega(gauss_dir: np.ndarray, gauss_len: np.ndarray) -> np.ndarray:

@@ -39,11 +39,20 @@ int launch_gen_features(const TensorDev& X, int n, int d, float scale, float alp
                         hipStream_t st);
 int launch_gen_kmax(const GenSide& ks, int Lk, int BH, int H, int M, int d, uint32_t* kmax_u, hipStream_t st);
 int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int H, int M, int d, int nv,
-                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tpart,
-                     hipStream_t st);
+                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u,
+                     const float* row_shift, float* Tpart, hipStream_t st);
 int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int prefix, hipStream_t st);
 int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
-                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, hipStream_t st);
+                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, float* den_out,
+                     float* shift_out, hipStream_t st);
+// Backward pass of non-causal attention (general-shape kernels).
+size_t gen_lds_bwd_side(int d, int ldt);
+int launch_bwd_ghat(const TensorDev& dY, float* buf, const float* den, int L, int BH, int H, int nv, int ldt,
+                    hipStream_t st);
+int launch_gen_bwd_side(const GenSide& sd, int side, const TensorDev& A, int a_cols, int append_ones, int L, int BH,
+                        int H, int M, int d, int nv, int ldt, const float* St, size_t state_stride,
+                        const uint32_t* kmax_u, const float* row_shift, const TensorDev& out1, int want_out1,
+                        const TensorDev& grad, hipStream_t st);
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
                       const TensorDev& Y, hipStream_t st);

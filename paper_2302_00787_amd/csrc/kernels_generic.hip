@@ -239,9 +239,11 @@ __global__ void __launch_bounds__(NT) k_gen_kmax(GenSide ks, int Lk, int H, int 
 // Key-side partial states (Section 2.1, S^T C): Tpart[bh][seg][m][v] = sum_{j in seg} exp2(E2[j,m] - kmax) * V1[j,v].
 // grid (nseg, ceil(M/32), B*H).
 // ---------------------------------------------------------------------------------------------------
+// With row_shift != nullptr the kernel serves the backward pass on the query side: features of side 1 with the
+// per-row shifts the forward pass used (no row term in the exponent), "values" = the rows of the output gradient.
 __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int Lk, int H, int M, int d, int nv,
                                                   int append_ones, int ldt, int rows_per_seg, int nseg,
-                                                  const uint32_t* kmax_u, float* Tpart) {
+                                                  const uint32_t* kmax_u, const float* row_shift, float* Tpart) {
   extern __shared__ float smem[];
   const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
   float* Xs = smem;
@@ -253,10 +255,11 @@ __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int L
   const int seg = blockIdx.x, m0 = blockIdx.y * MB, bh = blockIdx.z, b = bh / H, h = bh % H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int pg = group_of(ks.pgroups, b, h, H);
-  const float* W = ks.W + ((size_t)pg * 2 + 1) * M * d;
-  const float* bias = ks.bias + ((size_t)pg * 2 + 1) * M;
+  const int side = row_shift == nullptr ? 1 : 0;
+  const float* W = ks.W + ((size_t)pg * 2 + side) * M * d;
+  const float* bias = ks.bias + ((size_t)pg * 2 + side) * M;
   const float* Cmat = side_cmat(ks, b, h, H);
-  const float c = ordered_to_float(kmax_u[bh]);
+  const float c = row_shift == nullptr ? ordered_to_float(kmax_u[bh]) : 0.f;
   const int nvt = ldt / 16, ntiles = 2 * nvt;
 
   load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
@@ -270,7 +273,8 @@ __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int L
     load_rows(Xs, ld, ks.X, b * ks.X.sb + h * ks.X.sh, row0, row_end, d, dpad, ks.scale);
     load_values(Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, append_ones);
     __syncthreads();
-    row_terms(rterm, Xs, ld, d, Cmat, ks.alpha);
+    if (row_shift == nullptr) row_terms(rterm, Xs, ld, d, Cmat, ks.alpha);
+    else if (threadIdx.x < TR) rterm[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * Lk + row0 + threadIdx.x] : 0.f;
     __syncthreads();
     const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
     const int f = (w & 1) * 16 + (lane & 15);
@@ -343,7 +347,7 @@ __device__ void store_result(const float* Os, int ldo, const TensorDev& Y, long 
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int M, int d, int nv, int ldt,
                                                   const float* T, size_t state_stride, const uint32_t* kmax_u,
-                                                  int matvec, TensorDev Y) {
+                                                  int matvec, TensorDev Y, float* den_out, float* shift_out) {
   extern __shared__ float smem[];
   const int dpad = (d + 3) & ~3, ld = dpad + 1, ldts = ldt + 1, lds = MB + 1;
   float* Xs = smem;
@@ -414,6 +418,11 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
   }
   __syncthreads();
   store_result(Os, ldts, Y, b * Y.sb + h * Y.sh, row0, Lq, nv, matvec, rscale);
+  // for the backward pass: the (shifted) denominators and the shifts themselves, so that it rebuilds the same features
+  if (den_out != nullptr && threadIdx.x < TR && row0 + threadIdx.x < Lq) {
+    den_out[(size_t)bh * Lq + row0 + threadIdx.x] = Os[threadIdx.x * ldts + nv];
+    shift_out[(size_t)bh * Lq + row0 + threadIdx.x] = ordered_to_float(rowmax_u[threadIdx.x]);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -631,6 +640,195 @@ __global__ void k_stats_final(const float* part, int B, int H, int nchunks, int 
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Backward pass of non-causal attention (chain rule on Section 2.2's attention equation with K_hat = P S^T;
+// theta and omega are constants).  With V1 = [V 1], T = S^T V1, Yhat = P T:
+//   G1_i = [dY_i / den_i, -(dY_i . Y_i) / den_i],  dP = G1 T^T,  R = P^T G1,  dV1 = S R,  dS = V1 R^T,
+//   dE = F * dF  (F = P or S),   dx = dE W + rowsum(dE) (C + C^T) x,   d(input) = qk_scale dx.
+// The exponent shifts of the forward pass (one per query row, one per sequence for the keys) cancel in every
+// product above, so the kernels work on the shifted quantities throughout.
+// ---------------------------------------------------------------------------------------------------
+
+// In place: row i of `buf` ([bh][L][ldt], holding Y_i in its first nv columns) becomes G1_i (zero padded).
+// One thread per row.
+__global__ void k_bwd_ghat(TensorDev dY, float* buf, const float* den, int L, int H, int nv, int ldt, size_t rows) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows) return;
+  const int bh = (int)(i / L), row = (int)(i - (size_t)bh * L), b = bh / H, h = bh % H;
+  float* g = buf + i * ldt;
+  const float dn = den[i];
+  const float inv = dn > 0.f ? 1.f / dn : 0.f;
+  const long long base = b * dY.sb + h * dY.sh + (long long)row * dY.sl;
+  float dot = 0.f;
+  for (int c = 0; c < nv; ++c) {
+    const float gy = load_elem(dY, base + c);
+    dot += gy * g[c];
+    g[c] = gy * inv;
+  }
+  g[nv] = -dot * inv;
+  for (int c = nv + 1; c < ldt; ++c) g[c] = 0.f;
+}
+
+// One side of the backward pass for a tile of 32 rows.  F = this side's features (query side: per-row shifts from
+// the forward pass, no row term; key side: the sequence's key shift and the row term), A = the rows' "left" factor
+// (query side: G1; key side: V1), St = the state it is contracted with (query side: T; key side: R).
+//   out1 = F St          (key side only: its first nv columns are dV)
+//   dF   = A St^T,  dE = F * dF,  grad = scale (dE W / log2e + rowsum(dE) (C + C^T) x)
+// grid (ceil(L/32), B*H).
+__global__ void __launch_bounds__(NT) k_gen_bwd_side(GenSide sd, int side, TensorDev A, int a_cols, int append_ones, int L,
+                                                     int H, int M, int d, int nv, int ldt, const float* St,
+                                                     size_t state_stride, const uint32_t* kmax_u, const float* row_shift,
+                                                     TensorDev out1, int want_out1, TensorDev grad) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldts = ldt + 1, lds = MB + 1;
+  float* Xs = smem;
+  float* Ws = Xs + TR * ld;          // also the gradient tile (32 x ld) at the end
+  float* As = Ws + MB * ld;
+  float* Sts = As + TR * ldts;       // also the out1 tile (32 x ldts) at the end
+  float* Fs = Sts + MB * ldts;
+  float* dEs = Fs + TR * lds;
+  float* bias_s = dEs + TR * lds;
+  float* rterm = bias_s + MB;        // what is added to the exponent per row (row term - shift)
+  float* rsum = rterm + TR;
+  const int bh = blockIdx.y, b = bh / H, h = bh % H, row0 = blockIdx.x * TR;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pg = group_of(sd.pgroups, b, h, H);
+  const float* W = sd.W + ((size_t)pg * 2 + side) * M * d;
+  const float* bias = sd.bias + ((size_t)pg * 2 + side) * M;
+  const float* Cmat = side_cmat(sd, b, h, H);
+  const float* Sb = St + (size_t)bh * state_stride;
+  const int nvt = ldt / 16, ntiles = 2 * nvt, nct = dpad / 16 + ((dpad & 15) ? 1 : 0), ngt = 2 * nct;
+
+  load_rows(Xs, ld, sd.X, b * sd.X.sb + h * sd.X.sh, row0, L, d, dpad, sd.scale);
+  load_values(As, ldts, A, b * A.sb + h * A.sh, row0, L, a_cols, ldt, append_ones);
+  __syncthreads();
+  if (side == 1) {
+    row_terms(rterm, Xs, ld, d, Cmat, sd.alpha);
+    __syncthreads();
+    if (threadIdx.x < TR) rterm[threadIdx.x] -= ordered_to_float(kmax_u[bh]);
+  } else if (threadIdx.x < TR) {
+    rterm[threadIdx.x] = row0 + threadIdx.x < L ? -row_shift[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
+  }
+
+  f32x4 acc_o[ACC_PER_WAVE], acc_g[4];
+#pragma unroll
+  for (int t = 0; t < ACC_PER_WAVE; ++t) acc_o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) acc_g[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float rs_part = 0.f;               // thread (row = tid / 8, part = tid % 8): its share of rowsum(dE)
+
+  for (int m0 = 0; m0 < M; m0 += MB) {
+    __syncthreads();
+    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+    for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
+      const int f = idx / ldt, c = idx - f * ldt;
+      Sts[f * ldts + c] = (m0 + f < M) ? Sb[(size_t)(m0 + f) * ldt + c] : 0.f;
+    }
+    __syncthreads();
+    const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
+    const int f = (w & 1) * 16 + (lane & 15);
+    float fv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+      fv[r] = (m0 + f < M && row0 + row < L) ? fast_exp2(e[r] + bias_s[f] + rterm[row]) : 0.f;
+      Fs[row * lds + f] = fv[r];
+    }
+    // dF tile of this wave (rows (w>>1)*16.., features (w&1)*16..): A[i][k=v] = As[i][v], B[k=v][n=m] = Sts[m][v]
+    {
+      const float* ap = As + ((w >> 1) * 16 + (lane & 15)) * ldts + (lane >> 4);
+      const float* bp = Sts + ((w & 1) * 16 + (lane & 15)) * ldts + (lane >> 4);
+      f32x4 df = {0.f, 0.f, 0.f, 0.f};
+      for (int k = 0; k < ldt; k += 4) df = mfma4(ap[k], bp[k], df);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+        dEs[row * lds + f] = fv[r] * df[r];
+      }
+    }
+    __syncthreads();
+    if (want_out1) {
+#pragma unroll
+      for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ntiles) {
+          const int rt = t & 1, vt = t >> 1;
+          const float* ap = Fs + (rt * 16 + (lane & 15)) * lds + (lane >> 4);     // A[i][k=m] = Fs[i][m]
+          const float* bp = Sts + (lane >> 4) * ldts + vt * 16 + (lane & 15);     // B[k=m][n=v] = Sts[m][v]
+          for (int k = 0; k < MB; k += 4) acc_o[tl] = mfma4(ap[k], bp[k * ldts], acc_o[tl]);
+        }
+      }
+    }
+#pragma unroll
+    for (int tl = 0; tl < 4; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ngt) {
+        const int rt = t & 1, ct = t >> 1;
+        const float* ap = dEs + (rt * 16 + (lane & 15)) * lds + (lane >> 4);      // A[i][k=m] = dEs[i][m]
+        const float* bp = Ws + (lane >> 4) * ld + ct * 16 + (lane & 15);          // B[k=m][n=c] = Ws[m][c]
+        f32x4 a = acc_g[tl];
+        for (int k = 0; k < MB; k += 4) a = mfma4(ap[k], (ct * 16 + (lane & 15) < dpad) ? bp[k * ld] : 0.f, a);
+        acc_g[tl] = a;
+      }
+    }
+    {
+      const int row = threadIdx.x >> 3, part = threadIdx.x & 7;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) rs_part += dEs[row * lds + part * 4 + q];
+    }
+  }
+  __syncthreads();
+  // tiles back to LDS
+  float* Gs = Ws;
+  float* Os = Sts;
+#pragma unroll
+  for (int tl = 0; tl < 4; ++tl) {
+    const int t = w + 4 * tl;
+    if (t < ngt) {
+      const int rt = t & 1, ct = t >> 1, col = ct * 16 + (lane & 15);
+      if (col < dpad) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Gs[(rt * 16 + 4 * (lane >> 4) + r) * ld + col] = acc_g[tl][r];
+      }
+    }
+  }
+  if (want_out1) {
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Os[(rt * 16 + 4 * (lane >> 4) + r) * ldts + vt * 16 + (lane & 15)] = acc_o[tl][r];
+      }
+    }
+  }
+  rs_part += __shfl_xor(rs_part, 1);
+  rs_part += __shfl_xor(rs_part, 2);
+  rs_part += __shfl_xor(rs_part, 4);
+  if ((threadIdx.x & 7) == 0) rsum[threadIdx.x >> 3] = rs_part;
+  __syncthreads();
+  // grad[i][c] = scale (Gs[i][c] / log2e + rsum_i ((C + C^T) x_i)[c]);  C = -I/2: (C + C^T) x = -x
+  for (int idx = threadIdx.x; idx < TR * d; idx += NT) {
+    const int r = idx / d, c = idx - r * d;
+    if (row0 + r >= L) continue;
+    float cx;
+    if (Cmat == nullptr) cx = -Xs[r * ld + c];
+    else {
+      cx = 0.f;
+      for (int a = 0; a < d; ++a) cx += (Cmat[c * d + a] + Cmat[a * d + c]) * Xs[r * ld + a];
+    }
+    const float v = sd.scale * (Gs[r * ld + c] * kLn2 + rsum[r] * (cx + 2.f * sd.alpha * Xs[r * ld + c]));
+    store_elem(grad, b * grad.sb + h * grad.sh + (long long)(row0 + r) * grad.sl + c, v);
+  }
+  if (want_out1) {
+    for (int idx = threadIdx.x; idx < TR * nv; idx += NT) {
+      const int r = idx / nv, c = idx - r * nv;
+      if (row0 + r < L) store_elem(out1, b * out1.sb + h * out1.sh + (long long)(row0 + r) * out1.sl + c, Os[r * ldts + c]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------------
 static size_t lds_floats_basic(int d) { const int ld = ((d + 3) & ~3) + 1; return (size_t)(TR + MB) * ld + MB + 2 * TR + TR; }
@@ -697,12 +895,12 @@ int launch_gen_kmax(const GenSide& ks, int Lk, int BH, int H, int M, int d, uint
 }
 
 int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int H, int M, int d, int nv,
-                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tpart,
-                     hipStream_t st) {
+                     int append_ones, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u,
+                     const float* row_shift, float* Tpart, hipStream_t st) {
   const size_t lds = gen_lds_state(d, ldt);
   if (int rc = set_lds((const void*)k_gen_state, lds)) return rc;
   hipLaunchKernelGGL(k_gen_state, dim3(nseg, (M + MB - 1) / MB, BH), dim3(NT), lds, st, ks, V, Lk, H, M, d, nv,
-                     append_ones, ldt, rows_per_seg, nseg, kmax_u, Tpart);
+                     append_ones, ldt, rows_per_seg, nseg, kmax_u, row_shift, Tpart);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -716,11 +914,37 @@ int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int pref
 }
 
 int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
-                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, hipStream_t st) {
+                     size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, float* den_out,
+                     float* shift_out, hipStream_t st) {
   const size_t lds = gen_lds_apply(d, ldt);
   if (int rc = set_lds((const void*)k_gen_apply, lds)) return rc;
   hipLaunchKernelGGL(k_gen_apply, dim3((Lq + TR - 1) / TR, BH), dim3(NT), lds, st, qs, Lq, H, M, d, nv, ldt, T,
-                     state_stride, kmax_u, matvec, Y);
+                     state_stride, kmax_u, matvec, Y, den_out, shift_out);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+size_t gen_lds_bwd_side(int d, int ldt) {
+  const int ld = ((d + 3) & ~3) + 1;
+  return ((size_t)(TR + MB) * ld + (size_t)(TR + MB) * (ldt + 1) + (size_t)2 * TR * (MB + 1) + MB + 2 * TR) * 4;
+}
+
+int launch_bwd_ghat(const TensorDev& dY, float* buf, const float* den, int L, int BH, int H, int nv, int ldt,
+                    hipStream_t st) {
+  const size_t rows = (size_t)BH * L;
+  hipLaunchKernelGGL(k_bwd_ghat, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, dY, buf, den, L, H, nv, ldt, rows);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_gen_bwd_side(const GenSide& sd, int side, const TensorDev& A, int a_cols, int append_ones, int L, int BH,
+                        int H, int M, int d, int nv, int ldt, const float* St, size_t state_stride,
+                        const uint32_t* kmax_u, const float* row_shift, const TensorDev& out1, int want_out1,
+                        const TensorDev& grad, hipStream_t st) {
+  const size_t lds = gen_lds_bwd_side(d, ldt);
+  if (int rc = set_lds((const void*)k_gen_bwd_side, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_bwd_side, dim3((L + TR - 1) / TR, BH), dim3(NT), lds, st, sd, side, A, a_cols, append_ones, L,
+                     H, M, d, nv, ldt, St, state_stride, kmax_u, row_shift, out1, want_out1, grad);
   FS_LAUNCH_CHECK();
   return 0;
 }

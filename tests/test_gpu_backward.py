@@ -1,0 +1,128 @@
+"""GPU parity of favorsharp_attention_backward against the oracle's attention_backward (non-causal).
+
+Tolerance: the kernels accumulate in fp32, the oracle in fp64; the gradients are sums of products of the same
+quantities as the forward pass plus one more contraction, so they are held to the forward bar per (b, h): relative
+Frobenius error <= 1e-4 times a factor 3 for the extra chain of contractions (f32 inputs) and the same for bf16
+inputs (the oracle sees the rounded inputs; all arithmetic of this path is fp32), 2e-2 when the gradients themselves
+are stored as bf16."""
+import numpy as np
+import pytest
+
+from oracle import favorsharp_oracle as orc
+from paper_2302_00787_amd import synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fs():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2302_00787_amd import binding
+    binding.lib()
+    return binding
+
+
+def _theta_block(variant, Q, K, scale):
+    vecs = []
+    for h in range(Q.shape[1]):
+        d = Q.shape[-1]
+        th = orc.fit(variant, scale * Q[:, h].reshape(-1, d).astype(np.float64), scale * K[:, h].reshape(-1, d).astype(np.float64))
+        vecs.append(util.theta_vec_from_oracle(th))
+    return np.stack(vecs)
+
+
+def _rel(a, b):
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def _check_backward(fs, Q, K, V, dY, Omega, scale, variant, dtype, tol, grad_dtype=None):
+    import torch
+    B, H, Lq, d = Q.shape
+    theta = _theta_block(variant, Q, K, scale)
+    gQ, gK, gV = fs.attention_backward(torch.from_numpy(theta).cuda(), util.to_device(Q, dtype), util.to_device(K, dtype),
+                                       util.to_device(V, dtype), util.to_device(dY, dtype), scale,
+                                       torch.from_numpy(Omega).cuda(), grad_dtype=grad_dtype)
+    torch.cuda.synchronize()
+    gQ, gK, gV = util.to_host(gQ), util.to_host(gK), util.to_host(gV)
+    assert np.isfinite(gQ).all() and np.isfinite(gK).all() and np.isfinite(gV).all()
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            th = util.oracle_theta_from_vec(theta[h], d)
+            rq, rk, rv = orc.attention_backward(th, Omega[h], Q[b, h], K[b, h], V[b, h], dY[b, h], scale, False)
+            errs = (_rel(gQ[b, h], rq), _rel(gK[b, h], rk), _rel(gV[b, h], rv))
+            worst = max(worst, *errs)
+            assert max(errs) <= tol, (b, h, errs)
+    return worst
+
+
+@pytest.mark.parametrize("variant", ["sderf", "aderf", "saderf", "gerf"])
+def test_backward_f32_small_ragged_different_lengths(fs, variant):
+    rng = np.random.default_rng(61)
+    B, H, Lq, Lk, d, dv, M = 2, 2, 70, 45, 12, 20, 50      # row starts must be 16-byte aligned: d, dv multiples of 4
+    Q = (rng.standard_normal((B, H, Lq, d)) * np.linspace(0.5, 1.2, d) + 0.1).astype(np.float32)
+    K = (rng.standard_normal((B, H, Lk, d)) * np.linspace(1.1, 0.6, d) - 0.05).astype(np.float32)
+    V = rng.standard_normal((B, H, Lk, dv)).astype(np.float32)
+    dY = rng.standard_normal((B, H, Lq, dv)).astype(np.float32)
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, variant, "f32", 3e-4)
+
+
+@pytest.mark.parametrize("L,M,d,dv", [(1, 1, 4, 4), (33, 16, 8, 4), (64, 200, 128, 128)])
+def test_backward_degenerate_and_maximum_sizes(fs, L, M, d, dv):
+    rng = np.random.default_rng(62)
+    Q = (0.7 * rng.standard_normal((1, 1, L, d))).astype(np.float32)
+    K = (0.7 * rng.standard_normal((1, 1, L, d))).astype(np.float32)
+    V = rng.standard_normal((1, 1, L, dv)).astype(np.float32)
+    dY = rng.standard_normal((1, 1, L, dv)).astype(np.float32)
+    Om = rng.standard_normal((1, M, d)).astype(np.float32)
+    _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, "sderf" if L > 1 else "posrf", "f32", 3e-4)
+
+
+def test_backward_c3_shape_bf16_inputs(fs):
+    """The non-causal bf16 workload at its real d, M and statistics, shortened so the oracle finishes in seconds:
+    bf16 inputs, fp32 gradients; and once more with bf16 gradients."""
+    w = synth.make("c3", B=1, H=2, L=704)
+    rng = np.random.default_rng(63)
+    dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+    import torch
+    worst = _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 3e-4,
+                            grad_dtype=torch.float32)
+    assert worst > 0.0
+    _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 2e-2)
+
+
+def test_backward_value_gradients_sum_to_output_gradients_at_full_c3_size(fs):
+    """At the full size of the non-causal workload the oracle cannot run; what holds at any size: the attention
+    weights of a row sum to one, so sum_j dV_j = sum_i dY_i per (b, h); and sampled rows of dV against the oracle's
+    weights W^T dY restricted to a subset of the queries' contribution is not available, so only the invariant is
+    checked here."""
+    import torch
+    w = synth.make("c3")
+    rng = np.random.default_rng(64)
+    dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+    theta = _theta_block("sderf", w["Q"][:1], w["K"][:1], w["qk_scale"])
+    gQ, gK, gV = fs.attention_backward(torch.from_numpy(theta).cuda(), util.to_device(w["Q"], "bf16"),
+                                       util.to_device(w["K"], "bf16"), util.to_device(w["V"], "bf16"),
+                                       util.to_device(dY, "bf16"), w["qk_scale"], torch.from_numpy(w["Omega"]).cuda(),
+                                       grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    gV = util.to_host(gV).astype(np.float64)
+    assert np.isfinite(util.to_host(gQ)).all() and np.isfinite(util.to_host(gK)).all()
+    want = dY.astype(np.float64).sum(axis=2)
+    got = gV.sum(axis=2)
+    scale = np.abs(dY).astype(np.float64).sum(axis=2).max()
+    assert np.abs(got - want).max() <= 1e-5 * scale
+
+
+def test_backward_error_paths(fs):
+    import torch
+    Q = torch.zeros((1, 1, 8, 8), device="cuda")
+    th = torch.from_numpy(util.theta_vec_from_oracle(orc.fit_posrf(8))[None]).cuda()
+    Om = torch.zeros((1, 4, 8), device="cuda")
+    with pytest.raises(fs.FavorSharpError) as err:
+        fs.attention_backward(th, Q, Q, Q, Q, 1.0, Om, causal=True)
+    assert err.value.status in (2, 4)       # unsupported (the workspace query already says so with 0 bytes)
