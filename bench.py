@@ -143,27 +143,30 @@ def bench_matvec(args, cfg, fs, synth, util, torch):
 
 
 def bench_backward(args, fs, synth, util, torch):
-    """The backward pass of non-causal attention on the c3 shapes (bf16 inputs, bf16 gradients): one step = one
-    favorsharp_attention_backward call with theta and omega resident.  It runs on the general-shape kernels (fp32
-    arithmetic on fp32 MFMA tiles), so the bound is the fp32 MFMA peak.  Algorithmic flops per head-token: the two
-    projections twice (features are rebuilt, and dE W) 8 d M, and six M x (dv + 1) contractions (T, P T, G1 T^T,
-    P^T G1, S R, [V 1] R^T) 12 M (dv + 1)."""
-    cfg = dict(synth.WORKLOADS["c3"])
-    B, H, L, d, M = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"]
+    """The backward pass of attention on the c3 (non-causal) or c4 (causal) shapes, bf16 inputs and gradients: one
+    step = one favorsharp_attention_backward call with theta and omega resident.  It runs on the general-shape
+    kernels (fp32 arithmetic on fp32 MFMA tiles), so the bound is the fp32 MFMA peak.  Algorithmic flops per
+    head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six M x (dv + 1) contractions
+    (T, P T, G1 T^T, P^T G1, S R, [V 1] R^T) 12 M (dv + 1), and when causal the intra-chunk triangles of 64 rows
+    (scores and G1 V1^T and their four products: three times the forward pass's extra term)."""
+    name = args.workload.split("_")[0]
+    cfg = dict(synth.WORKLOADS[name])
+    B, H, L, d, M, causal = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"], bool(cfg["causal"])
+    nsets = 3 if name == "c3" else 2
     sets = []
-    for i in range(3):
-        w = synth.make("c3", seed=cfg["seed"] + i)
+    for i in range(nsets):
+        w = synth.make(name, seed=cfg["seed"] + i)
         rng = np.random.default_rng(900 + i)
         Q, K, V = (util.to_device(w[k], "bf16") for k in "QKV")
         dY = util.to_device(synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32)), "bf16")
         theta = fs.fit_params("sderf", Q, K, w["qk_scale"], groups=H)
         sets.append((theta, Q, K, V, dY, torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"]))
-    ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, False, H, H), dtype=torch.uint8,
+    ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8,
                      device="cuda")
 
     def step(i):
-        theta, Q, K, V, dY, Om, s = sets[i % 3]
-        return fs.attention_backward(theta, Q, K, V, dY, s, Om, workspace=ws)
+        theta, Q, K, V, dY, Om, s = sets[i % nsets]
+        return fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
 
     for i in range(args.warmup):
         step(i)
@@ -174,15 +177,19 @@ def bench_backward(args, fs, synth, util, torch):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
     assert all(torch.isfinite(g.float()).all().item() for g in grads)
-    flops = B * H * L * (8 * d * M + 12 * M * (d + 1))
+    chunk = cfg.get("chunk", 64)
+    per_token = 8 * d * M + 12 * M * (d + 1) + (3 * (chunk + 1) // 2 * (2 * M + 2 * (d + 1)) if causal else 0)
+    flops = B * H * L * per_token
     tf = flops / (ms * 1e-3) / 1e12
     print(json.dumps({
-        "metric": "FAVOR# attention backward tokens/s (c3 shapes: non-causal, B=8 H=8 L=4096 d=64 M=256)",
+        "metric": f"FAVOR# attention backward tokens/s ({name} shapes: {'causal' if causal else 'non-causal'}, "
+                  f"B={B} H={H} L={L} d={d} M={M})",
         "value": B * L / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "c3_backward: gradients of non-causal attention w.r.t. Q, K, V, bf16 in and out, fp32 "
-                               "arithmetic (general-shape kernels), SDERF per head, theta and omega resident"},
+        "config": {"workload": f"{args.workload}: gradients of {'causal' if causal else 'non-causal'} attention w.r.t. "
+                               "Q, K, V, bf16 in and out, fp32 arithmetic (general-shape kernels), SDERF per head, "
+                               "theta and omega resident"},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
                      "traffic": None}}), flush=True)
 
@@ -192,7 +199,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c3_backward"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c3_backward", "c4_backward"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
@@ -209,7 +216,7 @@ def main():
     from tests import util
 
     fs.lib()
-    if args.workload == "c3_backward":
+    if args.workload.endswith("_backward"):
         bench_backward(args, fs, synth, util, torch)
         return
     cfg = dict(synth.WORKLOADS[args.workload])

@@ -159,8 +159,8 @@ int favorsharp_attention(const float* theta, int groups, const fs_tensor* Q, con
  * Nothing from the forward call is needed: the state, the outputs and the denominators are recomputed.
  *   Q, K, V as in favorsharp_attention; dY: [B,H,Lq,dv] (f32 or bf16); dQ: [B,H,Lq,d], dK: [B,H,Lk,d],
  *   dV: [B,H,Lk,dv] are written (->ptr; f32 or bf16 each).
- *   causal must be 0 (the paper's attention is bidirectional; the causal variant's backward pass is not built:
- *   FS_ERR_UNSUPPORTED).  Asynchronous on `stream`.
+ *   causal = 1 differentiates the causal variant (sum over j <= i; requires Lq == Lk): a forward sweep with the
+ *   prefix states and a backward sweep with the suffix sums of P^T G1.  Asynchronous on `stream`.
  */
 size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M,
                                                      int causal, int groups, int omega_groups);

@@ -359,7 +359,7 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
   if (event_main_begin && hipEventRecord((hipEvent_t)event_main_begin, st) != hipSuccess) return FS_ERR_DEVICE;
   int rc;
   if (causal)
-    rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), st);
+    rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), nullptr, nullptr, st);
   else
     rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), nullptr, nullptr, st);
   if (rc) return rc;
@@ -371,27 +371,29 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
 namespace {
 struct BwdPlan {
   AttnPlan k, q;           // key-side and query-side segmentations (the projection constants live in `k`)
-  size_t off_ghat, off_den, off_shift, off_rstate, total;
+  size_t off_ghat, off_den, off_shift, off_rstate, off_state2, total;
 };
 
-void plan_backward(int BH, int pgroups, int Lq, int Lk, int d, int dv, int M, BwdPlan* p) {
-  plan_contraction(BH, pgroups, Lk, d, M, dv + 1, 0, &p->k);
-  plan_contraction(BH, pgroups, Lq, d, M, dv + 1, 0, &p->q);
+void plan_backward(int BH, int pgroups, int Lq, int Lk, int d, int dv, int M, int causal, BwdPlan* p) {
+  plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p->k);
+  plan_contraction(BH, pgroups, Lq, d, M, dv + 1, causal, &p->q);
   size_t off = p->k.total;
   p->off_ghat = off;   off = align_up(off + (size_t)BH * Lq * p->k.ldt * sizeof(float));
   p->off_den = off;    off = align_up(off + (size_t)BH * Lq * sizeof(float));
   p->off_shift = off;  off = align_up(off + (size_t)BH * Lq * sizeof(float));
   p->off_rstate = off; off = align_up(off + (size_t)BH * p->q.nseg * M * p->k.ldt * sizeof(float));
+  p->off_state2 = off; off = align_up(off + (causal ? (size_t)BH * p->k.nseg * M * p->k.ldt * sizeof(float) : 0));
   p->total = off;
 }
 }  // namespace
 
 size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M, int causal,
                                                      int groups, int omega_groups) {
-  if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1 || causal != 0) return 0;
+  if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1) return 0;
+  if ((causal != 0 && causal != 1) || (causal && Lq != Lk)) return 0;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
   BwdPlan p;
-  plan_backward(B * H, std::max(groups, omega_groups), Lq, Lk, d, dv, M, &p);
+  plan_backward(B * H, std::max(groups, omega_groups), Lq, Lk, d, dv, M, causal, &p);
   return p.total;
 }
 
@@ -403,17 +405,18 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
-  if (causal || d > 128 || dv > 128) return FS_ERR_UNSUPPORTED;
+  if (d > 128 || dv > 128 || (causal && Lq != Lk)) return FS_ERR_UNSUPPORTED;
   if (theta == nullptr || Omega == nullptr || workspace == nullptr || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
   if (!tensor_ok(Q, d) || !tensor_ok(K, d) || !tensor_ok(V, dv) || !tensor_ok(dY, dv)) return FS_ERR_INVALID_ARG;
   if (!tensor_ok(dQ, d) || !tensor_ok(dK, d) || !tensor_ok(dV, dv)) return FS_ERR_INVALID_ARG;
   if (Q->dtype != K->dtype || Q->dtype != V->dtype) return FS_ERR_INVALID_ARG;
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
   BwdPlan p;
-  plan_backward(BH, pgroups, Lq, Lk, d, dv, M, &p);
+  plan_backward(BH, pgroups, Lq, Lk, d, dv, M, causal, &p);
   if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
   const int ldt = p.k.ldt;
-  const size_t lds_need = std::max({gen_lds_state(d, ldt), gen_lds_apply(d, ldt), gen_lds_bwd_side(d, ldt)});
+  const size_t lds_need = causal ? std::max({gen_lds_state(d, ldt), gen_lds_causal(d, ldt), gen_lds_bwd_causal(d, ldt)})
+                                 : std::max({gen_lds_state(d, ldt), gen_lds_apply(d, ldt), gen_lds_bwd_side(d, ldt)});
   if ((int)lds_need > device_lds_limit()) return FS_ERR_UNSUPPORTED;
 
   hipStream_t st = (hipStream_t)stream;
@@ -427,10 +430,12 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   float* den = (float*)(ws + p.off_den);
   float* shift = (float*)(ws + p.off_shift);
   float* rstate = (float*)(ws + p.off_rstate);
+  float* state2 = (float*)(ws + p.off_state2);
   const size_t dd = (size_t)d * d, per_state = (size_t)M * ldt;
   const long long tf = (long long)favorsharp_theta_floats(d);
 
-  // forward quantities: T = S^T [V 1], then Y, the denominators and the query shifts
+  // forward quantities: segment states of S^T [V 1] (summed, or their exclusive prefix when causal), then Y, the
+  // denominators and the query shifts
   if (int rc = launch_prep(theta, groups, Omega, omega_groups, pgroups, B, H, M, d, W, Wbf, bias, st)) return rc;
   if (int rc = launch_fill_u32(kmax, 0u, BH, st)) return rc;
   GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
@@ -438,15 +443,27 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
   if (int rc = launch_gen_state(ks, dev(V), Lk, BH, H, M, d, dv, 1, ldt, p.k.rows_per_seg, p.k.nseg, kmax, nullptr, state, st))
     return rc;
-  if (int rc = launch_gen_reduce(state, BH, p.k.nseg, per_state, 0, st)) return rc;
+  if (int rc = launch_gen_reduce(state, BH, p.k.nseg, per_state, causal, st)) return rc;
   const TensorDev gbuf{ghat, 0, (long long)H * Lq * ldt, (long long)Lq * ldt, (long long)ldt};
-  if (int rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, ldt, state, (size_t)p.k.nseg * per_state, kmax, 0, gbuf, den, shift, st))
-    return rc;
-  // G1 in place of Y, then R = P^T G1 (the query-side twin of the state pass)
+  if (causal) {
+    // the forward kernel advances its copy of the prefix states; the backward query kernel needs them afresh
+    if (hipMemcpyAsync(state2, state, (size_t)BH * p.k.nseg * per_state * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
+      return FS_ERR_DEVICE;
+    if (int rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, ldt, p.k.rows_per_seg, p.k.nseg, kmax, state, gbuf, den,
+                                   shift, st))
+      return rc;
+  } else {
+    if (int rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, ldt, state, (size_t)p.k.nseg * per_state, kmax, 0, gbuf, den, shift, st))
+      return rc;
+  }
+  // G1 in place of Y, then the segment sums of P^T G1 (the query-side twin of the state pass)
   if (int rc = launch_bwd_ghat(dev(dY), ghat, den, Lq, BH, H, dv, ldt, st)) return rc;
   if (int rc = launch_gen_state(qs, gbuf, Lq, BH, H, M, d, ldt, 0, ldt, p.q.rows_per_seg, p.q.nseg, kmax, shift, rstate, st))
     return rc;
-  if (int rc = launch_gen_reduce(rstate, BH, p.q.nseg, per_state, 0, st)) return rc;
+  if (int rc = launch_gen_reduce(rstate, BH, p.q.nseg, per_state, causal ? 2 : 0, st)) return rc;
+  if (causal)
+    return launch_gen_bwd_causal(qs, ks, dev(V), ghat, Lk, BH, H, M, d, dv, ldt, p.k.rows_per_seg, p.k.nseg, kmax, shift,
+                                 state2, rstate, dev(dQ), dev(dK), dev(dV), st);
   // query side: dP = G1 T^T -> dQ;  key side: dV = S R, dS = [V 1] R^T -> dK
   if (int rc = launch_gen_bwd_side(qs, 0, gbuf, ldt, 0, Lq, BH, H, M, d, dv, ldt, state, (size_t)p.k.nseg * per_state, kmax,
                                    shift, dev(dV), 0, dev(dQ), st))

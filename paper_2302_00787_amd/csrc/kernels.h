@@ -55,7 +55,12 @@ int launch_gen_bwd_side(const GenSide& sd, int side, const TensorDev& A, int a_c
                         const TensorDev& grad, hipStream_t st);
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
-                      const TensorDev& Y, hipStream_t st);
+                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st);
+size_t gen_lds_bwd_causal(int d, int ldt);
+int launch_gen_bwd_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, const float* ghat, int L, int BH, int H,
+                          int M, int d, int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u,
+                          const float* row_shift, float* Tstate, float* Rstate, const TensorDev& dQ, const TensorDev& dK,
+                          const TensorDev& dV, hipStream_t st);
 bool stats_bf16_supported(const TensorDev& X, const TensorDev& Y, int d);
 int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
                       int rows_per_chunk, int nchunks, float* part, hipStream_t st);

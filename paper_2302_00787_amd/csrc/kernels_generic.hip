@@ -310,13 +310,22 @@ __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int L
   }
 }
 
-// Sum (prefix = 0: result in segment 0's slot) or exclusive prefix (prefix = 1, in place) over the segments.
+// Sum (prefix = 0: result in segment 0's slot), exclusive prefix (prefix = 1, in place) or exclusive suffix
+// (prefix = 2, in place) over the segments.
 __global__ void k_gen_reduce(float* Tpart, int nseg, size_t per_state, size_t total, int prefix) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= total) return;
   const size_t bh = i / per_state, e = i - bh * per_state;
   float* p = Tpart + bh * nseg * per_state + e;
   float run = 0.f;
+  if (prefix == 2) {
+    for (int s = nseg - 1; s >= 0; --s) {
+      const float v = p[(size_t)s * per_state];
+      p[(size_t)s * per_state] = run;
+      run += v;
+    }
+    return;
+  }
   for (int s = 0; s < nseg; ++s) {
     const float v = p[(size_t)s * per_state];
     if (prefix) p[(size_t)s * per_state] = run;
@@ -433,7 +442,8 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, TensorDev V, int L, int H, int M, int d,
                                                    int nv, int ldt, int rows_per_seg, int nseg,
-                                                   const uint32_t* kmax_u, float* Tstate, TensorDev Y) {
+                                                   const uint32_t* kmax_u, float* Tstate, TensorDev Y, float* den_out,
+                                                   float* shift_out) {
   extern __shared__ float smem[];
   const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
   float* Qs = smem;
@@ -562,6 +572,10 @@ __global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, Tenso
     }
     __syncthreads();
     store_result(Os, ldv, Y, b * Y.sb + h * Y.sh, row0, row_end, nv, 0, nullptr);
+    if (den_out != nullptr && threadIdx.x < TR && row0 + threadIdx.x < row_end) {   // for the backward pass
+      den_out[(size_t)bh * L + row0 + threadIdx.x] = Os[threadIdx.x * ldv + nv];
+      shift_out[(size_t)bh * L + row0 + threadIdx.x] = ordered_to_float(rowmax_u[threadIdx.x]);
+    }
   }
 }
 
@@ -829,6 +843,404 @@ __global__ void __launch_bounds__(NT) k_gen_bwd_side(GenSide sd, int side, Tenso
 }
 
 // ---------------------------------------------------------------------------------------------------
+// Backward pass of causal attention.  With T_i the prefix state (keys j <= i) and R_j the suffix sum
+// sum_{i >= j} P_i^T G1_i, per chunk c of 32 rows (A = tril(G1_c V1_c^T), B = tril(P_c S_c^T)):
+//   dP_c  = G1_c T_{c-1}^T + A S_c                 dV1_c = S_c R_{c+1} + B^T G1_c
+//   dS_c  = V1_c R_{c+1}^T + A^T P_c               and dE = F * dF, dx = dE W + rowsum(dE) (C + C^T) x as above.
+// The query kernel walks a segment forwards with the running prefix state (initialised with the exclusive prefix
+// of the segment states), the key kernel walks it backwards with the running suffix sum (initialised with the
+// exclusive suffix of the segments' P^T G1).  G1, the denominators and the query shifts come from a forward pass.
+// grid (nseg, B*H) both.
+// ---------------------------------------------------------------------------------------------------
+struct BwdCausalSmem {
+  float *Qs, *Ks, *Ws, *Vs, *Gs, *Ts, *Ps, *Ss, *dEs, *As, *Bs, *bias_s, *rterm, *qsh, *rsum;
+};
+__device__ __forceinline__ BwdCausalSmem bwd_causal_carve(float* smem, int ld, int ldv, int lds) {
+  BwdCausalSmem m;
+  m.Qs = smem;
+  m.Ks = m.Qs + TR * ld;
+  m.Ws = m.Ks + TR * ld;
+  m.Vs = m.Ws + MB * ld;
+  m.Gs = m.Vs + TR * ldv;
+  m.Ts = m.Gs + TR * ldv;
+  m.Ps = m.Ts + MB * ldv;
+  m.Ss = m.Ps + TR * lds;
+  m.dEs = m.Ss + TR * lds;
+  m.As = m.dEs + TR * lds;
+  m.Bs = m.As + TR * lds;
+  m.bias_s = m.Bs + TR * lds;
+  m.rterm = m.bias_s + MB;
+  m.qsh = m.rterm + TR;
+  m.rsum = m.qsh + TR;
+  return m;
+}
+
+// As[i][j] = (j <= i) ? G1_i . V1_j : 0 for the chunk's 32 x 32 (query, key) pairs; wave w owns tile (w>>1, w&1).
+__device__ __forceinline__ void bwd_causal_amat(float* As, const float* Gs, const float* Vs, int ldv, int lds, int ldt) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const float* ap = Gs + ((w >> 1) * 16 + (lane & 15)) * ldv + (lane >> 4);   // A[i][k=v] = Gs[i][v]
+  const float* bp = Vs + ((w & 1) * 16 + (lane & 15)) * ldv + (lane >> 4);    // B[k=v][n=j] = Vs[j][v]
+  f32x4 a = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < ldt; k += 4) a = mfma4(ap[k], bp[k], a);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = (w >> 1) * 16 + 4 * (lane >> 4) + r, j = (w & 1) * 16 + (lane & 15);
+    As[i * lds + j] = (j <= i) ? a[r] : 0.f;
+  }
+}
+
+// grad rows of a 32-row tile from the accumulated dE W tile (Gsrc, stride ld), the row sums and x.
+__device__ __forceinline__ void bwd_store_grad(const TensorDev& grad, long long base, int row0, int row_end, int d, int ld,
+                                               const float* Gsrc, const float* rsum, const float* Xs, const float* Cmat,
+                                               float scale, float alpha) {
+  for (int idx = threadIdx.x; idx < TR * d; idx += NT) {
+    const int r = idx / d, c = idx - r * d;
+    if (row0 + r >= row_end) continue;
+    float cx;
+    if (Cmat == nullptr) cx = -Xs[r * ld + c];
+    else {
+      cx = 0.f;
+      for (int a = 0; a < d; ++a) cx += (Cmat[c * d + a] + Cmat[a * d + c]) * Xs[r * ld + a];
+    }
+    const float v = scale * (Gsrc[r * ld + c] * kLn2 + rsum[r] * (cx + 2.f * alpha * Xs[r * ld + c]));
+    store_elem(grad, base + (long long)(row0 + r) * grad.sl + c, v);
+  }
+}
+
+__global__ void __launch_bounds__(NT) k_gen_bwd_causal_q(GenSide qs, GenSide ks, TensorDev V, const float* ghat, int L,
+                                                         int H, int M, int d, int nv, int ldt, int rows_per_seg, int nseg,
+                                                         const uint32_t* kmax_u, const float* row_shift, float* Tstate,
+                                                         TensorDev dQ) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
+  const BwdCausalSmem m = bwd_causal_carve(smem, ld, ldv, lds);
+  const int seg = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pg = group_of(qs.pgroups, b, h, H);
+  const float* W1 = qs.W + ((size_t)pg * 2) * M * d;
+  const float* bias1 = qs.bias + ((size_t)pg * 2) * M;
+  const float* W2 = ks.W + ((size_t)pg * 2 + 1) * M * d;
+  const float* bias2 = ks.bias + ((size_t)pg * 2 + 1) * M;
+  const float* Cmat1 = side_cmat(qs, b, h, H);
+  const float* Cmat2 = side_cmat(ks, b, h, H);
+  const float c = ordered_to_float(kmax_u[bh]);
+  float* Tg = Tstate + ((size_t)bh * nseg + seg) * M * ldt;
+  const TensorDev G{ghat, 0, (long long)H * L * ldt, (long long)L * ldt, (long long)ldt};
+  const int nvt = ldt / 16, ntiles = 2 * nvt, nct = (dpad + 15) / 16, ngt = 2 * nct;
+  const long long qbase = b * qs.X.sb + h * qs.X.sh, kbase = b * ks.X.sb + h * ks.X.sh;
+
+  const int row_end = min(L, (seg + 1) * rows_per_seg);
+  for (int row0 = seg * rows_per_seg; row0 < row_end; row0 += TR) {
+    __syncthreads();
+    load_rows(m.Qs, ld, qs.X, qbase, row0, row_end, d, dpad, qs.scale);
+    load_rows(m.Ks, ld, ks.X, kbase, row0, row_end, d, dpad, ks.scale);
+    load_values(m.Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, 1);
+    load_values(m.Gs, ldv, G, b * G.sb + h * G.sh, row0, row_end, ldt, ldt, 0);
+    if (threadIdx.x < TR) m.qsh[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
+    __syncthreads();
+    row_terms(m.rterm, m.Ks, ld, d, Cmat2, 0.f);
+    bwd_causal_amat(m.As, m.Gs, m.Vs, ldv, lds, ldt);
+
+    f32x4 acc_g[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc_g[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float rs_part = 0.f;
+    for (int m0 = 0; m0 < M; m0 += MB) {
+      const int f = (w & 1) * 16 + (lane & 15);
+      __syncthreads();
+      load_wblock(m.Ws, m.bias_s, ld, W2, bias2, m0, M, d, dpad);
+      for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
+        const int ff = idx / ldt, cc = idx - ff * ldt;
+        m.Ts[ff * ldv + cc] = (m0 + ff < M) ? Tg[(size_t)(m0 + ff) * ldt + cc] : 0.f;
+      }
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(m.Ks, m.Ws, ld, dpad);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          m.Ss[row * lds + f] = (m0 + f < M && row0 + row < row_end) ? fast_exp2(e[r] + m.bias_s[f] + m.rterm[row] - c) : 0.f;
+        }
+      }
+      __syncthreads();
+      load_wblock(m.Ws, m.bias_s, ld, W1, bias1, m0, M, d, dpad);
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(m.Qs, m.Ws, ld, dpad);
+        float fv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          fv[r] = (m0 + f < M && row0 + row < row_end) ? fast_exp2(e[r] + m.bias_s[f] + m.qsh[row]) : 0.f;
+        }
+        // dP tile (rows (w>>1)*16.., features (w&1)*16..) = G1 T_prev^T + A S
+        f32x4 df = {0.f, 0.f, 0.f, 0.f};
+        {
+          const float* ap = m.Gs + ((w >> 1) * 16 + (lane & 15)) * ldv + (lane >> 4);   // A[i][k=v] = Gs[i][v]
+          const float* bp = m.Ts + ((w & 1) * 16 + (lane & 15)) * ldv + (lane >> 4);    // B[k=v][n=m] = Ts[m][v]
+          for (int k = 0; k < ldt; k += 4) df = mfma4(ap[k], bp[k], df);
+        }
+        {
+          const float* ap = m.As + ((w >> 1) * 16 + (lane & 15)) * lds + (lane >> 4);   // A[i][k=j] = As[i][j]
+          const float* bp = m.Ss + (lane >> 4) * lds + (w & 1) * 16 + (lane & 15);      // B[k=j][n=m] = Ss[j][m]
+          for (int k = 0; k < TR; k += 4) df = mfma4(ap[k], bp[k * lds], df);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          m.dEs[row * lds + f] = fv[r] * df[r];
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int tl = 0; tl < 4; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ngt) {
+          const int rt = t & 1, ct = t >> 1;
+          const float* ap = m.dEs + (rt * 16 + (lane & 15)) * lds + (lane >> 4);        // A[i][k=m] = dEs[i][m]
+          const float* bp = m.Ws + (lane >> 4) * ld + ct * 16 + (lane & 15);            // B[k=m][n=c] = Ws[m][c]
+          const bool in = ct * 16 + (lane & 15) < dpad;
+          f32x4 a = acc_g[tl];
+          for (int k = 0; k < MB; k += 4) a = mfma4(ap[k], in ? bp[k * ld] : 0.f, a);
+          acc_g[tl] = a;
+        }
+      }
+      {
+        const int row = threadIdx.x >> 3, part = threadIdx.x & 7;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rs_part += m.dEs[row * lds + part * 4 + q];
+      }
+      // the state takes this chunk's keys (after its last use above): T[m][v] += sum_j Ss[j][m] Vs[j][v]
+#pragma unroll
+      for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ntiles) {
+          const int rt = t & 1, vt = t >> 1;
+          f32x4 up = {0.f, 0.f, 0.f, 0.f};
+          const float* ap = m.Ss + (lane >> 4) * lds + rt * 16 + (lane & 15);
+          const float* bp = m.Vs + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+          for (int k = 0; k < TR; k += 4) up = mfma4(ap[k * lds], bp[k * ldv], up);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int mm = m0 + rt * 16 + 4 * (lane >> 4) + r;
+            if (mm < M) Tg[(size_t)mm * ldt + vt * 16 + (lane & 15)] += up[r];
+          }
+        }
+      }
+    }
+    __syncthreads();
+    float* Gd = m.Ws;
+#pragma unroll
+    for (int tl = 0; tl < 4; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ngt) {
+        const int rt = t & 1, ct = t >> 1, col = ct * 16 + (lane & 15);
+        if (col < dpad) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) Gd[(rt * 16 + 4 * (lane >> 4) + r) * ld + col] = acc_g[tl][r];
+        }
+      }
+    }
+    rs_part += __shfl_xor(rs_part, 1);
+    rs_part += __shfl_xor(rs_part, 2);
+    rs_part += __shfl_xor(rs_part, 4);
+    if ((threadIdx.x & 7) == 0) m.rsum[threadIdx.x >> 3] = rs_part;
+    __syncthreads();
+    bwd_store_grad(dQ, b * dQ.sb + h * dQ.sh, row0, row_end, d, ld, Gd, m.rsum, m.Qs, Cmat1, qs.scale, 0.f);
+  }
+}
+
+__global__ void __launch_bounds__(NT) k_gen_bwd_causal_k(GenSide qs, GenSide ks, TensorDev V, const float* ghat, int L,
+                                                         int H, int M, int d, int nv, int ldt, int rows_per_seg, int nseg,
+                                                         const uint32_t* kmax_u, const float* row_shift, float* Rstate,
+                                                         TensorDev dK, TensorDev dV) {
+  extern __shared__ float smem[];
+  const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
+  const BwdCausalSmem m = bwd_causal_carve(smem, ld, ldv, lds);
+  const int seg = blockIdx.x, bh = blockIdx.y, b = bh / H, h = bh % H;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int pg = group_of(qs.pgroups, b, h, H);
+  const float* W1 = qs.W + ((size_t)pg * 2) * M * d;
+  const float* bias1 = qs.bias + ((size_t)pg * 2) * M;
+  const float* W2 = ks.W + ((size_t)pg * 2 + 1) * M * d;
+  const float* bias2 = ks.bias + ((size_t)pg * 2 + 1) * M;
+  const float* Cmat2 = side_cmat(ks, b, h, H);
+  const float c = ordered_to_float(kmax_u[bh]);
+  float* Rg = Rstate + ((size_t)bh * nseg + seg) * M * ldt;
+  const TensorDev G{ghat, 0, (long long)H * L * ldt, (long long)L * ldt, (long long)ldt};
+  const int nvt = ldt / 16, ntiles = 2 * nvt, nct = (dpad + 15) / 16, ngt = 2 * nct;
+  const long long qbase = b * qs.X.sb + h * qs.X.sh, kbase = b * ks.X.sb + h * ks.X.sh;
+
+  const int row_beg = seg * rows_per_seg, row_end = min(L, (seg + 1) * rows_per_seg);
+  const int nchunk = (row_end - row_beg + TR - 1) / TR;
+  for (int ch = nchunk - 1; ch >= 0; --ch) {
+    const int row0 = row_beg + ch * TR;
+    __syncthreads();
+    load_rows(m.Qs, ld, qs.X, qbase, row0, row_end, d, dpad, qs.scale);
+    load_rows(m.Ks, ld, ks.X, kbase, row0, row_end, d, dpad, ks.scale);
+    load_values(m.Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, 1);
+    load_values(m.Gs, ldv, G, b * G.sb + h * G.sh, row0, row_end, ldt, ldt, 0);
+    if (threadIdx.x < TR) m.qsh[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
+    __syncthreads();
+    row_terms(m.rterm, m.Ks, ld, d, Cmat2, 0.f);
+    bwd_causal_amat(m.As, m.Gs, m.Vs, ldv, lds, ldt);
+
+    f32x4 acc_o[ACC_PER_WAVE], acc_g[4];
+#pragma unroll
+    for (int t = 0; t < ACC_PER_WAVE; ++t) acc_o[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc_g[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 sc = {0.f, 0.f, 0.f, 0.f};      // scores tile (query tile w>>1, key tile w&1)
+    float rs_part = 0.f;
+    for (int m0 = 0; m0 < M; m0 += MB) {
+      const int f = (w & 1) * 16 + (lane & 15);
+      __syncthreads();
+      load_wblock(m.Ws, m.bias_s, ld, W1, bias1, m0, M, d, dpad);
+      for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
+        const int ff = idx / ldt, cc = idx - ff * ldt;
+        m.Ts[ff * ldv + cc] = (m0 + ff < M) ? Rg[(size_t)(m0 + ff) * ldt + cc] : 0.f;
+      }
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(m.Qs, m.Ws, ld, dpad);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          m.Ps[row * lds + f] = (m0 + f < M && row0 + row < row_end) ? fast_exp2(e[r] + m.bias_s[f] + m.qsh[row]) : 0.f;
+        }
+      }
+      __syncthreads();
+      load_wblock(m.Ws, m.bias_s, ld, W2, bias2, m0, M, d, dpad);
+      __syncthreads();
+      {
+        const f32x4 e = proj_tile(m.Ks, m.Ws, ld, dpad);
+        float fv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          fv[r] = (m0 + f < M && row0 + row < row_end) ? fast_exp2(e[r] + m.bias_s[f] + m.rterm[row] - c) : 0.f;
+          m.Ss[row * lds + f] = fv[r];
+        }
+        // dS tile (keys (w>>1)*16.., features (w&1)*16..) = V1 R_next^T + A^T P
+        f32x4 ds = {0.f, 0.f, 0.f, 0.f};
+        {
+          const float* ap = m.Vs + ((w >> 1) * 16 + (lane & 15)) * ldv + (lane >> 4);   // A[j][k=v] = Vs[j][v]
+          const float* bp = m.Ts + ((w & 1) * 16 + (lane & 15)) * ldv + (lane >> 4);    // B[k=v][n=m] = Rs[m][v]
+          for (int k = 0; k < ldt; k += 4) ds = mfma4(ap[k], bp[k], ds);
+        }
+        {
+          const float* ap = m.As + (lane >> 4) * lds + (w >> 1) * 16 + (lane & 15);     // A[j][k=i] = As[i][j]
+          const float* bp = m.Ps + (lane >> 4) * lds + (w & 1) * 16 + (lane & 15);      // B[k=i][n=m] = Ps[i][m]
+          for (int k = 0; k < TR; k += 4) ds = mfma4(ap[k * lds], bp[k * lds], ds);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = (w >> 1) * 16 + 4 * (lane >> 4) + r;
+          m.dEs[row * lds + f] = fv[r] * ds[r];
+        }
+      }
+      __syncthreads();
+      {   // scores: A[i][k=m] = Ps[i][m], B[k=m][n=j] = Ss[j][m]
+        const float* ap = m.Ps + ((w >> 1) * 16 + (lane & 15)) * lds + (lane >> 4);
+        const float* bp = m.Ss + ((w & 1) * 16 + (lane & 15)) * lds + (lane >> 4);
+        for (int k = 0; k < MB; k += 4) sc = mfma4(ap[k], bp[k], sc);
+      }
+#pragma unroll
+      for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ntiles) {
+          const int rt = t & 1, vt = t >> 1;
+          {   // dV1 += S R_next: A[j][k=m] = Ss[j][m], B[k=m][n=v] = Rs[m][v]
+            const float* ap = m.Ss + (rt * 16 + (lane & 15)) * lds + (lane >> 4);
+            const float* bp = m.Ts + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+            for (int k = 0; k < MB; k += 4) acc_o[tl] = mfma4(ap[k], bp[k * ldv], acc_o[tl]);
+          }
+          {   // the suffix sum takes this chunk's queries (after its last use): R[m][v] += sum_i Ps[i][m] Gs[i][v]
+            f32x4 up = {0.f, 0.f, 0.f, 0.f};
+            const float* ap = m.Ps + (lane >> 4) * lds + rt * 16 + (lane & 15);
+            const float* bp = m.Gs + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+            for (int k = 0; k < TR; k += 4) up = mfma4(ap[k * lds], bp[k * ldv], up);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int mm = m0 + rt * 16 + 4 * (lane >> 4) + r;
+              if (mm < M) Rg[(size_t)mm * ldt + vt * 16 + (lane & 15)] += up[r];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int tl = 0; tl < 4; ++tl) {
+        const int t = w + 4 * tl;
+        if (t < ngt) {
+          const int rt = t & 1, ct = t >> 1;
+          const float* ap = m.dEs + (rt * 16 + (lane & 15)) * lds + (lane >> 4);
+          const float* bp = m.Ws + (lane >> 4) * ld + ct * 16 + (lane & 15);
+          const bool in = ct * 16 + (lane & 15) < dpad;
+          f32x4 a = acc_g[tl];
+          for (int k = 0; k < MB; k += 4) a = mfma4(ap[k], in ? bp[k * ld] : 0.f, a);
+          acc_g[tl] = a;
+        }
+      }
+      {
+        const int row = threadIdx.x >> 3, part = threadIdx.x & 7;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) rs_part += m.dEs[row * lds + part * 4 + q];
+      }
+    }
+    // B = tril(P S^T); dV1 += B^T G1: A[j][k=i] = Bs[i][j], B[k=i][n=v] = Gs[i][v]
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int i = (w >> 1) * 16 + 4 * (lane >> 4) + r, j = (w & 1) * 16 + (lane & 15);
+      m.Bs[i * lds + j] = (j <= i) ? sc[r] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+        const float* ap = m.Bs + (lane >> 4) * lds + rt * 16 + (lane & 15);
+        const float* bp = m.Gs + (lane >> 4) * ldv + vt * 16 + (lane & 15);
+        for (int k = 0; k < TR; k += 4) acc_o[tl] = mfma4(ap[k * lds], bp[k * ldv], acc_o[tl]);
+      }
+    }
+    __syncthreads();
+    float* Gd = m.Ws;
+    float* Os = m.Ts;
+#pragma unroll
+    for (int tl = 0; tl < 4; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ngt) {
+        const int rt = t & 1, ct = t >> 1, col = ct * 16 + (lane & 15);
+        if (col < dpad) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) Gd[(rt * 16 + 4 * (lane >> 4) + r) * ld + col] = acc_g[tl][r];
+        }
+      }
+    }
+#pragma unroll
+    for (int tl = 0; tl < ACC_PER_WAVE; ++tl) {
+      const int t = w + 4 * tl;
+      if (t < ntiles) {
+        const int rt = t & 1, vt = t >> 1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Os[(rt * 16 + 4 * (lane >> 4) + r) * ldv + vt * 16 + (lane & 15)] = acc_o[tl][r];
+      }
+    }
+    rs_part += __shfl_xor(rs_part, 1);
+    rs_part += __shfl_xor(rs_part, 2);
+    rs_part += __shfl_xor(rs_part, 4);
+    if ((threadIdx.x & 7) == 0) m.rsum[threadIdx.x >> 3] = rs_part;
+    __syncthreads();
+    bwd_store_grad(dK, b * dK.sb + h * dK.sh, row0, row_end, d, ld, Gd, m.rsum, m.Ks, Cmat2, ks.scale, 0.f);
+    for (int idx = threadIdx.x; idx < TR * nv; idx += NT) {
+      const int r = idx / nv, cc = idx - r * nv;
+      if (row0 + r < row_end) store_elem(dV, b * dV.sb + h * dV.sh + (long long)(row0 + r) * dV.sl + cc, Os[r * ldv + cc]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
 // host launchers
 // ---------------------------------------------------------------------------------------------------
 static size_t lds_floats_basic(int d) { const int ld = ((d + 3) & ~3) + 1; return (size_t)(TR + MB) * ld + MB + 2 * TR + TR; }
@@ -949,13 +1361,34 @@ int launch_gen_bwd_side(const GenSide& sd, int side, const TensorDev& A, int a_c
   return 0;
 }
 
+size_t gen_lds_bwd_causal(int d, int ldt) {
+  const int ld = ((d + 3) & ~3) + 1;
+  return ((size_t)(2 * TR + MB) * ld + (size_t)(2 * TR + MB) * (ldt + 1) + (size_t)5 * TR * (MB + 1) + MB + 3 * TR) * 4;
+}
+
+int launch_gen_bwd_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, const float* ghat, int L, int BH, int H,
+                          int M, int d, int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u,
+                          const float* row_shift, float* Tstate, float* Rstate, const TensorDev& dQ, const TensorDev& dK,
+                          const TensorDev& dV, hipStream_t st) {
+  const size_t lds = gen_lds_bwd_causal(d, ldt);
+  if (int rc = set_lds((const void*)k_gen_bwd_causal_q, lds)) return rc;
+  if (int rc = set_lds((const void*)k_gen_bwd_causal_k, lds)) return rc;
+  hipLaunchKernelGGL(k_gen_bwd_causal_q, dim3(nseg, BH), dim3(NT), lds, st, qs, ks, V, ghat, L, H, M, d, nv, ldt,
+                     rows_per_seg, nseg, kmax_u, row_shift, Tstate, dQ);
+  FS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_gen_bwd_causal_k, dim3(nseg, BH), dim3(NT), lds, st, qs, ks, V, ghat, L, H, M, d, nv, ldt,
+                     rows_per_seg, nseg, kmax_u, row_shift, Rstate, dK, dV);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
-                      const TensorDev& Y, hipStream_t st) {
+                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st) {
   const size_t lds = gen_lds_causal(d, ldt);
   if (int rc = set_lds((const void*)k_gen_causal, lds)) return rc;
   hipLaunchKernelGGL(k_gen_causal, dim3(nseg, BH), dim3(NT), lds, st, qs, ks, V, L, H, M, d, nv, ldt, rows_per_seg,
-                     nseg, kmax_u, Tstate, Y);
+                     nseg, kmax_u, Tstate, Y, den_out, shift_out);
   FS_LAUNCH_CHECK();
   return 0;
 }

@@ -1,4 +1,4 @@
-"""GPU parity of favorsharp_attention_backward against the oracle's attention_backward (non-causal).
+"""GPU parity of favorsharp_attention_backward against the oracle's attention_backward (non-causal and causal).
 
 Tolerance: the kernels accumulate in fp32, the oracle in fp64; the gradients are sums of products of the same
 quantities as the forward pass plus one more contraction, so they are held to the forward bar per (b, h): relative
@@ -38,13 +38,13 @@ def _rel(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def _check_backward(fs, Q, K, V, dY, Omega, scale, variant, dtype, tol, grad_dtype=None):
+def _check_backward(fs, Q, K, V, dY, Omega, scale, variant, dtype, tol, grad_dtype=None, causal=False):
     import torch
     B, H, Lq, d = Q.shape
     theta = _theta_block(variant, Q, K, scale)
     gQ, gK, gV = fs.attention_backward(torch.from_numpy(theta).cuda(), util.to_device(Q, dtype), util.to_device(K, dtype),
                                        util.to_device(V, dtype), util.to_device(dY, dtype), scale,
-                                       torch.from_numpy(Omega).cuda(), grad_dtype=grad_dtype)
+                                       torch.from_numpy(Omega).cuda(), causal=causal, grad_dtype=grad_dtype)
     torch.cuda.synchronize()
     gQ, gK, gV = util.to_host(gQ), util.to_host(gK), util.to_host(gV)
     assert np.isfinite(gQ).all() and np.isfinite(gK).all() and np.isfinite(gV).all()
@@ -52,7 +52,7 @@ def _check_backward(fs, Q, K, V, dY, Omega, scale, variant, dtype, tol, grad_dty
     for b in range(B):
         for h in range(H):
             th = util.oracle_theta_from_vec(theta[h], d)
-            rq, rk, rv = orc.attention_backward(th, Omega[h], Q[b, h], K[b, h], V[b, h], dY[b, h], scale, False)
+            rq, rk, rv = orc.attention_backward(th, Omega[h], Q[b, h], K[b, h], V[b, h], dY[b, h], scale, causal)
             errs = (_rel(gQ[b, h], rq), _rel(gK[b, h], rk), _rel(gV[b, h], rv))
             worst = max(worst, *errs)
             assert max(errs) <= tol, (b, h, errs)
@@ -118,11 +118,46 @@ def test_backward_value_gradients_sum_to_output_gradients_at_full_c3_size(fs):
     assert np.abs(got - want).max() <= 1e-5 * scale
 
 
+@pytest.mark.parametrize("variant", ["sderf", "aderf", "saderf", "gerf"])
+def test_backward_causal_f32_small_ragged(fs, variant):
+    """Causal variant: several segments, several 32-row steps per segment and a ragged tail."""
+    rng = np.random.default_rng(71)
+    B, H, L, d, dv, M = 2, 2, 333, 12, 20, 50
+    Q = (rng.standard_normal((B, H, L, d)) * np.linspace(0.5, 1.2, d) + 0.1).astype(np.float32)
+    K = (rng.standard_normal((B, H, L, d)) * np.linspace(1.1, 0.6, d) - 0.05).astype(np.float32)
+    V = rng.standard_normal((B, H, L, dv)).astype(np.float32)
+    dY = rng.standard_normal((B, H, L, dv)).astype(np.float32)
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, variant, "f32", 3e-4, causal=True)
+
+
+@pytest.mark.parametrize("L,M,d,dv", [(1, 1, 4, 4), (33, 16, 8, 4), (64, 200, 128, 128)])
+def test_backward_causal_degenerate_and_maximum_sizes(fs, L, M, d, dv):
+    rng = np.random.default_rng(72)
+    Q = (0.7 * rng.standard_normal((1, 1, L, d))).astype(np.float32)
+    K = (0.7 * rng.standard_normal((1, 1, L, d))).astype(np.float32)
+    V = rng.standard_normal((1, 1, L, dv)).astype(np.float32)
+    dY = rng.standard_normal((1, 1, L, dv)).astype(np.float32)
+    Om = rng.standard_normal((1, M, d)).astype(np.float32)
+    _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, "sderf" if L > 1 else "posrf", "f32", 3e-4, causal=True)
+
+
+def test_backward_causal_c4_shape_bf16_inputs(fs):
+    """The causal bf16 workload at its real d, M and statistics, shortened so the oracle finishes in seconds."""
+    import torch
+    w = synth.make("c4", B=1, H=2, L=1216)
+    rng = np.random.default_rng(73)
+    dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+    _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 3e-4,
+                    grad_dtype=torch.float32, causal=True)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
+    K = torch.zeros((1, 1, 12, 8), device="cuda")
     th = torch.from_numpy(util.theta_vec_from_oracle(orc.fit_posrf(8))[None]).cuda()
     Om = torch.zeros((1, 4, 8), device="cuda")
-    with pytest.raises(fs.FavorSharpError) as err:
-        fs.attention_backward(th, Q, Q, Q, Q, 1.0, Om, causal=True)
+    with pytest.raises(fs.FavorSharpError) as err:          # causal needs as many queries as keys
+        fs.attention_backward(th, Q, K, K, Q, 1.0, Om, causal=True)
     assert err.value.status in (2, 4)       # unsupported (the workspace query already says so with 0 bytes)
