@@ -663,23 +663,25 @@ __global__ void k_stats_final(const float* part, int B, int H, int nchunks, int 
 // ---------------------------------------------------------------------------------------------------
 
 // In place: row i of `buf` ([bh][L][ldt], holding Y_i in its first nv columns) becomes G1_i (zero padded).
-// One thread per row.
+// Sixteen lanes per row (consecutive columns: coalesced), 16 rows per workgroup of 256 threads.
 __global__ void k_bwd_ghat(TensorDev dY, float* buf, const float* den, int L, int H, int nv, int ldt, size_t rows) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= rows) return;
-  const int bh = (int)(i / L), row = (int)(i - (size_t)bh * L), b = bh / H, h = bh % H;
-  float* g = buf + i * ldt;
-  const float dn = den[i];
+  const size_t i = (size_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int l = threadIdx.x & 15;
+  const bool live = i < rows;
+  const size_t ii = live ? i : 0;
+  const int bh = (int)(ii / L), row = (int)(ii - (size_t)bh * L), b = bh / H, h = bh % H;
+  float* g = buf + ii * ldt;
+  const float dn = den[ii];
   const float inv = dn > 0.f ? 1.f / dn : 0.f;
   const long long base = b * dY.sb + h * dY.sh + (long long)row * dY.sl;
   float dot = 0.f;
-  for (int c = 0; c < nv; ++c) {
-    const float gy = load_elem(dY, base + c);
-    dot += gy * g[c];
-    g[c] = gy * inv;
-  }
-  g[nv] = -dot * inv;
-  for (int c = nv + 1; c < ldt; ++c) g[c] = 0.f;
+  for (int c = l; c < nv; c += 16) dot += load_elem(dY, base + c) * g[c];
+  dot += __shfl_xor(dot, 1);
+  dot += __shfl_xor(dot, 2);
+  dot += __shfl_xor(dot, 4);
+  dot += __shfl_xor(dot, 8);
+  if (!live) return;
+  for (int c = l; c < ldt; c += 16) g[c] = c < nv ? load_elem(dY, base + c) * inv : (c == nv ? -dot * inv : 0.f);
 }
 
 // One side of the backward pass for a tile of 32 rows.  F = this side's features (query side: per-row shifts from
@@ -1344,7 +1346,7 @@ size_t gen_lds_bwd_side(int d, int ldt) {
 int launch_bwd_ghat(const TensorDev& dY, float* buf, const float* den, int L, int BH, int H, int nv, int ldt,
                     hipStream_t st) {
   const size_t rows = (size_t)BH * L;
-  hipLaunchKernelGGL(k_bwd_ghat, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, st, dY, buf, den, L, H, nv, ldt, rows);
+  hipLaunchKernelGGL(k_bwd_ghat, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st, dY, buf, den, L, H, nv, ldt, rows);
   FS_LAUNCH_CHECK();
   return 0;
 }
