@@ -158,7 +158,8 @@ __device__ __forceinline__ void store_rows_s(const RowRegs& r, uint16_t (*tile)[
   }
 }
 
-__device__ __forceinline__ void store_query_rows(const RowRegs& r, Smem& sm, int buf, float wmax) {
+template <class S>
+__device__ __forceinline__ void store_query_rows(const RowRegs& r, S& sm, int buf, float wmax) {
   float n2[2];
   store_rows_s(r, sm.q[buf], n2);
 #pragma unroll
@@ -372,6 +373,52 @@ __device__ __forceinline__ void exchange_finish(Smem& sm, const TensorDev& Y, lo
       for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = own[vt] * inv;
     }
   }
+}
+
+// ---- bf16 exchange of partial output tiles and their sum on the MFMA pipe -----------------------------------------
+constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the bf16 exchange buffer: 176 bytes = 44 dwords: 16-byte accesses of 8 consecutive rows hit 32 different banks
+
+// Partial tile of token tile `it` from source `src` (rows v = 16 vt + 4g + r of token column c), as bf16.
+template <class S>
+__device__ __forceinline__ void exchange_put_bf16(S& sm, const f32x4 (&y)[NVT], int it, int src, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) *(bf16x4*)(&sm.xch[it][src][c][16 * vt + 4 * g]) = __builtin_convertvector(y[vt], bf16x4);
+}
+
+// Finish of token tile `it` of a chunk (value tiles vt0, vt0 + 1): the sum over the four sources' partial tiles is a
+// contraction on the MFMA pipe.  B[k = 8g + e][n = token] = partial of source g, column 16 vt + 8 h + e: one 16-byte
+// read straight from the exchange buffer; A_h[i][8g + e] = 1 iff e = i - 8h routes it to accumulator row i (two
+// MFMAs, h = 0, 1, fill a 16 x 16 tile).
+template <class S>
+__device__ __forceinline__ void finish_tiles(f32x4 (&fs)[4], const S& sm, int it, int vt0, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  const uint32_t one = (c & 1) ? 0x3f800000u : 0x3f80u;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    u32x4 av = {0u, 0u, 0u, 0u};
+    const bool mine = (c >> 3) == h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) av[i] = (mine && ((c & 7) >> 1) == i) ? one : 0u;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bf16x8 bv = *(const bf16x8*)(&sm.xch[it][g][c][16 * (vt0 + u) + 8 * h]);
+      fs[vt0 + u] = mfma(__builtin_bit_cast(bf16x8, av), bv, fs[vt0 + u]);
+    }
+  }
+}
+// Normaliser of token tile `it`: column 64 of the four partial tiles, summed and copied to every row by an MFMA; the
+// sums are scaled in place.
+template <class S>
+__device__ __forceinline__ void finish_norm(f32x4 (&fs)[4], const S& sm, int it, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  const bf16x8 bd = *(const bf16x8*)(&sm.xch[it][g][c][D]);
+  const u32x4 ad = {0x3f80u, 0u, 0u, 0u};
+  const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), bd, f32x4{0.f, 0.f, 0.f, 0.f});
+  const float den = dn[0];
+  const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+#pragma unroll
+  for (int vt = 0; vt < 4; ++vt) fs[vt] *= inv;
 }
 
 }  // namespace fast

@@ -166,11 +166,19 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
 
 // ---------------------------------------------------------------------------------------------------
 // Query side of the non-causal contraction: Y = (P T) normalised by its last column (Sections 2.1, 2.2) for a block
-// of query rows; T = total state of the (b,h) (slot 0 of Tpart).  grid (nblk, B*H), block 256.
+// of query rows; T = total state of the (b,h) (slot 0 of Tpart).  Four waves of 64 features; the partial output
+// tiles cross the waves as bf16 and are summed on the MFMA pipe.  The kernel needs a third of the LDS of the
+// key-side kernels and at most 256 registers, so two workgroups share a CU (two waves per SIMD: one's exp2 and
+// convert work beside the other's MFMAs and memory waits).  grid (nblk, B*H), block 256.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(NT) k_fast_apply(FastArgs a, int Lq, int rows_per_blk) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
+struct SmemApply {
+  __attribute__((aligned(16))) uint16_t q[2][TC][LDR];            // query rows
+  float qadd[2][TC];                                              // per query token: - row_shift
+  __attribute__((aligned(16))) uint16_t xch[NW][NW][16][LDXB];    // partial outputs (bf16): [token tile][source wave][token][column]
+};
+
+__global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int rows_per_blk) {
+  __shared__ SmemApply sm;
   const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
@@ -213,9 +221,28 @@ __global__ void __launch_bounds__(NT) k_fast_apply(FastArgs a, int Lq, int rows_
         y[vt] = mfma(tb[vt][0], p[0], f32x4{0.f, 0.f, 0.f, 0.f});
         y[vt] = mfma(tb[vt][1], p[1], y[vt]);
       }
-      exchange_put(sm, y, it);
+      exchange_put_bf16(sm, y, it, w, lane);
     }
-    exchange_finish(sm, a.Y, ybase, row0, row_end);
+    __syncthreads();
+    // wave w sums the four partial tiles of token tile w, normalises and stores
+    {
+      f32x4 fs[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+      finish_tiles(fs, sm, w, 0, lane);
+      finish_tiles(fs, sm, w, 2, lane);
+      finish_norm(fs, sm, w, lane);
+      const int token = row0 + 16 * w + c;
+      if (token < row_end) {
+        if (a.Y.dtype == 1) {
+          uint16_t* yp = (uint16_t*)a.Y.ptr + ybase + (long long)token * a.Y.sl + 4 * g;
+#pragma unroll
+          for (int vt = 0; vt < 4; ++vt) *(bf16x4*)(yp + 16 * vt) = __builtin_convertvector(fs[vt], bf16x4);
+        } else {
+          float* yp = (float*)a.Y.ptr + ybase + (long long)token * a.Y.sl + 4 * g;
+#pragma unroll
+          for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = fs[vt];
+        }
+      }
+    }
     if (more) store_query_rows(qr, sm, buf ^ 1, wmax);
     __syncthreads();
   }
@@ -236,14 +263,6 @@ void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub) {
   *nseg = (L + *rows_per_seg - 1) / *rows_per_seg;
   // the key-side kernel runs two workgroups per CU: give it half-segments when they are whole chunks
   *sub = (*rows_per_seg % (2 * TC) == 0) ? 2 : 1;
-}
-
-static int set_fast_lds(const void* fn) {
-  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Smem)) != hipSuccess) {
-    (void)hipGetLastError();
-    return 2;
-  }
-  return 0;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -325,7 +344,6 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
   hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * f.pgroups + rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
                      f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk);
   FS_LAUNCH_CHECK();
-  if (int rc = set_fast_lds((const void*)k_fast_apply)) return rc;
   // the last segment's states are never needed by the causal pass
   const int nstate = (f.causal ? f.nseg - 1 : f.nseg) * f.sub;
   if (nstate > 0) {
@@ -339,9 +357,11 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
   if (f.causal) {
     if (int rc = launch_fast_causal_kernel(a, BH, st)) return rc;
   } else {
-    int nblk, rows_per_blk, unused;
-    fast_plan(BH, f.Lq, &nblk, &rows_per_blk, &unused);
-    hipLaunchKernelGGL(k_fast_apply, dim3(nblk, BH), dim3(NT), sizeof(Smem), st, a, f.Lq, rows_per_blk);
+    // two workgroups per CU: about 512 blocks in all, whole chunks each
+    const int want = std::max(1, std::min((512 + BH - 1) / BH, (f.Lq + TC - 1) / TC));
+    const int rows_per_blk = (((f.Lq + want - 1) / want) + TC - 1) / TC * TC;
+    const int nblk = (f.Lq + rows_per_blk - 1) / rows_per_blk;
+    hipLaunchKernelGGL(k_fast_apply, dim3(nblk, BH), dim3(NT), 0, st, a, f.Lq, rows_per_blk);
     FS_LAUNCH_CHECK();
   }
   if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;

@@ -38,7 +38,6 @@ using namespace fast;
 namespace pc {
 
 constexpr int NT8 = 512;           // threads per workgroup
-constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the exchange buffer: 176 bytes = 44 dwords: 16-byte accesses of 8 consecutive rows hit 32 different banks
 
 struct SmemPC {
   uint16_t k[2][TC][LDR];          // key rows, bf16 bits
@@ -176,38 +175,6 @@ __device__ __forceinline__ void feature_tile64(const W64& ws, const B64* qb, con
     img[blk] = WITH_BIAS ? pack8(exp2v(acc[2 * blk] + add), exp2v(acc[2 * blk + 1] + add)) : pack8(exp2v(acc[2 * blk]), exp2v(acc[2 * blk + 1]));
 }
 
-// Finish of token tile `it` of a chunk (all 64 value columns): the sum over the four consumers' partial tiles is a
-// contraction on the MFMA pipe.  B[k = 8g + e][n = token] = partial of source g, column 16 vt + 8 h + e: one 16-byte
-// read straight from the exchange buffer; A_h[i][8g + e] = 1 iff e = i - 8h routes it to accumulator row i (two
-// MFMAs, h = 0, 1, fill a 16 x 16 tile); for the normaliser (column 64) A copies e = 0 to every row.
-__device__ __forceinline__ void finish_tiles(f32x4 (&fs)[4], const SmemPC& sm, int it, int vt0, int lane) {
-  const int g = lane >> 4, c = lane & 15;
-  const uint32_t one = (c & 1) ? 0x3f800000u : 0x3f80u;
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    u32x4 av = {0u, 0u, 0u, 0u};
-    const bool mine = (c >> 3) == h;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) av[i] = (mine && ((c & 7) >> 1) == i) ? one : 0u;
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bf16x8 bv = *(const bf16x8*)(&sm.xch[it][g][c][16 * (vt0 + u) + 8 * h]);
-      fs[vt0 + u] = mfma(__builtin_bit_cast(bf16x8, av), bv, fs[vt0 + u]);
-    }
-  }
-}
-// Normaliser of token tile `it`: column 64 of the four partial tiles, summed and copied to every row by an MFMA; the
-// sums are scaled in place.
-__device__ __forceinline__ void finish_norm(f32x4 (&fs)[4], const SmemPC& sm, int it, int lane) {
-  const int g = lane >> 4, c = lane & 15;
-  const bf16x8 bd = *(const bf16x8*)(&sm.xch[it][g][c][D]);
-  const u32x4 ad = {0x3f80u, 0u, 0u, 0u};
-  const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), bd, f32x4{0.f, 0.f, 0.f, 0.f});
-  const float den = dn[0];
-  const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
-#pragma unroll
-  for (int vt = 0; vt < 4; ++vt) fs[vt] *= inv;
-}
 // `ychunk`: first output row of the chunk (bytes); `nv`: its number of valid rows (0: nothing is stored).
 __device__ __forceinline__ void finish_store(const f32x4 (&fs)[4], const TensorDev& Y, const char* ychunk, int nv, int it, int lane) {
   const int g = lane >> 4, c = lane & 15;
