@@ -311,12 +311,25 @@ __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int L
 }
 
 // Sum (prefix = 0: result in segment 0's slot), exclusive prefix (prefix = 1, in place) or exclusive suffix
-// (prefix = 2, in place) over the segments.
-__global__ void k_gen_reduce(float* Tpart, int nseg, size_t per_state, size_t total, int prefix) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total) return;
-  const size_t bh = i / per_state, e = i - bh * per_state;
+// (prefix = 2, in place) over the segments.  block (64, 4): 64 consecutive elements, and for the plain sum four
+// interleaved groups of segments that are added up through LDS (the scans run on the first group alone).
+__global__ void __launch_bounds__(256) k_gen_reduce(float* Tpart, int nseg, size_t per_state, size_t total, int prefix) {
+  __shared__ float part[4][64];
+  const size_t i = (size_t)blockIdx.x * 64 + threadIdx.x;
+  const int grp = threadIdx.y;
+  const bool live = i < total;
+  const size_t bh = live ? i / per_state : 0, e = live ? i - bh * per_state : 0;
   float* p = Tpart + bh * nseg * per_state + e;
+  if (prefix == 0) {
+    float run = 0.f;
+    if (live)
+      for (int s = grp; s < nseg; s += 4) run += p[(size_t)s * per_state];
+    part[grp][threadIdx.x] = run;
+    __syncthreads();
+    if (live && grp == 0) p[0] = (part[0][threadIdx.x] + part[1][threadIdx.x]) + (part[2][threadIdx.x] + part[3][threadIdx.x]);
+    return;
+  }
+  if (!live || grp != 0) return;
   float run = 0.f;
   if (prefix == 2) {
     for (int s = nseg - 1; s >= 0; --s) {
@@ -324,14 +337,13 @@ __global__ void k_gen_reduce(float* Tpart, int nseg, size_t per_state, size_t to
       p[(size_t)s * per_state] = run;
       run += v;
     }
-    return;
+  } else {
+    for (int s = 0; s < nseg; ++s) {
+      const float v = p[(size_t)s * per_state];
+      p[(size_t)s * per_state] = run;
+      run += v;
+    }
   }
-  for (int s = 0; s < nseg; ++s) {
-    const float v = p[(size_t)s * per_state];
-    if (prefix) p[(size_t)s * per_state] = run;
-    run += v;
-  }
-  if (!prefix) p[0] = run;
 }
 
 // Normalise (attention) or rescale (operator) an accumulated 32 x ldt tile held in LDS and store it.
@@ -1321,7 +1333,7 @@ int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int 
 
 int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int prefix, hipStream_t st) {
   const size_t total = (size_t)BH * per_state;
-  hipLaunchKernelGGL(k_gen_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, Tpart, nseg, per_state,
+  hipLaunchKernelGGL(k_gen_reduce, dim3((unsigned)((total + 63) / 64)), dim3(64, 4), 0, st, Tpart, nseg, per_state,
                      total, prefix);
   FS_LAUNCH_CHECK();
   return 0;
