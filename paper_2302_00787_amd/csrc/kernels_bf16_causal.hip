@@ -55,7 +55,7 @@ struct SmemPC {
 // Global memory of a chunk is addressed through buffer descriptors: a uniform base (the chunk's first row), a 32-bit
 // byte offset per thread, and a byte count that ends with the last valid row, so that reads past the end of the
 // segment return zero and writes there are dropped, without branches or 64-bit address registers.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void* base, long long sl_bytes, int rows_valid, int row_bytes) {
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void* base, int sl_bytes, int rows_valid, int row_bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0,
                                            rows_valid > 0 ? (int)((rows_valid - 1) * sl_bytes + row_bytes) : 0, 0x00020000);
 }
@@ -95,14 +95,15 @@ __device__ __forceinline__ void stage_store(const Stage& s, SmemPC& sm, int buf,
     for (int i = 0; i < 2; ++i) {
       const int row = (tid >> 3) + 32 * i;
       const float nq2 = store_row_piece(s.q[i], sm.q[buf], row, tid & 7);
-      if ((tid & 7) == 0) sm.qadd[buf][4 * (row & 15) + (row >> 4)] = -row_shift(nq2, wmax1);
+      // the eight lanes of a row hold the same sum and write the same word: no branch
+      sm.qadd[buf][4 * (row & 15) + (row >> 4)] = -row_shift(nq2, wmax1);
     }
   } else if (part == 1) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int row = (tid >> 3) + 32 * i;
       const float nk2 = store_row_piece(s.k[i], sm.k[buf], row, tid & 7);
-      if ((tid & 7) == 0) {
+      {
         const bool valid = row0 + row < row_end;
         const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * nk2 : s.rk[i];
         sm.kadd[buf][4 * (row & 15) + (row >> 4)] = rt;
@@ -179,13 +180,13 @@ __device__ __forceinline__ void feature_tile64(const W64& ws, const B64* qb, con
 __device__ __forceinline__ void finish_store(const f32x4 (&fs)[4], const TensorDev& Y, const char* ychunk, int nv, int it, int lane) {
   const int g = lane >> 4, c = lane & 15;
   if (Y.dtype == 1) {
-    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 2 * Y.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 2 * (int)Y.sl, nv, 2 * D);
     const int off = 2 * ((16 * it + c) * (int)Y.sl + 4 * g);
 #pragma unroll
     for (int vt = 0; vt < 4; ++vt)
       __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(fs[vt], bf16x4)), ry, off + 32 * vt, 0, 0);
   } else {
-    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 4 * Y.sl, nv, 4 * D);
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(ychunk, 4 * (int)Y.sl, nv, 4 * D);
     const int off = 4 * ((16 * it + c) * (int)Y.sl + 4 * g);
 #pragma unroll
     for (int vt = 0; vt < 4; ++vt)
@@ -228,11 +229,11 @@ struct ChunkPtr { const uint16_t *q, *k, *v; const float* rk; };   // first row 
 __device__ __forceinline__ void stage_load_part(Stage& s, const ChunkPtr& cp, const SegCtx& cx, const FastArgs& a, int nv, int tid, int part) {
   const int row = tid >> 3, pc = tid & 7, j = tid & 63, pv = tid >> 6;
   if (part == 0) {
-    const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(cp.q, 2 * a.Q.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rq = chunk_rsrc(cp.q, 2 * (int)a.Q.sl, nv, 2 * D);
 #pragma unroll
     for (int i = 0; i < 2; ++i) s.q[i] = __builtin_amdgcn_raw_buffer_load_b128(rq, 2 * ((row + 32 * i) * (int)a.Q.sl + pc * 8), 0, 0);
   } else if (part == 1) {
-    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(cp.k, 2 * a.K.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rk = chunk_rsrc(cp.k, 2 * (int)a.K.sl, nv, 2 * D);
     // key row terms of a dense C2 (an empty range, hence zeros, when the closed form -|k|^2/2 applies)
     const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(cp.rk), 0,
                                                                         cx.isoC ? 0 : 4 * max(nv, 0), 0x00020000);
@@ -243,7 +244,7 @@ __device__ __forceinline__ void stage_load_part(Stage& s, const ChunkPtr& cp, co
     }
   } else {
     const int i = part - 2;
-    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(cp.v, 2 * a.V.sl, nv, 2 * D);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(cp.v, 2 * (int)a.V.sl, nv, 2 * D);
     s.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, 2 * (j * (int)a.V.sl + (pv + 4 * i) * 8), 0, 0);
   }
 }
@@ -310,6 +311,9 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
     const f32x4 kadd4 = *(const f32x4*)(&sm.kadd[buf][4 * c_here]);
     const f32x4 qadd4 = *(const f32x4*)(&sm.qadd[buf][4 * c_here]);
     cp.q += qstep; cp.k += kstep; cp.v += vstep; cp.rk += TC;     // now the chunk after the next
+    // running pointers stay loop-carried scalars (the compiler would otherwise rebuild each of them from the chunk
+    // counter with a 64-bit multiplication per chunk)
+    asm volatile("" : "+s"(cp.q), "+s"(cp.k), "+s"(cp.v), "+s"(cp.rk));
     const int nv2 = min(TC, cx.row_end - row0 - 2 * TC);
     f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 
@@ -353,6 +357,7 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
       FS_STEP_BARRIER();
     }
     yprev += ystep;
+    asm volatile("" : "+s"(yprev));
   }
   FS_STEP_BARRIER();               // the consumers' last step: every partial tile of the last chunk is written
   if (cx.row_end > cx.row_beg) {
