@@ -18,6 +18,7 @@ SOURCES = {
     "kernels_generic.hip": [],
     "kernels_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_causal.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "kernels_bf16_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_fit.hip": [],
     "host_fit.cpp": [],
 }

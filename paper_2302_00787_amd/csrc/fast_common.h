@@ -407,24 +407,43 @@ __device__ __forceinline__ void finish_tiles(f32x4 (&fs)[4], const S& sm, int it
     }
   }
 }
-// Normaliser of token tile `it`: column 64 of the four partial tiles, summed and copied to every row by an MFMA; the
-// sums are scaled in place.
+// Column 64 of the four partial tiles of token tile `it`, summed and copied to every row by an MFMA: every lane
+// (g, c) gets the sum for token c.
 template <class S>
-__device__ __forceinline__ void finish_norm(f32x4 (&fs)[4], const S& sm, int it, int lane) {
+__device__ __forceinline__ float finish_col64(const S& sm, int it, int lane) {
   const int g = lane >> 4, c = lane & 15;
   const bf16x8 bd = *(const bf16x8*)(&sm.xch[it][g][c][D]);
   const u32x4 ad = {0x3f80u, 0u, 0u, 0u};
   const f32x4 dn = mfma(__builtin_bit_cast(bf16x8, ad), bd, f32x4{0.f, 0.f, 0.f, 0.f});
-  const float den = dn[0];
+  return dn[0];
+}
+// Normaliser of token tile `it` (column 64); the sums are scaled in place.  Returns 1 / normaliser (0 if it is 0).
+template <class S>
+__device__ __forceinline__ float finish_norm(f32x4 (&fs)[4], const S& sm, int it, int lane) {
+  const float den = finish_col64(sm, it, lane);
   const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
 #pragma unroll
   for (int vt = 0; vt < 4; ++vt) fs[vt] *= inv;
+  return inv;
 }
+
+// Shared memory of the query-side kernels that keep their state in registers (64 kB: two workgroups per CU).
+struct SmemApply {
+  __attribute__((aligned(16))) uint16_t q[2][TC][LDR];            // rows (queries, or keys in the backward pass)
+  float qadd[2][TC];                                              // per token: what is added to its exponents
+  __attribute__((aligned(16))) uint16_t xch[NW][NW][16][LDXB];    // partial outputs (bf16): [token tile][source wave][token][column]
+};
 
 }  // namespace fast
 
 // Launcher of the causal segment kernel (its own translation unit: it is compiled with different code-generation
 // options than the other kernels of the path).
 int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st);
+// Backward pass (kernels_bf16_bwd.hip) and the reduction it borrows from the forward pass (kernels_bf16.hip).
+void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st);
+int launch_fast_backward(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
+                         const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
+                         float* rcstar, int rslots, int rows_per_rslot, hipStream_t st);
+size_t fast_bwd_lds_bytes();
 
 }  // namespace fs

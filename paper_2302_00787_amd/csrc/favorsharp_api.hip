@@ -387,6 +387,29 @@ void plan_backward(int BH, int pgroups, int Lq, int Lk, int d, int dv, int M, in
 }
 }  // namespace
 
+namespace {
+// bf16 path of the non-causal backward pass: the forward plan plus G1 rows and the query-side segment sums.
+struct FastBwdPlan {
+  FastPlan f;
+  int rslots, rows_per_rslot;
+  size_t off_gh, off_rpart, off_rcpart, off_rcstar, total;
+};
+
+void plan_fast_backward(int BH, int pgroups, int Lq, int Lk, FastBwdPlan* p) {
+  plan_fast(BH, pgroups, Lk, &p->f);
+  int nseg, rows_per_seg, sub;
+  fast_plan(BH, Lq, &nseg, &rows_per_seg, &sub);
+  p->rslots = nseg * sub;
+  p->rows_per_rslot = rows_per_seg / sub;
+  size_t off = p->f.total;
+  p->off_gh = off;     off = align_up(off + (size_t)BH * Lq * 80 * sizeof(uint16_t));
+  p->off_rpart = off;  off = align_up(off + (size_t)BH * p->rslots * 256 * 80 * sizeof(float));
+  p->off_rcpart = off; off = align_up(off + (size_t)BH * p->rslots * sizeof(float));
+  p->off_rcstar = off; off = align_up(off + (size_t)BH * sizeof(float));
+  p->total = off;
+}
+}  // namespace
+
 size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M, int causal,
                                                      int groups, int omega_groups) {
   if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1) return 0;
@@ -394,7 +417,13 @@ size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int L
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
   BwdPlan p;
   plan_backward(B * H, std::max(groups, omega_groups), Lq, Lk, d, dv, M, causal, &p);
-  return p.total;
+  size_t total = p.total;
+  if (!causal && fast_supported(FS_BF16, d, dv, M)) {      // the query does not know the dtype: cover both paths
+    FastBwdPlan fp;
+    plan_fast_backward(B * H, std::max(groups, omega_groups), Lq, Lk, &fp);
+    total = std::max(total, fp.total);
+  }
+  return total;
 }
 
 int favorsharp_attention_backward(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
@@ -411,9 +440,30 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   if (!tensor_ok(dQ, d) || !tensor_ok(dK, d) || !tensor_ok(dV, dv)) return FS_ERR_INVALID_ARG;
   if (Q->dtype != K->dtype || Q->dtype != V->dtype) return FS_ERR_INVALID_ARG;
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
+  if (workspace_bytes < favorsharp_attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups))
+    return FS_ERR_WORKSPACE_TOO_SMALL;
+  // bf16 kernels: non-causal, d = dv = 64, M = 256, bf16 inputs and output gradient, rows addressable with 32 bits
+  const long long max_sl = 1ll << 23;
+  if (!causal && fast_supported(Q->dtype, d, dv, M) && dY->dtype == FS_BF16 && Q->stride_l < max_sl && K->stride_l < max_sl &&
+      V->stride_l < max_sl && (int)std::max(fast_lds_bytes(), fast_bwd_lds_bytes()) <= device_lds_limit()) {
+    FastBwdPlan fp;
+    plan_fast_backward(BH, pgroups, Lq, Lk, &fp);
+    char* w8 = (char*)workspace;
+    FastLaunch f;
+    f.Q = dev(Q); f.K = dev(K); f.V = dev(V); f.Y = dev(dV);     // no forward output is written on this path
+    f.theta = theta; f.Omega = Omega;
+    f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
+    f.B = B; f.H = H; f.Lq = Lq; f.Lk = Lk; f.causal = 0;
+    f.nseg = fp.f.nseg; f.rows_per_seg = fp.f.rows_per_seg; f.sub = fp.f.sub; f.scale = qk_scale;
+    f.Wbf = (uint16_t*)(w8 + fp.f.off_Wbf); f.bias = (float*)(w8 + fp.f.off_bias); f.wnorm = (float*)(w8 + fp.f.off_wnorm);
+    f.rk = (float*)(w8 + fp.f.off_rk); f.Tpart = (float*)(w8 + fp.f.off_state); f.cpart = (float*)(w8 + fp.f.off_cpart);
+    f.cstar = (float*)(w8 + fp.f.off_cstar);
+    return launch_fast_attention_backward(f, dev(dY), dev(dQ), dev(dK), dev(dV), (uint16_t*)(w8 + fp.off_gh),
+                                          (float*)(w8 + fp.off_rpart), (float*)(w8 + fp.off_rcpart),
+                                          (float*)(w8 + fp.off_rcstar), fp.rslots, fp.rows_per_rslot, (hipStream_t)stream);
+  }
   BwdPlan p;
   plan_backward(BH, pgroups, Lq, Lk, d, dv, M, causal, &p);
-  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
   const int ldt = p.k.ldt;
   const size_t lds_need = causal ? std::max({gen_lds_state(d, ldt), gen_lds_causal(d, ldt), gen_lds_bwd_causal(d, ldt)})
                                  : std::max({gen_lds_state(d, ldt), gen_lds_apply(d, ldt), gen_lds_bwd_side(d, ldt)});

@@ -98,5 +98,9 @@ size_t fast_lds_bytes();
 bool fast_supported(int dtype, int d, int dv, int M);
 void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub);
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
+int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, const TensorDev& dQ, const TensorDev& dK,
+                                   const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart, float* rcstar,
+                                   int rslots, int rows_per_rslot, hipStream_t st);
+size_t fast_bwd_lds_bytes();
 
 }  // namespace fs

@@ -171,12 +171,6 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
 // key-side kernels and at most 256 registers, so two workgroups share a CU (two waves per SIMD: one's exp2 and
 // convert work beside the other's MFMAs and memory waits).  grid (nblk, B*H), block 256.
 // ---------------------------------------------------------------------------------------------------
-struct SmemApply {
-  __attribute__((aligned(16))) uint16_t q[2][TC][LDR];            // query rows
-  float qadd[2][TC];                                              // per query token: - row_shift
-  __attribute__((aligned(16))) uint16_t xch[NW][NW][16][LDXB];    // partial outputs (bf16): [token tile][source wave][token][column]
-};
-
 __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int rows_per_blk) {
   __shared__ SmemApply sm;
   const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
@@ -331,8 +325,8 @@ int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int
   return 0;
 }
 
-int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
-  FastArgs a;
+// Projection constants, key-side segment states and their reduction (sum, or exclusive prefix when causal).
+static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st) {
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
   a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.theta = f.theta; a.rk = f.rk;
   a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
@@ -353,6 +347,18 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
                      a.nslot, nstate, f.causal, f.sub);
   FS_LAUNCH_CHECK();
+  return 0;
+}
+
+// Sum of `nslot` segment states per (b,h) into slot 0 (the reduction kernel of the forward pass on another buffer).
+void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st) {
+  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, part, cpart, cstar, nslot, nslot, 0, 1);
+}
+
+int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
+  FastArgs a;
+  if (int rc = launch_fast_state_pass(f, a, st)) return rc;
+  const int BH = f.B * f.H;
   if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
   if (f.causal) {
     if (int rc = launch_fast_causal_kernel(a, BH, st)) return rc;
@@ -366,6 +372,15 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
   }
   if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;
   return 0;
+}
+
+// Backward pass of a non-causal call: the forward state pass, then the kernels of kernels_bf16_bwd.hip.
+int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, const TensorDev& dQ, const TensorDev& dK,
+                                   const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart, float* rcstar,
+                                   int rslots, int rows_per_rslot, hipStream_t st) {
+  FastArgs a;
+  if (int rc = launch_fast_state_pass(f, a, st)) return rc;
+  return launch_fast_backward(f, a, dY, dQ, dK, dV, gh, Rpart, rcpart, rcstar, rslots, rows_per_rslot, st);
 }
 
 }  // namespace fs

@@ -86,16 +86,33 @@ def test_backward_degenerate_and_maximum_sizes(fs, L, M, d, dv):
 
 
 def test_backward_c3_shape_bf16_inputs(fs):
-    """The non-causal bf16 workload at its real d, M and statistics, shortened so the oracle finishes in seconds:
-    bf16 inputs, fp32 gradients; and once more with bf16 gradients."""
-    w = synth.make("c3", B=1, H=2, L=704)
+    """The non-causal bf16 workload at its real d, M and statistics, shortened so the oracle finishes in seconds.
+    This shape runs on the bf16 MFMA kernels (bf16 operands, fp32 accumulation): the bar is the bf16 one, 2e-2, for
+    fp32 and for bf16 gradients.  The length is not a multiple of the tile sizes (ragged tails in every kernel)."""
+    w = synth.make("c3", B=2, H=2, L=712)
     rng = np.random.default_rng(63)
     dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
     import torch
-    worst = _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 3e-4,
+    worst = _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 2e-2,
                             grad_dtype=torch.float32)
     assert worst > 0.0
     _check_backward(fs, w["Q"], w["K"], w["V"], dY, w["Omega"], w["qk_scale"], "sderf", "bf16", 2e-2)
+
+
+@pytest.mark.parametrize("variant", ["aderf", "saderf", "gerf"])
+def test_backward_bf16_path_other_families_and_lengths(fs, variant):
+    """Dense C (ADERF: row terms from the precomputed table, dense derivative of the row term), diagonal C (SADERF)
+    and the scalar family on the bf16 kernels, with different numbers of queries and keys."""
+    import torch
+    rng = np.random.default_rng(65)
+    B, H, Lq, Lk, d, M = 1, 2, 200, 333, 64, 256
+    sc = np.linspace(0.6, 1.1, d)
+    Q = synth.round_to_bf16((rng.standard_normal((B, H, Lq, d)) * sc + 0.05).astype(np.float32))
+    K = synth.round_to_bf16((rng.standard_normal((B, H, Lk, d)) * sc[::-1] - 0.05).astype(np.float32))
+    V = synth.round_to_bf16(rng.standard_normal((B, H, Lk, d)).astype(np.float32))
+    dY = synth.round_to_bf16(rng.standard_normal((B, H, Lq, d)).astype(np.float32))
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, variant, "bf16", 2e-2, grad_dtype=torch.float32)
 
 
 def test_backward_value_gradients_sum_to_output_gradients_at_full_c3_size(fs):
@@ -118,7 +135,9 @@ def test_backward_value_gradients_sum_to_output_gradients_at_full_c3_size(fs):
     want = dY.astype(np.float64).sum(axis=2)
     got = gV.sum(axis=2)
     scale = np.abs(dY).astype(np.float64).sum(axis=2).max()
-    assert np.abs(got - want).max() <= 1e-5 * scale
+    # bf16 kernels: every dV row carries a relative rounding error of about 2^-9; the column sums of 4096 of them
+    # against the sum of absolute values
+    assert np.abs(got - want).max() <= 1e-3 * scale
 
 
 @pytest.mark.parametrize("variant", ["sderf", "aderf", "saderf", "gerf"])
