@@ -445,5 +445,9 @@ int launch_fast_backward(const FastLaunch& f, const fast::FastArgs& a, const Ten
                          const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
                          float* rcstar, int rslots, int rows_per_rslot, hipStream_t st);
 size_t fast_bwd_lds_bytes();
+int launch_fast_backward_causal(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
+                                const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
+                                hipStream_t st);
+size_t fast_bwd_causal_lds_bytes();
 
 }  // namespace fs

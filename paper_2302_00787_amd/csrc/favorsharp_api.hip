@@ -418,7 +418,7 @@ size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int L
   BwdPlan p;
   plan_backward(B * H, std::max(groups, omega_groups), Lq, Lk, d, dv, M, causal, &p);
   size_t total = p.total;
-  if (!causal && fast_supported(FS_BF16, d, dv, M)) {      // the query does not know the dtype: cover both paths
+  if (fast_supported(FS_BF16, d, dv, M)) {      // the query does not know the dtype: cover both paths
     FastBwdPlan fp;
     plan_fast_backward(B * H, std::max(groups, omega_groups), Lq, Lk, &fp);
     total = std::max(total, fp.total);
@@ -442,10 +442,11 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
   if (workspace_bytes < favorsharp_attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups))
     return FS_ERR_WORKSPACE_TOO_SMALL;
-  // bf16 kernels: non-causal, d = dv = 64, M = 256, bf16 inputs and output gradient, rows addressable with 32 bits
+  // bf16 kernels: d = dv = 64, M = 256, bf16 inputs and output gradient, rows addressable with 32 bits
   const long long max_sl = 1ll << 23;
-  if (!causal && fast_supported(Q->dtype, d, dv, M) && dY->dtype == FS_BF16 && Q->stride_l < max_sl && K->stride_l < max_sl &&
-      V->stride_l < max_sl && (int)std::max(fast_lds_bytes(), fast_bwd_lds_bytes()) <= device_lds_limit()) {
+  if (fast_supported(Q->dtype, d, dv, M) && dY->dtype == FS_BF16 && Q->stride_l < max_sl && K->stride_l < max_sl &&
+      V->stride_l < max_sl &&
+      (int)std::max({fast_lds_bytes(), fast_bwd_lds_bytes(), fast_bwd_causal_lds_bytes()}) <= device_lds_limit()) {
     FastBwdPlan fp;
     plan_fast_backward(BH, pgroups, Lq, Lk, &fp);
     char* w8 = (char*)workspace;
@@ -453,7 +454,7 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
     f.Q = dev(Q); f.K = dev(K); f.V = dev(V); f.Y = dev(dV);     // no forward output is written on this path
     f.theta = theta; f.Omega = Omega;
     f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
-    f.B = B; f.H = H; f.Lq = Lq; f.Lk = Lk; f.causal = 0;
+    f.B = B; f.H = H; f.Lq = Lq; f.Lk = Lk; f.causal = causal;
     f.nseg = fp.f.nseg; f.rows_per_seg = fp.f.rows_per_seg; f.sub = fp.f.sub; f.scale = qk_scale;
     f.Wbf = (uint16_t*)(w8 + fp.f.off_Wbf); f.bias = (float*)(w8 + fp.f.off_bias); f.wnorm = (float*)(w8 + fp.f.off_wnorm);
     f.rk = (float*)(w8 + fp.f.off_rk); f.Tpart = (float*)(w8 + fp.f.off_state); f.cpart = (float*)(w8 + fp.f.off_cpart);

@@ -102,5 +102,6 @@ int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, con
                                    const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart, float* rcstar,
                                    int rslots, int rows_per_rslot, hipStream_t st);
 size_t fast_bwd_lds_bytes();
+size_t fast_bwd_causal_lds_bytes();
 
 }  // namespace fs

@@ -326,7 +326,8 @@ int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int
 }
 
 // Projection constants, key-side segment states and their reduction (sum, or exclusive prefix when causal).
-static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st) {
+// `every_slot`: states of all slots (the last segment's too) and, when causal, the exclusive prefix of every slot.
+static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st, bool every_slot = false) {
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
   a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.theta = f.theta; a.rk = f.rk;
   a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
@@ -339,13 +340,13 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
                      f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk);
   FS_LAUNCH_CHECK();
   // the last segment's states are never needed by the causal pass
-  const int nstate = (f.causal ? f.nseg - 1 : f.nseg) * f.sub;
+  const int nstate = (f.causal && !every_slot ? f.nseg - 1 : f.nseg) * f.sub;
   if (nstate > 0) {
     hipLaunchKernelGGL(k_fast_state, dim3(nstate, BH), dim3(NT), offsetof(Smem, q), st, a);
     FS_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
-                     a.nslot, nstate, f.causal, f.sub);
+                     a.nslot, nstate, f.causal, every_slot ? 1 : f.sub);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -379,6 +380,10 @@ int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, con
                                    const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart, float* rcstar,
                                    int rslots, int rows_per_rslot, hipStream_t st) {
   FastArgs a;
+  if (f.causal) {
+    if (int rc = launch_fast_state_pass(f, a, st, true)) return rc;
+    return launch_fast_backward_causal(f, a, dY, dQ, dK, dV, gh, Rpart, rcpart, st);
+  }
   if (int rc = launch_fast_state_pass(f, a, st)) return rc;
   return launch_fast_backward(f, a, dY, dQ, dK, dV, gh, Rpart, rcpart, rcstar, rslots, rows_per_rslot, st);
 }

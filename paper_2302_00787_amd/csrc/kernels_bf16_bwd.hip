@@ -19,25 +19,13 @@
 //   k_bwd_apply<2>   keys:    dV = S R
 //   k_bwd_grad<0/1>  queries / keys: dF = (state) (left rows)^T, dE = F * dF, gradient rows
 // All of them keep a wave's 64 features of every operand in registers, as the forward kernels do.
-#include "fast_common.h"
+#include "fast_bwd.h"
 
 namespace fs {
 
 using namespace fast;
 
 namespace bwd {
-
-struct BwdArgs {
-  FastArgs f;                // forward arguments; Tpart slot 0 holds the total state, cstar the key shifts
-  TensorDev dY, dQ, dK, dV;
-  uint16_t* gh;              // [BH][Lq][80] bf16: G1 rows (columns 65.. are zero)
-  float* Rpart;              // [BH][rslots][256][80]
-  float* rcpart;             // [BH][rslots] zeros (shifts of the R segments: none)
-  int Lq, Lk, rslots, rows_per_rslot;
-};
-
-// Three 16-byte pieces per thread for tiles of up to 768 pieces.
-struct RowRegs3 { u32x4 p[3]; };
 
 // ---------------------------------------------------------------------------------------------------------------
 // MODE 1 (queries): rows of G1.  MODE 2 (keys): dV = S R.  Structure of k_fast_apply.  grid (nblk, B*H).
@@ -166,30 +154,6 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
 // Segment sums of P^T G1 (structure of k_fast_state: query features with their per-row shifts, "values" = rows of
 // G1, all 80 columns).  grid (rslots, B*H); LDS: the first members of Smem (rows, transposed values, shifts).
 // ---------------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void load_g80_g(RowRegs3& r, const uint16_t* base, int row0, int row_end) {
-  const int j = threadIdx.x & 63;
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int pc = (threadIdx.x >> 6) + 4 * i;
-    r.p[i] = u32x4{0u, 0u, 0u, 0u};
-    if (pc < DVP / 8 && row0 + j < row_end) r.p[i] = *(const u32x4*)(base + (size_t)(row0 + j) * DVP + pc * 8);
-  }
-}
-// Transposed into vt[column][token]; lane pairs swap halves so that every lane writes whole dwords.
-__device__ __forceinline__ void store_g80_s(const RowRegs3& r, uint16_t (*vt)[LDJ]) {
-  const int j = threadIdx.x & 63, odd = j & 1;
-#pragma unroll
-  for (int i = 0; i < 3; ++i) {
-    const int pc = (threadIdx.x >> 6) + 4 * i;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const uint32_t mine = r.p[i][e], other = dpp_u<0xB1>(mine);
-      const uint32_t wv = odd ? ((other >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (other << 16));
-      if (pc < DVP / 8) *(uint32_t*)(&vt[pc * 8 + 2 * e + odd][j & ~1]) = wv;
-    }
-  }
-}
-
 __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
@@ -283,9 +247,6 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
 // features; a row of ones appended: row sum of dE) x dE.  The four waves' partial gradient tiles are summed through
 // LDS on the MFMA pipe.  grid (nblk, B*H); 66 kB of dynamic LDS: two workgroups per CU.
 // ---------------------------------------------------------------------------------------------------------------
-constexpr int KL = 96;             // contraction length of dF: 80 columns padded to three MFMA steps
-constexpr int LDL = KL + 8;        // row stride (bf16) of the left-rows tile: 52 dwords, conflict-free 16-byte reads
-
 struct SmemGrad {
   __attribute__((aligned(16))) uint16_t q[1][TC][LDR];            // rows of the chunk (one buffer)
   float qadd[TC];
@@ -517,6 +478,13 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
   }
 }
 
+#define FS_LAUNCH_CHECK_() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
+int launch_bwd_rstate(const BwdArgs& ba, int BH, hipStream_t st) {
+  hipLaunchKernelGGL(k_bwd_rstate, dim3(ba.rslots, BH), dim3(NT), offsetof(Smem, q), st, ba);
+  FS_LAUNCH_CHECK_();
+  return 0;
+}
+
 }  // namespace bwd
 
 using namespace bwd;
@@ -549,8 +517,7 @@ int launch_fast_backward(const FastLaunch& f, const FastArgs& a, const TensorDev
   }
   hipLaunchKernelGGL(k_bwd_apply<1>, dim3(nq, BH), dim3(NT), 0, st, ba, rq);
   FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_bwd_rstate, dim3(rslots, BH), dim3(NT), offsetof(Smem, q), st, ba);
-  FS_LAUNCH_CHECK();
+  if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
   launch_fast_reduce_sum(Rpart, rcpart, rcstar, rslots, BH, st);
   FS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_bwd_apply<2>, dim3(nk, BH), dim3(NT), 0, st, ba, rk);
