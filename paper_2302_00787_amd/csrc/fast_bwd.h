@@ -51,4 +51,9 @@ constexpr int LDL = KL + 8;        // row stride (bf16) of the left-rows tile: 5
 int launch_bwd_rstate(const BwdArgs& ba, int BH, hipStream_t st);
 
 }  // namespace bwd
+
+// Gradient rows dQ, dK of the causal variant (kernels_bf16_bwd_cgrad.hip).  grid (nslot, B*H) each.
+int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t st);
+size_t bwd_cgrad_pc_lds_bytes();
+
 }  // namespace fs

@@ -15,65 +15,28 @@ namespace bwd {
 // c of 64 tokens (A = tril(G1_c V1_c^T), B = tril(P_c S_c^T), both 64 x 64 with the diagonal):
 //   dP_c  = G1_c T_{c-1}^T + A S_c               dV1_c = S_c R_{c+1} + B^T G1_c
 //   dS_c  = V1_c R_{c+1}^T + A^T P_c
-// Every kernel below walks one slot (a run of whole chunks) of one sequence with four waves of 64 features and the
-// running state (T forwards, R backwards) in registers; the key features use ONE shift per sequence (the largest
-// bound over all its tokens) so that the states of different slots, G1 and the gradients all live on one scale.
+// Every kernel walks one slot (a run of whole chunks) of one sequence with the running state (T forwards, R
+// backwards) in registers; the key features use ONE shift per sequence (the largest bound over all its tokens) so
+// that the states of different slots, G1 and the gradients all live on one scale.
 //   k_bwd_cfwd      forward walk: Yhat, normaliser, Y, G1 rows                 (T from the exclusive prefix per slot)
-//   k_bwd_rstate    (above) per-slot sums of P^T G1;  k_bwd_suffix  their exclusive suffix per slot
-//   k_bwd_cgrad<0>  forward walk: dQ;   k_bwd_cgrad<1>  backward walk: dK, dV
-// The state is needed with rows = features and the value columns as contraction index; it is rebuilt once per chunk
-// from the accumulators by an MFMA against the selection matrices (a register-level transpose).
+//   k_bwd_rstate    (kernels_bf16_bwd.hip) per-slot sums of P^T G1;  k_bwd_suffix  their exclusive suffix per slot
+//   k_bwd_cdv       backward walk: dV
+//   k_bwd_cgrad_pc  (kernels_bf16_bwd_cgrad.hip) dQ (forward walk) and dK (backward walk)
 // ===============================================================================================================
 struct SmemCB {
   __attribute__((aligned(16))) uint16_t q[TC][LDR];       // query rows
   __attribute__((aligned(16))) uint16_t k[TC][LDR];       // key rows
   __attribute__((aligned(16))) uint16_t vt[DVP][LDJ];     // [V 1] transposed: [column][token]
   __attribute__((aligned(16))) uint16_t gt[DVP][LDJ];     // G1 transposed
-  __attribute__((aligned(16))) uint16_t lamg[TC][LDL];    // G1 rows, zero from column 80 on
-  __attribute__((aligned(16))) uint16_t lamv[TC][LDL];    // [V 1] rows, zero from column 65 on
   float qadd[TC];                                         // - row_shift of the query rows
   float kadd[TC];                                         // row term - sequence shift of the key rows (-inf past the end)
   __attribute__((aligned(16))) uint16_t xch[NW][NW][16][LDXB];
-  __attribute__((aligned(16))) uint16_t xch2[NW][NW][16][LDXB];
 };
-
-// Row operand with the plain contraction order: lane <-> row 16 t + c, k = 8g + e <-> column 32 kk + 8g + e.
-__device__ __forceinline__ bf16x8 rowop(const uint16_t (*tile)[LDL], int t, int kk, int lane) {
-  return *(const bf16x8*)(&tile[16 * t + (lane & 15)][32 * kk + 8 * (lane >> 4)]);
-}
-// Row operand with the stacked order of two accumulator tiles: k = 8g + e <-> column 32 kk + 16 (e/4) + 4g + e%4.
-__device__ __forceinline__ bf16x8 rowop_stacked(const uint16_t (*tile)[LDL], int t, int kk, int lane) {
-  const int g = lane >> 4, c = lane & 15;
-  const u32x2 lo = *(const u32x2*)(&tile[16 * t + c][32 * kk + 4 * g]);
-  const u32x2 hi = *(const u32x2*)(&tile[16 * t + c][32 * kk + 16 + 4 * g]);
-  const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// State (rows = features in the accumulators) as A operands with rows = features 16 mt + c and the value columns
-// as contraction index in the stacked order: sa[mt][kk], kk = 0..2 (columns 80..95 are zero).
-__device__ __forceinline__ void state_as_rows(const f32x4 (&T)[4][NVT], const bf16x8 (&sel)[2], bf16x8 (&sa)[4][3]) {
-  f32x4 t2[NVT][4];
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt)
-#pragma unroll
-    for (int bk = 0; bk < 2; ++bk) {
-      const bf16x8 tb = pack8(T[2 * bk][vt], T[2 * bk + 1][vt]);
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) t2[vt][2 * bk + hh] = mfma(tb, sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-    }
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt) {
-    sa[mt][0] = pack8(t2[0][mt], t2[1][mt]);
-    sa[mt][1] = pack8(t2[2][mt], t2[3][mt]);
-    sa[mt][2] = pack8(t2[4][mt], f32x4{0.f, 0.f, 0.f, 0.f});
-  }
-}
 
 // Everything a chunk needs in LDS, staged through registers one chunk ahead.
 struct ChunkRegs {
-  RowRegs q, k, vrow, vcol;
-  RowRegs3 grow, gcol;
+  RowRegs q, k, vcol;
+  RowRegs3 gcol;
 };
 
 template <bool WITH_G>
@@ -82,17 +45,8 @@ __device__ __forceinline__ void chunk_load(ChunkRegs& r, const BwdArgs& ba, cons
   const FastArgs& a = ba.f;
   load_rows_g(r.q, Qb, a.Q.sl, row0, row_end);
   load_rows_g(r.k, Kb, a.K.sl, row0, row_end);
-  load_rows_g(r.vrow, Vb, a.V.sl, row0, row_end);
   load_vals_g(r.vcol, Vb, a.V.sl, row0, row_end);
-  if (WITH_G) {
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const int q = threadIdx.x + NT * i, row = q / 10, pc = q - 10 * row;
-      r.grow.p[i] = u32x4{0u, 0u, 0u, 0u};
-      if (q < TC * 10 && row0 + row < row_end) r.grow.p[i] = *(const u32x4*)(Gb + (size_t)(row0 + row) * DVP + pc * 8);
-    }
-    load_g80_g(r.gcol, Gb, row0, row_end);
-  }
+  if (WITH_G) load_g80_g(r.gcol, Gb, row0, row_end);
 }
 
 template <bool WITH_G>
@@ -117,27 +71,12 @@ __device__ __forceinline__ void chunk_store(const ChunkRegs& r, SmemCB& sm, cons
       sm.kadd[row] = valid ? rt - cs : -INFINITY;
     }
   }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int q = threadIdx.x + NT * i, row = q >> 3, pc = q & 7;
-    *(u32x4*)(&sm.lamv[row][pc * 8]) = r.vrow.p[i];
-  }
-  if (threadIdx.x < TC) sm.lamv[threadIdx.x][D] = row0 + threadIdx.x < row_end ? 0x3f80u : 0u;   // the ones column
   store_vals_s(r.vcol, sm.vt, row0, row_end);
-  if (WITH_G) {
-#pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const int q = threadIdx.x + NT * i, row = q / 10, pc = q - 10 * row;
-      if (q < TC * 10) *(u32x4*)(&sm.lamg[row][pc * 8]) = r.grow.p[i];
-    }
-    store_g80_s(r.gcol, sm.gt);
-  }
+  if (WITH_G) store_g80_s(r.gcol, sm.gt);
 }
 
-// Zero padding the staging never writes: lamg columns 80.., lamv columns 65.., vt rows 65..
+// Zero padding the staging never writes: vt rows 65..
 __device__ __forceinline__ void chunk_zero_pad(SmemCB& sm) {
-  for (int idx = threadIdx.x; idx < TC * (LDL - DVP); idx += NT) sm.lamg[idx / (LDL - DVP)][DVP + idx % (LDL - DVP)] = 0;
-  for (int idx = threadIdx.x; idx < TC * (LDL - D - 1); idx += NT) sm.lamv[idx / (LDL - D - 1)][D + 1 + idx % (LDL - D - 1)] = 0;
   for (int idx = threadIdx.x; idx < (DVP - D - 1) * LDJ; idx += NT) sm.vt[D + 1 + idx / LDJ][idx % LDJ] = 0;
 }
 
@@ -325,20 +264,16 @@ __global__ void k_bwd_suffix(float* Rpart, int nslot) {
   }
 }
 
-// Gradient rows of the causal variant.  KEY = 0: forward walk with the prefix state, dQ.  KEY = 1: backward walk
-// with the suffix sum, dK and dV.  grid (nslot, B*H), block 256, one workgroup per CU.
-template <int KEY>
-__global__ void __launch_bounds__(NT) k_bwd_cgrad(BwdArgs ba) {
+// dV of the causal variant: backward walk of one slot with the suffix sum R in registers,
+//   dV1_c = S_c R_{c+1} + tril(P_c S_c^T)^T G1_c,   R_c = R_{c+1} + P_c^T G1_c.
+// grid (nslot, B*H), block 256, one workgroup per CU.
+__global__ void __launch_bounds__(NT) k_bwd_cdv(BwdArgs ba) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   SmemCB& sm = *reinterpret_cast<SmemCB*>(smem_raw);
   const FastArgs& a = ba.f;
   const int slot = blockIdx.x, bh = blockIdx.y;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const SlotCtx x = slot_ctx(ba, slot, bh);
-  const TensorDev& G = KEY ? ba.dK : ba.dQ;
-  const float* th = a.theta + (size_t)group_of(a.groups, x.b, x.h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
-  const float* C2 = th + FS_THETA_HEADER_ + D + 3 * (size_t)D * D;
-  const uint16_t* Wg = a.Wbf + ((size_t)x.pg * 2 + KEY) * M * D;
 
   WSlice wq, wk;
   load_wslice(wq, a.Wbf + ((size_t)x.pg * 2) * M * D);
@@ -347,27 +282,9 @@ __global__ void __launch_bounds__(NT) k_bwd_cgrad(BwdArgs ba) {
   load_qbias(qb, a.bias + ((size_t)x.pg * 2) * M, x.amax1);
   bf16x8 sel[2];
   make_sel(sel);
-  // W~^T of this side as A operand of the gradient tile (a row of ones appended: the row sum of dE)
-  bf16x8 wt[NVT][2];
-#pragma unroll
-  for (int dt = 0; dt < NVT; ++dt)
-#pragma unroll
-    for (int bk = 0; bk < 2; ++bk) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int f = 64 * w + 32 * bk + 16 * (e >> 2) + 4 * g + (e & 3);
-        uint32_t bits;
-        if (dt < 4) bits = Wg[(size_t)f * D + 16 * dt + c];
-        else bits = c == 0 ? 0x3f80u : 0u;
-        v[e >> 1] |= bits << (16 * (e & 1));
-      }
-      wt[dt][bk] = __builtin_bit_cast(bf16x8, v);
-    }
-  // running state: prefix of S^T V1 (queries, forwards) or suffix of P^T G1 (keys, backwards)
-  f32x4 T[4][NVT];
+  f32x4 T[4][NVT];     // suffix of P^T G1
   {
-    const float* Tg = (KEY ? ba.Rpart : a.Tpart) + ((size_t)bh * a.nslot + slot) * M * DVP;
+    const float* Tg = ba.Rpart + ((size_t)bh * a.nslot + slot) * M * DVP;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -377,7 +294,7 @@ __global__ void __launch_bounds__(NT) k_bwd_cgrad(BwdArgs ba) {
   }
   chunk_zero_pad(sm);
   const int nchunk = (x.row_end - x.row_beg + TC - 1) / TC;
-  auto chunk_row = [&](int i) { return x.row_beg + (KEY ? nchunk - 1 - i : i) * TC; };
+  auto chunk_row = [&](int i) { return x.row_beg + (nchunk - 1 - i) * TC; };
   ChunkRegs cr;
   if (nchunk > 0) chunk_load<true>(cr, ba, x.Qb, x.Kb, x.Vb, x.Gb, chunk_row(0), x.row_end);
   __syncthreads();
@@ -388,241 +305,88 @@ __global__ void __launch_bounds__(NT) k_bwd_cgrad(BwdArgs ba) {
     const bool more = ci + 1 < nchunk;
     if (more) chunk_load<true>(cr, ba, x.Qb, x.Kb, x.Vb, x.Gb, chunk_row(ci + 1), x.row_end);
 
-    bf16x8 sa[4][3];
-    state_as_rows(T, sel, sa);
-    bf16x8 s[4][2], st[4][2];
-    key_tiles(wk, sm, sel, s, st);
-    if (!KEY) {
-      // ---- dQ: per query tile  dF = T_prev G1^T + S^T A^T,  A^T[j][i] = V1_j . G1_i for j <= i
+    // query tiles and their transposes
+    bf16x8 p[4][2], pt[4][2];
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        bf16x8 p[2];
-        feature_tile<true>(wq, &qb, sm.q, it, sm.qadd[16 * it + c], p);
-        f32x4 df[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    for (int ip = 0; ip < 2; ++ip) {
+      f32x4 tr[2][4];
 #pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-          const bf16x8 gop = rowop_stacked(sm.lamg, it, kk, lane);
+      for (int ii = 0; ii < 2; ++ii) {
+        const int it = 2 * ip + ii;
+        feature_tile<true>(wq, &qb, sm.q, it, sm.qadd[16 * it + c], p[it]);
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) df[mt] = mfma(sa[mt][kk], gop, df[mt]);
-        }
+        for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int jp = 0; jp < 2; ++jp) {
-          if (2 * jp <= it) {
-            f32x4 ac[2];
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-              const int jt = 2 * jp + jj;
-              ac[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
-              if (jt <= it) {
-#pragma unroll
-                for (int kk = 0; kk < 3; ++kk) ac[jj] = mfma(rowop(sm.lamv, jt, kk, lane), rowop(sm.lamg, it, kk, lane), ac[jj]);
-                if (jt == it) {
-#pragma unroll
-                  for (int r = 0; r < 4; ++r) ac[jj][r] = (4 * g + r <= c) ? ac[jj][r] : 0.f;
-                }
-              }
-            }
-            const bf16x8 ab = pack8(ac[0], ac[1]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) df[mt] = mfma(st[mt][jp], ab, df[mt]);
-          }
-        }
-        bf16x8 eimg[2];
-#pragma unroll
-        for (int bk = 0; bk < 2; ++bk) {
-          const f32x8 fv = __builtin_convertvector(p[bk], f32x8);
-          const f32x4 lo = {fv[0] * df[2 * bk][0], fv[1] * df[2 * bk][1], fv[2] * df[2 * bk][2], fv[3] * df[2 * bk][3]};
-          const f32x4 hi = {fv[4] * df[2 * bk + 1][0], fv[5] * df[2 * bk + 1][1], fv[6] * df[2 * bk + 1][2], fv[7] * df[2 * bk + 1][3]};
-          eimg[bk] = pack8(lo, hi);
-        }
-        f32x4 gtile[NVT];
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          gtile[dt] = mfma(wt[dt][0], eimg[0], f32x4{0.f, 0.f, 0.f, 0.f});
-          gtile[dt] = mfma(wt[dt][1], eimg[1], gtile[dt]);
-        }
-        gtile[4] = f32x4{0.f, 0.f, 0.f, 0.f};
-        exchange_put_bf16(sm, gtile, it, w, lane);
+          for (int hh = 0; hh < 2; ++hh) tr[ii][2 * mb + hh] = mfma(p[it][mb], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
       }
-      // the prefix state takes this chunk's keys
 #pragma unroll
-      for (int jp = 0; jp < 2; ++jp)
+      for (int mt = 0; mt < 4; ++mt) pt[mt][ip] = pack8(tr[0][mt], tr[1][mt]);
+    }
+    bf16x8 rb[NVT][2];
 #pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) {
-          const bf16x8 vop = load_vop(sm.vt, jp, vt);
+    for (int vt = 0; vt < NVT; ++vt) {
+      rb[vt][0] = pack8(T[0][vt], T[1][vt]);
+      rb[vt][1] = pack8(T[2][vt], T[3][vt]);
+    }
 #pragma unroll
-          for (int mt = 0; mt < 4; ++mt) T[mt][vt] = mfma(st[mt][jp], vop, T[mt][vt]);
-        }
-    } else {
-      // ---- dK, dV: query tiles and their transposes first
-      bf16x8 p[4][2], pt[4][2];
+    for (int jt = 0; jt < 4; ++jt) {
+      bf16x8 s[2];
+      feature_tile<false>(wk, nullptr, sm.k, jt, sm.kadd[16 * jt + c], s);
+      // dV1 tile = R_next^T x S  +  G1^T x B  (B[i][j] = P_i . S_j over this wave's features, i >= j)
+      f32x4 y[NVT];
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) {
+        y[vt] = mfma(rb[vt][0], s[0], f32x4{0.f, 0.f, 0.f, 0.f});
+        y[vt] = mfma(rb[vt][1], s[1], y[vt]);
+      }
 #pragma unroll
       for (int ip = 0; ip < 2; ++ip) {
-        f32x4 tr[2][4];
+        if (2 * ip + 1 >= jt) {
+          f32x4 bc[2];
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-          const int it = 2 * ip + ii;
-          feature_tile<true>(wq, &qb, sm.q, it, sm.qadd[16 * it + c], p[it]);
+          for (int ii = 0; ii < 2; ++ii) {
+            const int it = 2 * ip + ii;
+            bc[ii] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (it >= jt) {
+              bc[ii] = mfma(p[it][0], s[0], bc[ii]);
+              bc[ii] = mfma(p[it][1], s[1], bc[ii]);
+              if (it == jt) {
 #pragma unroll
-          for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) tr[ii][2 * mb + hh] = mfma(p[it][mb], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) pt[mt][ip] = pack8(tr[0][mt], tr[1][mt]);
-      }
-#pragma unroll
-      for (int jt = 0; jt < 4; ++jt) {
-        // dS tile = V1 R_next^T + A^T P  (A[i][j] = G1_i . V1_j for i >= j)
-        f32x4 df[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-        for (int kk = 0; kk < 3; ++kk) {
-          const bf16x8 vop = rowop_stacked(sm.lamv, jt, kk, lane);
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt) df[mt] = mfma(sa[mt][kk], vop, df[mt]);
-        }
-        // dV1 tile = R_next^T-operand x S  +  G1^T x B  (B[i][j] = P_i . S_j over this wave's features, i >= j)
-        f32x4 y[NVT];
-#pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) {
-          const bf16x8 r0 = pack8(T[0][vt], T[1][vt]), r1 = pack8(T[2][vt], T[3][vt]);
-          y[vt] = mfma(r0, s[jt][0], f32x4{0.f, 0.f, 0.f, 0.f});
-          y[vt] = mfma(r1, s[jt][1], y[vt]);
-        }
-#pragma unroll
-        for (int ip = 0; ip < 2; ++ip) {
-          if (2 * ip + 1 >= jt) {
-            f32x4 ac[2], bc[2];
-#pragma unroll
-            for (int ii = 0; ii < 2; ++ii) {
-              const int it = 2 * ip + ii;
-              ac[ii] = f32x4{0.f, 0.f, 0.f, 0.f};
-              bc[ii] = f32x4{0.f, 0.f, 0.f, 0.f};
-              if (it >= jt) {
-#pragma unroll
-                for (int kk = 0; kk < 3; ++kk) ac[ii] = mfma(rowop(sm.lamg, it, kk, lane), rowop(sm.lamv, jt, kk, lane), ac[ii]);
-                bc[ii] = mfma(p[it][0], s[jt][0], bc[ii]);
-                bc[ii] = mfma(p[it][1], s[jt][1], bc[ii]);
-                if (it == jt) {
-#pragma unroll
-                  for (int r = 0; r < 4; ++r) {
-                    ac[ii][r] = (4 * g + r >= c) ? ac[ii][r] : 0.f;
-                    bc[ii][r] = (4 * g + r >= c) ? bc[ii][r] : 0.f;
-                  }
-                }
+                for (int r = 0; r < 4; ++r) bc[ii][r] = (4 * g + r >= c) ? bc[ii][r] : 0.f;
               }
             }
-            const bf16x8 ab = pack8(ac[0], ac[1]), bb = pack8(bc[0], bc[1]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) df[mt] = mfma(pt[mt][ip], ab, df[mt]);
-#pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(load_vop(sm.gt, ip, vt), bb, y[vt]);
           }
-        }
-        exchange_put_bf16(sm, y, jt, w, lane);       // -> xch (dV)
-        bf16x8 eimg[2];
+          const bf16x8 bb = pack8(bc[0], bc[1]);
 #pragma unroll
-        for (int bk = 0; bk < 2; ++bk) {
-          const f32x8 fv = __builtin_convertvector(s[jt][bk], f32x8);
-          const f32x4 lo = {fv[0] * df[2 * bk][0], fv[1] * df[2 * bk][1], fv[2] * df[2 * bk][2], fv[3] * df[2 * bk][3]};
-          const f32x4 hi = {fv[4] * df[2 * bk + 1][0], fv[5] * df[2 * bk + 1][1], fv[6] * df[2 * bk + 1][2], fv[7] * df[2 * bk + 1][3]};
-          eimg[bk] = pack8(lo, hi);
-        }
-        f32x4 gtile[NVT];
-#pragma unroll
-        for (int dt = 0; dt < NVT; ++dt) {
-          gtile[dt] = mfma(wt[dt][0], eimg[0], f32x4{0.f, 0.f, 0.f, 0.f});
-          gtile[dt] = mfma(wt[dt][1], eimg[1], gtile[dt]);
-        }
-        {   // -> xch2 (dK)
-#pragma unroll
-          for (int vt = 0; vt < NVT; ++vt)
-            *(bf16x4*)(&sm.xch2[jt][w][c][16 * vt + 4 * g]) = __builtin_convertvector(gtile[vt], bf16x4);
+          for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(load_vop(sm.gt, ip, vt), bb, y[vt]);
         }
       }
-      // the suffix sum takes this chunk's queries
-#pragma unroll
-      for (int ip = 0; ip < 2; ++ip)
-#pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) {
-          const bf16x8 gop = load_vop(sm.gt, ip, vt);
-#pragma unroll
-          for (int mt = 0; mt < 4; ++mt) T[mt][vt] = mfma(pt[mt][ip], gop, T[mt][vt]);
-        }
+      exchange_put_bf16(sm, y, jt, w, lane);
     }
+    // the suffix sum takes this chunk's queries
+#pragma unroll
+    for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) {
+        const bf16x8 gop = load_vop(sm.gt, ip, vt);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) T[mt][vt] = mfma(pt[mt][ip], gop, T[mt][vt]);
+      }
     __syncthreads();
     {
-      const int trow = 16 * w + c, token = row0 + trow;
-      const bool valid = token < x.row_end;
-      if (KEY) {
-        // dV rows (xch)
-        f32x4 fv[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-        finish_tiles(fv, sm, w, 0, lane);
-        finish_tiles(fv, sm, w, 2, lane);
-        if (valid) {
-          if (ba.dV.dtype == 1) {
-            uint16_t* yp = (uint16_t*)ba.dV.ptr + x.b * ba.dV.sb + x.h * ba.dV.sh + (long long)token * ba.dV.sl + 4 * g;
+      const int token = row0 + 16 * w + c;
+      f32x4 fv[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+      finish_tiles(fv, sm, w, 0, lane);
+      finish_tiles(fv, sm, w, 2, lane);
+      if (token < x.row_end) {
+        if (ba.dV.dtype == 1) {
+          uint16_t* yp = (uint16_t*)ba.dV.ptr + x.b * ba.dV.sb + x.h * ba.dV.sh + (long long)token * ba.dV.sl + 4 * g;
 #pragma unroll
-            for (int vt = 0; vt < 4; ++vt) *(bf16x4*)(yp + 16 * vt) = __builtin_convertvector(fv[vt], bf16x4);
-          } else {
-            float* yp = (float*)ba.dV.ptr + x.b * ba.dV.sb + x.h * ba.dV.sh + (long long)token * ba.dV.sl + 4 * g;
-#pragma unroll
-            for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = fv[vt];
-          }
-        }
-      }
-      // gradient rows: xch (queries) / xch2 (keys); the same routing-matrix sum on the second buffer
-      f32x4 fs[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-      float rs = 0.f;
-      if (KEY) {
-        struct X2 { const uint16_t (*xch)[NW][16][LDXB]; };
-        const X2 v2{sm.xch2};
-        finish_tiles(fs, v2, w, 0, lane);
-        finish_tiles(fs, v2, w, 2, lane);
-        rs = finish_col64(v2, w, lane) * a.scale * a.scale;
-      } else {
-        finish_tiles(fs, sm, w, 0, lane);
-        finish_tiles(fs, sm, w, 2, lane);
-      }
-      if (KEY) {
-        if (x.isoC) {
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) fs[dt][r] = kLn2 * fs[dt][r] - rs * bf16_bits_to_f32(sm.k[trow][16 * dt + 4 * g + r]);
+          for (int vt = 0; vt < 4; ++vt) *(bf16x4*)(yp + 16 * vt) = __builtin_convertvector(fv[vt], bf16x4);
         } else {
-#pragma unroll 1
-          for (int dt = 0; dt < 4; ++dt) {
-            f32x4 u = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-            for (int e = 0; e < D; ++e) {
-              const float ke = bf16_bits_to_f32(sm.k[trow][e]);
+          float* yp = (float*)ba.dV.ptr + x.b * ba.dV.sb + x.h * ba.dV.sh + (long long)token * ba.dV.sl + 4 * g;
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const int dd = 16 * dt + 4 * g + r;
-                u[r] += (C2[dd * D + e] + C2[e * D + dd]) * ke;
-              }
-            }
-            const f32x4 o = kLn2 * fs[dt] + rs * u;
-            fs[0] = dt == 0 ? o : fs[0];
-            fs[1] = dt == 1 ? o : fs[1];
-            fs[2] = dt == 2 ? o : fs[2];
-            fs[3] = dt == 3 ? o : fs[3];
-          }
-        }
-      } else {
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) fs[dt] *= kLn2;
-      }
-      if (valid) {
-        if (G.dtype == 1) {
-          uint16_t* yp = (uint16_t*)G.ptr + x.b * G.sb + x.h * G.sh + (long long)token * G.sl + 4 * g;
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt) *(bf16x4*)(yp + 16 * dt) = __builtin_convertvector(fs[dt], bf16x4);
-        } else {
-          float* yp = (float*)G.ptr + x.b * G.sb + x.h * G.sh + (long long)token * G.sl + 4 * g;
-#pragma unroll
-          for (int dt = 0; dt < 4; ++dt) *(f32x4*)(yp + 16 * dt) = fs[dt];
+          for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = fv[vt];
         }
       }
     }
@@ -649,7 +413,7 @@ int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const Te
   ba.gh = gh; ba.Rpart = Rpart; ba.rcpart = rcpart;
   ba.Lq = f.Lq; ba.Lk = f.Lk; ba.rslots = a.nslot; ba.rows_per_rslot = a.rows_per_seg / a.sub;
   const int BH = f.B * f.H;
-  const void* fns[3] = {(const void*)k_bwd_cfwd, (const void*)k_bwd_cgrad<0>, (const void*)k_bwd_cgrad<1>};
+  const void* fns[2] = {(const void*)k_bwd_cfwd, (const void*)k_bwd_cdv};
   for (const void* fn : fns)
     if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemCB)) != hipSuccess) {
       (void)hipGetLastError();
@@ -660,11 +424,9 @@ int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const Te
   if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
   hipLaunchKernelGGL(k_bwd_suffix, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
   FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_bwd_cgrad<0>, dim3(a.nslot, BH), dim3(NT), sizeof(SmemCB), st, ba);
+  hipLaunchKernelGGL(k_bwd_cdv, dim3(a.nslot, BH), dim3(NT), sizeof(SmemCB), st, ba);
   FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_bwd_cgrad<1>, dim3(a.nslot, BH), dim3(NT), sizeof(SmemCB), st, ba);
-  FS_LAUNCH_CHECK();
-  return 0;
+  return launch_bwd_cgrad_pc(ba, a.nslot, BH, st);
 }
 
 size_t fast_bwd_causal_lds_bytes() { return sizeof(SmemCB); }
