@@ -52,8 +52,10 @@ int launch_bwd_rstate(const BwdArgs& ba, int BH, hipStream_t st);
 
 }  // namespace bwd
 
-// Gradient rows dQ, dK of the causal variant (kernels_bf16_bwd_cgrad.hip).  grid (nslot, B*H) each.
+// Kernels of the causal variant with producer and consumer waves (kernels_bf16_bwd_pc.hip), grid (nslot, B*H) each:
+// gradient rows dQ and dK; forward walk that leaves the G1 rows (mode 0) and backward walk for dV (mode 1).
 int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t st);
-size_t bwd_cgrad_pc_lds_bytes();
+int launch_bwd_walk_pc(const bwd::BwdArgs& ba, int mode, int nslot, int BH, hipStream_t st);
+size_t bwd_pc_lds_bytes();
 
 }  // namespace fs

@@ -413,22 +413,14 @@ int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const Te
   ba.gh = gh; ba.Rpart = Rpart; ba.rcpart = rcpart;
   ba.Lq = f.Lq; ba.Lk = f.Lk; ba.rslots = a.nslot; ba.rows_per_rslot = a.rows_per_seg / a.sub;
   const int BH = f.B * f.H;
-  const void* fns[2] = {(const void*)k_bwd_cfwd, (const void*)k_bwd_cdv};
-  for (const void* fn : fns)
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemCB)) != hipSuccess) {
-      (void)hipGetLastError();
-      return 2;
-    }
-  hipLaunchKernelGGL(k_bwd_cfwd, dim3(a.nslot, BH), dim3(NT), sizeof(SmemCB), st, ba);
-  FS_LAUNCH_CHECK();
+  if (int rc = launch_bwd_walk_pc(ba, 0, a.nslot, BH, st)) return rc;
   if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
   hipLaunchKernelGGL(k_bwd_suffix, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
   FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_bwd_cdv, dim3(a.nslot, BH), dim3(NT), sizeof(SmemCB), st, ba);
-  FS_LAUNCH_CHECK();
+  if (int rc = launch_bwd_walk_pc(ba, 1, a.nslot, BH, st)) return rc;
   return launch_bwd_cgrad_pc(ba, a.nslot, BH, st);
 }
 
-size_t fast_bwd_causal_lds_bytes() { return sizeof(SmemCB); }
+size_t fast_bwd_causal_lds_bytes() { return bwd_pc_lds_bytes(); }
 
 }  // namespace fs

@@ -150,8 +150,8 @@ __device__ __forceinline__ void store_u_rows(const StageG& s, SmemCG& sm, int nv
     if (pv + 4 * i < DVP / 8) store_u_piece(s.g[i], grows, j, pv + 4 * i);
 }
 
-template <int KEY>
-__device__ __forceinline__ void store_u_transposed(const StageG& s, SmemCG& sm, int nv, int tid) {
+template <int KEY, class SM>
+__device__ __forceinline__ void store_u_transposed(const StageG& s, SM& sm, int nv, int tid) {
   const int j = tid & 63, pv = tid >> 6;
   if (KEY) {
 #pragma unroll
@@ -508,6 +508,277 @@ __global__ void __launch_bounds__(NT8) k_bwd_cgrad_pc(BwdArgs ba) {
   else consumer<KEY>(ba, sm, cx, slot, w - 4);
 }
 
+
+// ===============================================================================================================
+// The two walks that have the shape of the forward pass, on the same producer/consumer split:
+//   MODE 0  forward walk:  Yhat_c = tril(P_c S_c^T) V1_c + P_c T_{c-1},  T_c = T_{c-1} + S_c^T V1_c;  the producers
+//           normalise, read dY and write the G1 rows [dY / den, -(dY . Y) / den].
+//   MODE 1  backward walk: dV1_c = tril(P_c S_c^T)^T G1_c + S_c R_{c+1},  R_c = R_{c+1} + P_c^T G1_c  (the same
+//           dataflow with queries and keys exchanged, G1 in the place of V1 and the mask mirrored); the producers
+//           write dV.
+// The FIRST side (keys in MODE 0, queries in MODE 1) builds the state and is produced in steps 0 and 1, the SECOND
+// side in steps 2 and 3; all feature tiles are token-major, the consumer gets the first side's transposes from an
+// MFMA against a selection matrix, as in the forward pass.  LDS: xoth / xown = rows of the first / second side,
+// uothT = transposed value rows of the first side (written in step 3 for the next chunk, read by the consumers in
+// intervals 4c+1 and 4c+2).
+// ===============================================================================================================
+struct SmemWalk {
+  __attribute__((aligned(16))) uint16_t xoth[TC][LDR];
+  __attribute__((aligned(16))) uint16_t xown[TC][LDR];
+  __attribute__((aligned(16))) uint16_t uothT[DVP][LDJ];
+  __attribute__((aligned(16))) float add_oth[TC];
+  __attribute__((aligned(16))) float add_own[TC];
+  __attribute__((aligned(16))) uint16_t feat[2][4][4][64][8]; // [slot][2 (tile of the step) + block][pair][lane]
+  __attribute__((aligned(16))) uint16_t xch[4][4][16][LDXB];
+};
+
+template <int MODE>
+__device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, const Ctx& cx, int j) {
+  const FastArgs& a = ba.f;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const uint16_t* Xown = MODE ? cx.Kb : cx.Qb;
+  const uint16_t* Xoth = MODE ? cx.Qb : cx.Kb;
+  const long long sl_own = MODE ? a.K.sl : a.Q.sl, sl_oth = MODE ? a.Q.sl : a.K.sl;
+  const float wmaxq = max256(a.wnorm + ((size_t)cx.pg * 2) * M), amax = max256(a.bias + ((size_t)cx.pg * 2) * M);
+  const int b = cx.bh / a.H, h = cx.bh % a.H;
+
+  W64 wq, wk;
+  load_w64(wq, a.Wbf + ((size_t)cx.pg * 2) * M * D, j, lane);
+  load_w64(wk, a.Wbf + ((size_t)cx.pg * 2 + 1) * M * D, j, lane);
+  const W64& wown = MODE ? wk : wq;
+  const W64& woth = MODE ? wq : wk;
+  B64 qb;
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (a.bias[((size_t)cx.pg * 2) * M + 64 * j + 16 * mt + 4 * g + r] - amax);
+
+  StageG stg;
+  stg.rko[0] = stg.rko[1] = stg.rkw[0] = stg.rkw[1] = 0.f;
+  load_x<MODE>(stg.xo, stg.rko, !MODE, Xoth, sl_oth, a, cx, 0, tid);
+  load_u<MODE>(stg, a, cx, 0, tid);
+  store_x(stg.xo, stg.rko, !MODE, sm.xoth, sm.add_oth, a, cx, chunk_rows<MODE>(cx, 0), wmaxq, tid);
+  store_u_transposed<MODE>(stg, sm, chunk_rows<MODE>(cx, 0), tid);
+  load_x<MODE>(stg.xo, stg.rko, !MODE, Xoth, sl_oth, a, cx, 1, tid);
+  load_u<MODE>(stg, a, cx, 1, tid);
+  load_x<MODE>(stg.xw, stg.rkw, MODE, Xown, sl_own, a, cx, 0, tid);
+  __syncthreads();                 // barrier 0
+
+  XOp xo[2][2];
+  load_xop(xo[0][0], sm.xoth, 0, lane);
+  load_xop(xo[0][1], sm.xoth, 1, lane);
+  u32x2 gy[4];                     // dY pieces of token tile j of the chunk that is finished next (MODE 0)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) gy[i] = u32x2{0u, 0u};
+
+  auto load_dy = [&](int ci_done) {
+    const int r0 = chunk_row<MODE>(cx, ci_done);
+    const __amdgpu_buffer_rsrc_t rd = chunk_rsrc((const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)r0 * ba.dY.sl,
+                                                 2 * (int)ba.dY.sl, chunk_rows<MODE>(cx, ci_done), 2 * D);
+#pragma unroll
+    for (int vt = 0; vt < 4; ++vt)
+      gy[vt] = __builtin_amdgcn_raw_buffer_load_b64(rd, 2 * ((16 * j + c) * (int)ba.dY.sl + 16 * vt + 4 * g), 0, 0);
+  };
+  auto finish = [&](int ci_done) {
+    f32x4 fsum[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fsum[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    finish_tiles(fsum, sm, j, 0, lane);
+    finish_tiles(fsum, sm, j, 2, lane);
+    const int r0 = chunk_row<MODE>(cx, ci_done), nv = chunk_rows<MODE>(cx, ci_done);
+    if (MODE) {
+      const int esz = ba.dV.dtype == 1 ? 2 : 4;
+      const char* gp = (const char*)ba.dV.ptr + (b * ba.dV.sb + h * ba.dV.sh + (long long)r0 * ba.dV.sl) * esz;
+      finish_store(fsum, ba.dV, gp, nv, j, lane);
+    } else {
+      const float inv = finish_norm(fsum, sm, j, lane);        // fsum = Y rows now
+      f32x4 gv[4];
+      float dot = 0.f;
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) {
+        gv[vt] = __builtin_convertvector(__builtin_bit_cast(bf16x4, gy[vt]), f32x4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dot += gv[vt][r] * fsum[vt][r];
+      }
+      dot += __shfl_xor(dot, 16);
+      dot += __shfl_xor(dot, 32);
+      const __amdgpu_buffer_rsrc_t rg = chunk_rsrc(cx.Gb + (long long)r0 * DVP, 2 * DVP, nv, 2 * DVP);
+      const int off = 2 * ((16 * j + c) * DVP + 4 * g);
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt)
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(gv[vt] * inv, bf16x4)), rg, off + 32 * vt, 0, 0);
+      const f32x4 last = {g == 0 ? -dot * inv : 0.f, 0.f, 0.f, 0.f};
+      __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(last, bf16x4)), rg, off + 2 * D, 0, 0);
+    }
+  };
+
+  for (int ci = 0; ci < cx.nchunk; ++ci) {
+    const int nv = chunk_rows<MODE>(cx, ci);
+#pragma unroll
+    for (int S = 0; S < 4; ++S) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        if (S == 0) load_xop(xo[1][u], sm.xoth, 2 + u, lane);
+        else if (S == 1) load_xop(xo[0][u], sm.xown, u, lane);
+        else if (S == 2) load_xop(xo[1][u], sm.xown, 2 + u, lane);
+        else load_xop(xo[0][u], sm.xoth, u, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        bf16x8 img[2];
+        if (S < 2) feature_tile64<MODE != 0>(woth, &qb, xo[S & 1][u], sm.add_oth[16 * (2 * S + u) + c], img);
+        else feature_tile64<MODE == 0>(wown, &qb, xo[S & 1][u], sm.add_own[16 * (2 * (S - 2) + u) + c], img);
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) *(bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]) = img[blk];
+      }
+
+      if (S == 0) {
+        store_x(stg.xw, stg.rkw, MODE, sm.xown, sm.add_own, a, cx, nv, wmaxq, tid);
+        load_x<MODE>(stg.xw, stg.rkw, MODE, Xown, sl_own, a, cx, ci + 1, tid);
+        if (!MODE && ci > 0) load_dy(ci - 1);
+      } else if (S == 1) {
+        if (ci > 0) finish(ci - 1);
+      } else if (S == 2) {
+        store_x(stg.xo, stg.rko, !MODE, sm.xoth, sm.add_oth, a, cx, chunk_rows<MODE>(cx, ci + 1), wmaxq, tid);
+        load_x<MODE>(stg.xo, stg.rko, !MODE, Xoth, sl_oth, a, cx, ci + 2, tid);
+      } else {
+        store_u_transposed<MODE>(stg, sm, chunk_rows<MODE>(cx, ci + 1), tid);
+        load_u<MODE>(stg, a, cx, ci + 2, tid);
+      }
+      __syncthreads();
+    }
+  }
+  if (!MODE && cx.nchunk > 0) load_dy(cx.nchunk - 1);
+  __syncthreads();                 // the consumers' last step
+  if (cx.nchunk > 0) finish(cx.nchunk - 1);
+}
+
+template <int MODE>
+__device__ __forceinline__ void walk_consumer(const BwdArgs& ba, SmemWalk& sm, const Ctx& cx, int slot, int j) {
+  const FastArgs& a = ba.f;
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  f32x4 T[4][NVT];
+  {
+    const float* Tg = (MODE ? ba.Rpart : a.Tpart) + ((size_t)cx.bh * a.nslot + slot) * M * DVP;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * DVP + 16 * vt + c];
+  }
+  __syncthreads();                 // barrier 0
+  __syncthreads();                 // the producers' first step
+
+  for (int ci = 0; ci < cx.nchunk; ++ci) {
+    // state before this chunk as A operand (rows = value columns, contraction index <-> feature)
+    bf16x8 tb[2][NVT];
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) tb[blk][vt] = pack8(T[2 * blk][vt], T[2 * blk + 1][vt]);
+    bf16x8 sk[4][2];               // first-side feature tiles of the chunk
+    bf16x8 vop[2][NVT];            // value operands of the chunk
+#pragma unroll
+    for (int S = 0; S < 4; ++S) {
+      if (S < 2) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk) sk[2 * S + u][blk] = *(const bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]);
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) vop[S][vt] = load_vop_l(sm.uothT, S, vt, lane);
+        bf16x8 sel[2];
+        {
+          int lane_here = lane;
+          asm volatile("" : "+v"(lane_here));
+          make_sel32(sel, lane_here);
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const f32x4 tr0 = mfma(sk[2 * S][mt >> 1], sel[mt & 1], f32x4{0.f, 0.f, 0.f, 0.f});
+          const f32x4 tr1 = mfma(sk[2 * S + 1][mt >> 1], sel[mt & 1], f32x4{0.f, 0.f, 0.f, 0.f});
+          const bf16x8 stv = pack8(tr0, tr1);
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(stv, vop[S][vt], T[mt][vt]);
+        }
+      } else {
+        bf16x8 pq[2][2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int blk = 0; blk < 2; ++blk) pq[u][blk] = *(const bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int it = 2 * (S - 2) + u;
+          const bf16x8* p = pq[u];
+          f32x4 y[NVT];
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) {
+            y[vt] = mfma(tb[0][vt], p[0], f32x4{0.f, 0.f, 0.f, 0.f});
+            y[vt] = mfma(tb[1][vt], p[1], y[vt]);
+          }
+          // scores^T tiles (rows = first-side tokens 16 jt + 4g + r, column = second-side token 16 it + c), masked
+#pragma unroll
+          for (int jp = 0; jp < 2; ++jp) {
+            if (MODE ? 2 * jp + 1 >= it : 2 * jp <= it) {
+              f32x4 sc[2];
+#pragma unroll
+              for (int jj = 0; jj < 2; ++jj) {
+                const int jt = 2 * jp + jj;
+                sc[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (MODE ? jt >= it : jt <= it) {
+                  sc[jj] = mfma(sk[jt][0], p[0], sc[jj]);
+                  sc[jj] = mfma(sk[jt][1], p[1], sc[jj]);
+                  if (jt == it) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) sc[jj][r] = (MODE ? 4 * g + r >= c : 4 * g + r <= c) ? sc[jj][r] : 0.f;
+                  }
+                }
+              }
+              const bf16x8 sb = pack8(sc[0], sc[1]);
+#pragma unroll
+              for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(vop[jp][vt], sb, y[vt]);
+            }
+          }
+          exchange_put_bf16(sm, y, it, j, lane);
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// grid (nslot, B*H), block 512.
+template <int MODE>
+__global__ void __launch_bounds__(NT8) k_bwd_walk_pc(BwdArgs ba) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemWalk& sm = *reinterpret_cast<SmemWalk*>(smem_raw);
+  const FastArgs& a = ba.f;
+  const int slot = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
+  Ctx cx;
+  cx.isoC = ((int)th[2]) & 1;
+  cx.bh = bh;
+  cx.pg = group_of(a.pgroups, b, h, a.H);
+  cx.cs = a.cstar[bh];
+  cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
+  cx.Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
+  cx.Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
+  cx.Gb = ba.gh + (size_t)bh * ba.Lq * DVP;
+  cx.row_beg = min(ba.Lq, slot * ba.rows_per_rslot);
+  cx.row_end = min(ba.Lq, cx.row_beg + ba.rows_per_rslot);
+  cx.nchunk = (cx.row_end - cx.row_beg + TC - 1) / TC;
+  // the value columns fill rows 0..64 of the transposed tile only
+  for (int idx = threadIdx.x; idx < DVP * LDJ / 2; idx += NT8) ((uint32_t*)&sm.uothT[0][0])[idx] = 0u;
+  __syncthreads();
+  const int w = threadIdx.x >> 6;
+  if (w < 4) walk_producer<MODE>(ba, sm, cx, w);
+  else walk_consumer<MODE>(ba, sm, cx, slot, w - 4);
+}
+
 }  // namespace cg
 
 int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t st) {
@@ -524,6 +795,18 @@ int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t s
   return 0;
 }
 
-size_t bwd_cgrad_pc_lds_bytes() { return sizeof(cg::SmemCG); }
+int launch_bwd_walk_pc(const bwd::BwdArgs& ba, int mode, int nslot, int BH, hipStream_t st) {
+  const void* fn = mode ? (const void*)cg::k_bwd_walk_pc<1> : (const void*)cg::k_bwd_walk_pc<0>;
+  if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(cg::SmemWalk)) != hipSuccess) {
+    (void)hipGetLastError();
+    return 2;
+  }
+  if (mode) hipLaunchKernelGGL(cg::k_bwd_walk_pc<1>, dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
+  else hipLaunchKernelGGL(cg::k_bwd_walk_pc<0>, dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
+  if (hipGetLastError() != hipSuccess) return 5;
+  return 0;
+}
+
+size_t bwd_pc_lds_bytes() { return sizeof(cg::SmemCG) > sizeof(cg::SmemWalk) ? sizeof(cg::SmemCG) : sizeof(cg::SmemWalk); }
 
 }  // namespace fs
