@@ -144,9 +144,8 @@ def bench_matvec(args, cfg, fs, synth, util, torch):
 
 def bench_backward(args, fs, synth, util, torch):
     """The backward pass of attention on the c3 (non-causal) or c4 (causal) shapes, bf16 inputs and gradients: one
-    step = one favorsharp_attention_backward call with theta and omega resident.  The non-causal shapes run on the
-    bf16 MFMA kernels (bound: the bf16 MFMA peak), the causal ones on the general-shape kernels (fp32 arithmetic on
-    fp32 MFMA tiles; bound: the fp32 MFMA peak).  Algorithmic flops per
+    step = one favorsharp_attention_backward call with theta and omega resident.  Both run on the bf16 MFMA kernels
+    (bound: the bf16 MFMA peak).  Algorithmic flops per
     head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six M x (dv + 1) contractions
     (T, P T, G1 T^T, P^T G1, S R, [V 1] R^T) 12 M (dv + 1), and when causal the intra-chunk triangles of 64 rows
     (scores and G1 V1^T and their four products: three times the forward pass's extra term)."""
@@ -182,17 +181,16 @@ def bench_backward(args, fs, synth, util, torch):
     per_token = 8 * d * M + 12 * M * (d + 1) + (3 * (chunk + 1) // 2 * (2 * M + 2 * (d + 1)) if causal else 0)
     flops = B * H * L * per_token
     tf = flops / (ms * 1e-3) / 1e12
-    peak = 157.3 if causal else MFMA_BF16_PEAK_TFLOPS
+    peak = MFMA_BF16_PEAK_TFLOPS
     print(json.dumps({
         "metric": f"FAVOR# attention backward tokens/s ({name} shapes: {'causal' if causal else 'non-causal'}, "
                   f"B={B} H={H} L={L} d={d} M={M})",
         "value": B * L / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if causal else "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: gradients of {'causal' if causal else 'non-causal'} attention w.r.t. "
                                "Q, K, V, bf16 in and out, "
-                               + ("fp32 arithmetic (general-shape kernels)" if causal else "bf16 MFMA kernels, fp32 accumulation")
-                               + ", SDERF per head, theta and omega resident"},
+                               "bf16 MFMA kernels, fp32 accumulation, SDERF per head, theta and omega resident"},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
                      "traffic": None}}), flush=True)
 

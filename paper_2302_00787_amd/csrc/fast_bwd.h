@@ -1,4 +1,4 @@
-// Shared declarations of the bf16 backward kernels (kernels_bf16_bwd.hip: non-causal; kernels_bf16_bwd_causal.hip:
+// Shared declarations of the bf16 backward kernels (kernels_bf16_bwd.hip: non-causal; kernels_bf16_bwd_pc.hip:
 // causal).
 #pragma once
 #include "fast_common.h"

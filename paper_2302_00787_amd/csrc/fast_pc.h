@@ -1,6 +1,6 @@
 // Building blocks shared by the kernels whose waves are split into producers (staging, feature tiles, finishing)
 // and consumers (contractions with the state in registers): the causal segment kernel of the forward pass
-// (kernels_bf16_causal.hip) and the causal gradient kernels (kernels_bf16_bwd_cgrad.hip).
+// (kernels_bf16_causal.hip) and the causal gradient kernels (kernels_bf16_bwd_pc.hip).
 #pragma once
 #include "fast_common.h"
 

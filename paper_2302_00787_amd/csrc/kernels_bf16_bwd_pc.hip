@@ -1,5 +1,17 @@
-// Gradient rows dQ and dK of causal attention on the bf16 path (d = dv = 64, M = 256): one kernel template, the two
-// sides being mirror images of each other.
+// Backward pass of causal attention on the bf16 path (d = dv = 64, M = 256); see kernels_bf16_bwd.hip for the
+// non-causal variant and the notation.  With T_i the prefix state (keys j <= i) and R_j the suffix sum
+// sum_{i >= j} P_i^T G1_i, per chunk c of 64 tokens (A = tril(G1_c V1_c^T), B = tril(P_c S_c^T)):
+//   dP_c  = G1_c T_{c-1}^T + A S_c               dV1_c = S_c R_{c+1} + B^T G1_c
+//   dS_c  = V1_c R_{c+1}^T + A^T P_c
+// Every kernel walks one slot (a run of whole chunks) of one sequence; the key features use ONE shift per sequence
+// (the largest bound over all its tokens) so that the states of different slots, G1 and the gradients all live on
+// one scale.  One call:
+//   k_bwd_walk_pc<0>   forward walk: Yhat, normaliser, Y, G1 rows             (T from the exclusive prefix per slot)
+//   k_bwd_rstate       (kernels_bf16_bwd.hip) per-slot sums of P^T G1;  k_bwd_suffix  their exclusive suffix
+//   k_bwd_walk_pc<1>   backward walk: dV
+//   k_bwd_cgrad_pc<0>  forward walk: dQ;   k_bwd_cgrad_pc<1>  backward walk: dK
+//
+// ---- gradient rows dQ and dK: one kernel template, the two sides being mirror images of each other ----------------
 //
 // Per chunk of 64 tokens, with F the feature matrix of a side (P for queries, S for keys), U the 80-column rows that
 // go with it (G1 = [dY / den, -(dY . Y) / den] for queries, V1 = [V 1] for keys) and Z the running state built from
@@ -19,7 +31,7 @@
 //             registers a chunk ahead -> LDS), the masked 64 x 64 products U_oth U_own^T as operand images, and one
 //             chunk later the sum of the consumers' partial gradient tiles (MFMA against a routing matrix), the key
 //             row term and the store.
-//   consumer, step 0: state update with the previous chunk's tiles, then the new feature-major tiles into registers;
+//   consumer, step 0/1: state update with the previous chunk's tiles, then the new feature-major tiles into registers;
 //             step 2/3: dF tiles, the product with the own features, the contraction with W~^T and the partial
 //             tiles to LDS.
 // LDS lifetimes (interval t = 4 (chunk index) + step; the consumer's step s runs in interval 4c + s + 1):
@@ -28,7 +40,7 @@
 //                                   of the next chunk
 //   uown, uoth (U rows)             written in step 1, read by the producers in step 2 and by the consumers in their
 //                                   steps 2 and 3 (intervals 4c+3, 4c+4; the next write is in 4c+5)
-//   uothT (U_oth transposed)        written in step 3, read by the consumers' state update in interval 4c+5
+//   uothT (U_oth transposed)        written in step 3, read by the consumers' state update in intervals 4c+5, 4c+6
 //   ab (mask products)              written in step 2, read in intervals 4c+3 and 4c+4
 //   xch (partial tiles)             written in intervals 4c+3 and 4c+4, summed in step 1 of the next chunk (4c+5)
 #include "fast_bwd.h"
@@ -397,16 +409,15 @@ __device__ __forceinline__ void consumer(const BwdArgs& ba, SmemCG& sm, const Ct
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
       if (S < 2) {
-        if (S == 0 && ci > 0) {
-          // the state takes the previous chunk's tokens
+        if (ci > 0) {
+          // the state takes the previous chunk's tokens, one pair of token tiles per step (the pair whose registers
+          // are refilled next)
 #pragma unroll
-          for (int jp = 0; jp < 2; ++jp)
+          for (int vt = 0; vt < NVT; ++vt) {
+            const bf16x8 uop = load_vop_l(sm.uothT, S, vt, lane);
 #pragma unroll
-            for (int vt = 0; vt < NVT; ++vt) {
-              const bf16x8 uop = load_vop_l(sm.uothT, jp, vt, lane);
-#pragma unroll
-              for (int mt = 0; mt < 4; ++mt) Zt[vt][mt] = mfma(uop, st[mt][jp], Zt[vt][mt]);
-            }
+            for (int mt = 0; mt < 4; ++mt) Zt[vt][mt] = mfma(uop, st[mt][S], Zt[vt][mt]);
+          }
         }
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) st[mt][S] = *(const bf16x8*)(&sm.feat[S & 1][mt][j][lane][0]);
@@ -781,6 +792,24 @@ __global__ void __launch_bounds__(NT8) k_bwd_walk_pc(BwdArgs ba) {
 
 }  // namespace cg
 
+namespace bwd {
+
+// Exclusive suffix over the slots of one (b,h), in place.  grid (ceil(M*DVP/256), B*H).
+__global__ void k_bwd_suffix(float* Rpart, int nslot) {
+  const size_t per = (size_t)M * DVP;
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= per) return;
+  float* p = Rpart + (size_t)blockIdx.y * nslot * per + e;
+  float run = 0.f;
+  for (int s = nslot - 1; s >= 0; --s) {
+    const float v = p[(size_t)s * per];
+    p[(size_t)s * per] = run;
+    run += v;
+  }
+}
+
+}  // namespace bwd
+
 int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t st) {
   const void* fns[2] = {(const void*)cg::k_bwd_cgrad_pc<0>, (const void*)cg::k_bwd_cgrad_pc<1>};
   for (const void* fn : fns)
@@ -806,6 +835,29 @@ int launch_bwd_walk_pc(const bwd::BwdArgs& ba, int mode, int nslot, int BH, hipS
   if (hipGetLastError() != hipSuccess) return 5;
   return 0;
 }
+
+#define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
+
+// One causal backward call after the forward state pass over every slot (f.Tpart = exclusive prefix per slot on the
+// sequence's common shift f.cstar).
+int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
+                                const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
+                                hipStream_t st) {
+  bwd::BwdArgs ba;
+  ba.f = a;
+  ba.dY = dY; ba.dQ = dQ; ba.dK = dK; ba.dV = dV;
+  ba.gh = gh; ba.Rpart = Rpart; ba.rcpart = rcpart;
+  ba.Lq = f.Lq; ba.Lk = f.Lk; ba.rslots = a.nslot; ba.rows_per_rslot = a.rows_per_seg / a.sub;
+  const int BH = f.B * f.H;
+  if (int rc = launch_bwd_walk_pc(ba, 0, a.nslot, BH, st)) return rc;
+  if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
+  hipLaunchKernelGGL(bwd::k_bwd_suffix, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
+  FS_LAUNCH_CHECK();
+  if (int rc = launch_bwd_walk_pc(ba, 1, a.nslot, BH, st)) return rc;
+  return launch_bwd_cgrad_pc(ba, a.nslot, BH, st);
+}
+
+size_t fast_bwd_causal_lds_bytes() { return bwd_pc_lds_bytes(); }
 
 size_t bwd_pc_lds_bytes() { return sizeof(cg::SmemCG) > sizeof(cg::SmemWalk) ? sizeof(cg::SmemCG) : sizeof(cg::SmemWalk); }
 
