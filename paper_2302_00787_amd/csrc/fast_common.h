@@ -106,7 +106,7 @@ __device__ __forceinline__ float row_shift(float n2, float wmax) {
 struct Smem {
   uint16_t k[2][TC][LDR];       // key rows, bf16 bits
   uint16_t vt[2][DVP][LDJ];     // values transposed: [column][token]; row 64 = ones, rows 65.. = 0
-  float kadd[2][TC];            // per key token: row term log2e y^T C2 y
+  __attribute__((aligned(16))) float kadd[2][TC];   // per key token: row term log2e y^T C2 y
   __attribute__((aligned(16))) float kbnd[2][TC];   // per key token: row_shift + row term (-inf past the end)
   __attribute__((aligned(16))) uint16_t q[2][TC][LDR];       // query rows
   float qadd[2][TC];            // per query token: - row_shift
@@ -289,6 +289,36 @@ __device__ __forceinline__ void feature_tile(const WSlice& ws, const QBias* qb, 
   for (int mt = 0; mt < 4; ++mt) acc[mt] = exp2v(WITH_BIAS ? acc[mt] + add : acc[mt]);
   out[0] = pack8(acc[0], acc[1]);
   out[1] = pack8(acc[2], acc[3]);
+}
+
+// Features of one pair of token tiles, feature-major: st[mt] has lane <-> feature 64w + 16 mt + c and contraction
+// index <-> the pair's tokens {32 jp + 4g + r, 32 jp + 16 + 4g + r}: the projection MFMA with its operands swapped
+// (rows = tokens, columns = features), so the state update S^T [V 1] needs no transpose.  add[t] - sub is the
+// per-token part of the exponent; bcol[mt] the bias term of lane c's feature (WITH_BIAS).
+template <bool WITH_BIAS>
+__device__ __forceinline__ void feature_pair_major(const WSlice& ws, const float (&bcol)[4], const uint16_t (*tile)[LDR],
+                                                   const float* add, int jp, float sub, bf16x8 (&st)[4]) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  bf16x8 x[2][KS];
+  f32x4 addv[2];
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int jt = 2 * jp + jj;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) x[jj][ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+    addv[jj] = *(const f32x4*)(add + 16 * jt + 4 * g) - sub;
+  }
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    f32x4 acc[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      acc[jj] = mfma(x[jj][0], ws.w[mt][0], WITH_BIAS ? addv[jj] + bcol[mt] : addv[jj]);
+#pragma unroll
+      for (int ks = 1; ks < KS; ++ks) acc[jj] = mfma(x[jj][ks], ws.w[mt][ks], acc[jj]);
+    }
+    st[mt] = pack8(exp2v(acc[0]), exp2v(acc[1]));
+  }
 }
 
 // Key-side features of one pair of token tiles (tokens 32 jp .. 32 jp + 31) in both operand layouts: s[jj][mb]

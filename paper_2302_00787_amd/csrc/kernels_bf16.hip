@@ -89,8 +89,7 @@ __global__ void __launch_bounds__(NT) k_fast_state(FastArgs a) {
 
   WSlice wk;
   load_wslice(wk, a.Wbf + ((size_t)pg * 2 + 1) * M * D);
-  bf16x8 sel[2];
-  make_sel(sel);
+  const float nobias[4] = {0.f, 0.f, 0.f, 0.f};
   zero_pad_rows(sm);
   f32x4 T[4][NVT];
 #pragma unroll
@@ -117,8 +116,8 @@ __global__ void __launch_bounds__(NT) k_fast_state(FastArgs a) {
     dk = key_shift_update(sm, buf, dk, T);
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
-      bf16x8 sp[2][2], st[4];
-      key_pair(wk, sm, buf, jp, dk, sel, sp, st);
+      bf16x8 st[4];
+      feature_pair_major<false>(wk, nobias, sm.k[buf], sm.kadd[buf], jp, dk, st);
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) {
         const bf16x8 vop = load_vop(sm.vt[buf], jp, vt);

@@ -167,10 +167,9 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
 
   WSlice wq;
   load_wslice(wq, a.Wbf + ((size_t)pg * 2) * M * D);
-  QBias qb;
-  load_qbias(qb, a.bias + ((size_t)pg * 2) * M, amax);
-  bf16x8 sel[2];
-  make_sel(sel);
+  float bcol[4];         // 2 (bias - largest bias) of feature 64w + 16 mt + c
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) bcol[mt] = 2.f * (a.bias[((size_t)pg * 2) * M + 64 * w + 16 * mt + c] - amax);
   f32x4 R[4][NVT];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -205,21 +204,8 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
     }
 #pragma unroll
     for (int jp = 0; jp < 2; ++jp) {
-      // P tiles of the pair and their transposes (lane <-> feature) through the selection matrices
-      f32x4 tr[2][4];
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) {
-        const int jt = 2 * jp + jj;
-        bf16x8 s[2];
-        feature_tile<true>(wq, &qb, sm.k[buf], jt, sm.kadd[buf][16 * jt + c], s);
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int hh = 0; hh < 2; ++hh) tr[jj][2 * mb + hh] = mfma(s[mb], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-      }
       bf16x8 st[4];
-#pragma unroll
-      for (int mt = 0; mt < 4; ++mt) st[mt] = pack8(tr[0][mt], tr[1][mt]);
+      feature_pair_major<true>(wq, bcol, sm.k[buf], sm.kadd[buf], jp, 0.f, st);
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) {
         const bf16x8 vop = load_vop(sm.vt[buf], jp, vt);
