@@ -142,25 +142,26 @@ __global__ void __launch_bounds__(NT) k_fast_state(FastArgs a) {
 }
 
 // Brings the segment states of one (b,h) to the common shift c* = max_seg cpart and sums them (prefix = 0: total
-// in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  grid (ceil(M*DVP/256), B*H).
+// in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  grid (ceil(M*DVP/1024), B*H).
 __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, int nseg, int nseg_valid, int prefix,
                               int sub) {
   const int bh = blockIdx.y;
-  const size_t per = (size_t)M * DVP;
-  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  constexpr size_t per = (size_t)M * DVP;
+  const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);      // four consecutive numbers per thread
   float cs = -INFINITY;
   for (int s = 0; s < nseg_valid; ++s) cs = fmaxf(cs, cpart[(size_t)bh * nseg + s]);
   if (e == 0) cstar[bh] = cs;
   if (e >= per) return;
   float* p = Tpart + (size_t)bh * nseg * per + e;
-  float run = 0.f;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
   for (int s = 0; s < nseg; ++s) {
-    float v = 0.f;
-    if (s < nseg_valid) v = p[(size_t)s * per] * fast_exp2(cpart[(size_t)bh * nseg + s] - cs);
-    if (prefix && s % sub == 0) p[(size_t)s * per] = run;    // only the slots that open a segment are read back
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (s < nseg_valid) v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nseg + s] - cs);
+    if (prefix && s % sub == 0) *(f32x4*)(p + (size_t)s * per) = run;    // only the slots that open a segment are read back
     run += v;
   }
-  if (!prefix) p[0] = run;
+  if (!prefix) *(f32x4*)p = run;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -344,7 +345,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
     hipLaunchKernelGGL(k_fast_state, dim3(nstate, BH), dim3(NT), offsetof(Smem, q), st, a);
     FS_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
+  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
                      a.nslot, nstate, f.causal, every_slot ? 1 : f.sub);
   FS_LAUNCH_CHECK();
   return 0;
@@ -352,7 +353,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
 
 // Sum of `nslot` segment states per (b,h) into slot 0 (the reduction kernel of the forward pass on another buffer).
 void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st) {
-  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, part, cpart, cstar, nslot, nslot, 0, 1);
+  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, part, cpart, cstar, nslot, nslot, 0, 1);
 }
 
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {

@@ -794,16 +794,18 @@ __global__ void __launch_bounds__(NT8) k_bwd_walk_pc(BwdArgs ba) {
 
 namespace bwd {
 
-// Exclusive suffix over the slots of one (b,h), in place.  grid (ceil(M*DVP/256), B*H).
+// Exclusive suffix over the slots of one (b,h), in place; four consecutive numbers per thread.
+// grid (ceil(M*DVP/1024), B*H).
 __global__ void k_bwd_suffix(float* Rpart, int nslot) {
-  const size_t per = (size_t)M * DVP;
-  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  constexpr size_t per = (size_t)M * DVP;
+  const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
   if (e >= per) return;
   float* p = Rpart + (size_t)blockIdx.y * nslot * per + e;
-  float run = 0.f;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
   for (int s = nslot - 1; s >= 0; --s) {
-    const float v = p[(size_t)s * per];
-    p[(size_t)s * per] = run;
+    const f32x4 v = *(const f32x4*)(p + (size_t)s * per);
+    *(f32x4*)(p + (size_t)s * per) = run;
     run += v;
   }
 }
@@ -851,7 +853,7 @@ int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const Te
   const int BH = f.B * f.H;
   if (int rc = launch_bwd_walk_pc(ba, 0, a.nslot, BH, st)) return rc;
   if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
-  hipLaunchKernelGGL(bwd::k_bwd_suffix, dim3((M * DVP + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
+  hipLaunchKernelGGL(bwd::k_bwd_suffix, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
   FS_LAUNCH_CHECK();
   if (int rc = launch_bwd_walk_pc(ba, 1, a.nslot, BH, st)) return rc;
   return launch_bwd_cgrad_pc(ba, a.nslot, BH, st);
