@@ -95,6 +95,25 @@ void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
   p->total = off;
 }
 
+struct WidePlan {
+  int nslot, rows_per_slot;
+  size_t off_Wbf, off_bias, off_wnorm, off_rk, off_state, off_cpart, off_cstar, off_ypart, total;
+};
+
+void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
+  wide_plan(BH, L, &p->nslot, &p->rows_per_slot);
+  size_t off = 0;
+  p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 512 * 128 * sizeof(uint16_t));
+  p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 512 * sizeof(float));
+  p->off_wnorm = off;  off = align_up(off + (size_t)pgroups * 2 * 512 * sizeof(float));
+  p->off_rk = off;     off = align_up(off + (size_t)BH * L * sizeof(float));
+  p->off_state = off;  off = align_up(off + (size_t)BH * 2 * p->nslot * 256 * 144 * sizeof(float));
+  p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nslot * sizeof(float));
+  p->off_cstar = off;  off = align_up(off + (size_t)BH * sizeof(float));
+  p->off_ypart = off;  off = align_up(off + (size_t)2 * BH * L * 132 * sizeof(float));
+  p->total = off;
+}
+
 int device_lds_limit() {
   int dev_id = 0, v = 0;
   if (hipGetDevice(&dev_id) != hipSuccess) return 0;
@@ -283,6 +302,11 @@ size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d,
     plan_fast(B * H, std::max(groups, omega_groups), Lk, &fp);
     total = std::max(total, fp.total);
   }
+  if (wide_supported(FS_BF16, d, dv, M, causal) && Lq == Lk) {
+    WidePlan wp;
+    plan_wide(B * H, std::max(groups, omega_groups), Lk, &wp);
+    total = std::max(total, wp.total);
+  }
   return total;
 }
 
@@ -331,6 +355,20 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
     f.cstar = (float*)(w8 + fp.off_cstar);
     return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
+  }
+  if (wide_supported(Q->dtype, d, dv, M, causal) && small_strides && (int)wide_lds_bytes() <= lds_limit) {
+    WidePlan wp;
+    plan_wide(BH, pgroups, Lk, &wp);
+    char* w8 = (char*)workspace;
+    WideLaunch f;
+    f.Q = dev(Q); f.K = dev(K); f.V = dev(V); f.Y = dev(Y);
+    f.theta = theta; f.Omega = Omega;
+    f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
+    f.B = B; f.H = H; f.L = Lk; f.nslot = wp.nslot; f.rows_per_slot = wp.rows_per_slot; f.scale = qk_scale;
+    f.Wbf = (uint16_t*)(w8 + wp.off_Wbf); f.bias = (float*)(w8 + wp.off_bias); f.wnorm = (float*)(w8 + wp.off_wnorm);
+    f.rk = (float*)(w8 + wp.off_rk); f.Tpart = (float*)(w8 + wp.off_state); f.cpart = (float*)(w8 + wp.off_cpart);
+    f.cstar = (float*)(w8 + wp.off_cstar); f.Ypart = (float*)(w8 + wp.off_ypart);
+    return launch_wide_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
   }
   AttnPlan p;
   plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p);

@@ -94,6 +94,29 @@ struct FastLaunch {
   float* cstar;     // [B*H]
 };
 
+// bf16 path for causal calls with d = dv = 128, M = 512 (kernels_bf16_wide.hip).
+struct WideLaunch {
+  TensorDev Q, K, V, Y;
+  const float* theta;
+  const float* Omega;
+  int groups, omega_groups, pgroups;
+  int B, H, L;
+  int nslot, rows_per_slot;
+  float scale;
+  uint16_t* Wbf;    // [pgroups][2][512][128]
+  float* bias;      // [pgroups][2][512]
+  float* wnorm;     // [pgroups][2][512]
+  float* rk;        // [B*H][L]
+  float* Tpart;     // [B*H][2][nslot][256][144]
+  float* cpart;     // [B*H][nslot]
+  float* cstar;     // [B*H]
+  float* Ypart;     // [2][B*H][L][132]
+};
+bool wide_supported(int dtype, int d, int dv, int M, int causal);
+size_t wide_lds_bytes();
+void wide_plan(int BH, int L, int* nslot, int* rows_per_slot);
+int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
+
 size_t fast_lds_bytes();
 bool fast_supported(int dtype, int d, int dv, int M);
 void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub);

@@ -680,86 +680,7 @@ __device__ __forceinline__ void walk_consumer(const BwdArgs& ba, SmemWalk& sm, c
 #pragma unroll
         for (int r = 0; r < 4; ++r) T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * DVP + 16 * vt + c];
   }
-  __syncthreads();                 // barrier 0
-  __syncthreads();                 // the producers' first step
-
-  for (int ci = 0; ci < cx.nchunk; ++ci) {
-    // state before this chunk as A operand (rows = value columns, contraction index <-> feature)
-    bf16x8 tb[2][NVT];
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) tb[blk][vt] = pack8(T[2 * blk][vt], T[2 * blk + 1][vt]);
-    bf16x8 sk[4][2];               // first-side feature tiles of the chunk
-    bf16x8 vop[2][NVT];            // value operands of the chunk
-#pragma unroll
-    for (int S = 0; S < 4; ++S) {
-      if (S < 2) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int blk = 0; blk < 2; ++blk) sk[2 * S + u][blk] = *(const bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]);
-#pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) vop[S][vt] = load_vop_l(sm.uothT, S, vt, lane);
-        bf16x8 sel[2];
-        {
-          int lane_here = lane;
-          asm volatile("" : "+v"(lane_here));
-          make_sel32(sel, lane_here);
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-          const f32x4 tr0 = mfma(sk[2 * S][mt >> 1], sel[mt & 1], f32x4{0.f, 0.f, 0.f, 0.f});
-          const f32x4 tr1 = mfma(sk[2 * S + 1][mt >> 1], sel[mt & 1], f32x4{0.f, 0.f, 0.f, 0.f});
-          const bf16x8 stv = pack8(tr0, tr1);
-#pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(stv, vop[S][vt], T[mt][vt]);
-        }
-      } else {
-        bf16x8 pq[2][2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int blk = 0; blk < 2; ++blk) pq[u][blk] = *(const bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const int it = 2 * (S - 2) + u;
-          const bf16x8* p = pq[u];
-          f32x4 y[NVT];
-#pragma unroll
-          for (int vt = 0; vt < NVT; ++vt) {
-            y[vt] = mfma(tb[0][vt], p[0], f32x4{0.f, 0.f, 0.f, 0.f});
-            y[vt] = mfma(tb[1][vt], p[1], y[vt]);
-          }
-          // scores^T tiles (rows = first-side tokens 16 jt + 4g + r, column = second-side token 16 it + c), masked
-#pragma unroll
-          for (int jp = 0; jp < 2; ++jp) {
-            if (MODE ? 2 * jp + 1 >= it : 2 * jp <= it) {
-              f32x4 sc[2];
-#pragma unroll
-              for (int jj = 0; jj < 2; ++jj) {
-                const int jt = 2 * jp + jj;
-                sc[jj] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (MODE ? jt >= it : jt <= it) {
-                  sc[jj] = mfma(sk[jt][0], p[0], sc[jj]);
-                  sc[jj] = mfma(sk[jt][1], p[1], sc[jj]);
-                  if (jt == it) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) sc[jj][r] = (MODE ? 4 * g + r >= c : 4 * g + r <= c) ? sc[jj][r] : 0.f;
-                  }
-                }
-              }
-              const bf16x8 sb = pack8(sc[0], sc[1]);
-#pragma unroll
-              for (int vt = 0; vt < NVT; ++vt) y[vt] = mfma(vop[jp][vt], sb, y[vt]);
-            }
-          }
-          exchange_put_bf16(sm, y, it, j, lane);
-        }
-      }
-      __syncthreads();
-    }
-  }
+  walk_consume<MODE>(sm, T, cx.nchunk, j);
 }
 
 // grid (nslot, B*H), block 512.

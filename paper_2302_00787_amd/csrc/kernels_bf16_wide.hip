@@ -1,0 +1,576 @@
+// bf16 path of causal FAVOR# attention for d = dv = 128, M = 512 (the long-context shape).
+//
+// The kernels for d = dv = 64, M = 256 keep 64 features x 80 state columns per wave in registers.  This shape is
+// four such problems: the sums over features that make up numerator and normaliser split into two halves of 256
+// features, and the value columns into [V_0..63, 1] and [V_64..127].  One launch runs the four (feature half,
+// column half) combinations side by side; every combination is the producer / consumer walk of the forward pass
+// (fast_pc.h) with projections of depth 128, and leaves UNNORMALISED partial rows in fp32; a last kernel adds the
+// two feature halves and divides by the normaliser.  All four share every shift (the per-row query shift and the
+// per-sequence key shift are bounds over all 512 features), so their partial rows are on one scale.
+//
+//   k_wide_pre     projection constants for both sides (Section 4, evaluation recipe), key row terms for dense C2
+//   k_wide_state   per (slot, feature half): S^T [V 1] over the slot (eight waves of 32 features, all 129 columns)
+//   k_wide_reduce  exclusive prefix over the slots on the sequence's common shift
+//   k_wide_walk    per (slot, feature half, column half): the causal walk
+//   k_wide_finish  Y = (part_0 + part_1) / normaliser
+#include <algorithm>
+
+#include "fast_pc.h"
+
+namespace fs {
+
+using namespace fast;
+
+namespace wide {
+
+using namespace pc;
+
+constexpr int DW = 128;            // head and value dimension
+constexpr int MW = 512;            // random features
+constexpr int KSW = DW / 32;       // MFMA k-steps of a projection
+constexpr int LDRW = DW + 8;       // row stride (bf16) of a token tile in LDS: 68 dwords
+constexpr int NVW = 9;             // value tiles of the state kernel: 128 columns + the ones column + padding
+constexpr int TLD = NVW * 16;      // row stride (floats) of a state: 144; column 128 = normaliser
+constexpr int YLD = 132;           // row stride (floats) of a partial output row: 128 columns, normaliser at 128
+
+struct WideArgs {
+  TensorDev Q, K, V, Y;
+  const float* theta;
+  const float* Omega;
+  uint16_t* Wbf;     // [pg][2][512][128]
+  float* bias;       // [pg][2][512]
+  float* wnorm;      // [pg][2][512]
+  float* rk;         // [BH][L]
+  float* Tpart;      // [BH][2][nslot][256][144]
+  float* cpart;      // [BH][nslot]
+  float* cstar;      // [BH]
+  float* Ypart;      // [2][BH][L][132]
+  int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;
+  float scale;
+};
+
+__device__ __forceinline__ float max512(const float* p) {
+  const int lane = threadIdx.x & 63;
+  const f32x4 a = *(const f32x4*)(p + 4 * lane), b = *(const f32x4*)(p + 256 + 4 * lane);
+  const float m = wave_max(fmaxf(fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3])), fmaxf(fmaxf(b[0], b[1]), fmaxf(b[2], b[3]))));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, m)));
+}
+// Sum over the row of 16 lanes the lane belongs to.
+__device__ __forceinline__ float sum16(float v) {
+  v = sum8(v);
+  v += dpp_f<0x128>(v);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// grid 128 * 2 * pgroups + rowblocks * B*H workgroups of 256 threads; see k_fast_pre.  One wave per feature, lane c
+// handles columns c and c + 64; for the row terms one wave per token, lane a handles rows a and a + 64 of C2.
+// ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks) {
+  const size_t tf = FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW;
+  const int nprep = (MW / 4) * 2 * a.pgroups, H = a.H;
+  const int c = threadIdx.x & 63;
+  if ((int)blockIdx.x < nprep) {
+    const int pg = blockIdx.x / ((MW / 4) * 2), rem = blockIdx.x % ((MW / 4) * 2), side = rem / (MW / 4);
+    const int m = (rem % (MW / 4)) * 4 + (threadIdx.x >> 6);
+    int b = 0, h = 0;
+    if (a.pgroups == H && a.pgroups != 1) h = pg;
+    else if (a.pgroups != 1) { b = pg / H; h = pg % H; }
+    const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
+    const float* om = a.Omega + ((size_t)group_of(a.omega_groups, b, h, H) * MW + m) * DW;
+    const float* Bm = th + FS_THETA_HEADER_ + DW + (side ? (size_t)DW * DW : 0);
+    const float* A = th + FS_THETA_HEADER_;
+    const size_t o = ((size_t)pg * 2 + side) * MW + m;
+    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 8
+    for (int l = 0; l < DW; ++l) {
+      acc0 += om[l] * Bm[l * DW + c];
+      acc1 += om[l] * Bm[l * DW + c + 64];
+    }
+    const uint16_t b0 = f32_to_bf16_bits(acc0 * kLog2e * a.scale), b1 = f32_to_bf16_bits(acc1 * kLog2e * a.scale);
+    a.Wbf[o * DW + c] = b0;
+    a.Wbf[o * DW + c + 64] = b1;
+    const float r0 = bf16_bits_to_f32(b0), r1 = bf16_bits_to_f32(b1);
+    float n2 = r0 * r0 + r1 * r1, q = A[c] * om[c] * om[c] + A[c + 64] * om[c + 64] * om[c + 64];
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) { n2 += __shfl_xor(n2, s); q += __shfl_xor(q, s); }
+    if (c == 0) {
+      a.bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)MW));
+      a.wnorm[o] = sqrtf(n2);
+    }
+    return;
+  }
+  const int rb = blockIdx.x - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
+  const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
+  if (((int)th[2]) & 1) return;
+  const float* C2 = th + FS_THETA_HEADER_ + DW + 3 * (size_t)DW * DW;
+  for (int j = blk * 4 + (threadIdx.x >> 6); j < a.L; j += 4 * rowblocks) {
+    const uint16_t* row = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh + (long long)j * a.K.sl;
+    const float y0 = a.scale * bf16_bits_to_f32(row[c]), y1 = a.scale * bf16_bits_to_f32(row[c + 64]);
+    float t0 = 0.f, t1 = 0.f;
+#pragma unroll 8
+    for (int e = 0; e < 64; ++e) {
+      const float ye0 = __shfl(y0, e), ye1 = __shfl(y1, e);
+      t0 += C2[c * DW + e] * ye0 + C2[c * DW + e + 64] * ye1;
+      t1 += C2[(c + 64) * DW + e] * ye0 + C2[(c + 64) * DW + e + 64] * ye1;
+    }
+    float acc = y0 * t0 + y1 * t1;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) acc += __shfl_xor(acc, s);
+    if (c == 0) a.rk[(size_t)bh * a.L + j] = kLog2e * acc;
+  }
+}
+
+// Rows of 128 numbers: 16 pieces of 16 bytes; returns in every lane of the 16 that share the row its squared norm.
+__device__ __forceinline__ float store_row_piece_w(u32x4 p, uint16_t (*tile)[LDRW], int row, int pc) {
+  *(u32x4*)(&tile[row][pc * 8]) = p;
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float lo = __uint_as_float(p[e] << 16), hi = __uint_as_float(p[e] & 0xffff0000u);
+    s += lo * lo + hi * hi;
+  }
+  return sum16(s);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Key-side state of one slot and one feature half: Tpart = sum_j S'_j [V_j 1]^T / 2^cpart.  Eight waves of 32
+// features; feature tiles feature-major (projection MFMA with swapped operands).  grid (nslot, B*H, 2), block 512.
+// ---------------------------------------------------------------------------------------------------
+struct SmemWState {
+  __attribute__((aligned(16))) uint16_t k[2][TC][LDRW];
+  __attribute__((aligned(16))) uint16_t vt[2][TLD][LDJ];     // [column][token]; row 128 = ones, rows 129.. = 0
+  __attribute__((aligned(16))) float kadd[2][TC];
+  __attribute__((aligned(16))) float kbnd[2][TC];
+};
+
+__global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemWState& sm = *reinterpret_cast<SmemWState*>(smem_raw);
+  const int slot = blockIdx.x, bh = blockIdx.y, fh = blockIdx.z, b = bh / a.H, h = bh % a.H;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const int pg = group_of(a.pgroups, b, h, a.H);
+  const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW);
+  const bool isoC = ((int)th[2]) & 1;
+  const float wmax = max512(a.wnorm + ((size_t)pg * 2 + 1) * MW);
+  const uint16_t* Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
+  const uint16_t* Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
+  const int row_beg = min(a.L, slot * a.rows_per_slot), row_end = min(a.L, row_beg + a.rows_per_slot);
+
+  // projection slice as B operand: column = feature 256 fh + 32 w + 16 mt + c, k = 32 ks + 8g + e
+  bf16x8 wk[2][KSW];
+  {
+    const uint16_t* Wg = a.Wbf + ((size_t)pg * 2 + 1) * MW * DW;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int ks = 0; ks < KSW; ++ks)
+        wk[mt][ks] = *(const bf16x8*)(Wg + (size_t)(256 * fh + 32 * w + 16 * mt + c) * DW + 32 * ks + 8 * g);
+  }
+  for (int idx = tid; idx < 2 * (TLD - DW - 1) * LDJ; idx += 512) {
+    const int bb = idx / ((TLD - DW - 1) * LDJ), rem = idx - bb * (TLD - DW - 1) * LDJ;
+    sm.vt[bb][DW + 1 + rem / LDJ][rem % LDJ] = 0;
+  }
+  f32x4 T[2][NVW];
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int vt = 0; vt < NVW; ++vt) T[mt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float dk = -INFINITY;
+
+  // staging: two row pieces (rows tid/16 and tid/16 + 32) and two value pieces (token tid%64, pieces tid/64 and + 8)
+  u32x4 kr[2], vr[2];
+  float rkr[2] = {0.f, 0.f};
+  auto load = [&](int row0) {
+    const int nv = max(0, min(TC, row_end - row0));
+    const __amdgpu_buffer_rsrc_t rk_ = chunk_rsrc(Kb + (long long)row0 * a.K.sl, 2 * (int)a.K.sl, nv, 2 * DW);
+    const __amdgpu_buffer_rsrc_t rv_ = chunk_rsrc(Vb + (long long)row0 * a.V.sl, 2 * (int)a.V.sl, nv, 2 * DW);
+    const __amdgpu_buffer_rsrc_t rr_ = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.rk + (size_t)bh * a.L + row0), 0,
+                                                                         isoC ? 0 : 4 * nv, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = (tid >> 4) + 32 * i;
+      kr[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, 2 * (row * (int)a.K.sl + (tid & 15) * 8), 0, 0);
+      rkr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr_, 4 * row, 0, 0));
+      vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, 2 * ((tid & 63) * (int)a.V.sl + ((tid >> 6) + 8 * i) * 8), 0, 0);
+    }
+  };
+  auto store = [&](int buf, int row0) {
+    const int nv = max(0, min(TC, row_end - row0));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = (tid >> 4) + 32 * i;
+      const float n2 = store_row_piece_w(kr[i], sm.k[buf], row, tid & 15);
+      const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * n2 : rkr[i];
+      sm.kadd[buf][row] = rt;
+      sm.kbnd[buf][row] = row < nv ? row_shift(n2, wmax) + rt : -INFINITY;
+      store_val_piece(vr[i], sm.vt[buf], tid & 63, (tid >> 6) + 8 * i);
+    }
+    if (tid < 32) {
+      const int t0 = 2 * tid;
+      *(uint32_t*)(&sm.vt[buf][DW][t0]) = (t0 < nv ? 0x3f80u : 0u) | (t0 + 1 < nv ? 0x3f80u << 16 : 0u);
+    }
+  };
+  load(row_beg);
+  store(0, row_beg);
+  __syncthreads();
+
+  int buf = 0;
+  for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
+    const bool more = row0 + TC < row_end;
+    if (more) load(row0 + TC);
+    {
+      const f32x4 b4 = *(const f32x4*)(&sm.kbnd[buf][4 * c]);
+      const float dnew = max16(fmaxf(fmaxf(b4[0], b4[1]), fmaxf(b4[2], b4[3])));
+      if (dnew > dk) {
+        const float f = fast_exp2(dk - dnew);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+          for (int vt = 0; vt < NVW; ++vt) T[mt][vt] *= f;
+        dk = dnew;
+      }
+    }
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+      bf16x8 st[2];
+      {
+        bf16x8 x[2][KSW];
+        f32x4 addv[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          const int jt = 2 * jp + jj;
+#pragma unroll
+          for (int ks = 0; ks < KSW; ++ks) x[jj][ks] = *(const bf16x8*)(&sm.k[buf][16 * jt + c][32 * ks + 8 * g]);
+          addv[jj] = *(const f32x4*)(&sm.kadd[buf][16 * jt + 4 * g]) - dk;
+        }
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          f32x4 acc[2];
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj) {
+            acc[jj] = mfma(x[jj][0], wk[mt][0], addv[jj]);
+#pragma unroll
+            for (int ks = 1; ks < KSW; ++ks) acc[jj] = mfma(x[jj][ks], wk[mt][ks], acc[jj]);
+          }
+          st[mt] = pack8(exp2v(acc[0]), exp2v(acc[1]));
+        }
+      }
+#pragma unroll
+      for (int vt = 0; vt < NVW; ++vt) {
+        const bf16x8 vop = load_vop_l(sm.vt[buf], jp, vt, lane);
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) T[mt][vt] = mfma(st[mt], vop, T[mt][vt]);
+      }
+    }
+    if (more) store(buf ^ 1, row0 + TC);
+    __syncthreads();
+  }
+  float* out = a.Tpart + (((size_t)bh * 2 + fh) * a.nslot + slot) * 256 * TLD;
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int vt = 0; vt < NVW; ++vt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) out[(size_t)(32 * w + 16 * mt + 4 * g + r) * TLD + 16 * vt + c] = T[mt][vt][r];
+  if (tid == 0 && fh == 0) a.cpart[(size_t)bh * a.nslot + slot] = dk;
+}
+
+// Exclusive prefix over the slots of one (b,h, feature half) on the common shift c* = max over the slots' shifts
+// (written to cstar).  Four consecutive numbers per thread.  grid (ceil(256*144/1024), B*H*2).
+__global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot) {
+  const int bh2 = blockIdx.y, bh = bh2 >> 1;
+  constexpr size_t per = (size_t)256 * TLD;
+  const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
+  float cs = -INFINITY;
+  for (int s = 0; s < nslot; ++s) cs = fmaxf(cs, cpart[(size_t)bh * nslot + s]);
+  if (e == 0 && (bh2 & 1) == 0) cstar[bh] = cs;
+  if (e >= per) return;
+  float* p = Tpart + (size_t)bh2 * nslot * per + e;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int s = 0; s < nslot; ++s) {
+    const f32x4 v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nslot + s] - cs);
+    *(f32x4*)(p + (size_t)s * per) = run;
+    run += v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// The causal walk of one slot for one (feature half, column half).  grid (nslot, B*H, 4), block 512: four producer
+// and four consumer waves; the consumer side is the one of the 64 / 256 kernels (fast_pc.h), the producer side has
+// projections of depth 128 and stages rows of 128 numbers.  LDS lifetimes as in kernels_bf16_bwd_pc.hip (walks).
+// ---------------------------------------------------------------------------------------------------
+struct SmemWWalk {
+  __attribute__((aligned(16))) uint16_t xoth[TC][LDRW];       // key rows
+  __attribute__((aligned(16))) uint16_t xown[TC][LDRW];       // query rows
+  __attribute__((aligned(16))) uint16_t uothT[DVP][LDJ];      // value columns of this half, transposed (+ ones row)
+  __attribute__((aligned(16))) float add_oth[TC];
+  __attribute__((aligned(16))) float add_own[TC];
+  __attribute__((aligned(16))) uint16_t feat[2][4][4][64][8];
+  __attribute__((aligned(16))) uint16_t xch[4][4][16][LDXB];
+};
+
+struct WCtx {
+  const uint16_t *Qb, *Kb, *Vb;
+  int bh, pg, fh, ch, row_beg, row_end, nchunk;
+  bool isoC;
+  float cs;
+};
+__device__ __forceinline__ int wrow(const WCtx& cx, int ci) { return cx.row_beg + min(ci, cx.nchunk) * TC; }
+__device__ __forceinline__ int wrows(const WCtx& cx, int ci) { return ci < cx.nchunk ? min(TC, cx.row_end - wrow(cx, ci)) : 0; }
+
+struct WStage { u32x4 xo[4], xw[4], v[2]; float rk[4]; };
+struct XOpW { bf16x8 b[KSW]; };
+
+__device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, const WCtx& cx, int j) {
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
+  const int b = cx.bh / a.H, h = cx.bh % a.H;
+  const float wmaxq = max512(a.wnorm + ((size_t)cx.pg * 2) * MW), amax = max512(a.bias + ((size_t)cx.pg * 2) * MW);
+  const int f0 = 256 * cx.fh + 64 * j;
+
+  // both projection slices as A operands: row = feature f0 + 16 mt + c, k = 32 ks + 8g + e
+  bf16x8 wq[4][KSW], wk[4][KSW];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int ks = 0; ks < KSW; ++ks) {
+      wq[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
+      wk[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2 + 1) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
+    }
+  f32x4 qb[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) qb[mt][r] = 2.f * (a.bias[((size_t)cx.pg * 2) * MW + f0 + 16 * mt + 4 * g + r] - amax);
+
+  WStage stg;
+  auto load_x = [&](u32x4 (&p)[4], const uint16_t* base, long long sl, int ci, bool with_rk) {
+    const int r0 = wrow(cx, ci), nv = wrows(cx, ci);
+    const __amdgpu_buffer_rsrc_t rs = chunk_rsrc(base + (long long)r0 * sl, 2 * (int)sl, nv, 2 * DW);
+    const __amdgpu_buffer_rsrc_t rr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.rk + (size_t)cx.bh * a.L + r0), 0,
+                                                                        (with_rk && !cx.isoC) ? 4 * nv : 0, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = (tid >> 4) + 16 * i;
+      p[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, 2 * (row * (int)sl + (tid & 15) * 8), 0, 0);
+      if (with_rk) stg.rk[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, 4 * row, 0, 0));
+    }
+  };
+  auto store_x = [&](const u32x4 (&p)[4], bool key_side, uint16_t (*tile)[LDRW], float* add, int nv) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = (tid >> 4) + 16 * i;
+      const float n2 = store_row_piece_w(p[i], tile, row, tid & 15);
+      float t;
+      if (key_side) t = (cx.isoC ? -0.5f * kLog2e * a.scale * a.scale * n2 : stg.rk[i]) - cx.cs;
+      else t = -row_shift(n2, wmaxq);
+      add[row] = row < nv ? t : -INFINITY;
+    }
+  };
+  auto load_v = [&](int ci) {
+    const int r0 = wrow(cx, ci), nv = wrows(cx, ci);
+    const __amdgpu_buffer_rsrc_t rv = chunk_rsrc(cx.Vb + (long long)r0 * a.V.sl, 2 * (int)a.V.sl, nv, 2 * DW);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      stg.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, 2 * ((tid & 63) * (int)a.V.sl + 64 * cx.ch + ((tid >> 6) + 4 * i) * 8), 0, 0);
+  };
+  auto store_v = [&](int nv) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) store_val_piece(stg.v[i], sm.uothT, tid & 63, (tid >> 6) + 4 * i);
+    if (tid < 32) {
+      const int t0 = 2 * tid;
+      const uint32_t one = cx.ch == 0 ? 0x3f80u : 0u;          // the ones row belongs to the first column half
+      *(uint32_t*)(&sm.uothT[D][t0]) = (t0 < nv ? one : 0u) | (t0 + 1 < nv ? one << 16 : 0u);
+    }
+  };
+  auto load_xop = [&](XOpW& x, const uint16_t (*tile)[LDRW], int jt) {
+#pragma unroll
+    for (int ks = 0; ks < KSW; ++ks) x.b[ks] = *(const bf16x8*)(&tile[16 * jt + c][32 * ks + 8 * g]);
+  };
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) stg.rk[i] = 0.f;
+  load_x(stg.xo, cx.Kb, a.K.sl, 0, true);
+  load_v(0);
+  store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, 0));
+  store_v(wrows(cx, 0));
+  load_x(stg.xo, cx.Kb, a.K.sl, 1, true);
+  load_v(1);
+  load_x(stg.xw, cx.Qb, a.Q.sl, 0, false);
+  __syncthreads();                 // barrier 0
+
+  // partial rows of token tile j of a finished chunk: unnormalised sums over this workgroup's 256 features
+  auto finish = [&](int ci_done) {
+    f32x4 fsum[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fsum[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    finish_tiles(fsum, sm, j, 0, lane);
+    finish_tiles(fsum, sm, j, 2, lane);
+    const int r0 = wrow(cx, ci_done), nv = wrows(cx, ci_done);
+    float* yp = a.Ypart + (((size_t)cx.fh * a.B * a.H + cx.bh) * a.L + r0) * YLD;
+    const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(yp, 4 * YLD, nv, 4 * YLD);
+    const int off = 4 * ((16 * j + c) * YLD + 64 * cx.ch + 4 * g);
+#pragma unroll
+    for (int vt = 0; vt < 4; ++vt) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fsum[vt]), ry, off + 64 * vt, 0, 0);
+    if (cx.ch == 0) {
+      const float den = finish_col64(sm, j, lane);
+      if (g == 0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, den), ry, 4 * ((16 * j + c) * YLD + DW), 0, 0);
+    }
+  };
+
+  for (int ci = 0; ci < cx.nchunk; ++ci) {
+    const int nv = wrows(cx, ci);
+#pragma unroll
+    for (int S = 0; S < 4; ++S) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        XOpW x;
+        load_xop(x, S < 2 ? sm.xoth : sm.xown, 2 * (S & 1) + u);
+        const float add = S < 2 ? sm.add_oth[16 * (2 * S + u) + c] : sm.add_own[16 * (2 * (S - 2) + u) + c];
+        const f32x4 add4 = {add, add, add, add};
+        f32x4 acc[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          acc[mt] = mfma(S < 2 ? wk[mt][0] : wq[mt][0], x.b[0], S < 2 ? add4 : qb[mt]);
+#pragma unroll
+          for (int ks = 1; ks < KSW; ++ks) acc[mt] = mfma(S < 2 ? wk[mt][ks] : wq[mt][ks], x.b[ks], acc[mt]);
+        }
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+          const bf16x8 img = S < 2 ? pack8(exp2v(acc[2 * blk]), exp2v(acc[2 * blk + 1]))
+                                   : pack8(exp2v(acc[2 * blk] + add), exp2v(acc[2 * blk + 1] + add));
+          *(bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]) = img;
+        }
+      }
+
+      if (S == 0) {
+        store_x(stg.xw, false, sm.xown, sm.add_own, nv);
+        load_x(stg.xw, cx.Qb, a.Q.sl, ci + 1, false);
+      } else if (S == 1) {
+        if (ci > 0) finish(ci - 1);
+      } else if (S == 2) {
+        store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, ci + 1));
+        load_x(stg.xo, cx.Kb, a.K.sl, ci + 2, true);
+      } else {
+        store_v(wrows(cx, ci + 1));
+        load_v(ci + 2);
+      }
+      __syncthreads();
+    }
+  }
+  __syncthreads();                 // the consumers' last step
+  if (cx.nchunk > 0) finish(cx.nchunk - 1);
+}
+
+__global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemWWalk& sm = *reinterpret_cast<SmemWWalk*>(smem_raw);
+  const int slot = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW);
+  WCtx cx;
+  cx.isoC = ((int)th[2]) & 1;
+  cx.bh = bh;
+  cx.fh = blockIdx.z >> 1;
+  cx.ch = blockIdx.z & 1;
+  cx.pg = group_of(a.pgroups, b, h, a.H);
+  cx.cs = a.cstar[bh];
+  cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
+  cx.Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
+  cx.Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
+  cx.row_beg = min(a.L, slot * a.rows_per_slot);
+  cx.row_end = min(a.L, cx.row_beg + a.rows_per_slot);
+  cx.nchunk = (cx.row_end - cx.row_beg + TC - 1) / TC;
+  for (int idx = threadIdx.x; idx < DVP * LDJ / 2; idx += NT8) ((uint32_t*)&sm.uothT[0][0])[idx] = 0u;
+  __syncthreads();
+  const int w = threadIdx.x >> 6;
+  if (w < 4) {
+    wide_producer(a, sm, cx, w);
+  } else {
+    const int j = w - 4, lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+    // state slice: 64 features of this half x the 80 columns of this column half (tile 4 = the normaliser column
+    // for the first half, nothing for the second)
+    f32x4 T[4][NVT];
+    const float* Tg = a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + slot) * 256 * TLD;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int col = vt < 4 ? 64 * cx.ch + 16 * vt + c : DW + c;
+          const float v = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * TLD + col];
+          T[mt][vt][r] = (vt < 4 || cx.ch == 0) ? v : 0.f;
+        }
+    walk_consume<0>(sm, T, cx.nchunk, j);
+  }
+}
+
+// Y = (part_0 + part_1) / (normaliser_0 + normaliser_1).  One thread per four columns.  grid (ceil(L/8), B*H), block 256.
+__global__ void k_wide_finish(WideArgs a) {
+  const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int token = blockIdx.x * 8 + (threadIdx.x >> 5), q = threadIdx.x & 31;
+  if (token >= a.L) return;
+  const size_t half = (size_t)a.B * a.H * a.L * YLD;
+  const float* p0 = a.Ypart + ((size_t)bh * a.L + token) * YLD;
+  const f32x4 v = *(const f32x4*)(p0 + 4 * q) + *(const f32x4*)(p0 + half + 4 * q);
+  const float den = p0[DW] + p0[half + DW];
+  const float inv = den > 0.f ? 1.f / den : 0.f;
+  const f32x4 y = v * inv;
+  if (a.Y.dtype == 1) {
+    uint16_t* yp = (uint16_t*)a.Y.ptr + b * a.Y.sb + h * a.Y.sh + (long long)token * a.Y.sl + 4 * q;
+    *(bf16x4*)yp = __builtin_convertvector(y, bf16x4);
+  } else {
+    float* yp = (float*)a.Y.ptr + b * a.Y.sb + h * a.Y.sh + (long long)token * a.Y.sl + 4 * q;
+    *(f32x4*)yp = y;
+  }
+}
+
+}  // namespace wide
+
+using namespace wide;
+
+bool wide_supported(int dtype, int d, int dv, int M_, int causal) { return dtype == 1 && d == DW && dv == DW && M_ == MW && causal == 1; }
+
+size_t wide_lds_bytes() { return std::max(sizeof(SmemWState), sizeof(SmemWWalk)); }
+
+void wide_plan(int BH, int L, int* nslot, int* rows_per_slot) {
+  // four workgroups per (sequence, slot) in the walk: about 512 of them in all, whole chunks each
+  const int want = std::max(1, std::min((128 + BH - 1) / BH, (L + TC - 1) / TC));
+  *rows_per_slot = (((L + want - 1) / want) + TC - 1) / TC * TC;
+  *nslot = (L + *rows_per_slot - 1) / *rows_per_slot;
+}
+
+#define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
+
+int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
+  WideArgs a;
+  a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
+  a.theta = f.theta; a.Omega = f.Omega;
+  a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.rk = f.rk; a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
+  a.Ypart = f.Ypart;
+  a.groups = f.groups; a.omega_groups = f.omega_groups; a.pgroups = f.pgroups; a.B = f.B; a.H = f.H; a.L = f.L;
+  a.nslot = f.nslot; a.rows_per_slot = f.rows_per_slot; a.scale = f.scale;
+  const int BH = f.B * f.H;
+  if (hipFuncSetAttribute((const void*)k_wide_state, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWState)) != hipSuccess ||
+      hipFuncSetAttribute((const void*)k_wide_walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWWalk)) != hipSuccess) {
+    (void)hipGetLastError();
+    return 2;
+  }
+  const int rowblocks = std::min(64, (f.L + 3) / 4);
+  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * f.pgroups + rowblocks * BH), dim3(256), 0, st, a, rowblocks);
+  FS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
+  FS_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot);
+  FS_LAUNCH_CHECK();
+  if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
+  hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 4), dim3(NT8), sizeof(SmemWWalk), st, a);
+  FS_LAUNCH_CHECK();
+  if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;
+  hipLaunchKernelGGL(k_wide_finish, dim3((f.L + 7) / 8, BH), dim3(256), 0, st, a);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+}  // namespace fs

@@ -376,6 +376,38 @@ def test_bf16_path_lengths_and_variants(fs, causal, L, variant):
     print(f"bf16 path causal={causal} L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
 
 
+# ----------------------------------------------------------------------------- bf16 MFMA path (d = 128, M = 512)
+@pytest.mark.parametrize("variant,L", [("posrf", 1), ("sderf", 64), ("sderf", 100), ("sderf", 1000), ("aderf", 200),
+                                       ("aderf", 1000)])
+def test_bf16_wide_path_lengths_and_variants(fs, L, variant):
+    """The long-context shape (causal, d = dv = 128, M = 512: two feature halves x two column halves per call) on
+    single-token, chunk-exact, ragged and multi-slot lengths; ADERF (fitted on more than d rows, so that its
+    statistics are nonsingular) exercises the dense key-side quadratic form."""
+    w = synth.make("c5", B=1, H=2, L=L, seed=177 + L)
+    worst = _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], True, variant, "bf16", chunk=64)
+    print(f"bf16 wide path L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
+def test_bf16_wide_path_f32_output_and_strided_inputs(fs):
+    import torch
+    w = synth.make("c5", B=2, H=2, L=320)
+    Q, K, V, Om, s, d = w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], w["d"]
+    qkv = torch.empty((2, 320, 2, 3, d), dtype=torch.bfloat16, device="cuda")          # packed [B, L, H, 3, d]
+    for i, a in enumerate((Q, K, V)):
+        qkv[:, :, :, i] = util.to_device(a, "bf16").permute(0, 2, 1, 3)
+    Qd, Kd, Vd = (qkv[:, :, :, i].permute(0, 2, 1, 3) for i in range(3))
+    theta = fs.fit_params("sderf", Qd, Kd, s, groups=2)
+    th_host = util.to_host(theta).astype(np.float32)
+    Y = fs.attention(theta, Qd, Kd, Vd, s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32)
+    assert Y.dtype == torch.float32
+    Yh = util.to_host(Y)
+    for b in range(2):
+        for h in range(2):
+            ref = orc.attention(util.oracle_theta_from_vec(th_host[h], d), Om[h], Q[b, h], K[b, h], V[b, h], s, True)
+            fro, row = util.attention_errors(Yh[b, h], ref, V[b, h].astype(np.float64))
+            assert fro <= 2e-2 and row <= 8e-2, (b, h, fro, row)
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_attention_with_block_orthogonal_omega(fs, causal):
     """Orthogonal random features only change omega: the library's host-side generator and the oracle's build the same
@@ -453,7 +485,7 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name):
     assert torch.isfinite(Y.float()).all().item()
 
 
-@pytest.mark.parametrize("name", ["c3", "c4"])
+@pytest.mark.parametrize("name", ["c3", "c4", "c5"])
 def test_bf16_path_is_bitwise_reproducible(fs, name):
     """The kernels use no atomics and every LDS region is ordered by workgroup barriers, so two runs on the same
     inputs must agree bit for bit; a race in the producer / consumer hand-over or in the cross-workgroup scan would
