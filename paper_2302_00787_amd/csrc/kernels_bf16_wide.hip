@@ -329,15 +329,18 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
   const float wmaxq = max512(a.wnorm + ((size_t)cx.pg * 2) * MW), amax = max512(a.bias + ((size_t)cx.pg * 2) * MW);
   const int f0 = 256 * cx.fh + 64 * j;
 
-  // both projection slices as A operands: row = feature f0 + 16 mt + c, k = 32 ks + 8g + e
-  bf16x8 wq[4][KSW], wk[4][KSW];
+  // projection slice of the side in work as A operands: row = feature f0 + 16 mt + c, k = 32 ks + 8g + e.  One set
+  // of registers: the key side's slice for steps 0 and 1, the query side's for steps 2 and 3, each reloaded (from L2)
+  // right after the other's last use, a step and a barrier before its first.
+  bf16x8 wx[4][KSW];
+  auto load_w = [&](int side) {
 #pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int ks = 0; ks < KSW; ++ks) {
-      wq[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
-      wk[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2 + 1) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
-    }
+      for (int ks = 0; ks < KSW; ++ks)
+        wx[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2 + side) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
+  };
+  load_w(1);
   f32x4 qb[4];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -423,18 +426,20 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
     const int nv = wrows(cx, ci);
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
+      XOpW xs[2];                  // both tiles of the step are requested before the first is used
+#pragma unroll
+      for (int u = 0; u < 2; ++u) load_xop(xs[u], S < 2 ? sm.xoth : sm.xown, 2 * (S & 1) + u);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
-        XOpW x;
-        load_xop(x, S < 2 ? sm.xoth : sm.xown, 2 * (S & 1) + u);
+        const XOpW& x = xs[u];
         const float add = S < 2 ? sm.add_oth[16 * (2 * S + u) + c] : sm.add_own[16 * (2 * (S - 2) + u) + c];
         const f32x4 add4 = {add, add, add, add};
         f32x4 acc[4];
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
-          acc[mt] = mfma(S < 2 ? wk[mt][0] : wq[mt][0], x.b[0], S < 2 ? add4 : qb[mt]);
+          acc[mt] = mfma(wx[mt][0], x.b[0], S < 2 ? add4 : qb[mt]);
 #pragma unroll
-          for (int ks = 1; ks < KSW; ++ks) acc[mt] = mfma(S < 2 ? wk[mt][ks] : wq[mt][ks], x.b[ks], acc[mt]);
+          for (int ks = 1; ks < KSW; ++ks) acc[mt] = mfma(wx[mt][ks], x.b[ks], acc[mt]);
         }
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
@@ -443,6 +448,8 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
           *(bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]) = img;
         }
       }
+      if (S == 1) load_w(0);
+      if (S == 3) load_w(1);
 
       if (S == 0) {
         store_x(stg.xw, false, sm.xown, sm.add_own, nv);
