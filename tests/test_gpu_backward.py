@@ -212,6 +212,58 @@ def test_backward_bf16_path_single_token(fs, causal):
         assert np.linalg.norm(gV[0, h] - dY[0, h]) <= 2e-2 * np.linalg.norm(dY[0, h])
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_bf16_path_strided_inputs_and_shared_parameters(fs, causal):
+    """Q, K, V packed as [B, L, H, 3, d] and dY as [B, L, H, d] (row strides 3 H d and H d), one parameter set and
+    one omega for all heads, two batches: strides, batch offsets and parameter groups on the bf16 kernels."""
+    import torch
+    w = synth.make("c4", B=2, H=2, L=448, seed=83)
+    Q, K, V, s, d = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"]
+    Om = w["Omega"][:1]
+    rng = np.random.default_rng(84)
+    dY = synth.round_to_bf16(rng.standard_normal(V.shape).astype(np.float32))
+    X = np.concatenate([s * Q[b, h] for b in range(2) for h in range(2)]).astype(np.float64)
+    Yk = np.concatenate([s * K[b, h] for b in range(2) for h in range(2)]).astype(np.float64)
+    vec = util.theta_vec_from_oracle(orc.fit_sderf(X, Yk))
+    th = util.oracle_theta_from_vec(vec, d)
+    qkv = torch.empty((2, 448, 2, 3, d), dtype=torch.bfloat16, device="cuda")
+    for i, a in enumerate((Q, K, V)):
+        qkv[:, :, :, i] = util.to_device(a, "bf16").permute(0, 2, 1, 3)
+    Qd, Kd, Vd = (qkv[:, :, :, i].permute(0, 2, 1, 3) for i in range(3))
+    dYd = util.to_device(dY, "bf16").permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+    gQ, gK, gV = fs.attention_backward(torch.from_numpy(vec[None]).cuda(), Qd, Kd, Vd, dYd, s, torch.from_numpy(Om).cuda(),
+                                       causal=causal, grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    gQ, gK, gV = util.to_host(gQ), util.to_host(gK), util.to_host(gV)
+    for b in range(2):
+        for h in range(2):
+            rq, rk, rv = orc.attention_backward(th, Om[0], Q[b, h], K[b, h], V[b, h], dY[b, h], s, causal)
+            errs = tuple(float(np.linalg.norm(g - r) / np.linalg.norm(r)) for g, r in ((gQ[b, h], rq), (gK[b, h], rk), (gV[b, h], rv)))
+            assert max(errs) <= 2e-2, (b, h, errs)
+
+
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_backward_bf16_path_is_bitwise_reproducible(fs, name):
+    """No atomics, every LDS region ordered by workgroup barriers: repeated calls at the benchmark's full size must
+    agree bit for bit; a race in a producer / consumer hand-over or between the walks of a call would show up here."""
+    import torch
+    w = synth.make(name)
+    s, causal = w["qk_scale"], bool(w["causal"])
+    Qd, Kd, Vd = (util.to_device(w[k], "bf16") for k in ("Q", "K", "V"))
+    rng = np.random.default_rng(85)
+    dYd = util.to_device(synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32)), "bf16")
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    theta = fs.fit_params("sderf", Qd, Kd, s, groups=w["H"])
+    first = [g.clone() for g in fs.attention_backward(theta, Qd, Kd, Vd, dYd, s, Om, causal=causal)]
+    for rep in range(4):
+        scratch = torch.randn(1 << 22, device="cuda").sum().item()      # unrelated work in between
+        again = fs.attention_backward(theta, Qd, Kd, Vd, dYd, s, Om, causal=causal)
+        torch.cuda.synchronize()
+        for a, b in zip(first, again):
+            assert torch.equal(a, b), (name, rep)
+    assert all(torch.isfinite(g.float()).all().item() for g in first)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
