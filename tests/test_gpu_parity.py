@@ -485,6 +485,46 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name):
     assert torch.isfinite(Y.float()).all().item()
 
 
+@pytest.mark.parametrize("name,over", [("c1", {}), ("c4", dict(B=1, H=2, L=1216)), ("c5", dict(B=1, H=2, L=832))])
+def test_attention_call_replays_from_a_hip_graph(fs, name, over):
+    """The entry point only enqueues kernels on the caller's stream (no synchronisation, no allocation, no memset
+    nodes), so a caller may capture it: the graph is replayed three times, with eager work and synchronisations in
+    between, and every replay must reproduce the eager result bit for bit (general path, both bf16 paths)."""
+    import torch
+    w = synth.make(name, **over)
+    dt = w.get("dtype", "f32")
+    Q, K, V = (util.to_device(w[k], dt) for k in "QKV")
+    Om, s, causal = torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"], bool(w["causal"])
+    theta = fs.fit_params("sderf", Q, K, s, groups=w["H"])
+    B, H, L, d = Q.shape
+    ws = torch.empty(fs.attention_workspace_bytes(B, H, L, L, d, V.shape[-1], Om.shape[-2], causal, H, H), dtype=torch.uint8,
+                     device="cuda")
+    Y = torch.empty_like(V)
+
+    def call():
+        fs.attention(theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0), out=Y, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    ref = Y.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):           # warm-up on a side stream, as graph capture asks for
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        Y.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y, ref), (name, rep)
+        _ = torch.randn(1 << 20, device="cuda").sum().item()
+
+
 @pytest.mark.parametrize("name", ["c3", "c4", "c5"])
 def test_bf16_path_is_bitwise_reproducible(fs, name):
     """The kernels use no atomics and every LDS region is ordered by workgroup barriers, so two runs on the same
