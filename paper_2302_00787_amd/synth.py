@@ -111,3 +111,24 @@ def make(name: str, **override) -> dict:
         Q, K, V = round_to_bf16(Q), round_to_bf16(K), round_to_bf16(V)
     out.update(Q=Q, K=K, V=V, Omega=Omega)
     return out
+
+
+def clusters(seed: int = 6000, classes: int = 6, d: int = 32, n_train: int = 4096, n_test: int = 1024,
+             spread: float = 0.55) -> dict:
+    """Labelled points for the kernel-classification demo: `classes` Gaussian clusters in d dimensions with centres
+    drawn on the unit sphere, two clusters per class (so classes are not linearly separable), isotropic noise
+    `spread` / sqrt(d) per coordinate.  Returns float32 points, integer labels and one-hot label rows."""
+    rng = np.random.default_rng(seed)
+    centres = rng.standard_normal((2 * classes, d))
+    centres /= np.linalg.norm(centres, axis=1, keepdims=True)
+
+    def draw(n):
+        which = rng.integers(0, 2 * classes, n)
+        pts = centres[which] + spread / np.sqrt(d) * rng.standard_normal((n, d))
+        return pts.astype(np.float32), (which % classes).astype(np.int64)
+
+    Xtr, ytr = draw(n_train)
+    Xte, yte = draw(n_test)
+    onehot = np.zeros((n_train, classes), dtype=np.float32)
+    onehot[np.arange(n_train), ytr] = 1.0
+    return dict(train=Xtr, train_labels=ytr, train_onehot=onehot, test=Xte, test_labels=yte, classes=classes, d=d)
