@@ -408,6 +408,29 @@ def test_bf16_wide_path_f32_output_and_strided_inputs(fs):
             assert fro <= 2e-2 and row <= 8e-2, (b, h, fro, row)
 
 
+def test_bf16_wide_path_shared_parameters_and_extreme_scales(fs):
+    """One parameter set and one omega for all heads (groups = 1), key rows 20x larger than the rest late in the
+    sequence and query rows 3x larger: shifts that are bounds over all 512 features keep the four partial walks on
+    one scale and everything finite."""
+    import torch
+    w = synth.make("c5", B=1, H=2, L=576, seed=311)
+    Q, K, V, s, d = w["Q"].copy(), w["K"].copy(), w["V"], w["qk_scale"], w["d"]
+    K[0, 1, 400:404] *= 20.0
+    Q[0, 0, 100:102] *= 3.0
+    Q, K = synth.round_to_bf16(Q), synth.round_to_bf16(K)
+    Om = w["Omega"][:1]
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    th = util.oracle_theta_from_vec(vec, d)
+    Y = fs.attention(torch.from_numpy(vec[None]).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32)
+    Yh = util.to_host(Y)
+    assert np.isfinite(Yh).all()
+    for h in range(2):
+        ref = orc.attention(th, Om[0], Q[0, h], K[0, h], V[0, h], s, True)
+        fro, row = util.attention_errors(Yh[0, h], ref, V[0, h].astype(np.float64))
+        assert fro <= 2e-2 and row <= 8e-2, (h, fro, row)
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_attention_with_block_orthogonal_omega(fs, causal):
     """Orthogonal random features only change omega: the library's host-side generator and the oracle's build the same
