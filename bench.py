@@ -133,13 +133,30 @@ def bench_matvec(args, cfg, fs, synth, util, torch):
     assert torch.isfinite(out).all().item()
     flops = N * (2 * 2 * d * M + 2 * 2 * M * n)          # two projections, state update and state read
     tf = flops / (ms * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle on the whole operator (fit + both feature maps + the two products), fp64 numpy
+        from oracle import favorsharp_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        w = synth.make(args.workload, seed=cfg["seed"])
+        t1 = time.perf_counter()
+        Xs = w["qk_scale"] * w["X"].astype(np.float64)
+        orc.kernel_matvec(orc.fit_sderf(Xs, Xs), w["Omega"][0], Xs, Xs, w["C"].astype(np.float64), alpha)
+        dtc = time.perf_counter() - t1
+        cpu = dict(value=N / dtc, unit="points/s", cores=int(cores), kind="oracle",
+                   sample=f"the whole workload once (fit + operator, fp64 numpy), {dtc:.2f} s")
     print(json.dumps({
         "metric": "FAVOR# kernel operator points/s (c2: N=16384 d=32 M=512 n=8, alpha=-1/2)", "value": N / (ms * 1e-3),
         "unit": "points/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": "c2: kernel operator, fp32, X = Y, SDERF, theta and omega resident"},
         "roofline": {"bound": "mfma", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
-                     "traffic": None}}), flush=True)
+                     "traffic": None},
+        "cpu_baseline": cpu}), flush=True)
 
 
 def bench_backward(args, fs, synth, util, torch):
