@@ -62,6 +62,30 @@ __device__ void load_wblock(float* Ws, float* bias_s, int ld, const float* W, co
   if (threadIdx.x < MB) bias_s[threadIdx.x] = (m0 + threadIdx.x < M) ? bias[m0 + threadIdx.x] : 0.f;
 }
 
+// The same block travelling global -> registers -> LDS, so that the load of the next block is in flight while the
+// current one is used: thread t carries row f = t/8 of the block, columns t%8 + 8i (dpad <= 128: at most 16).
+struct WRegs { float w[16]; float b; };
+__device__ __forceinline__ void wblock_fetch(WRegs& r, const float* W, const float* bias, int m0, int M, int d, int dpad) {
+  const int f = threadIdx.x >> 3, c0 = threadIdx.x & 7;
+  const float* row = W + (long long)(m0 + f) * d;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = c0 + 8 * i;
+    r.w[i] = 0.f;
+    if (8 * i < dpad && m0 + f < M && c < d) r.w[i] = row[c];
+  }
+  r.b = (threadIdx.x < MB && m0 + threadIdx.x < M) ? bias[m0 + threadIdx.x] : 0.f;
+}
+__device__ __forceinline__ void wblock_put(const WRegs& r, float* Ws, float* bias_s, int ld, int dpad) {
+  const int f = threadIdx.x >> 3, c0 = threadIdx.x & 7;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = c0 + 8 * i;
+    if (8 * i < dpad && c < dpad) Ws[f * ld + c] = r.w[i];
+  }
+  if (threadIdx.x < MB) bias_s[threadIdx.x] = r.b;
+}
+
 // rterm[r] = log2e * (x_r^T C x_r + alpha |x_r|^2); Cmat == nullptr means C = -I/2.
 __device__ void row_terms(float* rterm, const float* Xs, int ld, int d, const float* Cmat, float alpha) {
   const int r = threadIdx.x >> 3, part = threadIdx.x & 7;
@@ -112,10 +136,13 @@ __device__ void rowmax_pass(uint32_t* rowmax_u, const float* Xs, float* Ws, floa
                             const float* bias, int M, int d, int dpad) {
   if (threadIdx.x < TR) rowmax_u[threadIdx.x] = 0u;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  WRegs wr;
+  wblock_fetch(wr, W, bias, 0, M, d, dpad);
   for (int m0 = 0; m0 < M; m0 += MB) {
     __syncthreads();
-    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
+    wblock_put(wr, Ws, bias_s, ld, dpad);
     __syncthreads();
+    if (m0 + MB < M) wblock_fetch(wr, W, bias, m0 + MB, M, d, dpad);
     const f32x4 acc = proj_tile(Xs, Ws, ld, dpad);
     const int f = (w & 1) * 16 + (lane & 15);
     float e[4];
@@ -399,14 +426,35 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
   f32x4 acc[ACC_PER_WAVE];
 #pragma unroll
   for (int t = 0; t < ACC_PER_WAVE; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // the projection block and the state block of the next step are fetched while the current step computes: thread
+  // t carries row t/8 of the state block, columns t%8 + 8i (ldt <= 144: at most 18)
+  WRegs wr;
+  float tr[18];
+  auto fetch_t = [&](int m0) {
+    const int f = threadIdx.x >> 3, c0 = threadIdx.x & 7;
+    const float* row = Tb + (size_t)(m0 + f) * ldt;
+#pragma unroll
+    for (int i = 0; i < 18; ++i) {
+      tr[i] = 0.f;
+      if (8 * i < ldt && m0 + f < M) tr[i] = row[c0 + 8 * i];
+    }
+  };
+  wblock_fetch(wr, W, bias, 0, M, d, dpad);
+  fetch_t(0);
   for (int m0 = 0; m0 < M; m0 += MB) {
     __syncthreads();
-    load_wblock(Ws, bias_s, ld, W, bias, m0, M, d, dpad);
-    for (int idx = threadIdx.x; idx < MB * ldt; idx += NT) {
-      const int f = idx / ldt, c = idx - f * ldt;
-      Ts[f * ldts + c] = (m0 + f < M) ? Tb[(size_t)(m0 + f) * ldt + c] : 0.f;
+    wblock_put(wr, Ws, bias_s, ld, dpad);
+    {
+      const int f = threadIdx.x >> 3, c0 = threadIdx.x & 7;
+#pragma unroll
+      for (int i = 0; i < 18; ++i)
+        if (8 * i < ldt) Ts[f * ldts + c0 + 8 * i] = tr[i];
     }
     __syncthreads();
+    if (m0 + MB < M) {
+      wblock_fetch(wr, W, bias, m0 + MB, M, d, dpad);
+      fetch_t(m0 + MB);
+    }
     const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
     const int f = (w & 1) * 16 + (lane & 15);
 #pragma unroll
