@@ -264,6 +264,31 @@ def test_backward_bf16_path_is_bitwise_reproducible(fs, name):
     assert all(torch.isfinite(g.float()).all().item() for g in first)
 
 
+@pytest.mark.parametrize("name", ["c3", "c4"])
+def test_backward_full_size_against_the_oracle_on_two_heads(fs, name):
+    """The bf16 workloads at their full size, in the launch configuration the benchmark times (c4: 32 sequences of
+    16384 tokens, eight slots of 32 chunks each); the oracle evaluates two whole (b, h) sequences (first and last)
+    and every gradient row of them is compared."""
+    import torch
+    w = synth.make(name)
+    B, H, L, d = w["B"], w["H"], w["L"], w["d"]
+    s, causal = w["qk_scale"], bool(w["causal"])
+    rng = np.random.default_rng(86)
+    dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+    Qd, Kd, Vd, dYd = (util.to_device(a, "bf16") for a in (w["Q"], w["K"], w["V"], dY))
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    theta = fs.fit_params("sderf", Qd, Kd, s, groups=H)
+    gQ, gK, gV = fs.attention_backward(theta, Qd, Kd, Vd, dYd, s, Om, causal=causal, grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    th_host = util.to_host(theta).astype(np.float32)
+    for b, h in [(0, 0), (B - 1, H - 1)]:
+        th = util.oracle_theta_from_vec(th_host[h], d)
+        rq, rk, rv = orc.attention_backward(th, w["Omega"][h], w["Q"][b, h], w["K"][b, h], w["V"][b, h], dY[b, h], s, causal)
+        errs = tuple(float(np.linalg.norm(util.to_host(g[b, h]) - r) / np.linalg.norm(r)) for g, r in ((gQ, rq), (gK, rk), (gV, rv)))
+        print(f"{name} backward full size (b={b}, h={h}): relative errors dQ {errs[0]:.2e}, dK {errs[1]:.2e}, dV {errs[2]:.2e}")
+        assert max(errs) <= 2e-2, (b, h, errs)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
