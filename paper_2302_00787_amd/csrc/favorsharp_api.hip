@@ -110,7 +110,7 @@ void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
   p->off_state = off;  off = align_up(off + (size_t)BH * 2 * p->nslot * 256 * 144 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nslot * sizeof(float));
   p->off_cstar = off;  off = align_up(off + (size_t)BH * sizeof(float));
-  p->off_ypart = off;  off = align_up(off + (size_t)2 * BH * L * 132 * sizeof(float));
+  p->off_ypart = off;  off = align_up(off + (size_t)BH * L * 132 * sizeof(float));
   p->total = off;
 }
 

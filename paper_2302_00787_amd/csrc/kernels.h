@@ -110,7 +110,7 @@ struct WideLaunch {
   float* Tpart;     // [B*H][2][nslot][256][144]
   float* cpart;     // [B*H][nslot]
   float* cstar;     // [B*H]
-  float* Ypart;     // [2][B*H][L][132]
+  float* Ypart;     // [B*H][L][132]
 };
 bool wide_supported(int dtype, int d, int dv, int M, int causal);
 size_t wide_lds_bytes();

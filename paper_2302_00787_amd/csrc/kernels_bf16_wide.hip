@@ -2,17 +2,18 @@
 //
 // The kernels for d = dv = 64, M = 256 keep 64 features x 80 state columns per wave in registers.  This shape is
 // four such problems: the sums over features that make up numerator and normaliser split into two halves of 256
-// features, and the value columns into [V_0..63, 1] and [V_64..127].  One launch runs the four (feature half,
-// column half) combinations side by side; every combination is the producer / consumer walk of the forward pass
-// (fast_pc.h) with projections of depth 128, and leaves UNNORMALISED partial rows in fp32; a last kernel adds the
-// two feature halves and divides by the normaliser.  All four share every shift (the per-row query shift and the
+// features, and the value columns into [V_0..63, 1] and [V_64..127, 1] (the normaliser column rides along in both:
+// the fifth value tile of a wave is there anyway).  Every (feature half, column half) combination is the producer /
+// consumer walk of the forward pass (fast_pc.h) with projections of depth 128.  Two launches: the first runs both
+// column halves of feature half 0 and leaves UNNORMALISED partial rows (fp32) and partial normalisers; the second
+// runs feature half 1, adds the first launch's partial rows to its own in the finishing step, divides by the sum
+// of the two partial normalisers and stores Y.  All combinations share every shift (the per-row query shift and the
 // per-sequence key shift are bounds over all 512 features), so their partial rows are on one scale.
 //
 //   k_wide_pre     projection constants for both sides (Section 4, evaluation recipe), key row terms for dense C2
 //   k_wide_state   per (slot, feature half): S^T [V 1] over the slot (eight waves of 32 features, all 129 columns)
 //   k_wide_reduce  exclusive prefix over the slots on the sequence's common shift
-//   k_wide_walk    per (slot, feature half, column half): the causal walk
-//   k_wide_finish  Y = (part_0 + part_1) / normaliser
+//   k_wide_walk    per (slot, column half), once per feature half: the causal walk; the second launch finishes Y
 #include <algorithm>
 
 #include "fast_pc.h"
@@ -31,7 +32,7 @@ constexpr int KSW = DW / 32;       // MFMA k-steps of a projection
 constexpr int LDRW = DW + 8;       // row stride (bf16) of a token tile in LDS: 68 dwords
 constexpr int NVW = 9;             // value tiles of the state kernel: 128 columns + the ones column + padding
 constexpr int TLD = NVW * 16;      // row stride (floats) of a state: 144; column 128 = normaliser
-constexpr int YLD = 132;           // row stride (floats) of a partial output row: 128 columns, normaliser at 128
+constexpr int YLD = 132;           // row stride (floats) of a partial output row: 128 columns, partial normaliser of column half ch at 128 + ch
 
 struct WideArgs {
   TensorDev Q, K, V, Y;
@@ -44,8 +45,9 @@ struct WideArgs {
   float* Tpart;      // [BH][2][nslot][256][144]
   float* cpart;      // [BH][nslot]
   float* cstar;      // [BH]
-  float* Ypart;      // [2][BH][L][132]
+  float* Ypart;      // [BH][L][132]: partial rows of feature half 0
   int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;
+  int fh;            // feature half of this launch of the walk
   float scale;
 };
 
@@ -297,7 +299,7 @@ __global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, in
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The causal walk of one slot for one (feature half, column half).  grid (nslot, B*H, 4), block 512: four producer
+// The causal walk of one slot for one column half and the launch's feature half.  grid (nslot, B*H, 2), block 512: four producer
 // and four consumer waves; the consumer side is the one of the 64 / 256 kernels (fast_pc.h), the producer side has
 // projections of depth 128 and stages rows of 128 numbers.  LDS lifetimes as in kernels_bf16_bwd_pc.hip (walks).
 // ---------------------------------------------------------------------------------------------------
@@ -383,7 +385,7 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
     for (int i = 0; i < 2; ++i) store_val_piece(stg.v[i], sm.uothT, tid & 63, (tid >> 6) + 4 * i);
     if (tid < 32) {
       const int t0 = 2 * tid;
-      const uint32_t one = cx.ch == 0 ? 0x3f80u : 0u;          // the ones row belongs to the first column half
+      const uint32_t one = 0x3f80u;                            // the ones row: both column halves carry the normaliser
       *(uint32_t*)(&sm.uothT[D][t0]) = (t0 < nv ? one : 0u) | (t0 + 1 < nv ? one << 16 : 0u);
     }
   };
@@ -403,22 +405,34 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
   load_x(stg.xw, cx.Qb, a.Q.sl, 0, false);
   __syncthreads();                 // barrier 0
 
-  // partial rows of token tile j of a finished chunk: unnormalised sums over this workgroup's 256 features
+  // rows of token tile j of a finished chunk.  Feature half 0: unnormalised sums over this workgroup's 256 features
+  // and their partial normaliser, to the partial buffer.  Feature half 1: the other half's partial rows are added,
+  // the row is divided by the sum of the two partial normalisers and stored.
   auto finish = [&](int ci_done) {
     f32x4 fsum[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) fsum[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     finish_tiles(fsum, sm, j, 0, lane);
     finish_tiles(fsum, sm, j, 2, lane);
+    float den = finish_col64(sm, j, lane);
     const int r0 = wrow(cx, ci_done), nv = wrows(cx, ci_done);
-    float* yp = a.Ypart + (((size_t)cx.fh * a.B * a.H + cx.bh) * a.L + r0) * YLD;
+    float* yp = a.Ypart + ((size_t)cx.bh * a.L + r0) * YLD;
     const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(yp, 4 * YLD, nv, 4 * YLD);
-    const int off = 4 * ((16 * j + c) * YLD + 64 * cx.ch + 4 * g);
+    const int off = 4 * ((16 * j + c) * YLD + 64 * cx.ch + 4 * g), doff = 4 * ((16 * j + c) * YLD + DW + cx.ch);
+    if (cx.fh == 0) {
 #pragma unroll
-    for (int vt = 0; vt < 4; ++vt) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fsum[vt]), ry, off + 64 * vt, 0, 0);
-    if (cx.ch == 0) {
-      const float den = finish_col64(sm, j, lane);
-      if (g == 0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, den), ry, 4 * ((16 * j + c) * YLD + DW), 0, 0);
+      for (int vt = 0; vt < 4; ++vt) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, fsum[vt]), ry, off + 64 * vt, 0, 0);
+      if (g == 0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, den), ry, doff, 0, 0);
+    } else {
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) fsum[vt] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ry, off + 64 * vt, 0, 0));
+      den += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, doff, 0, 0));
+      const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) fsum[vt] *= inv;
+      const int esz = a.Y.dtype == 1 ? 2 : 4;
+      const char* gp = (const char*)a.Y.ptr + (b * a.Y.sb + h * a.Y.sh + (long long)r0 * a.Y.sl + 64 * cx.ch) * esz;
+      finish_store(fsum, a.Y, gp, nv, j, lane);
     }
   };
 
@@ -478,8 +492,8 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   WCtx cx;
   cx.isoC = ((int)th[2]) & 1;
   cx.bh = bh;
-  cx.fh = blockIdx.z >> 1;
-  cx.ch = blockIdx.z & 1;
+  cx.fh = a.fh;
+  cx.ch = blockIdx.z;
   cx.pg = group_of(a.pgroups, b, h, a.H);
   cx.cs = a.cstar[bh];
   cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
@@ -495,8 +509,7 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
     wide_producer(a, sm, cx, w);
   } else {
     const int j = w - 4, lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
-    // state slice: 64 features of this half x the 80 columns of this column half (tile 4 = the normaliser column
-    // for the first half, nothing for the second)
+    // state slice: 64 features of this half x the 64 columns of this column half and the normaliser column (tile 4)
     f32x4 T[4][NVT];
     const float* Tg = a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + slot) * 256 * TLD;
 #pragma unroll
@@ -506,30 +519,9 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int col = vt < 4 ? 64 * cx.ch + 16 * vt + c : DW + c;
-          const float v = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * TLD + col];
-          T[mt][vt][r] = (vt < 4 || cx.ch == 0) ? v : 0.f;
+          T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * TLD + col];
         }
     walk_consume<0>(sm, T, cx.nchunk, j);
-  }
-}
-
-// Y = (part_0 + part_1) / (normaliser_0 + normaliser_1).  One thread per four columns.  grid (ceil(L/8), B*H), block 256.
-__global__ void k_wide_finish(WideArgs a) {
-  const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
-  const int token = blockIdx.x * 8 + (threadIdx.x >> 5), q = threadIdx.x & 31;
-  if (token >= a.L) return;
-  const size_t half = (size_t)a.B * a.H * a.L * YLD;
-  const float* p0 = a.Ypart + ((size_t)bh * a.L + token) * YLD;
-  const f32x4 v = *(const f32x4*)(p0 + 4 * q) + *(const f32x4*)(p0 + half + 4 * q);
-  const float den = p0[DW] + p0[half + DW];
-  const float inv = den > 0.f ? 1.f / den : 0.f;
-  const f32x4 y = v * inv;
-  if (a.Y.dtype == 1) {
-    uint16_t* yp = (uint16_t*)a.Y.ptr + b * a.Y.sb + h * a.Y.sh + (long long)token * a.Y.sl + 4 * q;
-    *(bf16x4*)yp = __builtin_convertvector(y, bf16x4);
-  } else {
-    float* yp = (float*)a.Y.ptr + b * a.Y.sb + h * a.Y.sh + (long long)token * a.Y.sl + 4 * q;
-    *(f32x4*)yp = y;
   }
 }
 
@@ -542,7 +534,7 @@ bool wide_supported(int dtype, int d, int dv, int M_, int causal) { return dtype
 size_t wide_lds_bytes() { return std::max(sizeof(SmemWState), sizeof(SmemWWalk)); }
 
 void wide_plan(int BH, int L, int* nslot, int* rows_per_slot) {
-  // four workgroups per (sequence, slot) in the walk: about 512 of them in all, whole chunks each
+  // two workgroups per (sequence, slot) and launch of the walk: about 256 of them, whole chunks each
   const int want = std::max(1, std::min((128 + BH - 1) / BH, (L + TC - 1) / TC));
   *rows_per_slot = (((L + want - 1) / want) + TC - 1) / TC * TC;
   *nslot = (L + *rows_per_slot - 1) / *rows_per_slot;
@@ -572,11 +564,12 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot);
   FS_LAUNCH_CHECK();
   if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
-  hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 4), dim3(NT8), sizeof(SmemWWalk), st, a);
-  FS_LAUNCH_CHECK();
+  for (int fh = 0; fh < 2; ++fh) {
+    a.fh = fh;
+    hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+    FS_LAUNCH_CHECK();
+  }
   if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;
-  hipLaunchKernelGGL(k_wide_finish, dim3((f.L + 7) / 8, BH), dim3(256), 0, st, a);
-  FS_LAUNCH_CHECK();
   return 0;
 }
 
