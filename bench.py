@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # script with --calibrate-copy, each counter scaled by what it reads for the 256 MiB copy (FETCH_SIZE x 2.0,
 # WRITE_SIZE x 1.0); figures and commands in profiles/c4_hbm_traffic.md.  The kernel reads Q, K, V and the prefix
 # states once and writes Y once, so the figure does not depend on how its instructions are scheduled.
-MEASURED_TRAFFIC_BYTES = {"c4": 291.9e6, "c3": 111.6e6, "c5": 3.04e9}     # c3, c5: profiles/c3_c5_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"c4": 291.9e6, "c3": 111.6e6, "c5": 3.31e9}     # c3, c5: profiles/c3_c5_hbm_traffic.md
 
 
 class HipEvents:
