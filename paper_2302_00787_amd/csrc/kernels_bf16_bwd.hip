@@ -349,7 +349,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
         const int q = threadIdx.x + NT * i, row = q >> 3, pc = q & 7;
         *(u32x4*)(&sm.lam[row][pc * 8]) = lr.p[i];
       }
-      if (threadIdx.x < TC) sm.lam[threadIdx.x][D] = row0 + threadIdx.x < row_end ? 0x3f80u : 0u;   // the ones column
+      if (threadIdx.x < TC) sm.lam[threadIdx.x][D] = row0 + (int)threadIdx.x < row_end ? 0x3f80u : 0u;   // the ones column
     } else {
 #pragma unroll
       for (int i = 0; i < 3; ++i) {
