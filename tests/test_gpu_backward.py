@@ -289,6 +289,33 @@ def test_backward_full_size_against_the_oracle_on_two_heads(fs, name):
         assert max(errs) <= 2e-2, (b, h, errs)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_forward_and_backward_bf16_path_one_parameter_set_per_sequence(fs, causal):
+    """groups = omega_groups = B*H: every (b, h) sequence has its own fitted parameters and its own omega."""
+    import torch
+    w = synth.make("c4", B=2, H=2, L=320, seed=87)
+    Q, K, V, s, d, M = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"], w["M"]
+    rng = np.random.default_rng(88)
+    dY = synth.round_to_bf16(rng.standard_normal(V.shape).astype(np.float32))
+    Om = rng.standard_normal((4, M, d)).astype(np.float32)
+    ths = [orc.fit_sderf(s * Q[b, h].astype(np.float64), s * K[b, h].astype(np.float64)) for b in range(2) for h in range(2)]
+    theta = torch.from_numpy(np.stack([util.theta_vec_from_oracle(t) for t in ths])).cuda()
+    Qd, Kd, Vd, dYd = (util.to_device(a, "bf16") for a in (Q, K, V, dY))
+    Y = util.to_host(fs.attention(theta, Qd, Kd, Vd, s, torch.from_numpy(Om).cuda(), causal=causal, out_dtype=torch.float32))
+    gQ, gK, gV = (util.to_host(g) for g in fs.attention_backward(theta, Qd, Kd, Vd, dYd, s, torch.from_numpy(Om).cuda(),
+                                                                  causal=causal, grad_dtype=torch.float32))
+    for b in range(2):
+        for h in range(2):
+            g = 2 * b + h
+            th = util.oracle_theta_from_vec(util.theta_vec_from_oracle(ths[g]), d)
+            ref = orc.attention(th, Om[g], Q[b, h], K[b, h], V[b, h], s, causal)
+            fro, row = util.attention_errors(Y[b, h], ref, V[b, h].astype(np.float64))
+            assert fro <= 2e-2 and row <= 8e-2, (b, h, fro, row)
+            rq, rk, rv = orc.attention_backward(th, Om[g], Q[b, h], K[b, h], V[b, h], dY[b, h], s, causal)
+            errs = tuple(float(np.linalg.norm(x - r) / np.linalg.norm(r)) for x, r in ((gQ[b, h], rq), (gK[b, h], rk), (gV[b, h], rv)))
+            assert max(errs) <= 2e-2, (b, h, errs)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
