@@ -117,11 +117,15 @@ def fit_gerf(X: np.ndarray, Y: np.ndarray) -> Theta:
 
 def fit_saderf(X: np.ndarray, Y: np.ndarray) -> Theta:
     """Simplified ADERF (Section 4.3): f1(w,x) = f_GE(w, Psi x), f2(w,y) = f_GE(w, Psi^-1 y)
-    with Psi_ll = (sum_j y_l^2 / sum_i x_l^2)^(1/4), then the GERF fit on the
-    rescaled sets."""
+    with Psi_ll = (mean_j y_l^2 / mean_i x_l^2)^(1/4), then the GERF fit on the
+    rescaled sets.  The objective of Section 4.3 is a mean over all pairs (i, j);
+    setting its derivative in Psi_ll to zero gives the ratio of the two per-set
+    MEANS.  The section prints the ratio of sums because it takes both sets to
+    have L elements; for sets of different sizes only the means form minimises
+    the pairwise-mean objective."""
     X = np.asarray(X, dtype=np.float64)
     Y = np.asarray(Y, dtype=np.float64)
-    psi = ((Y ** 2).sum(axis=0) / (X ** 2).sum(axis=0)) ** 0.25
+    psi = ((Y ** 2).mean(axis=0) / (X ** 2).mean(axis=0)) ** 0.25
     g = fit_gerf(X * psi, Y / psi)
     B = g.B1[0, 0]
     return Theta(A=g.A, B1=B * np.diag(psi), B2=B * np.diag(1.0 / psi),

@@ -174,6 +174,38 @@ def test_objective_ordering(kind):
     assert lb["aderf"] <= lb["saderf"] + 1e-12 <= lb["gerf"] + 2e-12
 
 
+def _saderf_from(psi, A, d):
+    B = np.sqrt(1 - 4 * A)
+    return orc.Theta(A=np.full(d, A), B1=B * np.diag(psi), B2=B * np.diag(1 / psi), C1=-0.5 * np.diag(psi ** 2),
+                     C2=-0.5 * np.diag(psi ** -2.0), logD=0.25 * d * np.log(1 - 4 * A))
+
+
+@pytest.mark.parametrize("Lx,Ly", [(40, 90), (75, 30)])
+def test_saderf_with_sets_of_different_sizes(Lx, Ly):
+    """Section 4.3 with |X| != |Y|: the objective is the mean over all pairs, so Psi is the ratio of per-set MEANS
+    (the printed ratio of sums assumes equal sizes).  Closed-form objective = brute force, no feasible Psi or A does
+    better, and the ratio-of-sums Psi is strictly worse."""
+    d = 6
+    rng = np.random.default_rng(21)
+    X = 0.5 * rng.standard_normal((Lx, d)) * np.linspace(0.3, 1.5, d) + 0.1
+    Y = 0.5 * rng.standard_normal((Ly, d)) * np.linspace(1.4, 0.4, d) - 0.05
+    th = orc.fit_saderf(X, Y)
+    base = orc.lbar_bruteforce(th, X, Y)
+    assert th.lbar == pytest.approx(base, abs=1e-10)
+    assert max(orc.validity_residuals(th)[k] for k in ("cross", "C1", "C2", "logD")) < 1e-12
+    psi = np.diag(th.B1) / np.sqrt(1 - 4 * th.A[0])
+    np.testing.assert_allclose(psi ** 4, (Y ** 2).mean(0) / (X ** 2).mean(0), rtol=1e-12)
+    for eps in (1e-3, 3e-2, 0.3):
+        for _ in range(20):
+            cand = _saderf_from(psi * np.exp(eps * rng.standard_normal(d)),
+                                min(th.A[0] + 0.2 * eps * rng.standard_normal(), 0.12), d)
+            assert orc.lbar_bruteforce(cand, X, Y) >= base - 1e-11
+    # the sums form differs by (Ly / Lx)^(1/4) in every coordinate; even with its own best A it loses
+    psi_sums = ((Y ** 2).sum(0) / (X ** 2).sum(0)) ** 0.25
+    g = orc.fit_gerf(X * psi_sums, Y / psi_sums)
+    assert orc.lbar_bruteforce(_saderf_from(psi_sums, g.A[0], d), X, Y) > base + 1e-6
+
+
 def _sderf_from(Avec, Qmat):
     d = len(Avec)
     B = np.diag(np.sqrt(1 - 4 * Avec)) @ Qmat
