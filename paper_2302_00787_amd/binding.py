@@ -163,6 +163,21 @@ def unpack_theta(vec: np.ndarray, d: int) -> dict:
                 C2=vec[o + d + 3 * dd:o + d + 4 * dd].reshape(d, d).copy())
 
 
+def to_device(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """Host array -> device tensor, float32 ("f32") or bfloat16 ("bf16": the values must already be representable,
+    as the input generators leave them; their upper 16 bits are uploaded)."""
+    if dtype == "bf16":
+        from . import synth
+        bits = synth.to_bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> float64 host array."""
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
 # ------------------------------------------------------------------ entry points
 def fit_workspace_bytes(B, H, Lx, Ly, d, groups) -> int:
     return int(lib().favorsharp_fit_workspace_bytes(B, H, Lx, Ly, d, groups))
@@ -266,16 +281,20 @@ def attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, o
 
 def attention_backward(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, dY: torch.Tensor,
                        qk_scale: float, Omega: torch.Tensor, causal: bool = False, grad_dtype=None,
-                       workspace: torch.Tensor | None = None):
-    """favorsharp_attention_backward: gradients of sum(Y * dY) -> (dQ, dK, dV), shaped like Q, K, V."""
+                       workspace: torch.Tensor | None = None, grads=None):
+    """favorsharp_attention_backward: gradients of sum(Y * dY) -> (dQ, dK, dV), shaped like Q, K, V
+    (`grads`: three preallocated tensors to write into, any row strides)."""
     B, H, Lq, d = Q.shape
     Lk, dv = K.shape[2], V.shape[3]
     groups = theta.shape[0] if theta.dim() == 2 else 1
     og, M = (Omega.shape[0], Omega.shape[1]) if Omega.dim() == 3 else (1, Omega.shape[0])
     gd = grad_dtype or Q.dtype
-    gQ = torch.empty((B, H, Lq, d), dtype=gd, device=Q.device)
-    gK = torch.empty((B, H, Lk, d), dtype=gd, device=Q.device)
-    gV = torch.empty((B, H, Lk, dv), dtype=gd, device=Q.device)
+    if grads is not None:
+        gQ, gK, gV = grads
+    else:
+        gQ = torch.empty((B, H, Lq, d), dtype=gd, device=Q.device)
+        gK = torch.empty((B, H, Lk, d), dtype=gd, device=Q.device)
+        gV = torch.empty((B, H, Lk, dv), dtype=gd, device=Q.device)
     nbytes = attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, og)
     ws = _workspace(nbytes, Q.device, workspace)
     descs = [_desc4(t) for t in (Q, K, V, dY, gQ, gK, gV)]

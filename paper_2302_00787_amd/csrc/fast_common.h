@@ -180,7 +180,8 @@ __device__ __forceinline__ void store_key_rows(const RowRegs& r, Smem& sm, int b
       const bool valid = row0 + row < row_end;
       float rt = -0.5f * kLog2e * a.scale * a.scale * n2[i];
       if (!isoC) rt = valid ? a.rk[(size_t)bh * a.L + row0 + row] : 0.f;
-      sm.kadd[buf][row] = rt;
+      // rows past the end get -inf: their features are exactly zero whatever the key shift is
+      sm.kadd[buf][row] = valid ? rt : -INFINITY;
       sm.kbnd[buf][row] = valid ? row_shift(n2[i], wmax) + rt : -INFINITY;
     }
   }

@@ -483,7 +483,8 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   // bf16 kernels: d = dv = 64, M = 256, bf16 inputs and output gradient, rows addressable with 32 bits
   const long long max_sl = 1ll << 23;
   if (fast_supported(Q->dtype, d, dv, M) && dY->dtype == FS_BF16 && Q->stride_l < max_sl && K->stride_l < max_sl &&
-      V->stride_l < max_sl &&
+      V->stride_l < max_sl && dY->stride_l < max_sl && dQ->stride_l < max_sl && dK->stride_l < max_sl &&
+      dV->stride_l < max_sl &&
       (int)std::max({fast_lds_bytes(), fast_bwd_lds_bytes(), fast_bwd_causal_lds_bytes()}) <= device_lds_limit()) {
     FastBwdPlan fp;
     plan_fast_backward(BH, pgroups, Lq, Lk, &fp);

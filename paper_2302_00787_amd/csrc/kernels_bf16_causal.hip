@@ -77,7 +77,8 @@ __device__ __forceinline__ void stage_store(const Stage& s, SmemPC& sm, int buf,
       {
         const bool valid = row0 + row < row_end;
         const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * nk2 : s.rk[i];
-        sm.kadd[buf][4 * (row & 15) + (row >> 4)] = rt;
+        // rows past the end get -inf: their features are exactly zero whatever the key shift is
+        sm.kadd[buf][4 * (row & 15) + (row >> 4)] = valid ? rt : -INFINITY;
         sm.kbnd[buf][row] = valid ? row_shift(nk2, wmax2) + rt : -INFINITY;
       }
     }
@@ -104,12 +105,6 @@ struct SegCtx {
 // Every barrier of the kernel goes through this macro; the two roles must execute the same number of them.
 #define FS_STEP_BARRIER() __syncthreads()
 
-#ifdef FS_PROFILE
-__device__ unsigned long long fs_prof[8 * 64 * 32];
-#define FS_TICK(wv, slot) do { if (prof_on && (threadIdx.x & 63) == 0) { __builtin_amdgcn_sched_barrier(0); fs_prof[((wv) * 64 + ci) * 32 + (slot)] = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0);} } while (0)
-#else
-#define FS_TICK(wv, slot)
-#endif
 
 // Per-part staging: the rows of a chunk travel in four parts (0: query rows, 1: key rows, 2 and 3: value pieces);
 // part p of chunk c+1 goes to LDS in step p of chunk c and its registers are refilled at once with part p of
@@ -179,14 +174,7 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
   load_xop(xo[0][0], sm.k[0], 0, lane);
   load_xop(xo[0][1], sm.k[0], 1, lane);
   int buf = 0;
-#ifdef FS_PROFILE
-  const bool prof_on = blockIdx.x == 3 && blockIdx.y == 5;
-  int ci = -1;
-#endif
   for (int row0 = cx.row_beg; row0 < cx.row_end; row0 += TC, buf ^= 1) {
-#ifdef FS_PROFILE
-    ++ci;
-#endif
     // Addresses that are used once per chunk are rebuilt from an opaque copy of the thread number instead of living
     // in registers through the whole loop.
     int tid_here = threadIdx.x;
@@ -209,7 +197,6 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
 
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
-      FS_TICK(j, 2 * S);
       // operands of the next step's two tiles (after the last step: the first two key tiles of the next chunk, whose
       // key rows went to the other buffer in step 1)
 #pragma unroll
@@ -243,7 +230,6 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
         finish_norm(fsum, sm, j, lane_here);
       }
       if (S == 3) finish_store(fsum, a.Y, yprev, row0 > cx.row_beg ? TC : 0, j, lane_here);
-      FS_TICK(j, 2 * S + 1);
       FS_STEP_BARRIER();
     }
     yprev += ystep;
@@ -277,14 +263,7 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
   FS_STEP_BARRIER();               // the producers' first step
 
   int buf = 0;
-#ifdef FS_PROFILE
-  const bool prof_on = blockIdx.x == 3 && blockIdx.y == 5;
-  int ci = -1;
-#endif
   for (int row0 = cx.row_beg; row0 < cx.row_end; row0 += TC, buf ^= 1) {
-#ifdef FS_PROFILE
-    ++ci;
-#endif
     // running key shift (every wave computes the same numbers); the state is rebased when it grows
     {
       const f32x4 b4 = *(const f32x4*)(&sm.kbnd[buf][4 * c]);
@@ -309,7 +288,6 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
     bf16x8 vop[2][NVT];            // value operands of the chunk
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
-      FS_TICK(4 + j, 2 * S);
       if (S < 2) {
         // key side: a pair of token tiles
 #pragma unroll
@@ -379,7 +357,6 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
             *(bf16x4*)(&sm.xch[it][j][c][16 * vt + 4 * g]) = __builtin_convertvector(y[vt], bf16x4);
         }
       }
-      FS_TICK(4 + j, 2 * S + 1);
       FS_STEP_BARRIER();
     }
   }
@@ -429,8 +406,3 @@ int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st) {
 
 }  // namespace fs
 
-#ifdef FS_PROFILE
-extern "C" int favorsharp_prof_read(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(fs::pc::fs_prof), sizeof(unsigned long long) * 8 * 64 * 32);
-}
-#endif

@@ -204,7 +204,8 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
       const int row = (tid >> 4) + 32 * i;
       const float n2 = store_row_piece_w(kr[i], sm.k[buf], row, tid & 15);
       const float rt = isoC ? -0.5f * kLog2e * a.scale * a.scale * n2 : rkr[i];
-      sm.kadd[buf][row] = rt;
+      // rows past the end get -inf: their features are exactly zero whatever the key shift is
+      sm.kadd[buf][row] = row < nv ? rt : -INFINITY;
       sm.kbnd[buf][row] = row < nv ? row_shift(n2, wmax) + rt : -INFINITY;
       store_val_piece(vr[i], sm.vt[buf], tid & 63, (tid >> 6) + 8 * i);
     }

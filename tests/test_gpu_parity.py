@@ -243,6 +243,34 @@ def test_fit_params_invariants(fs, variant, dtype, entry):
         assert orc.lbar_bruteforce(got, X[:200], Yk[:200]) == pytest.approx(orc.lbar_bruteforce(ref, X[:200], Yk[:200]), abs=2e-4)
 
 
+@pytest.mark.parametrize("entry", ["host", "device"])
+@pytest.mark.parametrize("variant", ["posrf", "gerf", "saderf", "aderf", "sderf"])
+def test_fit_params_sets_of_different_sizes(fs, variant, entry):
+    """Lx != Ly: every statistic is a mean over its own set (Section 4.3's Psi is then the ratio of per-set means,
+    not of sums), for all five families on both fit entry points."""
+    rng = np.random.default_rng(43)
+    B, H, Lx, Ly, d = 2, 2, 200, 520, 16
+    sc = np.linspace(0.4, 1.3, d)
+    Q = (rng.standard_normal((B, H, Lx, d)) * sc + 0.15).astype(np.float32)
+    K = (rng.standard_normal((B, H, Ly, d)) * sc[::-1] - 0.1).astype(np.float32)
+    s = d ** -0.25
+    theta = _fit(fs, entry, variant, util.to_device(Q, "f32"), util.to_device(K, "f32"), s, H)
+    for h in range(H):
+        X = s * Q[:, h].reshape(-1, d).astype(np.float64)
+        Yk = s * K[:, h].reshape(-1, d).astype(np.float64)
+        ref = orc.fit(variant, X, Yk)
+        got = util.oracle_theta_from_vec(theta[h], d)
+        np.testing.assert_allclose(np.sort(got.A), np.sort(ref.A), atol=2e-5)
+        assert got.logD == pytest.approx(ref.logD, abs=1e-4)
+        if ref.lbar is not None:
+            assert float(theta[h][1]) == pytest.approx(ref.lbar, abs=2e-4 * max(1.0, abs(ref.lbar)))
+        np.testing.assert_allclose(got.B1.T @ got.B1, ref.B1.T @ ref.B1, atol=3e-4)
+        np.testing.assert_allclose(got.B1.T @ got.B2, ref.B1.T @ ref.B2, atol=3e-4)
+        np.testing.assert_allclose(got.C1, ref.C1, atol=3e-4)
+        np.testing.assert_allclose(got.C2, ref.C2, atol=3e-4)
+        assert orc.lbar_bruteforce(got, X[:150], Yk[:200]) == pytest.approx(orc.lbar_bruteforce(ref, X[:150], Yk[:200]), abs=2e-4)
+
+
 @pytest.mark.parametrize("variant", ["sderf", "aderf"])
 @pytest.mark.parametrize("d", [9, 64, 128])
 def test_device_fit_dense_families_at_other_sizes(fs, variant, d):
@@ -478,6 +506,20 @@ def test_bf16_path_extreme_scales_stay_finite(fs):
     Q[0, 0, 100:102] *= 3.0
     Q, K = synth.round_to_bf16(Q), synth.round_to_bf16(K)
     _check_attention(fs, Q, K, w["V"], w["Omega"], w["qk_scale"], True, "posrf", "bf16")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_bf16_path_ragged_tail_with_uniformly_large_keys(fs, causal):
+    """Every key rescaled to the norm 21 (in the scaled space), so that the key shift (dominated by -|y|^2/2) is
+    below -128 in the log2 domain while the Cauchy-Schwarz bounds stay inside the documented range, and a last chunk
+    of 36 valid rows: the rows past the end must contribute exactly zero (not exp2(0 - shift) = inf times a zero
+    value).  All keys have one norm because a causal row only sees the keys before it: keys of one chunk whose row
+    terms differ by more than the fp32 exponent range cannot share a scale."""
+    w = synth.make("c4", B=1, H=2, L=100, seed=91)
+    K = w["K"].astype(np.float64)
+    K *= (21.0 / w["qk_scale"]) / np.linalg.norm(K, axis=-1, keepdims=True)
+    _check_attention(fs, w["Q"], synth.round_to_bf16(K.astype(np.float32)), w["V"], w["Omega"], w["qk_scale"], causal,
+                     "posrf", "bf16", chunk=64)
 
 
 @pytest.mark.parametrize("name", ["c3", "c4", "c5"])

@@ -20,15 +20,13 @@ def oracle_theta_from_vec(vec, d):
 
 
 def to_device(a: np.ndarray, dtype: str):
-    import torch
-    if dtype == "bf16":
-        bits = synth.to_bf16_bits(a)
-        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    from paper_2302_00787_amd import binding
+    return binding.to_device(a, dtype)
 
 
 def to_host(t) -> np.ndarray:
-    return t.detach().float().cpu().numpy().astype(np.float64)
+    from paper_2302_00787_amd import binding
+    return binding.to_host(t)
 
 
 def attention_errors(Y_gpu: np.ndarray, Y_ref: np.ndarray, V: np.ndarray):
@@ -36,4 +34,13 @@ def attention_errors(Y_gpu: np.ndarray, Y_ref: np.ndarray, V: np.ndarray):
     diff = Y_gpu - Y_ref
     fro = np.linalg.norm(diff) / max(np.linalg.norm(Y_ref), 1e-300)
     row = np.linalg.norm(diff, axis=1).max() / np.linalg.norm(V, axis=1).max()
+    return float(fro), float(row)
+
+
+def gradient_errors(g_gpu: np.ndarray, g_ref: np.ndarray, floor: float = 0.0):
+    """(relative Frobenius error, worst row error relative to the largest row norm of the reference) for one
+    gradient tensor of one (b, h); `floor` stands in for a reference that is zero by construction."""
+    diff = g_gpu - g_ref
+    fro = np.linalg.norm(diff) / max(np.linalg.norm(g_ref), floor, 1e-300)
+    row = np.linalg.norm(diff, axis=1).max() / max(np.linalg.norm(g_ref, axis=1).max(), floor, 1e-300)
     return float(fro), float(row)
