@@ -16,7 +16,8 @@
  * Conventions for every entry point
  *   - returns an fs_status; never throws, never aborts, never allocates device
  *     memory: the caller owns every buffer, including the workspace, whose
- *     size comes from the matching *_workspace_bytes query (same shapes);
+ *     size comes from the matching *_workspace_bytes query (same shapes)
+ *     (favorsharp_attention_noalloc alone uses a buffer the library owns);
  *   - pointers are DEVICE pointers unless the name starts with host_;
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
  *     default stream).  favorsharp_fit_params additionally waits for the
@@ -24,7 +25,8 @@
  *     return as soon as their kernels are enqueued;
  *   - outputs are fully overwritten, inputs are never modified; the workspace
  *     content is undefined afterwards; calls that share a workspace must be
- *     ordered by the caller; there is no global mutable state;
+ *     ordered by the caller; there is no global mutable state apart from
+ *     favorsharp_attention_noalloc's scratch array;
  *   - tensors are row-major; an fs_tensor carries element strides for the
  *     batch, head and row axes, the innermost (feature) axis has stride 1 and
  *     row starts must be 16-byte aligned (stride_l a multiple of 8 for bf16, of 4 for f32);
@@ -47,7 +49,8 @@ typedef enum {
   FS_ERR_UNSUPPORTED = 2,        /* valid but outside what the kernels cover (d > 128, causal with Lq != Lk, ...) */
   FS_ERR_NOT_PD = 3,             /* fit: statistics are singular where the theorem needs them nonsingular */
   FS_ERR_WORKSPACE_TOO_SMALL = 4,
-  FS_ERR_DEVICE = 5              /* a HIP call failed */
+  FS_ERR_DEVICE = 5,             /* a HIP call failed */
+  FS_ERR_SCRATCH_LIMIT = 6       /* favorsharp_attention_noalloc: the call needs more than FS_NOALLOC_SCRATCH_BYTES */
 } fs_status;
 
 typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype;
@@ -194,6 +197,24 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
                                int causal, int chunk, const fs_tensor* Y,
                                void* workspace, size_t workspace_bytes, void* stream,
                                void* event_main_begin, void* event_main_end);
+
+/*
+ * favorsharp_attention for callers that cannot allocate or pass device memory of their own: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as favorsharp_attention
+ * minus the workspace: the scratch memory is a fixed array of FS_NOALLOC_SCRATCH_BYTES that the library holds on
+ * every GPU it runs on until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine); its first call on a device looks the array's address up once.
+ *   FS_ERR_SCRATCH_LIMIT when favorsharp_attention_workspace_bytes(same shapes) exceeds FS_NOALLOC_SCRATCH_BYTES
+ *   (nothing is enqueued then); the other statuses as favorsharp_attention.
+ * All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams,
+ * different host threads) race and must be ordered by the caller.  The array keeps the last call's contents; the
+ * kernels write every part of it before they read it.
+ */
+#define FS_NOALLOC_SCRATCH_BYTES (64u << 20)
+int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                 const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv,
+                                 float qk_scale, const float* Omega, int omega_groups, int M,
+                                 int causal, int chunk, const fs_tensor* Y, void* stream);
 
 /*
  * Block-orthogonal random features (the appendix on the classification experiments says the omegas there are

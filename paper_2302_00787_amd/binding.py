@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
                                            c_void_p, c_int, c_int, c_int, c_int, P, c_void_p, c_size_t, c_void_p]
         L.favorsharp_attention_timed.restype = c_int
         L.favorsharp_attention_timed.argtypes = L.favorsharp_attention.argtypes + [c_void_p, c_void_p]
+        L.favorsharp_attention_noalloc.restype = c_int
+        L.favorsharp_attention_noalloc.argtypes = L.favorsharp_attention.argtypes[:18] + [c_void_p]
         L.favorsharp_attention_backward_workspace_bytes.restype = c_size_t
         L.favorsharp_attention_backward_workspace_bytes.argtypes = [c_int] * 10
         L.favorsharp_attention_backward.restype = c_int
@@ -271,6 +273,25 @@ def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
     else:       # (hipEvent_t begin, hipEvent_t end) as integers: favorsharp_attention_timed
         st = lib().favorsharp_attention_timed(*args, events[0], events[1])
     _check(st, "favorsharp_attention")
+    return out
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def attention_noalloc(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, qk_scale: float,
+                      Omega: torch.Tensor, out: torch.Tensor, causal: bool = False, chunk: int = 0) -> torch.Tensor:
+    """favorsharp_attention_noalloc: as `attention`, on the library's own scratch array; `out` is required (nothing
+    is allocated here either)."""
+    B, H, Lq, d = Q.shape
+    Lk, dv = K.shape[2], V.shape[3]
+    groups = theta.shape[0] if theta.dim() == 2 else 1
+    og, M = (Omega.shape[0], Omega.shape[1]) if Omega.dim() == 3 else (1, Omega.shape[0])
+    dq, dk, dvv, dy = _desc4(Q), _desc4(K), _desc4(V), _desc4(out)
+    st = lib().favorsharp_attention_noalloc(theta.data_ptr(), groups, ctypes.byref(dq), ctypes.byref(dk), ctypes.byref(dvv),
+                                            B, H, Lq, Lk, d, dv, qk_scale, Omega.data_ptr(), og, M, int(causal), chunk,
+                                            ctypes.byref(dy), _stream())
+    _check(st, "favorsharp_attention_noalloc")
     return out
 
 

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -114,6 +115,33 @@ void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
   p->total = off;
 }
 
+// Scratch memory of favorsharp_attention_noalloc: one array per GPU, owned by the library for the life of the
+// process.  In host code the array's name is only a handle for hipGetSymbolAddress; every use of its memory (kernel
+// arguments) goes through the per-device pointer obtained below.
+static __device__ __align__(256) unsigned char scratch[FS_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+int scratch_for_current_device(void** out) {
+  int dev_id = 0;
+  if (hipGetDevice(&dev_id) != hipSuccess) return FS_ERR_DEVICE;
+  if (dev_id < 0 || dev_id >= kMaxDevices) return FS_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_ptr[dev_id] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return FS_ERR_DEVICE;
+    }
+    scratch_ptr[dev_id] = p;
+  }
+  *out = scratch_ptr[dev_id];
+  return FS_OK;
+}
+
 int device_lds_limit() {
   int dev_id = 0, v = 0;
   if (hipGetDevice(&dev_id) != hipSuccess) return 0;
@@ -135,6 +163,7 @@ const char* favorsharp_status_string(int status) {
     case FS_ERR_NOT_PD: return "statistics are singular";
     case FS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     case FS_ERR_DEVICE: return "device error";
+    case FS_ERR_SCRATCH_LIMIT: return "problem needs more scratch memory than the library's fixed buffer holds";
     default: return "unknown status";
   }
 }
@@ -403,6 +432,20 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
   if (rc) return rc;
   if (event_main_end && hipEventRecord((hipEvent_t)event_main_end, st) != hipSuccess) return FS_ERR_DEVICE;
   return FS_OK;
+}
+
+int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                 const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv, float qk_scale,
+                                 const float* Omega, int omega_groups, int M, int causal, int chunk, const fs_tensor* Y,
+                                 void* stream) {
+  const size_t need = favorsharp_attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups);
+  if (need > (size_t)FS_NOALLOC_SCRATCH_BYTES) return FS_ERR_SCRATCH_LIMIT;
+  void* ws = nullptr;
+  if (need > 0)      // (0: the shapes are invalid or unsupported, and the call below says which)
+    if (int rc = scratch_for_current_device(&ws)) return rc;
+  // every kernel of the call writes the part of the workspace it later reads: nothing has to start at zero
+  return favorsharp_attention_timed(theta, groups, Q, K, V, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M,
+                                    causal, chunk, Y, ws, FS_NOALLOC_SCRATCH_BYTES, stream, nullptr, nullptr);
 }
 
 // ------------------------------------------------------------------------------------------ attention, backward

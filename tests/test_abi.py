@@ -65,6 +65,20 @@ def test_argument_errors_are_reported_before_any_device_work(lib):
                                         None) == 2
 
 
+def test_noalloc_entry_point_rejects_sizes_beyond_its_scratch_array_before_any_device_work(lib):
+    from paper_2302_00787_amd.binding import FsTensor, NOALLOC_SCRATCH_BYTES
+    t = FsTensor(None, 1, 0, 0, 128)
+    P = ctypes.byref
+    # the long-context workload needs far more than the fixed array
+    assert lib.favorsharp_attention_workspace_bytes(1, 16, 65536, 65536, 128, 128, 512, 1, 16, 16) > NOALLOC_SCRATCH_BYTES
+    assert lib.favorsharp_attention_noalloc(None, 16, P(t), P(t), P(t), 1, 16, 65536, 65536, 128, 128, 1.0, None, 16, 512,
+                                            1, 64, P(t), None) == 6
+    assert b"scratch" in lib.favorsharp_status_string(6)
+    # invalid shapes are still reported as such
+    assert lib.favorsharp_attention_noalloc(None, 3, P(t), P(t), P(t), 1, 16, 64, 64, 128, 128, 1.0, None, 16, 512, 1, 64,
+                                            P(t), None) == 1
+
+
 def test_pack_and_unpack_theta_roundtrip():
     import numpy as np
     from paper_2302_00787_amd import binding
