@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the FAVOR# hot path on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4] [--only] [--no-cpu-baseline]
 
 One "step" is one call of favorsharp_attention on the metric workload (causal, bf16, B=4 H=8 L=16384 d=64
 M=256, chunk 64): projection constants, both feature maps (fused, never stored) and the causal prefix-state
@@ -10,8 +10,16 @@ contraction, with Q, K, V, omega and the fitted parameters already resident in H
 device-resident variant of the same fit as `fit_device_ms`.
 Inputs rotate over three distinct sets so the 256 MB last-level cache cannot hold a set across steps.
 
-Prints ONE JSON line: throughput in tokens/s (B*L per step), the roofline of the dominant kernel measured
-with HIP events recorded by the library around that kernel, and the CPU oracle timed on a bounded sample.
+Timing: `ms_per_step` is the mean wall-clock time of K back-to-back calls between two device synchronisations (it
+includes every launch gap of a call); `main_kernel_ms` is the mean over the same K calls of the time between two HIP
+events that the library records on its stream right before and right after the dominant kernel.
+
+Prints ONE JSON line.  Headline fields: the metric workload.  `roofline`: the dominant kernel of the metric workload
+(`frac`) and the whole call (`call_frac`) against the tighter of the HBM / MFMA bounds on the algorithmic counts.
+`workloads`: the same measurements for the other four workloads and the two backward-pass workloads, taken in the
+same run (unless --only).  `parity`: measured errors of the library's results against the CPU oracle on the same
+inputs and the same float32 parameter block (computed in the CPU-baseline leg, which is the only part of this
+script that touches the oracle).  `cpu_baseline`: the oracle timed on a bounded sample of the metric workload.
 """
 from __future__ import annotations
 
@@ -29,11 +37,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_F32_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this
-# script with --calibrate-copy, each counter scaled by what it reads for the 256 MiB copy (FETCH_SIZE x 2.0,
-# WRITE_SIZE x 1.0); figures and commands in profiles/c4_hbm_traffic.md.  The kernel reads Q, K, V and the prefix
-# states once and writes Y once, so the figure does not depend on how its instructions are scheduled.
-MEASURED_TRAFFIC_BYTES = {"c4": 291.9e6, "c3": 111.6e6, "c5": 3.31e9}     # c3, c5: profiles/c3_c5_hbm_traffic.md
+# script (--only --calibrate-copy), each counter scaled by what it reads for the 256 MiB copy; figures, factors and
+# commands in the profiles/*_hbm_traffic.md file named beside each value.
+MEASURED_TRAFFIC_BYTES = {
+    "c4": (291.9e6, "profiles/c4_hbm_traffic.md"),
+    "c3": (111.6e6, "profiles/c3_c5_hbm_traffic.md"),
+    "c5": (3.31e9, "profiles/c3_c5_hbm_traffic.md"),
+}
+TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
 class HipEvents:
@@ -79,137 +92,312 @@ def algorithmic_counts(cfg: dict) -> dict:
     return dict(head_tokens=ht, bytes=ht * 4 * d * esz, flops=ht * flops)
 
 
-def cpu_baseline(w: dict, budget_s: float = 20.0) -> dict:
-    """The CPU oracle, as it stands, on whole (b, h) sequences of the same workload until ~budget_s is spent."""
-    from oracle import favorsharp_oracle as orc
+def host_cores() -> int:
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] + [1]))
     except Exception:
-        cores = os.cpu_count() or 1
-    s, d = w["qk_scale"], w["d"]
-    done, t0 = 0, time.perf_counter()
-    pairs = [(b, h) for b in range(w["B"]) for h in range(w["H"])]
-    for b, h in pairs:
-        th = orc.fit_sderf(s * w["Q"][:, h].reshape(-1, d).astype(np.float64),
-                           s * w["K"][:, h].reshape(-1, d).astype(np.float64))
-        orc.attention(th, w["Omega"][h], w["Q"][b, h], w["K"][b, h], w["V"][b, h], s, w["causal"])
-        done += 1
-        if time.perf_counter() - t0 > budget_s:
-            break
-    dt = time.perf_counter() - t0
-    head_tokens_per_s = done * w["L"] / dt
-    return dict(value=head_tokens_per_s / w["H"], unit="tokens/s", cores=int(cores), kind="oracle",
-                sample=f"{done} of {len(pairs)} (b,h) sequences of L={w['L']} (fit + attention, fp64 numpy), "
-                       f"{dt:.1f} s; head-tokens/s divided by H={w['H']}")
+        return int(os.cpu_count() or 1)
 
 
-def bench_matvec(args, cfg, fs, synth, util, torch):
-    """The kernel-operator workload (K^(alpha)(X, Y) C, Section 2.1): one step = one favorsharp_kernel_matvec call
-    with theta and omega resident; fp32 in and out, so the bound is the fp32 MFMA peak."""
+def timed(step, steps: int, warmup: int, torch) -> float:
+    """Mean wall-clock milliseconds of `steps` back-to-back calls after `warmup` untimed ones."""
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+# ---------------------------------------------------------------------------------------------- attention workloads
+def run_attention(name: str, steps: int, warmup: int, fs, synth, torch, nsets: int = 3, with_fit: bool = False,
+                  calibrate_copy: bool = False) -> dict:
+    """Times favorsharp_attention on workload `name`; returns the measurements, the first input set (host and
+    device) and that set's output for the parity leg."""
+    cfg = dict(synth.WORKLOADS[name])
+    dtype = cfg["dtype"]
+    B, H, L, d, M = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"]
+    causal, chunk = cfg["causal"], cfg.get("chunk", 0)
+    sets, w0 = [], None
+    for i in range(nsets):
+        w = synth.make(name, seed=cfg["seed"] + i)
+        w0 = w0 or w
+        sets.append(dict(Q=fs.to_device(w["Q"], dtype), K=fs.to_device(w["K"], dtype), V=fs.to_device(w["V"], dtype),
+                         Omega=torch.from_numpy(w["Omega"]).cuda()))
+        del w
+    s = w0["qk_scale"]
+    for st_ in sets:
+        st_["theta"] = fs.fit_params("sderf", st_["Q"], st_["K"], s, groups=H)
+    out = dict(cfg=cfg, w0=w0, theta0=sets[0]["theta"])
+    if with_fit:
+        # fit (timed separately): statistics on the GPU, closed form on the host
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fs.fit_params("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H)
+        torch.cuda.synchronize()
+        out["fit_ms"] = (time.perf_counter() - t0) * 1e3
+        # the same fit with the closed form on the device (asynchronous entry point; the timing includes the final sync)
+        fit_ws = torch.empty(fs.fit_device_workspace_bytes(B, H, L, L, d, H), dtype=torch.uint8, device="cuda")
+        fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, fit_status = fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
+        torch.cuda.synchronize()
+        out["fit_device_ms"] = (time.perf_counter() - t0) * 1e3
+        assert int(fit_status.abs().sum().item()) == 0
+        del fit_ws
+
+    ws = torch.empty(fs.attention_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8, device="cuda")
+    outs = [torch.empty_like(st_["V"]) for st_ in sets]
+    ev = HipEvents()
+    pairs = [(ev.create(), ev.create()) for _ in range(steps)]
+
+    def step(i, events=None):
+        st_ = sets[i % nsets]
+        fs.attention(st_["theta"], st_["Q"], st_["K"], st_["V"], s, st_["Omega"], causal=causal, chunk=chunk,
+                     out=outs[i % nsets], workspace=ws, events=events)
+
+    if calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i, pairs[i])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) / steps * 1e3
+    main_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs]))
+    for a, b in pairs:
+        ev.destroy(a)
+        ev.destroy(b)
+    assert all(torch.isfinite(o.float()).all().item() for o in outs)
+
+    counts = algorithmic_counts(cfg)
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    t_hbm = counts["bytes"] / (HBM_PEAK_GBS * 1e9)
+    t_mfma = counts["flops"] / (mfma_peak * 1e12)
+    traffic = MEASURED_TRAFFIC_BYTES.get(name)
+    if t_hbm >= t_mfma:
+        ach = counts["bytes"] / (main_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
+    else:
+        ach = counts["flops"] / (main_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s", "frac": ach / mfma_peak}
+    roofline.update({
+        "traffic": traffic[0] if traffic else None, "traffic_source": traffic[1] if traffic else None,
+        "call_frac": max(t_hbm, t_mfma) / (ms_per_step * 1e-3),
+        "kernel_hbm_frac": t_hbm / (main_ms * 1e-3), "kernel_mfma_frac": t_mfma / (main_ms * 1e-3),
+        "call_hbm_frac": t_hbm / (ms_per_step * 1e-3), "call_mfma_frac": t_mfma / (ms_per_step * 1e-3)})
+    out.update(ms_per_step=ms_per_step, main_kernel_ms=main_ms, roofline=roofline, counts=counts,
+               Y0=outs[0], sets=sets, tokens_per_s=B * L / (ms_per_step * 1e-3))
+    return out
+
+
+def describe_attention(name: str, cfg: dict) -> str:
+    causal = cfg["causal"]
+    return (f"{name}: {'causal' if causal else 'non-causal'} attention, {cfg['dtype']} in / f32 accumulate, "
+            f"B={cfg['B']} H={cfg['H']} L={cfg['L']} d={cfg['d']} M={cfg['M']}"
+            + (f" chunk={cfg.get('chunk', 0)}" if causal else "") + ", SDERF per head, theta and omega resident")
+
+
+def summary_of(r: dict) -> dict:
+    rf = r["roofline"]
+    return {"ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"], "main_kernel_ms": r["main_kernel_ms"],
+            "roofline": {"bound": rf["bound"], "frac": rf["frac"], "step_frac": rf["call_frac"], "unit": rf["unit"],
+                         "achieved": rf["achieved"], "peak": rf["peak"], "traffic": rf["traffic"]}}
+
+
+# ---------------------------------------------------------------------------------------------- kernel operator
+def run_matvec(steps: int, warmup: int, fs, synth, torch) -> dict:
+    """c2, the kernel operator K^(alpha)(X, Y) C of Section 2.1: one step = one favorsharp_kernel_matvec call with
+    theta and omega resident; fp32 in and out, so the bound is the fp32 MFMA peak."""
+    cfg = dict(synth.WORKLOADS["c2"])
     N, d, M, n, alpha = cfg["N"], cfg["d"], cfg["M"], cfg["n"], cfg["alpha"]
-    sets = []
+    sets, w0 = [], None
     for i in range(3):
-        w = synth.make(args.workload, seed=cfg["seed"] + i)
+        w = synth.make("c2", seed=cfg["seed"] + i)
+        w0 = w0 or w
         X = torch.from_numpy(w["X"].astype(np.float32)).cuda()
         C = torch.from_numpy(w["C"].astype(np.float32)).cuda()
         Om = torch.from_numpy(w["Omega"].astype(np.float32)).cuda()
         theta = fs.fit_params("sderf", X, X, w["qk_scale"], groups=1)
         sets.append((theta, X, C, Om, w["qk_scale"]))
     ws = torch.empty(fs.kernel_matvec_workspace_bytes(N, N, d, M, n), dtype=torch.uint8, device="cuda")
+    last = {}
 
     def step(i):
         theta, X, C, Om, s = sets[i % 3]
-        return fs.kernel_matvec(theta, X, X, s, alpha, Om, C, workspace=ws)
+        last[i % 3] = fs.kernel_matvec(theta, X, X, s, alpha, Om, C, workspace=ws)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        out = step(i)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
-    assert torch.isfinite(out).all().item()
+    ms = timed(step, steps, warmup, torch)
+    assert torch.isfinite(last[0]).all().item()
     flops = N * (2 * 2 * d * M + 2 * 2 * M * n)          # two projections, state update and state read
     tf = flops / (ms * 1e-3) / 1e12
-    cpu = None
-    if not args.no_cpu_baseline:
-        # the oracle on the whole operator (fit + both feature maps + the two products), fp64 numpy
-        from oracle import favorsharp_oracle as orc
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        w = synth.make(args.workload, seed=cfg["seed"])
-        t1 = time.perf_counter()
-        Xs = w["qk_scale"] * w["X"].astype(np.float64)
-        orc.kernel_matvec(orc.fit_sderf(Xs, Xs), w["Omega"][0], Xs, Xs, w["C"].astype(np.float64), alpha)
-        dtc = time.perf_counter() - t1
-        cpu = dict(value=N / dtc, unit="points/s", cores=int(cores), kind="oracle",
-                   sample=f"the whole workload once (fit + operator, fp64 numpy), {dtc:.2f} s")
-    print(json.dumps({
-        "metric": "FAVOR# kernel operator points/s (c2: N=16384 d=32 M=512 n=8, alpha=-1/2)", "value": N / (ms * 1e-3),
-        "unit": "points/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "c2: kernel operator, fp32, X = Y, SDERF, theta and omega resident"},
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
-                     "traffic": None},
-        "cpu_baseline": cpu}), flush=True)
+    return dict(cfg=cfg, w0=w0, theta0=sets[0][0], out0=last[0], ms_per_step=ms, points_per_s=N / (ms * 1e-3),
+                roofline={"bound": "mfma", "achieved": tf, "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tf / MFMA_F32_PEAK_TFLOPS, "step_frac": tf / MFMA_F32_PEAK_TFLOPS, "traffic": None})
 
 
-def bench_backward(args, fs, synth, util, torch):
-    """The backward pass of attention on the c3 (non-causal) or c4 (causal) shapes, bf16 inputs and gradients: one
-    step = one favorsharp_attention_backward call with theta and omega resident.  Both run on the bf16 MFMA kernels
-    (bound: the bf16 MFMA peak).  Algorithmic flops per
-    head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six M x (dv + 1) contractions
-    (T, P T, G1 T^T, P^T G1, S R, [V 1] R^T) 12 M (dv + 1), and when causal the intra-chunk triangles of 64 rows
-    (scores and G1 V1^T and their four products: three times the forward pass's extra term)."""
-    name = args.workload.split("_")[0]
+# ---------------------------------------------------------------------------------------------- backward pass
+def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
+    """Backward pass of attention on the c3 (non-causal) or c4 (causal) shapes, bf16 inputs and gradients: one step =
+    one favorsharp_attention_backward call with theta and omega resident (bf16 MFMA kernels; bound: the bf16 MFMA
+    peak).  Algorithmic flops per head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six
+    M x (dv + 1) contractions (T, P T, G1 T^T, P^T G1, S R, [V 1] R^T) 12 M (dv + 1), and when causal the
+    intra-chunk triangles of 64 rows (three times the forward pass's extra term)."""
     cfg = dict(synth.WORKLOADS[name])
     B, H, L, d, M, causal = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"], bool(cfg["causal"])
     nsets = 3 if name == "c3" else 2
-    sets = []
+    sets, w0, dY0 = [], None, None
     for i in range(nsets):
         w = synth.make(name, seed=cfg["seed"] + i)
         rng = np.random.default_rng(900 + i)
-        Q, K, V = (util.to_device(w[k], "bf16") for k in "QKV")
-        dY = util.to_device(synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32)), "bf16")
+        dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+        if w0 is None:
+            w0, dY0 = w, dY
+        Q, K, V = (fs.to_device(w[k], "bf16") for k in "QKV")
         theta = fs.fit_params("sderf", Q, K, w["qk_scale"], groups=H)
-        sets.append((theta, Q, K, V, dY, torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"]))
+        sets.append((theta, Q, K, V, fs.to_device(dY, "bf16"), torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"]))
     ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8,
                      device="cuda")
+    last = {}
 
     def step(i):
         theta, Q, K, V, dY, Om, s = sets[i % nsets]
-        return fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
+        last[i % nsets] = fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        grads = step(i)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) / args.steps * 1e3
-    assert all(torch.isfinite(g.float()).all().item() for g in grads)
+    ms = timed(step, steps, warmup, torch)
+    assert all(torch.isfinite(g.float()).all().item() for g in last[0])
     chunk = cfg.get("chunk", 64)
     per_token = 8 * d * M + 12 * M * (d + 1) + (3 * (chunk + 1) // 2 * (2 * M + 2 * (d + 1)) if causal else 0)
-    flops = B * H * L * per_token
-    tf = flops / (ms * 1e-3) / 1e12
-    peak = MFMA_BF16_PEAK_TFLOPS
-    print(json.dumps({
-        "metric": f"FAVOR# attention backward tokens/s ({name} shapes: {'causal' if causal else 'non-causal'}, "
-                  f"B={B} H={H} L={L} d={d} M={M})",
-        "value": B * L / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: gradients of {'causal' if causal else 'non-causal'} attention w.r.t. "
-                               "Q, K, V, bf16 in and out, "
-                               "bf16 MFMA kernels, fp32 accumulation, SDERF per head, theta and omega resident"},
-        "roofline": {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
-                     "traffic": None}}), flush=True)
+    tf = B * H * L * per_token / (ms * 1e-3) / 1e12
+    return dict(cfg=cfg, w0=w0, dY0=dY0, theta0=sets[0][0], grads0=last[0], ms_per_step=ms,
+                tokens_per_s=B * L / (ms * 1e-3),
+                roofline={"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tf / MFMA_BF16_PEAK_TFLOPS, "step_frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
+
+
+# ---------------------------------------------------------------------------------------------- CPU oracle leg
+class OracleLeg:
+    """Everything that touches the CPU oracle: the timed baseline and the parity figures.  Both sides see the same
+    inputs, the same omega and the library's own float32 parameter block (downloaded and handed to the oracle)."""
+
+    def __init__(self, fs):
+        from oracle import favorsharp_oracle as orc
+        self.orc, self.fs, self.cores = orc, fs, host_cores()
+
+    def theta(self, vec, d):
+        u = self.fs.unpack_theta(vec, d)
+        f = lambda a: np.asarray(a, dtype=np.float64)
+        return self.orc.Theta(A=f(u["A"]), B1=f(u["B1"]), B2=f(u["B2"]), C1=f(u["C1"]), C2=f(u["C2"]), logD=float(u["logD"]))
+
+    @staticmethod
+    def errors(got, ref, scale_rows):
+        diff = got - ref
+        fro = float(np.linalg.norm(diff) / max(np.linalg.norm(ref), 1e-300))
+        row = float(np.linalg.norm(diff, axis=1).max() / max(np.linalg.norm(scale_rows, axis=1).max(), 1e-300))
+        return fro, row
+
+    def attention_full(self, r: dict, budget_s: float):
+        """Whole (b, h) sequences of an attention workload until `budget_s` is spent: the oracle's own fit (timed, as
+        part of the baseline) and the oracle's attention at the library's parameter block (timed; it is also the
+        parity reference)."""
+        orc, w, cfg = self.orc, r["w0"], r["cfg"]
+        s, d, H = w["qk_scale"], w["d"], w["H"]
+        th_host = self.fs.to_host(r["theta0"]).astype(np.float32)
+        Y = r["Y0"]
+        pairs = [(b, h) for b in range(w["B"]) for h in range(H)]
+        done, worst, dt = 0, [0.0, 0.0], 0.0
+        for b, h in pairs:
+            t0 = time.perf_counter()
+            orc.fit_sderf(s * w["Q"][:, h].reshape(-1, d).astype(np.float64), s * w["K"][:, h].reshape(-1, d).astype(np.float64))
+            ref = orc.attention(self.theta(th_host[h], d), w["Omega"][h], w["Q"][b, h], w["K"][b, h], w["V"][b, h], s, cfg["causal"])
+            dt += time.perf_counter() - t0               # the comparison below is not part of the baseline's time
+            fro, row = self.errors(self.fs.to_host(Y[b, h]), ref, w["V"][b, h].astype(np.float64))
+            worst = [max(worst[0], fro), max(worst[1], row)]
+            done += 1
+            if dt > budget_s:
+                break
+        tol = TOL[cfg["dtype"]]
+        parity = {"reference": "CPU oracle (fp64), same inputs, omega and float32 parameter block",
+                  "rows": f"every row of {done} of {len(pairs)} (b,h) sequences", "worst_frobenius": worst[0],
+                  "worst_row": worst[1], "tol_frobenius": tol, "tol_row": 4 * tol,
+                  "ok": bool(worst[0] <= tol and worst[1] <= 4 * tol)}
+        base = dict(value=done * w["L"] / dt / H, unit="tokens/s", cores=self.cores, kind="oracle",
+                    sample=f"{done} of {len(pairs)} (b,h) sequences of L={w['L']} (fit + attention, fp64 numpy), "
+                           f"{dt:.1f} s; head-tokens/s divided by H={H}")
+        return base, parity
+
+    def attention_sampled(self, r: dict, npairs: int, nrows: int):
+        """Sampled output rows, evaluated one by one from the definition (rows of K_hat, masked when causal)."""
+        import torch
+        orc, w, cfg = self.orc, r["w0"], r["cfg"]
+        s, d, B, H, L = w["qk_scale"], w["d"], w["B"], w["H"], w["L"]
+        th_host = self.fs.to_host(r["theta0"]).astype(np.float32)
+        rng = np.random.default_rng(9)
+        fixed = [0, 1, 63, 64, 65, L // 2 - 1, L // 2, L - 2, L - 1]
+        worst, total = [0.0, 0.0], 0
+        for b, h in [(0, 0), (B - 1, H - 1), (B // 2, H // 2)][:npairs]:
+            rows = np.unique(np.concatenate([fixed, rng.integers(0, L, nrows)]))
+            ref = orc.attention_khat_definition(self.theta(th_host[h], d), w["Omega"][h], w["Q"][b, h], w["K"][b, h],
+                                                w["V"][b, h], s, cfg["causal"], rows=rows)
+            got = self.fs.to_host(r["Y0"][b, h][torch.from_numpy(rows).cuda()])
+            fro, row = self.errors(got, ref, w["V"][b, h].astype(np.float64))
+            worst = [max(worst[0], fro), max(worst[1], row)]
+            total += len(rows)
+        tol = TOL[cfg["dtype"]]
+        return {"reference": "CPU oracle (fp64), rows of K_hat from the definition, same inputs, omega and parameter block",
+                "rows": f"{total} sampled rows of {npairs} (b,h) sequences", "worst_frobenius": worst[0],
+                "worst_row": worst[1], "tol_frobenius": tol, "tol_row": 4 * tol,
+                "ok": bool(worst[0] <= tol and worst[1] <= 4 * tol)}
+
+    def matvec(self, r: dict):
+        orc, w = self.orc, r["w0"]
+        Xs = w["qk_scale"] * w["X"].astype(np.float64)
+        th = self.theta(self.fs.to_host(r["theta0"]).astype(np.float32)[0], w["d"])
+        t0 = time.perf_counter()
+        orc.fit_sderf(Xs, Xs)
+        ref = orc.kernel_matvec(th, w["Omega"][0], Xs, Xs, w["C"].astype(np.float64), w["alpha"])
+        dt = time.perf_counter() - t0
+        got = self.fs.to_host(r["out0"])
+        fro = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        worst_el = float(np.abs(got - ref).max() / np.abs(ref).max())
+        parity = {"reference": "CPU oracle (fp64), the whole operator, same inputs, omega and parameter block",
+                  "rows": "all", "worst_frobenius": fro, "worst_element_over_max": worst_el, "tol_frobenius": 1e-4,
+                  "ok": bool(fro <= 1e-4)}
+        base = dict(value=w["N"] / dt, unit="points/s", cores=self.cores, kind="oracle",
+                    sample=f"the whole workload once (fit + operator, fp64 numpy), {dt:.2f} s")
+        return base, parity
+
+    def backward(self, r: dict):
+        """One whole (b, h) sequence of a backward workload: every gradient row."""
+        orc, w, cfg = self.orc, r["w0"], r["cfg"]
+        s, d = w["qk_scale"], w["d"]
+        th = self.theta(self.fs.to_host(r["theta0"]).astype(np.float32)[0], d)
+        ref = orc.attention_backward(th, w["Omega"][0], w["Q"][0, 0], w["K"][0, 0], w["V"][0, 0], r["dY0"][0, 0], s, cfg["causal"])
+        worst = [0.0, 0.0]
+        for g, rf in zip(r["grads0"], ref):
+            fro, row = self.errors(self.fs.to_host(g[0, 0]), rf, rf)
+            worst = [max(worst[0], fro), max(worst[1], row)]
+        return {"reference": "CPU oracle (fp64) gradients of sum(Y * dY), same inputs, omega and parameter block",
+                "rows": "every row of dQ, dK, dV of one (b,h) sequence", "worst_frobenius": worst[0],
+                "worst_row": worst[1], "tol_frobenius": 2e-2, "tol_row": 8e-2,
+                "ok": bool(worst[0] <= 2e-2 and worst[1] <= 8e-2)}
+
+
+def free(r: dict, torch):
+    for k in ("sets", "Y0", "theta0", "grads0", "out0", "w0", "dY0"):
+        r.pop(k, None)
+    torch.cuda.empty_cache()
 
 
 def main():
@@ -217,8 +405,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c3_backward", "c4_backward"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c3_backward", "c4_backward"],
+                    help="the workload of the headline fields (default: the metric workload, c4)")
+    ap.add_argument("--only", action="store_true",
+                    help="time the headline workload only (no `workloads` object): for profiling runs")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg (no baseline, no parity)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (a kernel of known traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -231,115 +422,93 @@ def main():
     import torch
     from paper_2302_00787_amd import binding as fs
     from paper_2302_00787_amd import synth
-    from tests import util
 
     fs.lib()
-    if args.workload.endswith("_backward"):
-        bench_backward(args, fs, synth, util, torch)
-        return
-    cfg = dict(synth.WORKLOADS[args.workload])
-    if cfg.get("kind") == "matvec":
-        bench_matvec(args, cfg, fs, synth, util, torch)
-        return
-    dtype = cfg["dtype"]
-    nsets = 3
-    sets, w0 = [], None
-    for i in range(nsets):
-        w = synth.make(args.workload, seed=cfg["seed"] + i)
-        w0 = w0 or w
-        sets.append(dict(Q=util.to_device(w["Q"], dtype), K=util.to_device(w["K"], dtype),
-                         V=util.to_device(w["V"], dtype), Omega=torch.from_numpy(w["Omega"]).cuda()))
-    s = w0["qk_scale"]
-    B, H, L, d, M = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"]
-    causal, chunk = cfg["causal"], cfg.get("chunk", 0)
+    oracle = None if args.no_cpu_baseline else OracleLeg(fs)
+    base = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "data": "synthetic"}
+    parity = {}
 
-    # fit (timed separately): statistics on the GPU, closed form on the host
-    for st_ in sets:
-        st_["theta"] = fs.fit_params("sderf", st_["Q"], st_["K"], s, groups=H)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    fs.fit_params("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H)
-    torch.cuda.synchronize()
-    fit_ms = (time.perf_counter() - t0) * 1e3
-    # the same fit with the closed form on the device (asynchronous entry point; the timing includes the final sync)
-    fit_ws = torch.empty(fs.fit_device_workspace_bytes(B, H, L, L, d, H), dtype=torch.uint8, device="cuda")
-    fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    _, fit_status = fs.fit_params_device("sderf", sets[0]["Q"], sets[0]["K"], s, groups=H, workspace=fit_ws)
-    torch.cuda.synchronize()
-    fit_device_ms = (time.perf_counter() - t0) * 1e3
-    assert int(fit_status.abs().sum().item()) == 0
-
-    nbytes = fs.attention_workspace_bytes(B, H, L, L, d, d, M, causal, H, H)
-    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    outs = [torch.empty_like(st_["V"]) for st_ in sets]
-    ev = HipEvents()
-    pairs = [(ev.create(), ev.create()) for _ in range(args.steps)]
-
-    def step(i, events=None):
-        st_ = sets[i % nsets]
-        fs.attention(st_["theta"], st_["Q"], st_["K"], st_["V"], s, st_["Omega"], causal=causal, chunk=chunk,
-                     out=outs[i % nsets], workspace=ws, events=events)
-
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)          # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, pairs[i])
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    main_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs]))
-    for a, b in pairs:
-        ev.destroy(a)
-        ev.destroy(b)
-    assert all(torch.isfinite(o.float()).all().item() for o in outs)
-
-    ms_per_step = dt / args.steps * 1e3
-    counts = algorithmic_counts(cfg)
-    achieved = counts["bytes"] / (main_ms * 1e-3) / 1e9
-    mfma_peak = MFMA_BF16_PEAK_TFLOPS if dtype == "bf16" else 157.3
-    kernel_tflops = counts["flops"] / (main_ms * 1e-3) / 1e12
-    extra = {"kernel_hbm_gbs": achieved, "kernel_hbm_frac": achieved / HBM_PEAK_GBS,
-             "kernel_mfma_tflops": kernel_tflops, "kernel_mfma_frac": kernel_tflops / mfma_peak,
-             "step_hbm_frac": counts["bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-             "step_mfma_frac": counts["flops"] / (ms_per_step * 1e-3) / 1e12 / mfma_peak}
-    if counts["bytes"] / (HBM_PEAK_GBS * 1e9) >= counts["flops"] / (mfma_peak * 1e12):
-        roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), **extra}
+    # ---- headline workload
+    name = args.workload
+    if name == "c2":
+        r = run_matvec(args.steps, args.warmup, fs, synth, torch)
+        result = {"metric": "FAVOR# kernel operator points/s (c2: N=16384 d=32 M=512 n=8, alpha=-1/2)",
+                  "value": r["points_per_s"], "unit": "points/s", **base, "ms_per_step": r["ms_per_step"], "dtype": "f32",
+                  "config": {"workload": "c2: kernel operator, fp32, X = Y, SDERF, theta and omega resident"},
+                  "roofline": r["roofline"]}
+        if oracle:
+            result["cpu_baseline"], parity["c2"] = oracle.matvec(r)
+    elif name.endswith("_backward"):
+        short = name.split("_")[0]
+        r = run_backward(short, args.steps, args.warmup, fs, synth, torch)
+        cfg = r["cfg"]
+        result = {"metric": f"FAVOR# attention backward tokens/s ({short} shapes)", "value": r["tokens_per_s"],
+                  "unit": "tokens/s", **base, "ms_per_step": r["ms_per_step"], "dtype": "bf16",
+                  "config": {"workload": f"{name}: gradients of {'causal' if cfg['causal'] else 'non-causal'} attention "
+                                         f"w.r.t. Q, K, V, bf16 in and out, B={cfg['B']} H={cfg['H']} L={cfg['L']} "
+                                         f"d={cfg['d']} M={cfg['M']}, SDERF per head, theta and omega resident"},
+                  "roofline": r["roofline"]}
+        if oracle:
+            parity[name] = oracle.backward(r)
     else:
-        roofline = {"bound": "mfma", "achieved": kernel_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
-                    "frac": kernel_tflops / mfma_peak, "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), **extra}
-    result = {
-        "metric": "FAVOR# attn tokens/s, causal L=16k d=64 M=256; % of MFMA/HBM roofline",
-        "value": B * L / (ms_per_step * 1e-3),
-        "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {'causal' if causal else 'non-causal'} attention, {dtype} in / f32 "
-                               f"accumulate, B={B} H={H} L={L} d={d} M={M}"
-                               + (f" chunk={chunk}" if causal else "") + ", SDERF per head, theta and omega resident"},
-        "head_tokens_per_s": B * H * L / (ms_per_step * 1e-3),
-        "fit_ms": fit_ms,
-        "fit_device_ms": fit_device_ms,
-        "main_kernel_ms": main_ms,
-        "algorithmic_tflops": counts["flops"] / (ms_per_step * 1e-3) / 1e12,
-        # dominant kernel (k_fast_causal / k_fast_apply / k_wide_walk / the generic equivalents), against the tighter
-        # of the two rooflines on the algorithmic counts (c4: 33.6 us of HBM time against 32.1 us of MFMA time; c5 is on
-        # the MFMA side); the other one is reported beside it
-        "roofline": roofline,
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w0)
+        r = run_attention(name, args.steps, args.warmup, fs, synth, torch, nsets=2 if name == "c5" else 3,
+                          with_fit=True, calibrate_copy=args.calibrate_copy)
+        cfg = r["cfg"]
+        result = {
+            "metric": "FAVOR# attn tokens/s, causal L=16k d=64 M=256; % of MFMA/HBM roofline" if name == "c4"
+                      else f"FAVOR# attn tokens/s ({name})",
+            "value": r["tokens_per_s"], "unit": "tokens/s", **base, "ms_per_step": r["ms_per_step"],
+            "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+            "config": {"workload": describe_attention(name, cfg)},
+            "head_tokens_per_s": cfg["B"] * cfg["H"] * cfg["L"] / (r["ms_per_step"] * 1e-3),
+            "fit_ms": r["fit_ms"], "fit_device_ms": r["fit_device_ms"], "main_kernel_ms": r["main_kernel_ms"],
+            "algorithmic_tflops": r["counts"]["flops"] / (r["ms_per_step"] * 1e-3) / 1e12,
+            # dominant kernel (k_fast_causal / k_fast_apply / k_wide_walk / the generic equivalents) in `frac`, the whole
+            # call in `call_frac`, both against the tighter of the two bounds on the algorithmic counts
+            "roofline": r["roofline"],
+        }
+        if oracle:
+            if name in ("c1", "c4"):
+                result["cpu_baseline"], parity[name] = oracle.attention_full(r, 20.0 if name == "c4" else 5.0)
+            else:
+                parity[name] = oracle.attention_sampled(r, 2, 24)
+    free(r, torch)
+
+    # ---- the other workloads, same run, fewer steps
+    if not args.only and name == "c4":
+        steps, warmup = max(5, min(args.steps, 10)), max(2, min(args.warmup, 3))
+        others = {}
+        for other in ("c1", "c3", "c5"):
+            r = run_attention(other, steps, warmup, fs, synth, torch, nsets=2 if other == "c5" else 3, with_fit=other == "c5")
+            others[other] = summary_of(r)
+            others[other]["workload"] = describe_attention(other, r["cfg"])
+            if other == "c5":
+                others[other]["fit_ms"], others[other]["fit_device_ms"] = r["fit_ms"], r["fit_device_ms"]
+            if oracle:
+                parity[other] = oracle.attention_full(r, 5.0)[1] if other == "c1" else oracle.attention_sampled(r, 2, 24)
+            free(r, torch)
+        r = run_matvec(steps, warmup, fs, synth, torch)
+        others["c2"] = {"ms_per_step": r["ms_per_step"], "points_per_s": r["points_per_s"], "main_kernel_ms": None,
+                        "roofline": r["roofline"],
+                        "workload": "c2: kernel operator, fp32, N=16384 d=32 M=512 n=8, alpha=-1/2, X = Y, SDERF"}
+        if oracle:
+            others["c2"]["cpu_baseline"], parity["c2"] = oracle.matvec(r)
+        free(r, torch)
+        for short in ("c3", "c4"):
+            r = run_backward(short, steps, warmup, fs, synth, torch)
+            others[f"{short}_backward"] = {"ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"],
+                                           "main_kernel_ms": None, "roofline": r["roofline"],
+                                           "workload": f"{short} shapes: gradients w.r.t. Q, K, V, bf16 in and out"}
+            if oracle:
+                parity[f"{short}_backward"] = oracle.backward(r)
+            free(r, torch)
+        result["workloads"] = others
+        result["workloads_steps"], result["workloads_warmup"] = steps, warmup
+    if oracle:
+        result["parity"] = parity
+    elif "cpu_baseline" not in result:
+        result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)
 
 
