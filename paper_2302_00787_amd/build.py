@@ -12,12 +12,13 @@ OBJ = os.path.join(HERE, "_build")
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # Per-source extra flags.  Kernels that fit in 256 registers keep their MFMA results in ordinary vector registers
-# (no accumulator-register copies before the exp2 / convert steps).
+# (no accumulator-register copies before the exp2 / convert steps).  The files that use LDS float-maximum atomics from
+# a few lanes switch the compiler's wave-level pre-reduction of atomics off (it would turn each into a lane loop).
 SOURCES = {
     "favorsharp_api.hip": [],
     "kernels_generic.hip": [],
-    "kernels_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "kernels_bf16_causal.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "kernels_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
+    "kernels_bf16_causal.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
     "kernels_bf16_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_bwd_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],

@@ -129,6 +129,61 @@ struct FastArgs {
   float scale;
 };
 
+// ---- transposing LDS reads ----------------------------------------------------------------------------------------
+// ds_read_b64_tr_b16: every lane supplies the address of an 8-byte piece (four bf16 numbers); inside each row of 16
+// lanes the lane (a, b) = (c / 4, c % 4) receives element b of the pieces addressed by lanes a, 4 + a, 8 + a, 12 + a.
+// With lane c pointing at row c / 4 and 8-byte column group c % 4 of a row-major 4 x 16 block, lane c therefore
+// receives column c of rows 0 .. 3: the block read column-wise, which is what an MFMA operand needs when its
+// contraction index runs along the rows of the tile in memory.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ u32x2 lds_read_tr(const uint16_t* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
+  return __builtin_bit_cast(u32x2, v);
+}
+__device__ __forceinline__ bf16x8 join8(u32x2 lo, u32x2 hi) {
+  const u32x4 v = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Float maximum into an LDS word (every active lane takes part; the file is compiled with the compiler's wave-level
+// pre-reduction of atomics switched off: a handful of lanes hit one address, which the LDS serialises cheaply).
+__device__ __forceinline__ void lds_fmax(float* p, float v) {
+  __builtin_amdgcn_ds_fmaxf((__attribute__((address_space(3))) float*)p, v, 0, 0, false);
+}
+
+// Value rows kept row-major in LDS ([token][column]): 160-byte rows = 64 values, a one (the normaliser column) and
+// 15 zeros; 40 dwords per row, so that the four rows a transposing read touches per column group start 8 banks apart.
+constexpr int LDV = DVP;
+
+// Value operand of token pair jp and column tile vt: lane <-> column 16 vt + c, contraction index <-> tokens
+// {32 jp + 4g + r, 32 jp + 16 + 4g + r} (lane c addresses row 4g + c/4 of the pair's first / second tile, column
+// group c%4 of the tile, and receives column 4 (c/4) + c%4 = c of rows 4g .. 4g+3).
+__device__ __forceinline__ bf16x8 load_vop_tr(const uint16_t (*v)[LDV], int jp, int vt, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  const uint16_t* p = &v[32 * jp + 4 * g + (c >> 2)][16 * vt + 4 * (c & 3)];
+  return join8(lds_read_tr(p), lds_read_tr(p + 16 * LDV));
+}
+
+// The constant columns 64 .. 79 of `rows` value rows: a one, then zeros (the staging writes columns 0 .. 63 only).
+__device__ __forceinline__ void init_value_pad(uint16_t (*v)[LDV], int rows, int nthreads) {
+  for (int idx = threadIdx.x; idx < rows * (LDV - D); idx += nthreads) {
+    const int row = idx / (LDV - D), col = idx % (LDV - D);
+    v[row][D + col] = col == 0 ? 0x3f80 : 0;
+  }
+}
+
+// Squared norms of the 16 rows of a token tile as the diagonal of X X^T on the MFMA pipe (products of bf16 numbers
+// are exact in fp32; the sum is an fp32 sum).  `x0`, `x1`: the tile as MFMA operand (lane <-> row c, contraction
+// index 32 ks + 8g + e), which serves as both operands.  The entry of row c sits in lane (g, c) = (c / 4, c),
+// register c % 4: the returned value is the squared norm of row c in those 16 lanes (garbage in the others).
+__device__ __forceinline__ float tile_row_norms(bf16x8 x0, bf16x8 x1, int lane) {
+  f32x4 gm = mfma(x0, x0, f32x4{0.f, 0.f, 0.f, 0.f});
+  gm = mfma(x1, x1, gm);
+  const int r = lane & 3;
+  return r == 0 ? gm[0] : r == 1 ? gm[1] : r == 2 ? gm[2] : gm[3];
+}
+
 // ---- staging: global -> registers (one chunk ahead) -> LDS -------------------------------------------------------
 // Rows: each thread carries two 16-byte pieces of a 64 x 64 bf16 tile: piece q = tid + 256 i -> row q/8, bytes 16 (q%8).
 struct RowRegs { u32x4 p[2]; };
