@@ -199,6 +199,34 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
                                void* event_main_begin, void* event_main_end);
 
 /*
+ * Attention with the projection constants kept across calls.  The evaluation recipe of Section 4 precomputes
+ * B^T omega once per parameter set; favorsharp_attention does so on every call because theta and Omega may have
+ * changed.  When they have not, favorsharp_attention_prepare computes the constants (W~ = log2e qk_scale Omega B of
+ * both sides as bf16, the per-feature terms log2e (omega^T A omega + log D - 1/2 log M) and the row norms of W~)
+ * into a caller-owned buffer once, and favorsharp_attention_prepared runs the rest of favorsharp_attention from
+ * it.  Results are bit-identical to favorsharp_attention with the same theta, Omega and qk_scale.
+ *   favorsharp_prepared_bytes: size of that buffer; 0 for shapes without constants to keep (the kernels that keep
+ *     them are the bf16 ones: d = dv = 64 with M = 256, and d = dv = 128 with M = 512).
+ *   favorsharp_attention_prepare: theta, Omega, groups as in favorsharp_attention; prepared: device, overwritten;
+ *     host_dense_c2 (HOST pointer, out): 1 if some parameter set has a C2 other than -I/2 (ADERF, SADERF: the key
+ *     row terms y^T C2 y then still have to be recomputed from K on every call), else 0.  SYNCHRONOUS with respect to
+ *     `stream`.  FS_ERR_UNSUPPORTED for shapes with favorsharp_prepared_bytes = 0.
+ *   favorsharp_attention_prepared: `prepared`, `dense_c2` as left / reported by favorsharp_attention_prepare for the
+ *     same theta, Omega, groups, omega_groups, B, H, d, M and qk_scale (the caller vouches for that: the buffer is
+ *     not checked); all other arguments, the workspace and the statuses as favorsharp_attention.  Asynchronous.
+ */
+size_t favorsharp_prepared_bytes(int B, int H, int d, int M, int groups, int omega_groups);
+int favorsharp_attention_prepare(const float* theta, int groups, const float* Omega, int omega_groups,
+                                 int B, int H, int d, int M, float qk_scale,
+                                 void* prepared, size_t prepared_bytes, int* host_dense_c2, void* stream);
+int favorsharp_attention_prepared(const void* prepared, size_t prepared_bytes, int dense_c2,
+                                  const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                  const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv,
+                                  float qk_scale, const float* Omega, int omega_groups, int M,
+                                  int causal, int chunk, const fs_tensor* Y,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * favorsharp_attention for callers that cannot allocate or pass device memory of their own: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and result as favorsharp_attention
  * minus the workspace: the scratch memory is a fixed array of FS_NOALLOC_SCRATCH_BYTES that the library holds on

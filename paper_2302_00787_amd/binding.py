@@ -75,6 +75,13 @@ def lib() -> ctypes.CDLL:
                                            c_void_p, c_int, c_int, c_int, c_int, P, c_void_p, c_size_t, c_void_p]
         L.favorsharp_attention_timed.restype = c_int
         L.favorsharp_attention_timed.argtypes = L.favorsharp_attention.argtypes + [c_void_p, c_void_p]
+        L.favorsharp_prepared_bytes.restype = c_size_t
+        L.favorsharp_prepared_bytes.argtypes = [c_int] * 6
+        L.favorsharp_attention_prepare.restype = c_int
+        L.favorsharp_attention_prepare.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float,
+                                                   c_void_p, c_size_t, ctypes.POINTER(c_int), c_void_p]
+        L.favorsharp_attention_prepared.restype = c_int
+        L.favorsharp_attention_prepared.argtypes = [c_void_p, c_size_t, c_int] + L.favorsharp_attention.argtypes
         L.favorsharp_attention_noalloc.restype = c_int
         L.favorsharp_attention_noalloc.argtypes = L.favorsharp_attention.argtypes[:18] + [c_void_p]
         L.favorsharp_attention_backward_workspace_bytes.restype = c_size_t
@@ -273,6 +280,43 @@ def attention(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Te
     else:       # (hipEvent_t begin, hipEvent_t end) as integers: favorsharp_attention_timed
         st = lib().favorsharp_attention_timed(*args, events[0], events[1])
     _check(st, "favorsharp_attention")
+    return out
+
+
+def prepared_bytes(B, H, d, M, groups, omega_groups) -> int:
+    return int(lib().favorsharp_prepared_bytes(B, H, d, M, groups, omega_groups))
+
+
+def attention_prepare(theta: torch.Tensor, Omega: torch.Tensor, B: int, H: int, qk_scale: float):
+    """favorsharp_attention_prepare: the projection constants of (theta, Omega) -> (prepared buffer, dense_c2)."""
+    groups = theta.shape[0] if theta.dim() == 2 else 1
+    og, M, d = (Omega.shape[0], Omega.shape[1], Omega.shape[2]) if Omega.dim() == 3 else (1, Omega.shape[0], Omega.shape[1])
+    buf = torch.empty(max(prepared_bytes(B, H, d, M, groups, og), 256), dtype=torch.uint8, device=theta.device)
+    dense = c_int(0)
+    st = lib().favorsharp_attention_prepare(theta.data_ptr(), groups, Omega.data_ptr(), og, B, H, d, M, qk_scale,
+                                            buf.data_ptr(), buf.numel(), ctypes.byref(dense), _stream())
+    _check(st, "favorsharp_attention_prepare")
+    return buf, int(dense.value)
+
+
+def attention_prepared(prepared, theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, qk_scale: float,
+                       Omega: torch.Tensor, causal: bool = False, chunk: int = 0, out: torch.Tensor | None = None,
+                       out_dtype=None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """favorsharp_attention_prepared: `prepared` = what attention_prepare returned for the same theta, Omega, qk_scale."""
+    buf, dense = prepared
+    B, H, Lq, d = Q.shape
+    Lk, dv = K.shape[2], V.shape[3]
+    groups = theta.shape[0] if theta.dim() == 2 else 1
+    og, M = (Omega.shape[0], Omega.shape[1]) if Omega.dim() == 3 else (1, Omega.shape[0])
+    if out is None:
+        out = torch.empty((B, H, Lq, dv), dtype=out_dtype or Q.dtype, device=Q.device)
+    ws = _workspace(attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, og), Q.device, workspace)
+    dq, dk, dvv, dy = _desc4(Q), _desc4(K), _desc4(V), _desc4(out)
+    st = lib().favorsharp_attention_prepared(buf.data_ptr(), buf.numel(), dense, theta.data_ptr(), groups, ctypes.byref(dq),
+                                             ctypes.byref(dk), ctypes.byref(dvv), B, H, Lq, Lk, d, dv, qk_scale,
+                                             Omega.data_ptr(), og, M, int(causal), chunk, ctypes.byref(dy), ws.data_ptr(),
+                                             ws.numel(), _stream())
+    _check(st, "favorsharp_attention_prepared")
     return out
 
 

@@ -142,6 +142,32 @@ int scratch_for_current_device(void** out) {
   return FS_OK;
 }
 
+// Layout of the buffer favorsharp_attention_prepare fills: a header word (bit 0: some parameter set has a dense C2),
+// then the projection constants of the bf16 kernels.
+struct PreparedPlan {
+  int Mk, dk;            // the kernels' M and d (0: no bf16 kernels for this shape)
+  size_t off_flag, off_Wbf, off_bias, off_wnorm, total;
+};
+
+void plan_prepared(int d, int M, int pgroups, PreparedPlan* p) {
+  p->Mk = p->dk = 0;
+  p->total = 0;
+  if (fast_supported(FS_BF16, d, d, M)) { p->Mk = 256; p->dk = 64; }
+  else if (wide_supported(FS_BF16, d, d, M, 1)) { p->Mk = 512; p->dk = 128; }
+  else return;
+  size_t off = 0;
+  p->off_flag = off;  off = align_up(off + sizeof(int));
+  p->off_Wbf = off;   off = align_up(off + (size_t)pgroups * 2 * p->Mk * p->dk * sizeof(uint16_t));
+  p->off_bias = off;  off = align_up(off + (size_t)pgroups * 2 * p->Mk * sizeof(float));
+  p->off_wnorm = off; off = align_up(off + (size_t)pgroups * 2 * p->Mk * sizeof(float));
+  p->total = off;
+}
+
+int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V, int B,
+                   int H, int Lq, int Lk, int d, int dv, float qk_scale, const float* Omega, int omega_groups, int M,
+                   int causal, int chunk, const fs_tensor* Y, void* workspace, size_t workspace_bytes, void* stream,
+                   void* event_main_begin, void* event_main_end, const void* prepared, int dense_c2);
+
 int device_lds_limit() {
   int dev_id = 0, v = 0;
   if (hipGetDevice(&dev_id) != hipSuccess) return 0;
@@ -352,6 +378,69 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
                                const float* Omega, int omega_groups, int M, int causal, int chunk,
                                const fs_tensor* Y, void* workspace, size_t workspace_bytes, void* stream,
                                void* event_main_begin, void* event_main_end) {
+  return attention_impl(theta, groups, Q, K, V, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M, causal, chunk, Y,
+                        workspace, workspace_bytes, stream, event_main_begin, event_main_end, nullptr, 0);
+}
+
+size_t favorsharp_prepared_bytes(int B, int H, int d, int M, int groups, int omega_groups) {
+  if (B < 1 || H < 1 || d < 1 || M < 1 || !groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
+  PreparedPlan pp;
+  plan_prepared(d, M, std::max(groups, omega_groups), &pp);
+  return pp.total;
+}
+
+int favorsharp_attention_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int B, int H,
+                                 int d, int M, float qk_scale, void* prepared, size_t prepared_bytes,
+                                 int* host_dense_c2, void* stream) {
+  if (B < 1 || H < 1 || d < 1 || M < 1 || !groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H))
+    return FS_ERR_INVALID_ARG;
+  if (theta == nullptr || Omega == nullptr || prepared == nullptr || host_dense_c2 == nullptr || !(qk_scale > 0.f))
+    return FS_ERR_INVALID_ARG;
+  const int pgroups = std::max(groups, omega_groups);
+  PreparedPlan pp;
+  plan_prepared(d, M, pgroups, &pp);
+  if (pp.total == 0) return FS_ERR_UNSUPPORTED;
+  if (prepared_bytes < pp.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t st = (hipStream_t)stream;
+  char* p8 = (char*)prepared;
+  int* flag = (int*)(p8 + pp.off_flag);
+  if (int rc = launch_fill_u32((uint32_t*)flag, 0u, 1, st)) return rc;
+  const int rc = pp.dk == 64
+      ? launch_fast_prepare(theta, groups, Omega, omega_groups, pgroups, B, H, qk_scale, (uint16_t*)(p8 + pp.off_Wbf),
+                            (float*)(p8 + pp.off_bias), (float*)(p8 + pp.off_wnorm), flag, st)
+      : launch_wide_prepare(theta, groups, Omega, omega_groups, pgroups, B, H, qk_scale, (uint16_t*)(p8 + pp.off_Wbf),
+                            (float*)(p8 + pp.off_bias), (float*)(p8 + pp.off_wnorm), flag, st);
+  if (rc) return rc;
+  int host_flag = 0;
+  if (hipMemcpyAsync(&host_flag, flag, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return FS_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;
+  *host_dense_c2 = host_flag & 1;
+  return FS_OK;
+}
+
+int favorsharp_attention_prepared(const void* prepared, size_t prepared_bytes, int dense_c2, const float* theta,
+                                  int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V, int B, int H,
+                                  int Lq, int Lk, int d, int dv, float qk_scale, const float* Omega, int omega_groups,
+                                  int M, int causal, int chunk, const fs_tensor* Y, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (prepared == nullptr || (dense_c2 != 0 && dense_c2 != 1)) return FS_ERR_INVALID_ARG;
+  if (B < 1 || H < 1 || d < 1 || M < 1 || !groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H))
+    return FS_ERR_INVALID_ARG;
+  PreparedPlan pp;
+  plan_prepared(d, M, std::max(groups, omega_groups), &pp);
+  if (pp.total == 0 || dv != d) return FS_ERR_UNSUPPORTED;
+  if (prepared_bytes < pp.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  return attention_impl(theta, groups, Q, K, V, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M, causal, chunk, Y,
+                        workspace, workspace_bytes, stream, nullptr, nullptr, prepared, dense_c2);
+}
+
+}  // extern "C"
+
+namespace {
+int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V, int B,
+                   int H, int Lq, int Lk, int d, int dv, float qk_scale, const float* Omega, int omega_groups, int M,
+                   int causal, int chunk, const fs_tensor* Y, void* workspace, size_t workspace_bytes, void* stream,
+                   void* event_main_begin, void* event_main_end, const void* prepared, int dense_c2) {
   if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
@@ -383,6 +472,13 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     f.Wbf = (uint16_t*)(w8 + fp.off_Wbf); f.bias = (float*)(w8 + fp.off_bias); f.wnorm = (float*)(w8 + fp.off_wnorm);
     f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
     f.cstar = (float*)(w8 + fp.off_cstar);
+    if (prepared != nullptr) {
+      PreparedPlan pp;
+      plan_prepared(d, M, pgroups, &pp);
+      char* p8 = (char*)const_cast<void*>(prepared);
+      f.Wbf = (uint16_t*)(p8 + pp.off_Wbf); f.bias = (float*)(p8 + pp.off_bias); f.wnorm = (float*)(p8 + pp.off_wnorm);
+      f.pre_mode = dense_c2 ? 1 : 2;
+    }
     return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
   }
   if (wide_supported(Q->dtype, d, dv, M, causal) && small_strides && (int)wide_lds_bytes() <= lds_limit) {
@@ -397,8 +493,17 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
     f.Wbf = (uint16_t*)(w8 + wp.off_Wbf); f.bias = (float*)(w8 + wp.off_bias); f.wnorm = (float*)(w8 + wp.off_wnorm);
     f.rk = (float*)(w8 + wp.off_rk); f.Tpart = (float*)(w8 + wp.off_state); f.cpart = (float*)(w8 + wp.off_cpart);
     f.cstar = (float*)(w8 + wp.off_cstar); f.Ypart = (float*)(w8 + wp.off_ypart);
+    if (prepared != nullptr) {
+      PreparedPlan pp;
+      plan_prepared(d, M, pgroups, &pp);
+      char* p8 = (char*)const_cast<void*>(prepared);
+      f.Wbf = (uint16_t*)(p8 + pp.off_Wbf); f.bias = (float*)(p8 + pp.off_bias); f.wnorm = (float*)(p8 + pp.off_wnorm);
+      f.pre_mode = dense_c2 ? 1 : 2;
+    }
     return launch_wide_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
   }
+  // the general-shape kernels keep no constants across calls: a prepared call of such a shape (other dtype, strides
+  // beyond 32-bit offsets) recomputes them like favorsharp_attention
   AttnPlan p;
   plan_contraction(BH, pgroups, Lk, d, M, dv + 1, causal, &p);
   const size_t lds_need = causal ? gen_lds_causal(d, p.ldt) : std::max(gen_lds_state(d, p.ldt), gen_lds_apply(d, p.ldt));
@@ -433,6 +538,9 @@ int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* 
   if (event_main_end && hipEventRecord((hipEvent_t)event_main_end, st) != hipSuccess) return FS_ERR_DEVICE;
   return FS_OK;
 }
+}  // namespace
+
+extern "C" {
 
 int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
                                  const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv, float qk_scale,

@@ -92,6 +92,10 @@ struct FastLaunch {
   float* Tpart;     // [B*H][nseg*sub][256][80]
   float* cpart;     // [B*H][nseg*sub]
   float* cstar;     // [B*H]
+  // 0: compute the projection constants and the key row terms; 1: the constants are already in Wbf / bias / wnorm
+  // (prepared by an earlier call), only the row terms of parameter sets with a dense C2 are computed; 2: the
+  // constants are there and no parameter set has a dense C2: nothing to do
+  int pre_mode = 0;
 };
 
 // bf16 path for causal calls with d = dv = 128, M = 512 (kernels_bf16_wide.hip).
@@ -111,8 +115,15 @@ struct WideLaunch {
   float* cpart;     // [B*H][nslot]
   float* cstar;     // [B*H]
   float* Ypart;     // [B*H][L][132]
+  int pre_mode = 0; // as in FastLaunch
 };
 bool wide_supported(int dtype, int d, int dv, int M, int causal);
+// Projection constants only (for a later call with pre_mode 1 or 2); *dense_flag (device) is or-ed with 1 if any of
+// the parameter sets the kernel visits has a dense C2.
+int launch_wide_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                        float scale, uint16_t* Wbf, float* bias, float* wnorm, int* dense_flag, hipStream_t st);
+int launch_fast_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                        float scale, uint16_t* Wbf, float* bias, float* wnorm, int* dense_flag, hipStream_t st);
 size_t wide_lds_bytes();
 void wide_plan(int BH, int L, int* nslot, int* rows_per_slot);
 int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);

@@ -21,18 +21,22 @@ using namespace fast;
 // workgroups of sets with the -I/2 flag return at once (the kernels then use -|y|^2/2).  One wave per token
 // (grid-stride over the tokens of a sequence), lane a handles row a of C2.
 // ---------------------------------------------------------------------------------------------------
+// `first_block` is added to the block index (a launch of the row-term part alone starts at 128 pgroups);
+// dense_flag (optional) is or-ed with 1 when a visited parameter set has a dense C2.
 __global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups, const float* Omega, int omega_groups,
                                                   int pgroups, int B, int H, float scale, uint16_t* Wbf, float* bias,
-                                                  float* wnorm, TensorDev K, int L, int rowblocks, float* rk) {
+                                                  float* wnorm, TensorDev K, int L, int rowblocks, float* rk,
+                                                  int first_block, int* dense_flag) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D;
-  const int nprep = (M / 4) * 2 * pgroups;
-  if ((int)blockIdx.x < nprep) {
-    const int pg = blockIdx.x / ((M / 4) * 2), rem = blockIdx.x % ((M / 4) * 2), side = rem / (M / 4);
+  const int nprep = (M / 4) * 2 * pgroups, block = blockIdx.x + first_block;
+  if (block < nprep) {
+    const int pg = block / ((M / 4) * 2), rem = block % ((M / 4) * 2), side = rem / (M / 4);
     const int m = (rem % (M / 4)) * 4 + (threadIdx.x >> 6), c = threadIdx.x & 63;
     int b = 0, h = 0;
     if (pgroups == H && pgroups != 1) h = pg;
     else if (pgroups != 1) { b = pg / H; h = pg % H; }
     const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
+    if (dense_flag != nullptr && rem == 0 && threadIdx.x == 0 && !(((int)th[2]) & 1)) atomicOr(dense_flag, 1);
     const float* om = Omega + ((size_t)group_of(omega_groups, b, h, H) * M + m) * D;
     const float* Bm = th + FS_THETA_HEADER_ + D + (side ? (size_t)D * D : 0);
     const float* A = th + FS_THETA_HEADER_;
@@ -52,7 +56,7 @@ __global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups
     }
     return;
   }
-  const int rb = blockIdx.x - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
+  const int rb = block - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
   const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
   if (((int)th[2]) & 1) return;
   const float* C2 = th + FS_THETA_HEADER_ + D + 3 * (size_t)D * D;
@@ -444,10 +448,18 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   a.sub = f.sub; a.nslot = f.nseg * f.sub;
   a.scale = f.scale;
   const int BH = f.B * f.H;
-  const int rowblocks = std::min(64, (f.Lk + 3) / 4);
-  hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * f.pgroups + rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
-                     f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk);
-  FS_LAUNCH_CHECK();
+  const int rowblocks = std::min(64, (f.Lk + 3) / 4), nprep = (M / 4) * 2 * f.pgroups;
+  if (f.pre_mode == 0) {
+    hipLaunchKernelGGL(k_fast_pre, dim3(nprep + rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
+                       f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk, 0,
+                       (int*)nullptr);
+    FS_LAUNCH_CHECK();
+  } else if (f.pre_mode == 1) {      // the key row terms alone
+    hipLaunchKernelGGL(k_fast_pre, dim3(rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
+                       f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk,
+                       nprep, (int*)nullptr);
+    FS_LAUNCH_CHECK();
+  }
   // the last segment's states are never needed by the causal pass
   const int nstate = (f.causal && !every_slot ? f.nseg - 1 : f.nseg) * f.sub;
   if (nstate > 0) {
@@ -456,6 +468,14 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   }
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
                      a.nslot, nstate, f.causal, every_slot ? 1 : f.sub);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
+int launch_fast_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                        float scale, uint16_t* Wbf, float* bias, float* wnorm, int* dense_flag, hipStream_t st) {
+  hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * pgroups), dim3(256), 0, st, theta, groups, Omega, omega_groups, pgroups,
+                     B, H, scale, Wbf, bias, wnorm, TensorDev{nullptr, 1, 0, 0, 0}, 0, 1, (float*)nullptr, 0, dense_flag);
   FS_LAUNCH_CHECK();
   return 0;
 }

@@ -68,17 +68,18 @@ __device__ __forceinline__ float sum16(float v) {
 // grid 128 * 2 * pgroups + rowblocks * B*H workgroups of 256 threads; see k_fast_pre.  One wave per feature, lane c
 // handles columns c and c + 64; for the row terms one wave per token, lane a handles rows a and a + 64 of C2.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks) {
+__global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks, int first_block, int* dense_flag) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW;
-  const int nprep = (MW / 4) * 2 * a.pgroups, H = a.H;
+  const int nprep = (MW / 4) * 2 * a.pgroups, H = a.H, block = blockIdx.x + first_block;
   const int c = threadIdx.x & 63;
-  if ((int)blockIdx.x < nprep) {
-    const int pg = blockIdx.x / ((MW / 4) * 2), rem = blockIdx.x % ((MW / 4) * 2), side = rem / (MW / 4);
+  if (block < nprep) {
+    const int pg = block / ((MW / 4) * 2), rem = block % ((MW / 4) * 2), side = rem / (MW / 4);
     const int m = (rem % (MW / 4)) * 4 + (threadIdx.x >> 6);
     int b = 0, h = 0;
     if (a.pgroups == H && a.pgroups != 1) h = pg;
     else if (a.pgroups != 1) { b = pg / H; h = pg % H; }
     const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
+    if (dense_flag != nullptr && rem == 0 && threadIdx.x == 0 && !(((int)th[2]) & 1)) atomicOr(dense_flag, 1);
     const float* om = a.Omega + ((size_t)group_of(a.omega_groups, b, h, H) * MW + m) * DW;
     const float* Bm = th + FS_THETA_HEADER_ + DW + (side ? (size_t)DW * DW : 0);
     const float* A = th + FS_THETA_HEADER_;
@@ -102,7 +103,7 @@ __global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks) {
     }
     return;
   }
-  const int rb = blockIdx.x - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
+  const int rb = block - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
   if (((int)th[2]) & 1) return;
   const float* C2 = th + FS_THETA_HEADER_ + DW + 3 * (size_t)DW * DW;
@@ -543,6 +544,16 @@ void wide_plan(int BH, int L, int* nslot, int* rows_per_slot) {
 
 #define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
 
+int launch_wide_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
+                        float scale, uint16_t* Wbf, float* bias, float* wnorm, int* dense_flag, hipStream_t st) {
+  WideArgs a = {};
+  a.theta = theta; a.Omega = Omega; a.Wbf = Wbf; a.bias = bias; a.wnorm = wnorm;
+  a.groups = groups; a.omega_groups = omega_groups; a.pgroups = pgroups; a.B = B; a.H = H; a.scale = scale;
+  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * pgroups), dim3(256), 0, st, a, 1, 0, dense_flag);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
+
 int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   WideArgs a;
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
@@ -557,9 +568,14 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
     (void)hipGetLastError();
     return 2;
   }
-  const int rowblocks = std::min(64, (f.L + 3) / 4);
-  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * f.pgroups + rowblocks * BH), dim3(256), 0, st, a, rowblocks);
-  FS_LAUNCH_CHECK();
+  const int rowblocks = std::min(64, (f.L + 3) / 4), nprep = (MW / 4) * 2 * f.pgroups;
+  if (f.pre_mode == 0) {
+    hipLaunchKernelGGL(k_wide_pre, dim3(nprep + rowblocks * BH), dim3(256), 0, st, a, rowblocks, 0, (int*)nullptr);
+    FS_LAUNCH_CHECK();
+  } else if (f.pre_mode == 1) {      // the key row terms alone
+    hipLaunchKernelGGL(k_wide_pre, dim3(rowblocks * BH), dim3(256), 0, st, a, rowblocks, nprep, (int*)nullptr);
+    FS_LAUNCH_CHECK();
+  }
   hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
   FS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot);

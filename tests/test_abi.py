@@ -79,6 +79,20 @@ def test_noalloc_entry_point_rejects_sizes_beyond_its_scratch_array_before_any_d
                                             P(t), None) == 1
 
 
+def test_prepared_entry_points_validate_before_any_device_work(lib):
+    from paper_2302_00787_amd.binding import FsTensor
+    t = FsTensor(None, 1, 0, 0, 64)
+    P = ctypes.byref
+    assert lib.favorsharp_prepared_bytes(4, 8, 64, 256, 8, 8) > 2 * 8 * 2 * 256 * 64
+    assert lib.favorsharp_prepared_bytes(1, 16, 128, 512, 16, 16) > 0
+    assert lib.favorsharp_prepared_bytes(1, 1, 16, 64, 1, 1) == 0          # no constants are kept for this shape
+    dense = ctypes.c_int(7)
+    assert lib.favorsharp_attention_prepare(None, 8, None, 8, 4, 8, 64, 256, 1.0, None, 0, ctypes.byref(dense), None) == 1
+    assert lib.favorsharp_attention_prepared(None, 0, 0, None, 8, P(t), P(t), P(t), 4, 8, 64, 64, 64, 64, 1.0, None, 8, 256,
+                                             1, 64, P(t), None, 0, None) == 1
+    assert dense.value == 7
+
+
 def test_pack_and_unpack_theta_roundtrip():
     import numpy as np
     from paper_2302_00787_amd import binding

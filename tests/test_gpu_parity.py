@@ -590,6 +590,30 @@ def test_attention_call_replays_from_a_hip_graph(fs, name, over):
         _ = torch.randn(1 << 20, device="cuda").sum().item()
 
 
+@pytest.mark.parametrize("name,over,variant", [("c4", dict(B=2, H=2, L=1216), "sderf"), ("c4", dict(B=1, H=2, L=333), "aderf"),
+                                               ("c3", dict(B=2, H=2, L=712), "sderf"), ("c5", dict(B=1, H=2, L=832), "sderf"),
+                                               ("c5", dict(B=1, H=2, L=200), "aderf")])
+def test_prepared_constants_give_the_same_bits(fs, name, over, variant):
+    """favorsharp_attention_prepare + favorsharp_attention_prepared against favorsharp_attention: the projection
+    constants are the same numbers, so the outputs agree bit for bit; a second prepared call on other data of the
+    same shapes reuses the buffer (dense C2: the key row terms are recomputed per call)."""
+    import torch
+    w = synth.make(name, **over)
+    s, causal = w["qk_scale"], bool(w["causal"])
+    theta = torch.from_numpy(_fit_theta_block(variant, w["Q"], w["K"], s, None)).cuda()
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    prepared = fs.attention_prepare(theta, Om, w["B"], w["H"], s)
+    assert prepared[1] == (1 if variant == "aderf" else 0)
+    for seed in (w["seed"], w["seed"] + 7):
+        w2 = synth.make(name, **dict(over, seed=seed))
+        Qd, Kd, Vd = (util.to_device(w2[k], "bf16") for k in ("Q", "K", "V"))
+        want = fs.attention(theta, Qd, Kd, Vd, s, Om, causal=causal, chunk=64 if causal else 0)
+        got = fs.attention_prepared(prepared, theta, Qd, Kd, Vd, s, Om, causal=causal, chunk=64 if causal else 0)
+        torch.cuda.synchronize()
+        assert torch.isfinite(want.float()).all().item()
+        assert torch.equal(got, want), (name, variant, seed)
+
+
 @pytest.mark.parametrize("name", ["c3", "c4", "c5"])
 def test_bf16_path_is_bitwise_reproducible(fs, name):
     """The kernels use no atomics and every LDS region is ordered by workgroup barriers, so two runs on the same
