@@ -22,6 +22,7 @@ SOURCES = {
     "kernels_bf16_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_bwd_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "kernels_op.hip": [],
     "kernels_fit.hip": [],
     "host_fit.cpp": [],
 }

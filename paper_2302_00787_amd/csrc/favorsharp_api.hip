@@ -718,7 +718,9 @@ size_t favorsharp_kernel_matvec_workspace_bytes(int Nx, int Ny, int d, int M, in
   if (Nx < 0 || Ny < 1 || d < 1 || d > 128 || M < 1 || n < 1 || n > 128) return 0;
   AttnPlan p;
   plan_contraction(1, 1, Ny, d, M, n, 0, &p);
-  return p.total;
+  size_t total = p.total;
+  if (op_supported(FS_F32, FS_F32, d, M, n)) total = std::max(total, align_up(op_workspace_floats(Ny, d, M) * sizeof(float)));
+  return total;
 }
 
 int favorsharp_kernel_matvec(const float* theta, const fs_tensor* X, const fs_tensor* Y, int Nx, int Ny, int d,
@@ -732,8 +734,12 @@ int favorsharp_kernel_matvec(const float* theta, const fs_tensor* X, const fs_te
   if (Nx > 0 && out == nullptr) return FS_ERR_INVALID_ARG;
   AttnPlan p;
   plan_contraction(1, 1, Ny, d, M, n, 0, &p);
-  if (workspace_bytes < p.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  if (workspace_bytes < favorsharp_kernel_matvec_workspace_bytes(Nx, Ny, d, M, n)) return FS_ERR_WORKSPACE_TOO_SMALL;
   if (Nx == 0) return FS_OK;
+  // fp32 rows, a few right-hand sides: the dedicated kernels (contiguous columns, rows addressed by stride_l)
+  if (op_supported(X->dtype, Y->dtype, d, M, n))
+    return launch_op_matvec(theta, dev(X), dev(Y), Nx, Ny, d, qk_scale, alpha, Omega, M, C, n, out, (float*)workspace,
+                            (hipStream_t)stream);
   if ((int)std::max(gen_lds_state(d, p.ldt), gen_lds_apply(d, p.ldt)) > device_lds_limit()) return FS_ERR_UNSUPPORTED;
 
   hipStream_t st = (hipStream_t)stream;

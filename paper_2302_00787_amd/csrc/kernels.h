@@ -128,6 +128,12 @@ size_t wide_lds_bytes();
 void wide_plan(int BH, int L, int* nslot, int* rows_per_slot);
 int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
 
+// fp32 kernel operator for a few right-hand sides (kernels_op.hip).
+bool op_supported(int dtype_x, int dtype_y, int d, int M, int n);
+size_t op_workspace_floats(int Ny, int d, int M);
+int launch_op_matvec(const float* theta, const TensorDev& X, const TensorDev& Y, int Nx, int Ny, int d, float scale,
+                     float alpha, const float* Omega, int M, const float* C, int n, float* out, float* ws, hipStream_t st);
+
 size_t fast_lds_bytes();
 bool fast_supported(int dtype, int d, int dv, int M);
 void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub);
