@@ -339,6 +339,9 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
   }
   float dk = a.cstar[cx.bh];
   FS_STEP_BARRIER();               // barrier 0
+  bf16x8 vop[2][NVT];              // value operands of the chunk; the first pair's are requested one step early
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt) vop[0][vt] = load_vop_tr(sm.v[0], 0, vt, lane);
   FS_STEP_BARRIER();               // barrier 1
   FS_STEP_BARRIER();               // the producers' first step
 
@@ -364,7 +367,6 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
       for (int vt = 0; vt < NVT; ++vt) tb[blk][vt] = pack8(T[2 * blk][vt], T[2 * blk + 1][vt]);
 
     bf16x8 sk[4][2];               // key feature tiles of the chunk, token-major
-    bf16x8 vop[2][NVT];            // value operands of the chunk
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
       if (S < 2) {
@@ -386,11 +388,15 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
           sk[2 * S + 1][blk] = join8(lds_read_tr(blk1 + (2 * blk) * 256 + st), lds_read_tr(blk1 + (2 * blk + 1) * 256 + st));
         }
 #pragma unroll
-        for (int vt = 0; vt < NVT; ++vt) vop[S][vt] = load_vop_tr(sm.v[buf], S, vt, lane_here);
-#pragma unroll
         for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
           for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = mfma(stv[mt], vop[S][vt], T[mt][vt]);
+        // the value rows do not wait for the producers' current step: the second pair's operands are requested ahead
+        // of the barrier, so that they have arrived behind it
+        if (S == 0) {
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) vop[1][vt] = load_vop_tr(sm.v[buf], 1, vt, lane_here);
+        }
       } else {
         // both tiles' query images are requested before the first one is used
         bf16x8 pq[2][2];
@@ -435,6 +441,12 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
 #pragma unroll
           for (int vt = 0; vt < NVT; ++vt)
             *(bf16x4*)(&sm.xch[it][j][c][16 * vt + 4 * g]) = __builtin_convertvector(y[vt], bf16x4);
+        }
+        // the next chunk's value rows are in the other buffer since the producers' step 3 of this chunk (one interval
+        // ago): its first pair's operands, ahead of the barrier
+        if (S == 3) {
+#pragma unroll
+          for (int vt = 0; vt < NVT; ++vt) vop[0][vt] = load_vop_tr(sm.v[buf ^ 1], 0, vt, lane);
         }
       }
       FS_STEP_BARRIER();
