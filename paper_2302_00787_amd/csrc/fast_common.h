@@ -123,7 +123,7 @@ struct FastArgs {
   const float* rk;         // [BH][L] key row terms for parameter sets with a dense C2, else unused
   float* Tpart;            // [BH][nslot][M][DVP], nslot = nseg * sub: one state per sub-segment
   float* cpart;            // [BH][nslot]
-  float* cstar;            // [BH]
+  float* cstar;            // [BH] largest shift of each sequence, then [BH][nslot] the shift of each slot's prefix state
   int groups, pgroups, H, L, rows_per_seg, nseg;
   int sub, nslot;          // sub-segments per segment (key-side kernel granularity) and total state slots
   float scale;

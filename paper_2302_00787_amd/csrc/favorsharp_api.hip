@@ -92,7 +92,7 @@ void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
   p->off_rk = off;     off = align_up(off + (size_t)BH * Lk * sizeof(float));
   p->off_state = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * 256 * 80 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * sizeof(float));
-  p->off_cstar = off;  off = align_up(off + (size_t)BH * sizeof(float));
+  p->off_cstar = off;  off = align_up(off + (size_t)BH * (1 + (size_t)p->nseg * p->sub) * sizeof(float));
   p->total = off;
 }
 
@@ -110,7 +110,7 @@ void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
   p->off_rk = off;     off = align_up(off + (size_t)BH * L * sizeof(float));
   p->off_state = off;  off = align_up(off + (size_t)BH * 2 * p->nslot * 256 * 144 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nslot * sizeof(float));
-  p->off_cstar = off;  off = align_up(off + (size_t)BH * sizeof(float));
+  p->off_cstar = off;  off = align_up(off + (size_t)BH * (1 + (size_t)p->nslot) * sizeof(float));
   p->off_ypart = off;  off = align_up(off + (size_t)BH * L * 132 * sizeof(float));
   p->total = off;
 }

@@ -255,18 +255,40 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
 }
 
 // Brings the segment states of one (b,h) to the common shift c* = max_seg cpart and sums them (prefix = 0: total
-// in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  grid (ceil(M*DVP/1024), B*H).
+// in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  prefix = 2: exclusive prefix sums on
+// running shifts: the prefix of slot s is scaled by the largest shift of the slots before it (written behind the
+// per-sequence shifts, at cstar[B*H + bh * nseg + s]; -inf and a zero state for slot 0), so that keys late in the
+// sequence cannot push the states the earlier rows need out of the fp32 range.  grid (ceil(M*DVP/1024), B*H).
 __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, int nseg, int nseg_valid, int prefix,
                               int sub) {
   const int bh = blockIdx.y;
   constexpr size_t per = (size_t)M * DVP;
   const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);      // four consecutive numbers per thread
+  float* p = Tpart + (size_t)bh * nseg * per + e;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  if (prefix == 2) {
+    float* cpre = cstar + gridDim.y + (size_t)bh * nseg;
+    float cr = -INFINITY;
+    for (int s = 0; s < nseg; ++s) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (s < nseg_valid && e < per) v = *(const f32x4*)(p + (size_t)s * per);
+      if (s % sub == 0) {            // only the slots that open a segment are read back
+        if (e == 0) cpre[s] = cr;
+        if (e < per) *(f32x4*)(p + (size_t)s * per) = run;
+      }
+      if (s < nseg_valid) {
+        const float c = cpart[(size_t)bh * nseg + s];
+        if (c > cr) { run *= fast_exp2(cr - c); cr = c; }
+        run += v * fast_exp2(c - cr);
+      }
+    }
+    if (e == 0) cstar[bh] = cr;
+    return;
+  }
   float cs = -INFINITY;
   for (int s = 0; s < nseg_valid; ++s) cs = fmaxf(cs, cpart[(size_t)bh * nseg + s]);
   if (e == 0) cstar[bh] = cs;
   if (e >= per) return;
-  float* p = Tpart + (size_t)bh * nseg * per + e;
-  f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 4
   for (int s = 0; s < nseg; ++s) {
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
@@ -467,7 +489,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
     FS_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
-                     a.nslot, nstate, f.causal, every_slot ? 1 : f.sub);
+                     a.nslot, nstate, f.causal ? (every_slot ? 1 : 2) : 0, every_slot ? 1 : f.sub);
   FS_LAUNCH_CHECK();
   return 0;
 }

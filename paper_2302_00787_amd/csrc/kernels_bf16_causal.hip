@@ -211,7 +211,7 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
 #pragma unroll
       for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (a.bias[((size_t)cx.pg * 2) * M + 64 * j + 16 * mt + 4 * g + r] - amax1);
   }
-  float dk = a.cstar[cx.bh];       // shift of the prefix state (-inf when there is none)
+  float dk = a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)blockIdx.x * a.sub];   // shift of the prefix state (-inf for the first segment)
 
   // first chunk to LDS, second chunk into the staging registers
   Stage stg;
@@ -337,7 +337,7 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
 #pragma unroll
         for (int r = 0; r < 4; ++r) T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * DVP + 16 * vt + c];
   }
-  float dk = a.cstar[cx.bh];
+  float dk = a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)seg * a.sub];   // shift of the prefix state
   FS_STEP_BARRIER();               // barrier 0
   bf16x8 vop[2][NVT];              // value operands of the chunk; the first pair's are requested one step early
 #pragma unroll

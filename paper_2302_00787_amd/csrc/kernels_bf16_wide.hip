@@ -8,11 +8,11 @@
 // column halves of feature half 0 and leaves UNNORMALISED partial rows (fp32) and partial normalisers; the second
 // runs feature half 1, adds the first launch's partial rows to its own in the finishing step, divides by the sum
 // of the two partial normalisers and stores Y.  All combinations share every shift (the per-row query shift and the
-// per-sequence key shift are bounds over all 512 features), so their partial rows are on one scale.
+// per-slot key shift are bounds over all 512 features), so their partial rows are on one scale.
 //
 //   k_wide_pre     projection constants for both sides (Section 4, evaluation recipe), key row terms for dense C2
 //   k_wide_state   per (slot, feature half): S^T [V 1] over the slot (eight waves of 32 features, all 129 columns)
-//   k_wide_reduce  exclusive prefix over the slots on the sequence's common shift
+//   k_wide_reduce  exclusive prefix over the slots, each on the running maximum of the slots' shifts
 //   k_wide_walk    per (slot, column half), once per feature half: the causal walk; the second launch finishes Y
 #include <algorithm>
 
@@ -44,7 +44,7 @@ struct WideArgs {
   float* rk;         // [BH][L]
   float* Tpart;      // [BH][2][nslot][256][144]
   float* cpart;      // [BH][nslot]
-  float* cstar;      // [BH]
+  float* cstar;      // [BH] largest shift of each sequence, then [BH][nslot] the key shift of each slot
   float* Ypart;      // [BH][L][132]: partial rows of feature half 0
   int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;
   int fh;            // feature half of this launch of the walk
@@ -280,24 +280,31 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
   if (tid == 0 && fh == 0) a.cpart[(size_t)bh * a.nslot + slot] = dk;
 }
 
-// Exclusive prefix over the slots of one (b,h, feature half) on the common shift c* = max over the slots' shifts
-// (written to cstar).  Four consecutive numbers per thread.  grid (ceil(256*144/1024), B*H*2).
+// Exclusive prefix over the slots of one (b,h, feature half) on running shifts: the prefix of slot s is scaled by
+// the largest shift of the slots up to and including s, which is also the key shift of the slot's walk (written to
+// cstar[B*H + bh * nslot + s]; cstar[bh] = the sequence's largest).  Keys late in the sequence thus cannot push the
+// states that earlier rows need out of the fp32 range.  Four consecutive numbers per thread.
+// grid (ceil(256*144/1024), B*H*2).
 __global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot) {
   const int bh2 = blockIdx.y, bh = bh2 >> 1;
   constexpr size_t per = (size_t)256 * TLD;
   const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
-  float cs = -INFINITY;
-  for (int s = 0; s < nslot; ++s) cs = fmaxf(cs, cpart[(size_t)bh * nslot + s]);
-  if (e == 0 && (bh2 & 1) == 0) cstar[bh] = cs;
-  if (e >= per) return;
+  const bool writer = e == 0 && (bh2 & 1) == 0;
+  float* cpre = cstar + (gridDim.y >> 1) + (size_t)bh * nslot;
   float* p = Tpart + (size_t)bh2 * nslot * per + e;
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
+  float cr = -INFINITY;
   for (int s = 0; s < nslot; ++s) {
-    const f32x4 v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nslot + s] - cs);
-    *(f32x4*)(p + (size_t)s * per) = run;
-    run += v;
+    const float c = cpart[(size_t)bh * nslot + s];
+    if (c > cr) { run *= fast_exp2(cr - c); cr = c; }
+    if (writer) cpre[s] = cr;
+    if (e < per) {
+      const f32x4 v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(c - cr);
+      *(f32x4*)(p + (size_t)s * per) = run;
+      run += v;
+    }
   }
+  if (writer) cstar[bh] = cr;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -497,7 +504,7 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   cx.fh = a.fh;
   cx.ch = blockIdx.z;
   cx.pg = group_of(a.pgroups, b, h, a.H);
-  cx.cs = a.cstar[bh];
+  cx.cs = a.cstar[gridDim.y + (size_t)bh * a.nslot + slot];     // the slot's key shift (k_wide_reduce)
   cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   cx.Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
   cx.Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;

@@ -508,6 +508,36 @@ def test_bf16_path_extreme_scales_stay_finite(fs):
     _check_attention(fs, Q, K, w["V"], w["Omega"], w["qk_scale"], True, "posrf", "bf16")
 
 
+@pytest.mark.parametrize("name,L,stretch", [("c4", 1024, 2.2), ("c5", 2048, 1.7)])
+def test_bf16_causal_late_key_with_a_huge_bound_leaves_earlier_rows_intact(fs, name, L, stretch):
+    """The key shift follows a Cauchy-Schwarz bound over all features (the bound less 120 binary orders); for a key
+    whose norm matches the longest omega it is far above the key's actual features.  Omega is stretched here so that
+    this shift exceeds 2^200 for one key late in the sequence (its own features stay negligible): on a shift common
+    to the whole sequence the states of every earlier segment would leave the fp32 range.  The prefix states are kept on running shifts instead, so every
+    row in a segment before the outlier's must stay within tolerance; the rows behind it are beyond the documented
+    range of the shifts (their state is rescaled by the bound) and are only required to be finite."""
+    import torch
+    w = synth.make(name, B=1, H=1, L=L, seed=17)
+    Q, K, V, s, d = w["Q"], w["K"].copy(), w["V"], w["qk_scale"], w["d"]
+    Om = (stretch * w["Omega"]).astype(np.float32)
+    longest = float(np.linalg.norm(Om[0], axis=1).max())
+    late = L - 100
+    K[0, 0, late] *= (longest / s) / np.linalg.norm(K[0, 0, late])
+    K = synth.round_to_bf16(K)
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    th = util.oracle_theta_from_vec(vec, d)
+    shift_log2 = (longest * longest / 2.0) / np.log(2.0) - 120.0
+    assert shift_log2 > 200.0, shift_log2
+    Y = fs.attention(torch.from_numpy(vec[None]).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32)
+    Yh = util.to_host(Y)[0, 0]
+    assert np.isfinite(Yh).all()
+    ref = orc.attention(th, Om[0], Q[0, 0], K[0, 0], V[0, 0], s, True)
+    safe = (late // 64) * 64           # segments and slots are whole chunks of 64 rows
+    fro, row = util.attention_errors(Yh[:safe], ref[:safe], V[0, 0, :safe].astype(np.float64))
+    assert fro <= 2e-2 and row <= 8e-2, (fro, row)
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_bf16_path_ragged_tail_with_uniformly_large_keys(fs, causal):
     """Every key rescaled to the norm 21 (in the scaled space), so that the key shift (dominated by -|y|^2/2) is
