@@ -64,6 +64,10 @@ int launch_gen_bwd_causal(const GenSide& qs, const GenSide& ks, const TensorDev&
 bool stats_bf16_supported(const TensorDev& X, const TensorDev& Y, int d);
 int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
                       int rows_per_chunk, int nchunks, float* part, hipStream_t st);
+// The same for bf16 rows of 128 numbers (kernels_bf16_wide.hip).
+bool stats_wide_supported(const TensorDev& X, const TensorDev& Y, int d);
+int launch_stats_wide(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
+                      int rows_per_chunk, int nchunks, float* part, hipStream_t st);
 // Device-resident closed-form fit (kernels_fit.hip): one workgroup per group; ws holds fit_device_workspace_doubles
 // doubles; status[g] receives an fs_status value.
 size_t fit_device_workspace_doubles(int d, int groups);

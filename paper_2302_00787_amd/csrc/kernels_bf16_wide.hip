@@ -534,9 +534,108 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Statistics scan of the fits for bf16 rows of 128 numbers (Section 4: mu4, mu5, M1, M2 are means of x, y, x x^T,
+// y y^T): per (b,h), tensor and row chunk, sum x and sum x x^T on bf16 MFMA tiles.  The rows of a 64-token tile stay
+// row-major in LDS; both operands of X^T X (lane <-> number, contraction index <-> tokens) are transposing reads,
+// and the column sums come from a constant operand of ones.  Rows of 72 dwords: the four rows that a transposing
+// read touches per group of 16 lanes start 8 banks apart, the next group's 32 banks further.  Wave w owns the Gram
+// tiles (2w .. 2w+1, 0 .. 7) and the column sums of those two blocks.  Rows past the end are staged as zeros.
+// Output layout as the general kernel's: part[which][bh][chunk][d*d + d], with qk_scale applied (squared on the
+// Gram part).  grid (nchunks, B*H, 2), block 256.
+// ---------------------------------------------------------------------------------------------------
+constexpr int LDSW = DW + 16;
+struct SmemWStats { __attribute__((aligned(16))) uint16_t x[2][TC][LDSW]; };
+
+// lane <-> number 16 ct + c, contraction index <-> tokens {32 jp + 4g + r, 32 jp + 16 + 4g + r}
+__device__ __forceinline__ bf16x8 load_cop_tr(const uint16_t (*x)[LDSW], int jp, int ct, int lane) {
+  const int g = lane >> 4, c = lane & 15;
+  const uint16_t* p = &x[32 * jp + 4 * g + (c >> 2)][16 * ct + 4 * (c & 3)];
+  return join8(lds_read_tr(p), lds_read_tr(p + 16 * LDSW));
+}
+
+__global__ void __launch_bounds__(NT) k_stats_wide(TensorDev X, TensorDev Yt, int Lx, int Ly, int H, float scale,
+                                                   int rows_per_chunk, int nchunks, float* part) {
+  __shared__ SmemWStats sm;
+  const int which = blockIdx.z, bh = blockIdx.y, b = bh / H, h = bh % H, chunk = blockIdx.x;
+  const TensorDev& T = which ? Yt : X;
+  const int L = which ? Ly : Lx;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
+  const uint16_t* base = (const uint16_t*)T.ptr + b * T.sb + h * T.sh;
+  const int row_beg = chunk * rows_per_chunk, row_end = min(L, row_beg + rows_per_chunk);
+  f32x4 acc[2][8], sums[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    sums[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int bt = 0; bt < 8; ++bt) acc[a][bt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const u32x4 ones_bits = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+  // sixteen consecutive threads fetch one row (256 bytes); four rows of the tile per thread
+  u32x4 r[4];
+  auto fetch = [&](int row0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = row0 + (tid >> 4) + 16 * i;
+      r[i] = u32x4{0u, 0u, 0u, 0u};
+      if (row < row_end) r[i] = *(const u32x4*)(base + (long long)row * T.sl + (tid & 15) * 8);
+    }
+  };
+  auto stage = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *(u32x4*)(&sm.x[buf][(tid >> 4) + 16 * i][(tid & 15) * 8]) = r[i];
+  };
+  fetch(row_beg);
+  stage(0);
+  __syncthreads();
+  int buf = 0;
+  for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
+    const bool more = row0 + TC < row_end;
+    if (more) fetch(row0 + TC);
+#pragma unroll
+    for (int jp = 0; jp < 2; ++jp) {
+      bf16x8 cop[8];
+#pragma unroll
+      for (int bt = 0; bt < 8; ++bt) cop[bt] = load_cop_tr(sm.x[buf], jp, bt, lane);
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        const bf16x8 mine = w == 0 ? cop[a] : w == 1 ? cop[2 + a] : w == 2 ? cop[4 + a] : cop[6 + a];
+#pragma unroll
+        for (int bt = 0; bt < 8; ++bt) acc[a][bt] = mfma(mine, cop[bt], acc[a][bt]);
+        sums[a] = mfma(ones, mine, sums[a]);
+      }
+    }
+    if (more) stage(buf ^ 1);
+    __syncthreads();
+  }
+  float* out = part + (((size_t)which * gridDim.y + bh) * nchunks + chunk) * ((size_t)DW * DW + DW);
+  const float s2 = scale * scale;
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+#pragma unroll
+    for (int bt = 0; bt < 8; ++bt)
+#pragma unroll
+      for (int rr = 0; rr < 4; ++rr) out[(size_t)(16 * (2 * w + a) + 4 * g + rr) * DW + 16 * bt + c] = s2 * acc[a][bt][rr];
+    if (g == 0) out[(size_t)DW * DW + 16 * (2 * w + a) + c] = scale * sums[a][0];
+  }
+}
+
 }  // namespace wide
 
 using namespace wide;
+
+bool stats_wide_supported(const TensorDev& X, const TensorDev& Y, int d) {
+  return X.dtype == 1 && Y.dtype == 1 && d == DW;
+}
+
+int launch_stats_wide(const TensorDev& X, const TensorDev& Y, int BH, int H, int Lx, int Ly, float scale,
+                      int rows_per_chunk, int nchunks, float* part, hipStream_t st) {
+  hipLaunchKernelGGL(k_stats_wide, dim3(nchunks, BH, 2), dim3(NT), 0, st, X, Y, Lx, Ly, H, scale, rows_per_chunk, nchunks,
+                     part);
+  if (hipGetLastError() != hipSuccess) return 5;
+  return 0;
+}
 
 bool wide_supported(int dtype, int d, int dv, int M_, int causal) { return dtype == 1 && d == DW && dv == DW && M_ == MW && causal == 1; }
 

@@ -1459,6 +1459,8 @@ int launch_stats(const TensorDev& X, const TensorDev& Y, int B, int H, int Lx, i
                  int rows_per_chunk, int nchunks, float* part, double* stats, hipStream_t st) {
   if (stats_bf16_supported(X, Y, d)) {
     if (int rc = launch_stats_bf16(X, Y, B * H, H, Lx, Ly, scale, rows_per_chunk, nchunks, part, st)) return rc;
+  } else if (stats_wide_supported(X, Y, d)) {
+    if (int rc = launch_stats_wide(X, Y, B * H, H, Lx, Ly, scale, rows_per_chunk, nchunks, part, st)) return rc;
   } else {
     const size_t lds = gen_lds_stats(d);
     if (int rc = set_lds((const void*)k_stats_partial, lds)) return rc;

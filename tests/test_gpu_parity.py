@@ -307,6 +307,38 @@ def test_device_fit_dense_families_at_other_sizes(fs, variant, d):
     np.testing.assert_allclose(got.B1.T @ got.B2, host.B1.T @ host.B2, atol=3e-4)
 
 
+@pytest.mark.parametrize("entry", ["host", "device"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fit_on_bf16_rows_scanned_by_the_mfma_statistics_kernels(fs, d, entry):
+    """bf16 rows of 64 and of 128 numbers take the MFMA statistics kernels.  Packed [B, L, H, d] storage (row stride
+    H d), a length that is neither a multiple of the 64-row tile nor of the scan's row chunk, one parameter set per
+    head: the fit is held to the oracle's on the same (bf16-rounded) numbers."""
+    import torch
+    rng = np.random.default_rng(500 + d)
+    B, H, L = 2, 2, 1333
+    U, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    spec = np.linspace(1.2, 0.3, d)
+    Q = synth.round_to_bf16(((rng.standard_normal((B, H, L, d)) * spec) @ U.T + 0.1).astype(np.float32))
+    K = synth.round_to_bf16(((rng.standard_normal((B, H, L, d)) * spec[::-1]) @ U.T - 0.05).astype(np.float32))
+    s = d ** -0.25
+    packed = torch.empty((B, L, H, 2, d), dtype=torch.bfloat16, device="cuda")
+    packed[:, :, :, 0] = util.to_device(Q, "bf16").permute(0, 2, 1, 3)
+    packed[:, :, :, 1] = util.to_device(K, "bf16").permute(0, 2, 1, 3)
+    Qd, Kd = packed[:, :, :, 0].permute(0, 2, 1, 3), packed[:, :, :, 1].permute(0, 2, 1, 3)
+    theta = _fit(fs, entry, "sderf", Qd, Kd, s, H)
+    for h in range(H):
+        X = s * Q[:, h].reshape(-1, d).astype(np.float64)
+        Yk = s * K[:, h].reshape(-1, d).astype(np.float64)
+        ref = orc.fit("sderf", X, Yk)
+        got = util.oracle_theta_from_vec(theta[h], d)
+        np.testing.assert_allclose(np.sort(got.A), np.sort(ref.A), atol=2e-5)
+        assert got.logD == pytest.approx(ref.logD, abs=1e-4 * max(1.0, abs(ref.logD)))
+        assert float(theta[h][1]) == pytest.approx(ref.lbar, abs=2e-4 * max(1.0, abs(ref.lbar)))
+        np.testing.assert_allclose(got.B1.T @ got.B1, ref.B1.T @ ref.B1, atol=3e-4)
+        np.testing.assert_allclose(got.B1.T @ got.B2, ref.B1.T @ ref.B2, atol=3e-4)
+        np.testing.assert_allclose(got.C2, ref.C2, atol=3e-4)
+
+
 def test_device_fit_reports_singular_statistics_per_group(fs):
     """ADERF needs nonsingular second moments: a head whose queries miss one coordinate gets FS_ERR_NOT_PD in its own
     status word, the other head is fitted; the host entry point returns the same code for the call."""
