@@ -39,13 +39,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_F32_PEAK_TFLOPS = 157.3
-# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of this
-# script (--only --calibrate-copy), each counter scaled by what it reads for the 256 MiB copy; figures, factors and
-# commands in the profiles/*_hbm_traffic.md file named beside each value.
+# HBM bytes per launch of the dominant kernel and per call, from `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE`
+# runs of this script (--only --calibrate-copy --workload <name>), each counter scaled by what it reads for the
+# 256 MiB copy; figures, factors and commands in the file named beside the values.
 MEASURED_TRAFFIC_BYTES = {
-    "c4": (291.9e6, "profiles/c4_hbm_traffic.md"),
-    "c3": (111.6e6, "profiles/c3_c5_hbm_traffic.md"),
-    "c5": (3.31e9, "profiles/c3_c5_hbm_traffic.md"),
+    "c4": (294.1e6, 508e6, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
+    "c3": (111.5e6, 270e6, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
+    "c5": (3.40e9, 4.07e9, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
 }
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
@@ -208,7 +208,8 @@ def run_attention(name: str, steps: int, warmup: int, fs, synth, torch, nsets: i
         ach = counts["flops"] / (main_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": mfma_peak, "unit": "TFLOP/s", "frac": ach / mfma_peak}
     roofline.update({
-        "traffic": traffic[0] if traffic else None, "traffic_source": traffic[1] if traffic else None,
+        "traffic": traffic[0] if traffic else None, "call_traffic": traffic[1] if traffic else None,
+        "traffic_source": traffic[2] if traffic else None,
         "call_frac": max(t_hbm, t_mfma) / (ms_per_step * 1e-3),
         "kernel_hbm_frac": t_hbm / (main_ms * 1e-3), "kernel_mfma_frac": t_mfma / (main_ms * 1e-3),
         "call_hbm_frac": t_hbm / (ms_per_step * 1e-3), "call_mfma_frac": t_mfma / (ms_per_step * 1e-3)})
