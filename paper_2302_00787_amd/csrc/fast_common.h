@@ -525,6 +525,7 @@ struct SmemApply {
 // Launcher of the causal segment kernel (its own translation unit: it is compiled with different code-generation
 // options than the other kernels of the path).
 int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st);
+size_t fast_causal_lds_bytes();
 // Backward pass (kernels_bf16_bwd.hip) and the reduction it borrows from the forward pass (kernels_bf16.hip).
 void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st);
 int launch_fast_backward(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,

@@ -382,7 +382,8 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
 // ---------------------------------------------------------------------------------------------------
 #define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
 
-size_t fast_lds_bytes() { return sizeof(Smem); }
+// Largest dynamic / static LDS request of the forward kernels of this path (the causal kernel's is the largest).
+size_t fast_lds_bytes() { return std::max({sizeof(SmemState), sizeof(SmemApply), fast_causal_lds_bytes()}); }
 
 bool fast_supported(int dtype, int d, int dv, int M_) { return dtype == 1 && d == D && dv == D && M_ == M; }
 

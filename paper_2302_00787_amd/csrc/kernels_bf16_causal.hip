@@ -481,6 +481,8 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
   else consumer(a, sm, cx, seg, w - 4);
 }
 
+size_t fast_causal_lds_bytes() { return sizeof(SmemPC); }
+
 int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st) {
   if (hipFuncSetAttribute((const void*)k_fast_causal, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPC)) !=
       hipSuccess) {

@@ -44,15 +44,43 @@ struct FitShared {
   int flag;
 };
 
+// Batched access to a pair of strided vectors for the sizes where every lane of a pair handles exactly NI elements
+// (n = NI x lanes per pair: 32, 64, 128 with 512 threads).  Every request is issued before the first use, so a pair
+// costs one memory latency, not one per element as in the general loops (whose stores may alias the next loads).
+template <int NI>
+__device__ __forceinline__ void fetch_pair(const double* xp, const double* xq, int stride, int r0, int tpp,
+                                           double (&x)[NI], double (&y)[NI]) {
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const size_t r = (size_t)(r0 + i * tpp) * stride;
+    x[i] = xp[r];
+    y[i] = xq[r];
+  }
+}
+// (xp, xq) <- (c xp - s xq, s xp + c xq) on those elements.
+template <int NI>
+__device__ __forceinline__ void store_rotated(double* xp, double* xq, int stride, int r0, int tpp, const double (&x)[NI],
+                                              const double (&y)[NI], double c, double s) {
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const size_t r = (size_t)(r0 + i * tpp) * stride;
+    xp[r] = c * x[i] - s * y[i];
+    xq[r] = s * x[i] + c * y[i];
+  }
+}
+
 // One-sided Jacobi on the columns of g (n x n, column c at g + c * ldg): g <- g R with mutually orthogonal columns,
 // v <- v R if v != nullptr (column c at v + c * ldv).  All FIT_NT threads must call; n <= FIT_DMAX.  The function is
 // inlined at each call site so that the address spaces of g and v (LDS or global) are known to the compiler.
+// NI > 0: n = NI x (lanes per pair), batched accesses; NI = 0: any n.
+template <int NI>
 __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int ldg, int ldv, FitShared& sh) {
   const int np = (n + 1) / 2;        // pairs per round
   const int m = 2 * np;              // players of the tournament (player n is a bye when n is odd)
   int tpp = 64;                      // lanes per pair
   while (tpp * np > FIT_NT) tpp >>= 1;
   const int t = threadIdx.x, pair = t / tpp, r0 = t % tpp;
+  constexpr int NA = NI > 0 ? NI : 1;
   for (int sweep = 0; sweep < 40; ++sweep) {
     if (t == 0) sh.flag = 0;
     __syncthreads();
@@ -68,9 +96,16 @@ __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int 
           double* gp = g + (size_t)p * ldg;
           double* gq = g + (size_t)q * ldg;
           double al = 0.0, be = 0.0, ga = 0.0;
-          for (int r = r0; r < n; r += tpp) {
-            const double a = gp[r], b = gq[r];
-            al += a * a; be += b * b; ga += a * b;
+          double x[NA], y[NA];
+          if constexpr (NI > 0) {
+            fetch_pair<NA>(gp, gq, 1, r0, tpp, x, y);
+#pragma unroll
+            for (int i = 0; i < NA; ++i) { al += x[i] * x[i]; be += y[i] * y[i]; ga += x[i] * y[i]; }
+          } else {
+            for (int r = r0; r < n; r += tpp) {
+              const double a = gp[r], b = gq[r];
+              al += a * a; be += b * b; ga += a * b;
+            }
           }
           al = lanes_sum(al, tpp); be = lanes_sum(be, tpp); ga = lanes_sum(ga, tpp);
           // The rotation must be orthogonal to fp64 accuracy, its angle need not be: the tangent is computed in fp32
@@ -81,18 +116,25 @@ __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int 
           if (ga * ga > kJacobiEps * kJacobiEps * al * be && tn32 != 0.f && isfinite(tn32)) {
             const double tn = (double)tn32;
             const double c = rsqrt(1.0 + tn * tn), s = c * tn;
-            for (int r = r0; r < n; r += tpp) {
-              const double a = gp[r], b = gq[r];
-              gp[r] = c * a - s * b;
-              gq[r] = s * a + c * b;
-            }
-            if (v != nullptr) {
-              double* vp = v + (size_t)p * ldv;
-              double* vq = v + (size_t)q * ldv;
+            if constexpr (NI > 0) {
+              double vx[NA], vy[NA];
+              if (v != nullptr) fetch_pair<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy);
+              store_rotated<NA>(gp, gq, 1, r0, tpp, x, y, c, s);
+              if (v != nullptr) store_rotated<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy, c, s);
+            } else {
               for (int r = r0; r < n; r += tpp) {
-                const double a = vp[r], b = vq[r];
-                vp[r] = c * a - s * b;
-                vq[r] = s * a + c * b;
+                const double a = gp[r], b = gq[r];
+                gp[r] = c * a - s * b;
+                gq[r] = s * a + c * b;
+              }
+              if (v != nullptr) {
+                double* vp = v + (size_t)p * ldv;
+                double* vq = v + (size_t)q * ldv;
+                for (int r = r0; r < n; r += tpp) {
+                  const double a = vp[r], b = vq[r];
+                  vp[r] = c * a - s * b;
+                  vq[r] = s * a + c * b;
+                }
               }
             }
             if (r0 == 0) sh.flag = 1;
@@ -114,12 +156,16 @@ __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int 
 // which no other pair of the round touches; the round applies all column rotations, a barrier, all row rotations.
 // No inner products and no cross-lane sums are needed, and the sweep count follows the conditioning of a itself
 // (the one-sided iteration on a symmetric matrix works on its square).  `scale`: largest |a_ii| at the start.
+// NI as above; with NI > 0 the columns of a and of v are requested together with the 2 x 2 block, before the
+// rotation is known, so that a round is a chain of two memory latencies and two barriers.
+template <int NI>
 __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, int lda, int ldv, double scale, FitShared& sh) {
   const int np = (n + 1) / 2;
   const int m = 2 * np;
   int tpp = 64;
   while (tpp * np > FIT_NT) tpp >>= 1;
   const int t = threadIdx.x, pair = t / tpp, r0 = t % tpp;
+  constexpr int NA = NI > 0 ? NI : 1;
   for (int sweep = 0; sweep < 40; ++sweep) {
     if (t == 0) sh.flag = 0;
     __syncthreads();
@@ -128,11 +174,16 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
       bool rot = false;
       double c = 1.0, s = 0.0;
       int p = 0, q = 0;
+      double x[NA], y[NA], vx[NA], vy[NA];
       if (pair < np) {
         p = pair == 0 ? m - 1 : pa;
         q = pair == 0 ? round : pb;
         if (p > q) { const int w = p; p = q; q = w; }
         if (q < n) {
+          if constexpr (NI > 0) {
+            fetch_pair<NA>(a + (size_t)p * lda, a + (size_t)q * lda, 1, r0, tpp, x, y);
+            if (v != nullptr) fetch_pair<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy);
+          }
           const double app = a[(size_t)p * lda + p], aqq = a[(size_t)q * lda + q], apq = a[(size_t)q * lda + p];
           const float zeta = (float)(aqq - app) / (2.f * (float)apq);
           const float tn32 = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
@@ -147,27 +198,37 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
       if (rot) {
         double* ap = a + (size_t)p * lda;
         double* aq = a + (size_t)q * lda;
-        for (int r = r0; r < n; r += tpp) {
-          const double x = ap[r], y = aq[r];
-          ap[r] = c * x - s * y;
-          aq[r] = s * x + c * y;
-        }
-        if (v != nullptr) {
-          double* vp = v + (size_t)p * ldv;
-          double* vq = v + (size_t)q * ldv;
+        if constexpr (NI > 0) {
+          store_rotated<NA>(ap, aq, 1, r0, tpp, x, y, c, s);
+          if (v != nullptr) store_rotated<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy, c, s);
+        } else {
           for (int r = r0; r < n; r += tpp) {
-            const double x = vp[r], y = vq[r];
-            vp[r] = c * x - s * y;
-            vq[r] = s * x + c * y;
+            const double xx = ap[r], yy = aq[r];
+            ap[r] = c * xx - s * yy;
+            aq[r] = s * xx + c * yy;
+          }
+          if (v != nullptr) {
+            double* vp = v + (size_t)p * ldv;
+            double* vq = v + (size_t)q * ldv;
+            for (int r = r0; r < n; r += tpp) {
+              const double xx = vp[r], yy = vq[r];
+              vp[r] = c * xx - s * yy;
+              vq[r] = s * xx + c * yy;
+            }
           }
         }
       }
       __syncthreads();
       if (rot) {
-        for (int k = r0; k < n; k += tpp) {
-          const double x = a[(size_t)k * lda + p], y = a[(size_t)k * lda + q];
-          a[(size_t)k * lda + p] = c * x - s * y;
-          a[(size_t)k * lda + q] = s * x + c * y;
+        if constexpr (NI > 0) {
+          fetch_pair<NA>(a + p, a + q, lda, r0, tpp, x, y);
+          store_rotated<NA>(a + p, a + q, lda, r0, tpp, x, y, c, s);
+        } else {
+          for (int k = r0; k < n; k += tpp) {
+            const double xx = a[(size_t)k * lda + p], yy = a[(size_t)k * lda + q];
+            a[(size_t)k * lda + p] = c * xx - s * yy;
+            a[(size_t)k * lda + q] = s * xx + c * yy;
+          }
         }
         if (r0 == 0) sh.flag = 1;
       }
@@ -178,6 +239,21 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
     const int again = sh.flag;
     __syncthreads();
     if (!again) break;
+  }
+}
+
+// The iteration for the sizes with a batched form (n = 64: 4 elements per lane, n = 128: 16), else the general one.
+__device__ __forceinline__ void jacobi_any(double* a, double* v, int n, int lda, int ldv, bool symmetric, double scale,
+                                           FitShared& sh) {
+  if (n == 64) {
+    if (symmetric) jacobi_symmetric<4>(a, v, n, lda, ldv, scale, sh);
+    else jacobi_columns<4>(a, v, n, lda, ldv, sh);
+  } else if (n == 128) {
+    if (symmetric) jacobi_symmetric<16>(a, v, n, lda, ldv, scale, sh);
+    else jacobi_columns<16>(a, v, n, lda, ldv, sh);
+  } else {
+    if (symmetric) jacobi_symmetric<0>(a, v, n, lda, ldv, scale, sh);
+    else jacobi_columns<0>(a, v, n, lda, ldv, sh);
   }
 }
 
@@ -228,22 +304,19 @@ __device__ __forceinline__ void decompose(double* g, double* v, int n, int k, bo
   }
   if (v == nullptr) {
     __syncthreads();
-    if (symmetric) jacobi_symmetric(wg, nullptr, n, ld, 0, sh.red[1], sh);
-    else jacobi_columns(wg, nullptr, n, ld, 0, sh);
+    jacobi_any(wg, nullptr, n, ld, 0, symmetric, sh.red[1], sh);
     rank_columns(wg, nullptr, n, ld, 0, k, symmetric, sh);
   } else if (n <= kLdsBoth) {
     double* wv = lds + (size_t)n * ld;
     for (int e = t; e < nn; e += FIT_NT) wv[(e / n) * ld + e % n] = (e / n == e % n) ? 1.0 : 0.0;
     __syncthreads();
-    if (symmetric) jacobi_symmetric(wg, wv, n, ld, ld, sh.red[1], sh);
-    else jacobi_columns(wg, wv, n, ld, ld, sh);
+    jacobi_any(wg, wv, n, ld, ld, symmetric, sh.red[1], sh);
     rank_columns(wg, wv, n, ld, ld, k, symmetric, sh);
     for (int e = t; e < nn; e += FIT_NT) v[e] = wv[(e / n) * ld + e % n];
   } else {
     for (int e = t; e < nn; e += FIT_NT) v[e] = (e / n == e % n) ? 1.0 : 0.0;
     __syncthreads();
-    if (symmetric) jacobi_symmetric(wg, v, n, ld, n, sh.red[1], sh);
-    else jacobi_columns(wg, v, n, ld, n, sh);
+    jacobi_any(wg, v, n, ld, n, symmetric, sh.red[1], sh);
     rank_columns(wg, v, n, ld, n, k, symmetric, sh);
   }
   for (int e = t; e < nn; e += FIT_NT) g[e] = wg[(e / n) * ld + e % n];
