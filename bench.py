@@ -12,8 +12,9 @@ device-resident variant of the same fit as `fit_device_ms`.
 Inputs rotate over three distinct sets so the 256 MB last-level cache cannot hold a set across steps.
 
 Timing: `ms_per_step` is the mean wall-clock time of K back-to-back calls between two device synchronisations (it
-includes every launch gap of a call); `main_kernel_ms` is the mean over the same K calls of the time between two HIP
-events that the library records on its stream right before and right after the dominant kernel.
+includes every launch gap of a call); `main_kernel_ms` is the mean, over K more calls made right after the timed
+ones, of the time between two HIP events that the library attaches to the dispatch of the dominant kernel (its own
+begin and end on the stream the library launches on).
 
 Prints ONE JSON line.  Headline fields: the metric workload.  `roofline`: the dominant kernel of the metric workload
 (`frac`) and the whole call (`call_frac`) against the tighter of the HBM / MFMA bounds on the algorithmic counts.
@@ -184,17 +185,14 @@ def run_attention(name: str, steps: int, warmup: int, fs, synth, torch, nsets: i
         dst.copy_(src)          # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    # dominant kernel: events recorded by the library around it (these calls are not the ones timed as steps: recording
-    # two events per call costs launch gaps of its own)
-    for i in range(warmup):
-        step(i)
-    torch.cuda.synchronize()
+    ms_unprepared = timed(step, steps, warmup, torch)
+    ms_per_step = timed(step_prepared, steps, warmup, torch) if prepared_ok else ms_unprepared
+    # dominant kernel: events attached by the library to its dispatch, in a loop of calls right after the timed ones
+    # (not in them: the steps are timed by the wall clock between two synchronisations, without events)
     for i in range(steps):
         step(i, pairs[i])
     torch.cuda.synchronize()
     main_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs]))
-    ms_unprepared = timed(step, steps, warmup, torch)
-    ms_per_step = timed(step_prepared, steps, warmup, torch) if prepared_ok else ms_unprepared
     for a, b in pairs:
         ev.destroy(a)
         ev.destroy(b)
@@ -428,8 +426,10 @@ def free(r: dict, torch):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    # the clocks of the chip settle only after some tens of milliseconds of load (the first calls of a process run
+    # the main kernel about 15 % slower than the steady state): the default warm-up covers that
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5", "c3_backward", "c4_backward"],
                     help="the workload of the headline fields (default: the metric workload, c4)")
     ap.add_argument("--only", action="store_true",
@@ -504,7 +504,7 @@ def main():
 
     # ---- the other workloads, same run, fewer steps
     if not args.only and name == "c4":
-        steps, warmup = max(5, min(args.steps, 10)), max(2, min(args.warmup, 3))
+        steps, warmup = max(5, min(args.steps, 50)), max(2, min(args.warmup, 25))
         others = {}
         for other in ("c1", "c3", "c5"):
             r = run_attention(other, steps, warmup, fs, synth, torch, nsets=2 if other == "c5" else 3, with_fit=other == "c5")

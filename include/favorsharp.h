@@ -186,10 +186,12 @@ int favorsharp_kernel_matvec(const float* theta, const fs_tensor* X, const fs_te
                              void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * favorsharp_attention with two optional hipEvent_t handles (NULL to skip): event_main_begin is recorded on
- * `stream` right before the kernel that performs the contraction of Section 2.1 / 2.2 for most of the rows
- * (the causal segment pass, or the query-side pass when causal = 0), event_main_end right after it.  For
- * measuring that kernel alone from outside; the result is identical to favorsharp_attention.
+ * favorsharp_attention with two optional hipEvent_t handles (NULL to skip) around the kernel that performs the
+ * contraction of Section 2.1 / 2.2 for most of the rows (the causal segment pass, or the query-side pass when
+ * causal = 0): on the bf16 paths the events are attached to that kernel's dispatch and carry its own begin and end
+ * times (for d = dv = 128: begin of the first, end of the second launch of the walk); on the general path
+ * event_main_begin is recorded on `stream` right before the kernel and event_main_end right after it.  For measuring
+ * that kernel alone from outside; the result is identical to favorsharp_attention.
  */
 int favorsharp_attention_timed(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
                                const fs_tensor* V, int B, int H, int Lq, int Lk, int d, int dv,

@@ -524,7 +524,8 @@ struct SmemApply {
 
 // Launcher of the causal segment kernel (its own translation unit: it is compiled with different code-generation
 // options than the other kernels of the path).
-int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st);
+int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st, hipEvent_t ev_begin = nullptr,
+                              hipEvent_t ev_end = nullptr);
 size_t fast_causal_lds_bytes();
 // Backward pass (kernels_bf16_bwd.hip) and the reduction it borrows from the forward pass (kernels_bf16.hip).
 void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st);

@@ -1,6 +1,8 @@
 // bf16 path of FAVOR# attention (d = dv = 64, M = 256): projection constants, key-side segment states, their
 // reduction / prefix, the non-causal query-side kernel, and the host-side launcher of the whole call.
 // The design is described in fast_common.h; the causal segment kernel lives in kernels_bf16_causal.hip.
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 #include <cstddef>
 
@@ -512,18 +514,18 @@ int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_beg
   FastArgs a;
   if (int rc = launch_fast_state_pass(f, a, st)) return rc;
   const int BH = f.B * f.H;
-  if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
+  // the optional events are attached to the main kernel's dispatch: they carry its own begin and end times
   if (f.causal) {
-    if (int rc = launch_fast_causal_kernel(a, BH, st)) return rc;
+    if (int rc = launch_fast_causal_kernel(a, BH, st, ev_begin, ev_end)) return rc;
   } else {
     // two workgroups per CU: about 512 blocks in all, whole chunks each
     const int want = std::max(1, std::min((512 + BH - 1) / BH, (f.Lq + TC - 1) / TC));
     const int rows_per_blk = (((f.Lq + want - 1) / want) + TC - 1) / TC * TC;
     const int nblk = (f.Lq + rows_per_blk - 1) / rows_per_blk;
-    hipLaunchKernelGGL(k_fast_apply, dim3(nblk, BH), dim3(NT), 0, st, a, f.Lq, rows_per_blk);
+    if (ev_begin || ev_end) hipExtLaunchKernelGGL(k_fast_apply, dim3(nblk, BH), dim3(NT), 0, st, ev_begin, ev_end, 0, a, f.Lq, rows_per_blk);
+    else hipLaunchKernelGGL(k_fast_apply, dim3(nblk, BH), dim3(NT), 0, st, a, f.Lq, rows_per_blk);
     FS_LAUNCH_CHECK();
   }
-  if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;
   return 0;
 }
 

@@ -51,6 +51,8 @@
 // The per-token constants of chunk c+1 (row terms, query shifts) and the chunk's two maxima (largest key bound,
 // largest query shift: LDS float-maximum atomics from the lanes that hold a row norm) are written in interval 4c+3
 // and first read in interval 4c+4; the maxima of that parity were last read in interval 4c+1 and are reset in 4c+2.
+#include <hip/hip_ext.h>
+
 #include "fast_pc.h"
 
 namespace fs {
@@ -483,13 +485,16 @@ __global__ void __launch_bounds__(NT8) k_fast_causal(FastArgs a) {
 
 size_t fast_causal_lds_bytes() { return sizeof(SmemPC); }
 
-int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st) {
+int launch_fast_causal_kernel(const FastArgs& a, int BH, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   if (hipFuncSetAttribute((const void*)k_fast_causal, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemPC)) !=
       hipSuccess) {
     (void)hipGetLastError();
     return 2;
   }
-  hipLaunchKernelGGL(k_fast_causal, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, a);
+  // with events: they are attached to the dispatch itself and carry the kernel's own begin and end times (events
+  // recorded before and after it on the stream would add the gaps of two more queue packets)
+  if (ev_begin || ev_end) hipExtLaunchKernelGGL(k_fast_causal, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, ev_begin, ev_end, 0, a);
+  else hipLaunchKernelGGL(k_fast_causal, dim3(a.nseg, BH), dim3(NT8), sizeof(SmemPC), st, a);
   if (hipGetLastError() != hipSuccess) return 5;
   return 0;
 }

@@ -14,6 +14,8 @@
 //   k_wide_state   per (slot, feature half): S^T [V 1] over the slot (eight waves of 32 features, all 129 columns)
 //   k_wide_reduce  exclusive prefix over the slots, each on the running maximum of the slots' shifts
 //   k_wide_walk    per (slot, column half), once per feature half: the causal walk; the second launch finishes Y
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 #include "fast_pc.h"
@@ -686,13 +688,14 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   FS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot);
   FS_LAUNCH_CHECK();
-  if (ev_begin && hipEventRecord(ev_begin, st) != hipSuccess) return 5;
+  // the optional events are attached to the dispatches of the two walks: begin of the first, end of the second
   for (int fh = 0; fh < 2; ++fh) {
     a.fh = fh;
-    hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+    hipEvent_t e0 = fh == 0 ? ev_begin : nullptr, e1 = fh == 1 ? ev_end : nullptr;
+    if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
+    else hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
     FS_LAUNCH_CHECK();
   }
-  if (ev_end && hipEventRecord(ev_end, st) != hipSuccess) return 5;
   return 0;
 }
 
