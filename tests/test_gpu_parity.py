@@ -612,12 +612,18 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name):
     assert torch.isfinite(Y.float()).all().item()
 
 
-@pytest.mark.parametrize("name,over", [("c1", {}), ("c4", dict(B=1, H=2, L=1216)), ("c5", dict(B=1, H=2, L=832))])
-def test_attention_call_replays_from_a_hip_graph(fs, name, over):
+@pytest.mark.parametrize("name,over,prepared", [("c1", {}, False), ("c4", dict(B=1, H=2, L=1216), False),
+                                                ("c5", dict(B=1, H=2, L=832), False), ("c4", dict(B=1, H=2, L=1216), True),
+                                                ("c2", {}, False)])
+def test_attention_call_replays_from_a_hip_graph(fs, name, over, prepared):
     """The entry point only enqueues kernels on the caller's stream (no synchronisation, no allocation, no memset
     nodes), so a caller may capture it: the graph is replayed three times, with eager work and synchronisations in
-    between, and every replay must reproduce the eager result bit for bit (general path, both bf16 paths)."""
+    between, and every replay must reproduce the eager result bit for bit (general path, both bf16 paths, the call
+    on prepared projection constants, and the kernel operator on its fp32 MFMA kernels)."""
     import torch
+    if name == "c2":
+        _operator_graph_replay(fs)
+        return
     w = synth.make(name, **over)
     dt = w.get("dtype", "f32")
     Q, K, V = (util.to_device(w[k], dt) for k in "QKV")
@@ -628,9 +634,47 @@ def test_attention_call_replays_from_a_hip_graph(fs, name, over):
                      device="cuda")
     Y = torch.empty_like(V)
 
-    def call():
-        fs.attention(theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0), out=Y, workspace=ws)
+    prep = fs.attention_prepare(theta, Om, B, H, s) if prepared else None
 
+    def call():
+        if prepared:
+            fs.attention_prepared(prep, theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0), out=Y, workspace=ws)
+        else:
+            fs.attention(theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0), out=Y, workspace=ws)
+
+    _replay_and_compare(call, Y, name)
+
+
+def _operator_graph_replay(fs):
+    """favorsharp_kernel_matvec on the fp32 MFMA operator kernels (a reduced c2), captured and replayed."""
+    import torch
+    w = synth.make("c2", N=2048 + 37)
+    X, C, Om = w["X"], w["C"], w["Omega"][0]
+    Xd, Cd, Od = torch.from_numpy(X).cuda(), torch.from_numpy(C).cuda(), torch.from_numpy(Om).cuda()
+    theta = fs.fit_params("sderf", Xd[None, None], Xd[None, None], 1.0, groups=1)
+    N, d = X.shape
+    ws = torch.empty(fs.kernel_matvec_workspace_bytes(N, N, d, Om.shape[0], C.shape[1]), dtype=torch.uint8, device="cuda")
+    ref = fs.kernel_matvec(theta, Xd, Xd, 1.0, w["alpha"], Od, Cd, workspace=ws).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fs.kernel_matvec(theta, Xd, Xd, 1.0, w["alpha"], Od, Cd, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        res = fs.kernel_matvec(theta, Xd, Xd, 1.0, w["alpha"], Od, Cd, workspace=ws)
+    for rep in range(3):
+        res.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(res, ref), rep
+        _ = torch.randn(1 << 20, device="cuda").sum().item()
+
+
+def _replay_and_compare(call, Y, name):
+    import torch
     call()
     torch.cuda.synchronize()
     ref = Y.clone()
