@@ -126,6 +126,9 @@ struct FastArgs {
   float* cstar;            // [BH] largest shift of each sequence, then [BH][nslot] the shift of each slot's prefix state
   int groups, pgroups, H, L, rows_per_seg, nseg;
   int sub, nslot;          // sub-segments per segment (key-side kernel granularity) and total state slots
+  int timg;                // layout of a state in Tpart: 0 = [M][DVP] row-major; 1 = accumulator images, the four
+                           // numbers of lane l for tile (mt, vt) of wave w at ((w*4 + mt)*NVT + vt)*256 + 4 l
+                           // (16-byte accesses; the forward kernels, whose waves all hold a state that way)
   float scale;
 };
 

@@ -250,9 +250,14 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-    for (int vt = 0; vt < NVT; ++vt)
+    for (int vt = 0; vt < NVT; ++vt) {
+      if (a.timg) {
+        *(f32x4*)(out + (size_t)((w * 4 + mt) * NVT + vt) * 256 + 4 * lane) = T[mt][vt];
+      } else {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) out[(size_t)(64 * w + 16 * mt + 4 * g + r) * DVP + 16 * vt + c] = T[mt][vt][r];
+        for (int r = 0; r < 4; ++r) out[(size_t)(64 * w + 16 * mt + 4 * g + r) * DVP + 16 * vt + c] = T[mt][vt][r];
+      }
+    }
   if (threadIdx.x == 0) a.cpart[(size_t)bh * a.nslot + slot] = dk;
 }
 
@@ -328,10 +333,10 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
   for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb) {
-      f32x8 t;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = Tg[(size_t)(64 * w + 32 * mb + 16 * (e >> 2) + 4 * g + (e & 3)) * DVP + 16 * vt + c];
-      tb[vt][mb] = __builtin_convertvector(t, bf16x8);
+      // accumulator images of tiles (2 mb, vt) and (2 mb + 1, vt) of wave w (the forward state pass writes images)
+      const f32x4 lo = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb) * NVT + vt) * 256 + 4 * lane);
+      const f32x4 hi = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb + 1) * NVT + vt) * 256 + 4 * lane);
+      tb[vt][mb] = pack8(lo, hi);
     }
   const int row_beg = blk * rows_per_blk, row_end = min(Lq, row_beg + rows_per_blk);
   RowRegs qr;
@@ -465,12 +470,13 @@ int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int
 
 // Projection constants, key-side segment states and their reduction (sum, or exclusive prefix when causal).
 // `every_slot`: states of all slots (the last segment's too) and, when causal, the exclusive prefix of every slot.
-static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st, bool every_slot = false) {
+static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st, bool every_slot = false, bool images = false) {
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
   a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.theta = f.theta; a.rk = f.rk;
   a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
   a.groups = f.groups; a.pgroups = f.pgroups; a.H = f.H; a.L = f.Lk; a.rows_per_seg = f.rows_per_seg; a.nseg = f.nseg;
   a.sub = f.sub; a.nslot = f.nseg * f.sub;
+  a.timg = images ? 1 : 0;
   a.scale = f.scale;
   const int BH = f.B * f.H;
   const int rowblocks = std::min(64, (f.Lk + 3) / 4), nprep = (M / 4) * 2 * f.pgroups;
@@ -512,7 +518,7 @@ void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int n
 
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   FastArgs a;
-  if (int rc = launch_fast_state_pass(f, a, st)) return rc;
+  if (int rc = launch_fast_state_pass(f, a, st, false, true)) return rc;
   const int BH = f.B * f.H;
   // the optional events are attached to the main kernel's dispatch: they carry its own begin and end times
   if (f.causal) {

@@ -331,13 +331,12 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
   const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
   f32x4 T[4][NVT];
   {
+    // the prefix state as the state pass left it: accumulator images, 16 bytes per lane and tile
     const float* Tg = a.Tpart + ((size_t)cx.bh * a.nslot + (size_t)seg * a.sub) * M * DVP;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-      for (int vt = 0; vt < NVT; ++vt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * DVP + 16 * vt + c];
+      for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = *(const f32x4*)(Tg + (size_t)((j * 4 + mt) * NVT + vt) * 256 + 4 * lane);
   }
   float dk = a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)seg * a.sub];   // shift of the prefix state
   FS_STEP_BARRIER();               // barrier 0
