@@ -38,7 +38,6 @@ constexpr int NVT = 5;           // value tiles of 16 columns: 64 values + norma
 constexpr int DVP = NVT * 16;    // 80
 constexpr int LDR = D + 8;       // row stride (bf16 elements) of a token tile in LDS: 36 dwords, conflict-free b128 reads
 constexpr int LDJ = TC + 4;      // row stride of the transposed value tile in LDS: 34 dwords, conflict-free b64 reads
-constexpr int LDX = DVP + 4;     // row stride (floats) of the exchange buffer
 constexpr float kBeta = 0.5f;
 
 typedef __attribute__((ext_vector_type(8))) float f32x8;
@@ -101,16 +100,12 @@ __device__ __forceinline__ float row_shift(float n2, float wmax) {
   return fmaxf(kBeta * cs, cs - 120.f);
 }
 
-// The key-side kernel only touches the members up to `q`, and asks for that much LDS (so that two of its
-// workgroups fit on a CU).
+// LDS of a key-side state kernel in the layout with transposed values (the query-side state kernel of the
+// backward pass): double-buffered rows, values transposed, one constant per token.
 struct Smem {
-  uint16_t k[2][TC][LDR];       // key rows, bf16 bits
-  uint16_t vt[2][DVP][LDJ];     // values transposed: [column][token]; row 64 = ones, rows 65.. = 0
-  __attribute__((aligned(16))) float kadd[2][TC];   // per key token: row term log2e y^T C2 y
-  __attribute__((aligned(16))) float kbnd[2][TC];   // per key token: row_shift + row term (-inf past the end)
-  __attribute__((aligned(16))) uint16_t q[2][TC][LDR];       // query rows
-  float qadd[2][TC];            // per query token: - row_shift
-  __attribute__((aligned(16))) float xch[NW][NW][16][LDX];   // partial outputs: [token tile][source wave][token][column]
+  uint16_t k[2][TC][LDR];       // rows, bf16 bits
+  uint16_t vt[2][DVP][LDJ];     // values transposed: [column][token]
+  __attribute__((aligned(16))) float kadd[2][TC];   // per token: the constant added to its exponents
 };
 
 // Everything the kernels of one attention call share.
@@ -227,23 +222,6 @@ __device__ __forceinline__ void store_query_rows(const RowRegs& r, S& sm, int bu
   }
 }
 
-__device__ __forceinline__ void store_key_rows(const RowRegs& r, Smem& sm, int buf, const FastArgs& a, bool isoC, int bh,
-                                               int row0, int row_end, float wmax) {
-  float n2[2];
-  store_rows_s(r, sm.k[buf], n2);
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int q = threadIdx.x + NT * i, row = q >> 3;
-    if ((q & 7) == 0) {
-      const bool valid = row0 + row < row_end;
-      float rt = -0.5f * kLog2e * a.scale * a.scale * n2[i];
-      if (!isoC) rt = valid ? a.rk[(size_t)bh * a.L + row0 + row] : 0.f;
-      // rows past the end get -inf: their features are exactly zero whatever the key shift is
-      sm.kadd[buf][row] = valid ? rt : -INFINITY;
-      sm.kbnd[buf][row] = valid ? row_shift(n2[i], wmax) + rt : -INFINITY;
-    }
-  }
-}
 
 // Values: lane pairs (2t, 2t+1) exchange halves so that each lane writes whole dwords {token 2t, token 2t+1} of one
 // column: thread -> token tid%64, 16-byte pieces tid/64 and tid/64 + 4 of that token's row.
@@ -277,12 +255,6 @@ __device__ __forceinline__ void store_vals_s(const RowRegs& r, uint16_t (*vt)[LD
   }
 }
 
-__device__ __forceinline__ void zero_pad_rows(Smem& sm) {
-  for (int idx = threadIdx.x; idx < 2 * (DVP - D - 1) * LDJ; idx += NT) {
-    const int b = idx / ((DVP - D - 1) * LDJ), rem = idx - b * (DVP - D - 1) * LDJ;
-    sm.vt[b][D + 1 + rem / LDJ][rem % LDJ] = 0;
-  }
-}
 
 // ---- per-wave constants ----------------------------------------------------------------------------------------
 // The bias_m = log2e (w_m^T A w_m + log D - 1/2 log M) is the same for both sides (A and D are shared by f1 and f2,
@@ -313,18 +285,6 @@ __device__ __forceinline__ void load_qbias(QBias& qb, const float* bias, float a
     for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (bias[64 * w + 16 * mt + 4 * g + r] - amax);
 }
 
-// Selection matrices (B operands) that turn an A operand (lane <-> token, k <-> feature) into an accumulator with
-// lane <-> feature: sel[hh] has a one at (k, n) iff k addresses feature 16 hh + n of the 32-feature block.
-__device__ __forceinline__ void make_sel(bf16x8 sel[2]) {
-  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
-#pragma unroll
-  for (int hh = 0; hh < 2; ++hh) {
-    f32x8 t;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) t[e] = ((e >> 2) == hh && 4 * g + (e & 3) == c) ? 1.f : 0.f;
-    sel[hh] = __builtin_convertvector(t, bf16x8);
-  }
-}
 
 // Feature tile of 16 tokens: for each 32-feature block mb the packed exp2 values (A / B operand layout:
 // lane <-> token 16 jt + c, k <-> feature).  `add` is the per-token part of the exponent (lane c's token).
@@ -380,26 +340,6 @@ __device__ __forceinline__ void feature_pair_major(const WSlice& ws, const float
   }
 }
 
-// Key-side features of one pair of token tiles (tokens 32 jp .. 32 jp + 31) in both operand layouts: s[jj][mb]
-// (lane <-> token 16 (2 jp + jj) + c) for the scores and st[mt] (lane <-> feature 16 mt + c, k <-> tokens
-// {32 jp + 4g + r, 32 jp + 16 + 4g + r}) for the state update.
-__device__ __forceinline__ void key_pair(const WSlice& wk, const Smem& sm, int buf, int jp, float dk,
-                                         const bf16x8 sel[2], bf16x8 (&s)[2][2], bf16x8 (&st)[4]) {
-  const int c = threadIdx.x & 15;
-  f32x4 tr[2][4];      // [token tile within the pair][feature tile]
-#pragma unroll
-  for (int jj = 0; jj < 2; ++jj) {
-    const int jt = 2 * jp + jj;
-    feature_tile<false>(wk, nullptr, sm.k[buf], jt, sm.kadd[buf][16 * jt + c] - dk, s[jj]);
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh)
-        tr[jj][2 * mb + hh] = mfma(s[jj][mb], sel[hh], f32x4{0.f, 0.f, 0.f, 0.f});
-  }
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt) st[mt] = pack8(tr[0][mt], tr[1][mt]);
-}
 
 // B operand / A operand of the value tile: lane <-> column 16 vt + c, k <-> tokens {32 jp + 4g + r, 32 jp + 16 + 4g + r}.
 __device__ __forceinline__ bf16x8 load_vop(const uint16_t (*vt)[LDJ], int jp, int vtile) {
@@ -410,59 +350,8 @@ __device__ __forceinline__ bf16x8 load_vop(const uint16_t (*vt)[LDJ], int jp, in
   return __builtin_bit_cast(bf16x8, v);
 }
 
-// Running key shift: largest bound of this chunk's tokens; when it exceeds the current one the state is rebased.
-// Every wave computes the same numbers (same inputs, same operations).  Returns the new shift (relative to amax).
-__device__ __forceinline__ float key_shift_update(const Smem& sm, int buf, float dk, f32x4 (&T)[4][NVT]) {
-  const f32x4 b4 = *(const f32x4*)(&sm.kbnd[buf][4 * (threadIdx.x & 15)]);      // each row of 16 lanes sees all 64 tokens
-  const float dnew = max16(fmaxf(fmaxf(b4[0], b4[1]), fmaxf(b4[2], b4[3])));
-  if (dnew > dk) {
-    const float f = fast_exp2(dk - dnew);
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) T[mt][vt] *= f;
-    return dnew;
-  }
-  return dk;
-}
 
-// ---- exchange of the partial outputs between the four waves ------------------------------------------------------
-// Every wave hands over its partial result for token tile `it` (its own tile included: no branch in the chunk body).
-__device__ __forceinline__ void exchange_put(Smem& sm, const f32x4 (&y)[NVT], int it) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) *(f32x4*)(&sm.xch[it][w][c][16 * vt + 4 * g]) = y[vt];
-}
 
-// After every tile has been put: wave w adds the four parts of token tile w, normalises by row v = 64 and stores.
-__device__ __forceinline__ void exchange_finish(Smem& sm, const TensorDev& Y, long long ybase, int row0, int row_end) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
-  __syncthreads();
-  f32x4 own[NVT];
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt) {
-    own[vt] = *(const f32x4*)(&sm.xch[w][0][c][16 * vt + 4 * g]);
-#pragma unroll
-    for (int src = 1; src < NW; ++src) own[vt] += *(const f32x4*)(&sm.xch[w][src][c][16 * vt + 4 * g]);
-  }
-  const float den = __shfl(own[NVT - 1][0], c);          // row v = 64 lives in lane (g = 0, c), register 0
-  const float inv = den > 0.f ? 1.f / den : 0.f;
-  const int token = row0 + 16 * w + c;
-  if (token < row_end) {
-    if (Y.dtype == 1) {
-      uint16_t* yp = (uint16_t*)Y.ptr + ybase + (long long)token * Y.sl + 4 * g;
-#pragma unroll
-      for (int vt = 0; vt < 4; ++vt) {
-        const f32x4 v = own[vt] * inv;
-        *(bf16x4*)(yp + 16 * vt) = __builtin_convertvector(v, bf16x4);
-      }
-    } else {
-      float* yp = (float*)Y.ptr + ybase + (long long)token * Y.sl + 4 * g;
-#pragma unroll
-      for (int vt = 0; vt < 4; ++vt) *(f32x4*)(yp + 16 * vt) = own[vt] * inv;
-    }
-  }
-}
 
 // ---- bf16 exchange of partial output tiles and their sum on the MFMA pipe -----------------------------------------
 constexpr int LDXB = DVP + 8;      // row stride (bf16 elements) of the bf16 exchange buffer: 176 bytes = 44 dwords: 16-byte accesses of 8 consecutive rows hit 32 different banks

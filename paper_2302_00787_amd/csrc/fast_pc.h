@@ -125,7 +125,10 @@ __device__ __forceinline__ bf16x8 load_vop_l(const uint16_t (*vt)[LDJ], int jp, 
 }
 
 // Consumer side of a walk that has the shape of the forward pass (state T of 64 features x 80 columns in registers,
-// first-side tiles in steps 0 and 1 with the state update, second-side tiles in steps 2 and 3 with the output tiles):
+// first-side tiles in steps 0 and 1 with the state update, second-side tiles in steps 2 and 3 with the output tiles),
+// for producers that hand over token-major register images of both sides and values transposed in LDS: the walks of
+// the causal gradient kernels and of the d = dv = 128 shape.  (The forward kernel for d = dv = 64 has a consumer of
+// its own, built on row-major tiles and transposing reads, with a running key shift: kernels_bf16_causal.hip.)
 //   MODE 0: second-side token i sees first-side tokens j <= i;  MODE 1: j >= i.
 // `sm` needs feat[2][4][4][64][8], uothT[DVP][LDJ] and xch[4][4][16][LDXB].  Executes 2 + 4 nchunk barriers.
 template <int MODE, class SM>

@@ -152,7 +152,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
 
 // ---------------------------------------------------------------------------------------------------------------
 // Segment sums of P^T G1 (structure of k_fast_state: query features with their per-row shifts, "values" = rows of
-// G1, all 80 columns).  grid (rslots, B*H); LDS: the first members of Smem (rows, transposed values, shifts).
+// G1, all 80 columns).  grid (rslots, B*H); LDS: Smem (rows, transposed values, shifts).
 // ---------------------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -466,7 +466,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
 
 #define FS_LAUNCH_CHECK_() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
 int launch_bwd_rstate(const BwdArgs& ba, int BH, hipStream_t st) {
-  hipLaunchKernelGGL(k_bwd_rstate, dim3(ba.rslots, BH), dim3(NT), offsetof(Smem, q), st, ba);
+  hipLaunchKernelGGL(k_bwd_rstate, dim3(ba.rslots, BH), dim3(NT), sizeof(Smem), st, ba);
   FS_LAUNCH_CHECK_();
   return 0;
 }
