@@ -193,6 +193,9 @@ def run_attention(name: str, steps: int, warmup: int, fs, synth, torch, nsets: i
         step(i, pairs[i])
     torch.cuda.synchronize()
     main_ms = float(np.mean([ev.elapsed_ms(a, b) for a, b in pairs]))
+    if prepared_ok:      # the parity leg checks what the timed call produces: the first input set once more, prepared
+        step_prepared(0)
+        torch.cuda.synchronize()
     for a, b in pairs:
         ev.destroy(a)
         ev.destroy(b)
