@@ -23,6 +23,10 @@ constexpr int FIT_DMAX = 128;
 // A pair of columns counts as orthogonal below this cosine.  The statistics carry fp32 rounding of the inputs'
 // products, so nothing is gained by iterating to the last bits of fp64.
 constexpr double kJacobiEps = 1e-13;
+// A sweep is followed by another one only if it met a pair above this cosine: the iteration converges quadratically,
+// so a sweep whose largest cosine is below 1e-8 leaves nothing above 1e-15 behind, and the sweep that would only
+// confirm that is not run.
+constexpr double kJacobiAgain = 1e-8;
 
 // Scalar minimiser of log(1-4A) - 1/2 log(1-8A) + phi/(1-8A)  (appendix lemma on the scalar objective).
 __device__ __forceinline__ double a_star(double phi) {
@@ -137,7 +141,7 @@ __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int 
                 }
               }
             }
-            if (r0 == 0) sh.flag = 1;
+            if (r0 == 0 && ga * ga > kJacobiAgain * kJacobiAgain * al * be) sh.flag = 1;
           }
         }
       }
@@ -171,7 +175,7 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
     __syncthreads();
     int pa = pair % (m - 1), pb = (m - 1 - pair) % (m - 1);
     for (int round = 0; round < m - 1; ++round) {
-      bool rot = false;
+      bool rot = false, big = false;
       double c = 1.0, s = 0.0;
       int p = 0, q = 0;
       double x[NA], y[NA], vx[NA], vy[NA];
@@ -192,6 +196,7 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
             c = rsqrt(1.0 + tn * tn);
             s = c * tn;
             rot = true;
+            big = apq * apq > kJacobiAgain * kJacobiAgain * fabs(app * aqq);
           }
         }
       }
@@ -230,7 +235,7 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
             a[(size_t)k * lda + q] = s * xx + c * yy;
           }
         }
-        if (r0 == 0) sh.flag = 1;
+        if (r0 == 0 && big) sh.flag = 1;
       }
       pa = pa + 1 == m - 1 ? 0 : pa + 1;
       pb = pb + 1 == m - 1 ? 0 : pb + 1;
