@@ -67,7 +67,8 @@ struct FitPlan {
 
 void plan_fit(int B, int H, int Lx, int Ly, int d, int groups, FitPlan* p) {
   const int L = std::max(Lx, Ly);
-  const int want = std::max(1, std::min(ceil_div(1024, B * H), ceil_div(L, 32)));
+  // about two workgroups of the scan per CU and tensor; every chunk is one more partial sum for the final kernel
+  const int want = std::max(1, std::min(ceil_div(512, B * H), ceil_div(L, 32)));
   p->rows_per_chunk = ceil_div(ceil_div(L, want), 32) * 32;
   p->nchunks = ceil_div(L, p->rows_per_chunk);
   const size_t per = (size_t)d * d + d;

@@ -708,7 +708,15 @@ __global__ void k_stats_final(const float* part, int B, int H, int nchunks, int 
       if (group_of(groups, b, h, H) != g) continue;
       rows += which ? Ly : Lx;
       const float* p = part + (((size_t)which * B * H + (size_t)b * H + h) * nchunks) * per + e;
-      for (int c = 0; c < nchunks; ++c) s += (double)p[(size_t)c * per];
+      // four independent partial sums: the loads of a whole group of chunks are in flight together
+      double s4[4] = {0.0, 0.0, 0.0, 0.0};
+      int c = 0;
+      for (; c + 4 <= nchunks; c += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s4[u] += (double)p[(size_t)(c + u) * per];
+      }
+      for (; c < nchunks; ++c) s4[0] += (double)p[(size_t)c * per];
+      s += (s4[0] + s4[1]) + (s4[2] + s4[3]);
     }
   stats[i] = s / (double)rows;
 }
