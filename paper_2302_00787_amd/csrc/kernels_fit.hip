@@ -48,6 +48,26 @@ struct FitShared {
   int flag;
 };
 
+// Tangent of the Jacobi rotation that annihilates the off-diagonal entry `off` of a 2 x 2 block whose diagonal
+// entries differ by `diff`: t = sign(z) / (|z| + sqrt(1 + z^2)), z = diff / (2 off).  The rotation must be orthogonal
+// to fp64 accuracy, its angle need not be (an error of 1e-6 of the angle leaves 1e-6 of the pair's off-diagonal entry
+// for the next sweep): fp32 with the hardware reciprocal and square root.  0, inf or NaN when there is nothing to
+// rotate (the callers skip those).
+__device__ __forceinline__ float rotation_tangent(float diff, float off) {
+  const float zeta = diff * __builtin_amdgcn_rcpf(2.f * off);
+  return copysignf(1.f, zeta) * __builtin_amdgcn_rcpf(fabsf(zeta) + __builtin_amdgcn_sqrtf(1.f + zeta * zeta));
+}
+
+// Cosine 1 / sqrt(1 + t^2) of the rotation with tangent t, |t| <= 1, to fp64 accuracy: the fp32 hardware estimate
+// and two Newton steps (relative error 1e-7 -> 1e-14 -> below the rounding of fp64).
+__device__ __forceinline__ double rotation_cosine(double t) {
+  const double x = 1.0 + t * t;
+  double c = (double)__builtin_amdgcn_rsqf((float)x);
+  c = c * (1.5 - 0.5 * x * c * c);
+  c = c * (1.5 - 0.5 * x * c * c);
+  return c;
+}
+
 // Batched access to a pair of strided vectors for the sizes where every lane of a pair handles exactly NI elements
 // (n = NI x lanes per pair: 32, 64, 128 with 512 threads).  Every request is issued before the first use, so a pair
 // costs one memory latency, not one per element as in the general loops (whose stores may alias the next loads).
@@ -112,14 +132,11 @@ __device__ __forceinline__ void jacobi_columns(double* g, double* v, int n, int 
             }
           }
           al = lanes_sum(al, tpp); be = lanes_sum(be, tpp); ga = lanes_sum(ga, tpp);
-          // The rotation must be orthogonal to fp64 accuracy, its angle need not be: the tangent is computed in fp32
-          // (an error of 1e-7 of the angle leaves 1e-7 of the pair's inner product for the next sweep), cosine and
-          // sine from it in fp64.
-          const float zeta = (float)(be - al) / (2.f * (float)ga);
-          const float tn32 = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+          // tangent in fp32, cosine and sine from it in fp64
+          const float tn32 = rotation_tangent((float)(be - al), (float)ga);
           if (ga * ga > kJacobiEps * kJacobiEps * al * be && tn32 != 0.f && isfinite(tn32)) {
             const double tn = (double)tn32;
-            const double c = rsqrt(1.0 + tn * tn), s = c * tn;
+            const double c = rotation_cosine(tn), s = c * tn;
             if constexpr (NI > 0) {
               double vx[NA], vy[NA];
               if (v != nullptr) fetch_pair<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy);
@@ -189,11 +206,10 @@ __device__ __forceinline__ void jacobi_symmetric(double* a, double* v, int n, in
             if (v != nullptr) fetch_pair<NA>(v + (size_t)p * ldv, v + (size_t)q * ldv, 1, r0, tpp, vx, vy);
           }
           const double app = a[(size_t)p * lda + p], aqq = a[(size_t)q * lda + q], apq = a[(size_t)q * lda + p];
-          const float zeta = (float)(aqq - app) / (2.f * (float)apq);
-          const float tn32 = copysignf(1.f, zeta) / (fabsf(zeta) + sqrtf(1.f + zeta * zeta));
+          const float tn32 = rotation_tangent((float)(aqq - app), (float)apq);
           if (apq * apq > kJacobiEps * kJacobiEps * fabs(app * aqq) && fabs(apq) > 1e-18 * scale && tn32 != 0.f && isfinite(tn32)) {
             const double tn = (double)tn32;
-            c = rsqrt(1.0 + tn * tn);
+            c = rotation_cosine(tn);
             s = c * tn;
             rot = true;
             big = apq * apq > kJacobiAgain * kJacobiAgain * fabs(app * aqq);
@@ -418,13 +434,17 @@ __global__ void __launch_bounds__(FIT_NT) k_fit_device(int variant, int d, const
       C1[e] = C2[e] = l == c ? -0.5f : 0.f;
       if (c == 0) A[l] = (float)a;
     }
+    // the per-eigenvalue terms of log D and of the objective in parallel (the logarithms are the expensive part),
+    // their sums in eigenvalue order by one thread
+    if (t < d) {
+      const double lam = fmax(sh.nrm[0][sh.ord[0][t]], 0.0), a = a_star(lam);
+      sh.nrm[1][t] = 0.25 * log(1.0 - 4.0 * a);
+      sh.nrm[2][t] = log(1.0 - 4.0 * a) - 0.5 * log(1.0 - 8.0 * a) + (1.0 + 1.0 / (1.0 - 8.0 * a)) * lam;
+    }
+    __syncthreads();
     if (t == 0) {
       double logD = 0.0, lbar = -tr1 - tr2;
-      for (int l = 0; l < d; ++l) {
-        const double lam = fmax(sh.nrm[0][sh.ord[0][l]], 0.0), a = a_star(lam);
-        logD += 0.25 * log(1.0 - 4.0 * a);
-        lbar += log(1.0 - 4.0 * a) - 0.5 * log(1.0 - 8.0 * a) + (1.0 + 1.0 / (1.0 - 8.0 * a)) * lam;
-      }
+      for (int l = 0; l < d; ++l) { logD += sh.nrm[1][l]; lbar += sh.nrm[2][l]; }
       write_header(th, logD, lbar, 3, variant);
       status[grp] = 0;
     }
