@@ -15,8 +15,11 @@
 //   query side  E^T = W X^T    (A = W~, B = rows; the same two register images with their roles exchanged)
 //                                                      -> lane <-> row, registers <-> features: P^T as B operand
 //               out^T += T^T P^T (A = T rows 4g + r of the tile)
-// Exponents live in the log2 domain.  Shifts come from the Cauchy-Schwarz bound |W~_m| |x| (no pass over the features
-// to find exact maxima): any in-range shift is exact because it is multiplied back at the end.
+// Exponents live in the log2 domain.  Shifts come from the Cauchy-Schwarz bounds bias_m + |W~_m| |x|, maximised over
+// the features from their norms alone (no projection pass to find exact maxima): any shift that keeps the factors in
+// range is exact, because it is applied back at the end (through the exponent field: the sum of two bounds may
+// leave the fp32 exponent range although the result does not).  What the bounds cannot see is the angle between x
+// and W~_m: a row all of whose true exponents lie more than about 2^120 below its bound flushes to zero.
 #include <algorithm>
 
 #include "fast_common.h"
@@ -99,12 +102,20 @@ struct SmemOp {
   float xo[NWV][RW][NC + 1];      // partial out^T tiles of the waves: [wave][row][column]
   float rt[RW];                   // row term log2e (x^T C x + alpha |x|^2) - shift of the row / of the workgroup
   float sh[RW];                   // per-row shift (query side)
+  float cs[RW];                   // largest Cauchy-Schwarz term |W~_m| |x| of the row (-inf past the end)
   float red[NWV];
 };
 
-// Rows to LDS, row terms and Cauchy-Schwarz bounds.  Returns nothing; fills sm.x, sm.rt (row term) and sm.sh
-// (row_shift(|x|) + row term + largest bias: an upper bound of every exponent of the row, -inf past the end).
-__device__ __forceinline__ void stage_rows(SmemOp& sm, const OpArgs& a, int side, int row0, float wmax, float bmax) {
+// Rows to LDS, row terms and shifts.  Fills sm.x, sm.rt (row term) and sm.sh = row term + max over the features m of
+// (bias_m + row_shift(|x|, |W~_m|)), -inf past the end.  By Cauchy-Schwarz no exponent of the row exceeds its shift by
+// more than 120 binary orders, and ordinary rows end up near zero.  The maximum is taken feature by feature (not
+// largest bias + largest norm): features with a long W~_m have a very negative bias when A is far from zero, and
+// a bound that ignores that can sit hundreds of binary orders above every actual exponent, which would flush the
+// whole row to zero.  What no norm can see is the angle between x and W~_m: the shift of a row lies at most 1.5 x its
+// largest Cauchy-Schwarz term (sm.cs) above the row's largest exponent.  Workgroups with a row beyond kSafeCs = 60
+// (90 binary orders at most: safe) replace the shifts by exact maxima found in a projection pass of their own.
+constexpr float kSafeCs = 60.f;
+__device__ __forceinline__ void stage_rows(SmemOp& sm, const OpArgs& a, int side, int row0, const float* wnorm, const float* bias) {
   const float* Xp = (const float*)a.X.ptr;
   for (int idx = threadIdx.x; idx < RW * a.d; idx += NTH) {
     const int r = idx / a.d, c = idx - r * a.d;
@@ -127,10 +138,32 @@ __device__ __forceinline__ void stage_rows(SmemOp& sm, const OpArgs& a, int side
   }
   n2 += __shfl_xor(n2, 1); n2 += __shfl_xor(n2, 2); n2 += __shfl_xor(n2, 4);
   qf += __shfl_xor(qf, 1); qf += __shfl_xor(qf, 2); qf += __shfl_xor(qf, 4);
+  const float len = __builtin_amdgcn_sqrtf(n2);
+  float bound = -INFINITY, csmax = 0.f;
+  for (int m0 = 0; m0 < a.M; m0 += 64) {
+    // eight features per thread and trip, all sixteen loads in flight together (indices past the end are clamped:
+    // a feature counted twice does not change a maximum)
+    float wn[8], bs[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int m = min(m0 + part + 8 * u, a.M - 1);
+      wn[u] = wnorm[m];
+      bs[u] = bias[m];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float cs = wn[u] * len;
+      csmax = fmaxf(csmax, cs);
+      bound = fmaxf(bound, bs[u] + fmaxf(fast::kBeta * cs, cs - 120.f));
+    }
+  }
+  bound = fmaxf(bound, __shfl_xor(bound, 1)); bound = fmaxf(bound, __shfl_xor(bound, 2)); bound = fmaxf(bound, __shfl_xor(bound, 4));
+  csmax = fmaxf(csmax, __shfl_xor(csmax, 1)); csmax = fmaxf(csmax, __shfl_xor(csmax, 2)); csmax = fmaxf(csmax, __shfl_xor(csmax, 4));
   if (part == 0) {
     const float rt = kLog2e * ((iso ? -0.5f * n2 : qf) + a.alpha * n2);
     sm.rt[r] = rt;
-    sm.sh[r] = row0 + r < a.N ? fast::row_shift(n2, wmax) + rt + bmax : -INFINITY;
+    sm.sh[r] = row0 + r < a.N ? bound + rt : -INFINITY;
+    sm.cs[r] = row0 + r < a.N ? csmax : -INFINITY;
   }
   __syncthreads();
 }
@@ -146,13 +179,13 @@ __global__ void __launch_bounds__(NTH) k_op_state(OpArgs a) {
   const int row0 = blockIdx.x * RW, nk = a.d >> 2, ntile = a.M >> 4;
   const float* W2 = a.W + (size_t)a.M * a.d;
   const float* b2 = a.bias + a.M;
-  const float wmax = block_max(a.wnorm + a.M, a.M, sm.red), bmax = block_max(b2, a.M, sm.red);
-  stage_rows(sm, a, 1, row0, wmax, bmax);
+  stage_rows(sm, a, 1, row0, a.wnorm + a.M, b2);
   for (int idx = threadIdx.x; idx < RW * NC; idx += NTH) {
     const int r = idx / NC, col = idx - r * NC;
     sm.c[r][col] = (row0 + r < a.N && col < a.n) ? a.C[(size_t)(row0 + r) * a.n + col] : 0.f;
   }
-  const float twg = block_max(sm.sh, RW, sm.red);      // (its barriers also publish sm.c)
+  float twg = block_max(sm.sh, RW, sm.red);            // (its barriers also publish sm.c)
+  const bool exact = block_max(sm.cs, RW, sm.red) > kSafeCs;
   // row operands, right-hand-side operands and the per-row part of the exponent, for the whole kernel
   float xr[4][KMAX], cr[4][4];
   f32x4 add[4];
@@ -161,13 +194,44 @@ __global__ void __launch_bounds__(NTH) k_op_state(OpArgs a) {
 #pragma unroll
     for (int k4 = 0; k4 < KMAX; ++k4) xr[tt][k4] = k4 < nk ? sm.x[16 * tt + c][4 * k4 + g] : 0.f;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      cr[tt][r] = sm.c[16 * tt + 4 * g + r][c];
-      // rows past the end: -inf, their features are exactly zero
-      add[tt][r] = row0 + 16 * tt + 4 * g + r < a.N ? sm.rt[16 * tt + 4 * g + r] - twg : -INFINITY;
-    }
+    for (int r = 0; r < 4; ++r) cr[tt][r] = sm.c[16 * tt + 4 * g + r][c];
   }
   float wr[KMAX], wn[KMAX];
+  if (exact) {
+    // the workgroup's largest exponent itself: one projection pass without the exponentials
+    float emax = -INFINITY;
+    for (int ft = w; ft < ntile; ft += NWV) {
+#pragma unroll
+      for (int k4 = 0; k4 < KMAX; ++k4) wr[k4] = k4 < nk ? W2[(size_t)(16 * ft + c) * a.d + 4 * k4 + g] : 0.f;
+      const float bm = b2[16 * ft + c];
+      f32x4 e[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          e[tt][r] = row0 + 16 * tt + 4 * g + r < a.N ? sm.rt[16 * tt + 4 * g + r] + bm : -INFINITY;
+#pragma unroll
+      for (int k4 = 0; k4 < KMAX; ++k4)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) e[tt] = mfma4(xr[tt][k4], wr[k4], e[tt]);
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) emax = fmaxf(emax, e[tt][r]);
+    }
+    emax = fast::wave_max(emax);
+    if (lane == 0) sm.red[w] = emax;
+    __syncthreads();
+    twg = sm.red[0];
+#pragma unroll
+    for (int i = 1; i < NWV; ++i) twg = fmaxf(twg, sm.red[i]);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)   // rows past the end: -inf, their features are exactly zero
+      add[tt][r] = row0 + 16 * tt + 4 * g + r < a.N ? sm.rt[16 * tt + 4 * g + r] - twg : -INFINITY;
   int ft = w;
   if (ft < ntile) {
 #pragma unroll
@@ -232,20 +296,56 @@ __global__ void __launch_bounds__(NTH) k_op_apply(OpArgs a) {
   __shared__ SmemOp sm;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int row0 = blockIdx.x * RW, nk = a.d >> 2, ntile = a.M >> 4;
-  const float wmax = block_max(a.wnorm, a.M, sm.red), bmax = block_max(a.bias, a.M, sm.red);
-  stage_rows(sm, a, 0, row0, wmax, bmax);
+  stage_rows(sm, a, 0, row0, a.wnorm, a.bias);
+  const bool exact = block_max(sm.cs, RW, sm.red) > kSafeCs;
   float xr[4][KMAX], add[4];
 #pragma unroll
   for (int tt = 0; tt < 4; ++tt) {
 #pragma unroll
     for (int k4 = 0; k4 < KMAX; ++k4) xr[tt][k4] = k4 < nk ? sm.x[16 * tt + c][4 * k4 + g] : 0.f;
-    // the row's own part of the exponent minus its shift (rows past the end: their results are not stored)
-    add[tt] = row0 + 16 * tt + c < a.N ? sm.rt[16 * tt + c] - sm.sh[16 * tt + c] : 0.f;
   }
+  float wr[KMAX], wn[KMAX];
+  if (exact) {
+    // every row's largest exponent itself: one projection pass without the exponentials; a wave's maxima of row
+    // 16 tt + c end up in its lanes (., c), the waves meet in LDS
+    float rmax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    for (int ft = w; ft < ntile; ft += NWV) {
+#pragma unroll
+      for (int k4 = 0; k4 < KMAX; ++k4) wr[k4] = k4 < nk ? a.W[(size_t)(16 * ft + c) * a.d + 4 * k4 + g] : 0.f;
+      f32x4 bm;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) bm[r] = a.bias[16 * ft + 4 * g + r];
+      f32x4 e[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) e[tt] = bm + sm.rt[16 * tt + c];
+#pragma unroll
+      for (int k4 = 0; k4 < KMAX; ++k4)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) e[tt] = mfma4(wr[k4], xr[tt][k4], e[tt]);
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) rmax[tt] = fmaxf(rmax[tt], fmaxf(fmaxf(e[tt][0], e[tt][1]), fmaxf(e[tt][2], e[tt][3])));
+    }
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) {
+      rmax[tt] = fmaxf(rmax[tt], __shfl_xor(rmax[tt], 16));
+      rmax[tt] = fmaxf(rmax[tt], __shfl_xor(rmax[tt], 32));
+      if (g == 0) sm.xo[w][16 * tt + c][0] = rmax[tt];
+    }
+    __syncthreads();
+    if (threadIdx.x < RW) {
+      float m = sm.xo[0][threadIdx.x][0];
+#pragma unroll
+      for (int wv = 1; wv < NWV; ++wv) m = fmaxf(m, sm.xo[wv][threadIdx.x][0]);
+      sm.sh[threadIdx.x] = m;
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt)   // the row's own part of the exponent minus its shift (rows past the end: their results are not stored)
+    add[tt] = row0 + 16 * tt + c < a.N ? sm.rt[16 * tt + c] - sm.sh[16 * tt + c] : 0.f;
   f32x4 o[4];
 #pragma unroll
   for (int tt = 0; tt < 4; ++tt) o[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float wr[KMAX], wn[KMAX];
   f32x4 tr, tn;
   int ft = w;
   if (ft < ntile) {
@@ -292,7 +392,10 @@ __global__ void __launch_bounds__(NTH) k_op_apply(OpArgs a) {
       float v = 0.f;
 #pragma unroll
       for (int wv = 0; wv < NWV; ++wv) v += sm.xo[wv][r][col];
-      a.out[(size_t)(row0 + r) * a.n + col] = v * fast_exp2(sm.sh[r] + ts);
+      // v 2^(s_i + t*): the two shifts are bounds and may add up to more than the fp32 exponent range although the
+      // result is representable, so the power of two is applied through the exponent field, not as a factor
+      const float sft = sm.sh[r] + ts, whole = floorf(sft);
+      a.out[(size_t)(row0 + r) * a.n + col] = ldexpf(v * fast_exp2(sft - whole), (int)fminf(fmaxf(whole, -1000.f), 1000.f));
     }
   }
 }

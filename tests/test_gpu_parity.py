@@ -198,6 +198,30 @@ def test_kernel_matvec_small(fs, variant):
         np.testing.assert_allclose(out, ref, rtol=1e-3, atol=1e-4 * np.abs(ref).max())
 
 
+@pytest.mark.parametrize("variant", ["sderf", "aderf"])
+@pytest.mark.parametrize("Nx,Ny,d,M,n", [(70, 121, 12, 64, 5), (333, 1000, 32, 512, 16), (129, 64, 64, 48, 1), (1, 257, 4, 16, 3)])
+def test_kernel_matvec_on_the_operator_kernels(fs, variant, Nx, Ny, d, M, n):
+    """Shapes that take the fp32 MFMA operator kernels (fp32 rows, d a multiple of 4 up to 64, M a multiple of 16, at
+    most 16 right-hand sides): different and ragged set sizes, dense and isotropic quadratic forms, both exponents."""
+    import torch
+    rng = np.random.default_rng(1000 * d + M)
+    X = (rng.random((Nx, d)) * 1.2 - 0.1).astype(np.float32)
+    Yp = (rng.random((Ny, d)) * 0.9 + 0.05).astype(np.float32)
+    C = rng.standard_normal((Ny, n)).astype(np.float32)
+    Om = rng.standard_normal((M, d)).astype(np.float32)
+    fitX = X if Nx >= d + 2 else np.concatenate([X, Yp[: d + 2]])      # the dense families need a non-singular M1
+    vec = util.theta_vec_from_oracle(orc.fit(variant, fitX.astype(np.float64), Yp.astype(np.float64)))
+    th = util.oracle_theta_from_vec(vec, d)
+    for alpha in (0.0, -0.5):
+        ref = orc.kernel_matvec(th, Om, X, Yp, C, alpha)
+        out = util.to_host(fs.kernel_matvec(torch.from_numpy(vec).cuda(), torch.from_numpy(X).cuda(),
+                                            torch.from_numpy(Yp).cuda(), 1.0, alpha, torch.from_numpy(Om).cuda(),
+                                            torch.from_numpy(C).cuda()))
+        assert np.isfinite(out).all()
+        assert np.linalg.norm(out - ref) / np.linalg.norm(ref) <= 1e-4, (alpha, np.linalg.norm(out - ref) / np.linalg.norm(ref))
+        np.testing.assert_allclose(out, ref, rtol=1e-3, atol=1e-4 * np.abs(ref).max())
+
+
 # ----------------------------------------------------------------------------- fit
 def _fit(fs, entry, variant, Qd, Kd, s, groups):
     """theta [groups, floats] on the host from either fit entry point."""
