@@ -720,6 +720,43 @@ def _replay_and_compare(call, Y, name):
         _ = torch.randn(1 << 20, device="cuda").sum().item()
 
 
+@pytest.mark.parametrize("name,over", [("c1", {}), ("c3", dict(B=2, H=2, L=704)), ("c4", dict(B=1, H=2, L=1216)),
+                                       ("c5", dict(B=1, H=2, L=832))])
+def test_attention_timed_gives_the_same_result_and_a_kernel_time(fs, name, over):
+    """favorsharp_attention_timed: the two events bracket the main kernel (attached to its dispatch on the bf16 paths,
+    recorded around it on the general path); the result is that of favorsharp_attention bit for bit, and the time
+    between the events is positive and no longer than the whole call."""
+    import ctypes
+    import time
+    import torch
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    w = synth.make(name, **over)
+    dt = w.get("dtype", "f32")
+    Q, K, V = (util.to_device(w[k], dt) for k in "QKV")
+    Om, s, causal = torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"], bool(w["causal"])
+    theta = fs.fit_params("sderf", Q, K, s, groups=w["H"])
+    ref = fs.attention(theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0))
+    ev = [ctypes.c_void_p(), ctypes.c_void_p()]
+    for e in ev:
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    Y = fs.attention(theta, Q, K, V, s, Om, causal=causal, chunk=w.get("chunk", 0), events=(ev[0].value, ev[1].value))
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    assert hip.hipEventSynchronize(ev[1]) == 0
+    ms = ctypes.c_float()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), ev[0], ev[1]) == 0
+    for e in ev:
+        hip.hipEventDestroy(e)
+    assert torch.equal(Y, ref)
+    assert 0.0 < ms.value <= wall_ms, (ms.value, wall_ms)
+
+
 @pytest.mark.parametrize("name,over,variant", [("c4", dict(B=2, H=2, L=1216), "sderf"), ("c4", dict(B=1, H=2, L=333), "aderf"),
                                                ("c3", dict(B=2, H=2, L=712), "sderf"), ("c5", dict(B=1, H=2, L=832), "sderf"),
                                                ("c5", dict(B=1, H=2, L=200), "aderf")])
