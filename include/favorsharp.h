@@ -247,6 +247,22 @@ int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor
                                  int causal, int chunk, const fs_tensor* Y, void* stream);
 
 /*
+ * Denominator guard of the attention equation (Section 2.2: the row sums of K_hat divide the output).  With positive
+ * features the row sum is positive mathematically; in fp32 a query row whose largest feature exponent lies more than
+ * about 2^126 below the row's own shift, or that meets only key features flushed the same way, can still give a row
+ * sum of exactly 0.  Every attention entry point above then writes that output row as zeros instead of dividing, and
+ * counts it: the first 32-bit word of the call's workspace holds, once the call's kernels have finished, the number
+ * of such rows of that call (all (b, h) together; every call starts it at 0).  A caller that wants no host
+ * synchronisation reads that word from the workspace itself; this function does it for them:
+ *   workspace:  the workspace of the attention call in question (device), or NULL for the scratch array of
+ *               favorsharp_attention_noalloc on the current device;
+ *   host_count: (out, host) the counter.
+ * SYNCHRONOUS with respect to `stream` (pass the attention call's stream).  FS_ERR_INVALID_ARG on a null
+ * host_count, FS_ERR_DEVICE when the copy fails.
+ */
+int favorsharp_attention_flushed_rows(const void* workspace, int* host_count, void* stream);
+
+/*
  * Block-orthogonal random features (the appendix on the classification experiments says the omegas there are
  * orthogonal; the construction is not printed in the paper: this is the textbook one).  HOST function, host pointers:
  *   host_gauss_dir, host_gauss_len: [groups][M][d] float32, independent N(0,1) draws supplied by the caller;

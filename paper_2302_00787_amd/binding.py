@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.favorsharp_attention_prepared.argtypes = [c_void_p, c_size_t, c_int] + L.favorsharp_attention.argtypes
         L.favorsharp_attention_noalloc.restype = c_int
         L.favorsharp_attention_noalloc.argtypes = L.favorsharp_attention.argtypes[:18] + [c_void_p]
+        L.favorsharp_attention_flushed_rows.restype = c_int
+        L.favorsharp_attention_flushed_rows.argtypes = [c_void_p, ctypes.POINTER(c_int), c_void_p]
         L.favorsharp_attention_backward_workspace_bytes.restype = c_size_t
         L.favorsharp_attention_backward_workspace_bytes.argtypes = [c_int] * 10
         L.favorsharp_attention_backward.restype = c_int
@@ -337,6 +339,16 @@ def attention_noalloc(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: 
                                             ctypes.byref(dy), _stream())
     _check(st, "favorsharp_attention_noalloc")
     return out
+
+
+def attention_flushed_rows(workspace: torch.Tensor | None = None) -> int:
+    """favorsharp_attention_flushed_rows: how many output rows of the last attention call on `workspace` (None: the
+    scratch array of `attention_noalloc`) had a zero normaliser and were written as zeros.  Waits for the stream."""
+    n = c_int(0)
+    st = lib().favorsharp_attention_flushed_rows(None if workspace is None else workspace.data_ptr(), ctypes.byref(n),
+                                                 _stream())
+    _check(st, "favorsharp_attention_flushed_rows")
+    return int(n.value)
 
 
 def attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups) -> int:

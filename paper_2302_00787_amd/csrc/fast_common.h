@@ -125,6 +125,7 @@ struct FastArgs {
                            // numbers of lane l for tile (mt, vt) of wave w at ((w*4 + mt)*NVT + vt)*256 + 4 l
                            // (16-byte accesses; the forward kernels, whose waves all hold a state that way)
   float scale;
+  unsigned* flushed;       // counter of output rows with a zero normaliser (nullptr: not counted)
 };
 
 // ---- transposing LDS reads ----------------------------------------------------------------------------------------
@@ -396,13 +397,28 @@ __device__ __forceinline__ float finish_col64(const S& sm, int it, int lane) {
   return dn[0];
 }
 // Normaliser of token tile `it` (column 64); the sums are scaled in place.  Returns 1 / normaliser (0 if it is 0).
+// `zero_tokens` (optional) receives the tile's tokens whose normaliser is not positive as a bit mask (bit c = token
+// 16 it + c; wave-uniform): all of such a row's features, or all of the state it meets, flushed to zero, and the row
+// is written as zeros.
 template <class S>
-__device__ __forceinline__ float finish_norm(f32x4 (&fs)[4], const S& sm, int it, int lane) {
+__device__ __forceinline__ float finish_norm(f32x4 (&fs)[4], const S& sm, int it, int lane,
+                                             unsigned* zero_tokens = nullptr) {
   const float den = finish_col64(sm, it, lane);
   const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+  if (zero_tokens != nullptr) *zero_tokens = (unsigned)__ballot(!(den > 0.f)) & 0xffffu;     // lanes 0..15: g = 0, c = lane
 #pragma unroll
   for (int vt = 0; vt < 4; ++vt) fs[vt] *= inv;
   return inv;
+}
+// How many of the tokens in `zero_tokens` are among the first `nv` tokens of the chunk (wave-uniform arithmetic).
+__device__ __forceinline__ int count_zero_tokens(unsigned zero_tokens, int it, int nv) {
+  const int left = nv - 16 * it;
+  const unsigned valid = left >= 16 ? 0xffffu : (left > 0 ? (1u << left) - 1u : 0u);
+  return __builtin_popcount(zero_tokens & valid);
+}
+// One wave's count goes to the call's counter of rows with a zero normaliser (nothing to do in the usual case).
+__device__ __forceinline__ void report_zero_rows(unsigned* flushed, int n, int lane) {
+  if (flushed != nullptr && n > 0 && lane == 0) atomicAdd(flushed, (unsigned)n);
 }
 
 // Shared memory of the query-side kernels that keep their state in registers (64 kB: two workgroups per CU).

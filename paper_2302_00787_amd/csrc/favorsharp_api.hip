@@ -41,6 +41,9 @@ struct AttnPlan {
   size_t off_W, off_Wbf, off_bias, off_kmax, off_state, total;
 };
 
+// Every attention workspace starts with one 32-bit word (in a block of kAlign bytes): the number of output rows of the
+// last call whose normaliser came out as zero (favorsharp_attention_flushed_rows reads it).
+//
 // Shared by the workspace query and the call so that both agree.
 void plan_contraction(int BH, int pgroups, int Lk, int d, int M, int nv1, int causal, AttnPlan* p) {
   p->pgroups = pgroups;
@@ -51,11 +54,11 @@ void plan_contraction(int BH, int pgroups, int Lk, int d, int M, int nv1, int ca
   else want = std::max(1, std::min(ceil_div(2048, BH * nmb), ceil_div(Lk, 32)));
   p->rows_per_seg = ceil_div(ceil_div(Lk, want), 32) * 32;
   p->nseg = ceil_div(Lk, p->rows_per_seg);
-  size_t off = 0;
+  size_t off = kAlign;       // the counter word; the key maxima follow it so that one fill clears both
+  p->off_kmax = off; off = align_up(off + (size_t)BH * sizeof(uint32_t));
   p->off_W = off;    off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(float));
   p->off_Wbf = off;  off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(uint16_t));
   p->off_bias = off; off = align_up(off + (size_t)pgroups * 2 * M * sizeof(float));
-  p->off_kmax = off; off = align_up(off + (size_t)BH * sizeof(uint32_t));
   p->off_state = off; off = align_up(off + (size_t)BH * p->nseg * M * p->ldt * sizeof(float));
   p->total = off;
 }
@@ -86,7 +89,7 @@ struct FastPlan {
 void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
   p->pgroups = pgroups;
   fast_plan(BH, Lk, &p->nseg, &p->rows_per_seg, &p->sub);
-  size_t off = 0;
+  size_t off = kAlign;       // the counter word
   p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 256 * 64 * sizeof(uint16_t));
   p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 256 * sizeof(float));
   p->off_wnorm = off;  off = align_up(off + (size_t)pgroups * 2 * 256 * sizeof(float));
@@ -104,7 +107,7 @@ struct WidePlan {
 
 void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
   wide_plan(BH, L, &p->nslot, &p->rows_per_slot);
-  size_t off = 0;
+  size_t off = kAlign;       // the counter word
   p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 512 * 128 * sizeof(uint16_t));
   p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 512 * sizeof(float));
   p->off_wnorm = off;  off = align_up(off + (size_t)pgroups * 2 * 512 * sizeof(float));
@@ -318,7 +321,7 @@ size_t favorsharp_features_workspace_bytes(int n, int d, int M) {
   if (n < 0 || d < 1 || d > 128 || M < 1) return 0;
   AttnPlan p;
   plan_contraction(1, 1, 32, d, M, 1, 0, &p);
-  return p.off_kmax;       // projection constants only
+  return p.off_state;      // everything in front of the states: the projection constants are the part used here
 }
 
 int favorsharp_features(const float* theta, int side, const fs_tensor* X, int n, int d, float qk_scale, float alpha,
@@ -455,7 +458,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
   if (workspace_bytes < favorsharp_attention_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups))
     return FS_ERR_WORKSPACE_TOO_SMALL;
-  if (Lq == 0) return FS_OK;
+  if (Lq == 0) return launch_fill_u32((uint32_t*)workspace, 0u, 1, (hipStream_t)stream);     // no rows: the counter reads 0
   const int lds_limit = device_lds_limit();
   // the bf16 kernels address the rows of a chunk with 32-bit offsets
   const long long max_sl = 1ll << 23;
@@ -473,6 +476,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     f.Wbf = (uint16_t*)(w8 + fp.off_Wbf); f.bias = (float*)(w8 + fp.off_bias); f.wnorm = (float*)(w8 + fp.off_wnorm);
     f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
     f.cstar = (float*)(w8 + fp.off_cstar);
+    f.flushed = (unsigned*)w8;
     if (prepared != nullptr) {
       PreparedPlan pp;
       plan_prepared(d, M, pgroups, &pp);
@@ -494,6 +498,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     f.Wbf = (uint16_t*)(w8 + wp.off_Wbf); f.bias = (float*)(w8 + wp.off_bias); f.wnorm = (float*)(w8 + wp.off_wnorm);
     f.rk = (float*)(w8 + wp.off_rk); f.Tpart = (float*)(w8 + wp.off_state); f.cpart = (float*)(w8 + wp.off_cpart);
     f.cstar = (float*)(w8 + wp.off_cstar); f.Ypart = (float*)(w8 + wp.off_ypart);
+    f.flushed = (unsigned*)w8;
     if (prepared != nullptr) {
       PreparedPlan pp;
       plan_prepared(d, M, pgroups, &pp);
@@ -521,7 +526,9 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
   const long long tf = (long long)favorsharp_theta_floats(d);
 
   if (int rc = launch_prep(theta, groups, Omega, omega_groups, pgroups, B, H, M, d, W, Wbf, bias, st)) return rc;
-  if (int rc = launch_fill_u32(kmax, 0u, BH, st)) return rc;
+  // the counter word and the key maxima behind it
+  unsigned* flushed = (unsigned*)ws;
+  if (int rc = launch_fill_u32((uint32_t*)ws, 0u, p.off_kmax / sizeof(uint32_t) + BH, st)) return rc;
   GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
   GenSide ks{dev(K), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
   if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
@@ -532,9 +539,9 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
   if (event_main_begin && hipEventRecord((hipEvent_t)event_main_begin, st) != hipSuccess) return FS_ERR_DEVICE;
   int rc;
   if (causal)
-    rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), nullptr, nullptr, st);
+    rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, p.ldt, p.rows_per_seg, p.nseg, kmax, state, dev(Y), nullptr, nullptr, st, flushed);
   else
-    rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), nullptr, nullptr, st);
+    rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, p.ldt, state, (size_t)p.nseg * per_state, kmax, 0, dev(Y), nullptr, nullptr, st, flushed);
   if (rc) return rc;
   if (event_main_end && hipEventRecord((hipEvent_t)event_main_end, st) != hipSuccess) return FS_ERR_DEVICE;
   return FS_OK;
@@ -555,6 +562,21 @@ int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor
   // every kernel of the call writes the part of the workspace it later reads: nothing has to start at zero
   return favorsharp_attention_timed(theta, groups, Q, K, V, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M,
                                     causal, chunk, Y, ws, FS_NOALLOC_SCRATCH_BYTES, stream, nullptr, nullptr);
+}
+
+int favorsharp_attention_flushed_rows(const void* workspace, int* host_count, void* stream) {
+  if (host_count == nullptr) return FS_ERR_INVALID_ARG;
+  if (workspace == nullptr) {
+    void* ws = nullptr;
+    if (int rc = scratch_for_current_device(&ws)) return rc;
+    workspace = ws;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  unsigned v = 0;
+  if (hipMemcpyAsync(&v, workspace, sizeof(unsigned), hipMemcpyDeviceToHost, st) != hipSuccess) return FS_ERR_DEVICE;
+  if (hipStreamSynchronize(st) != hipSuccess) return FS_ERR_DEVICE;
+  *host_count = (int)std::min(v, 0x7fffffffu);
+  return FS_OK;
 }
 
 // ------------------------------------------------------------------------------------------ attention, backward

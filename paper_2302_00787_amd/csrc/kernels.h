@@ -44,7 +44,7 @@ int launch_gen_state(const GenSide& ks, const TensorDev& V, int Lk, int BH, int 
 int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int prefix, hipStream_t st);
 int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
                      size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, float* den_out,
-                     float* shift_out, hipStream_t st);
+                     float* shift_out, hipStream_t st, unsigned* flushed = nullptr);
 // Backward pass of non-causal attention (general-shape kernels).
 size_t gen_lds_bwd_side(int d, int ldt);
 int launch_bwd_ghat(const TensorDev& dY, float* buf, const float* den, int L, int BH, int H, int nv, int ldt,
@@ -55,7 +55,7 @@ int launch_gen_bwd_side(const GenSide& sd, int side, const TensorDev& A, int a_c
                         const TensorDev& grad, hipStream_t st);
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
-                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st);
+                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st, unsigned* flushed = nullptr);
 size_t gen_lds_bwd_causal(int d, int ldt);
 int launch_gen_bwd_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, const float* ghat, int L, int BH, int H,
                           int M, int d, int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u,
@@ -96,6 +96,7 @@ struct FastLaunch {
   float* Tpart;     // [B*H][nseg*sub][256][80]
   float* cpart;     // [B*H][nseg*sub]
   float* cstar;     // [B*H]
+  unsigned* flushed = nullptr;   // counter of output rows whose normaliser came out as zero (nullptr: not counted)
   // 0: compute the projection constants and the key row terms; 1: the constants are already in Wbf / bias / wnorm
   // (prepared by an earlier call), only the row terms of parameter sets with a dense C2 are computed; 2: the
   // constants are there and no parameter set has a dense C2: nothing to do
@@ -119,6 +120,7 @@ struct WideLaunch {
   float* cpart;     // [B*H][nslot]
   float* cstar;     // [B*H]
   float* Ypart;     // [B*H][L][132]
+  unsigned* flushed = nullptr;   // as in FastLaunch
   int pre_mode = 0; // as in FastLaunch
 };
 bool wide_supported(int dtype, int d, int dv, int M, int causal);

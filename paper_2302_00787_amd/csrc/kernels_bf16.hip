@@ -267,8 +267,10 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
 // per-sequence shifts, at cstar[B*H + bh * nseg + s]; -inf and a zero state for slot 0), so that keys late in the
 // sequence cannot push the states the earlier rows need out of the fp32 range.  grid (ceil(M*DVP/1024), B*H).
 __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, int nseg, int nseg_valid, int prefix,
-                              int sub) {
+                              int sub, unsigned* flushed) {
   const int bh = blockIdx.y;
+  // the query-side kernel of the call counts into this word: it starts every call at zero
+  if (flushed != nullptr && (blockIdx.x | blockIdx.y | threadIdx.x) == 0) *flushed = 0u;
   constexpr size_t per = (size_t)M * DVP;
   const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);      // four consecutive numbers per thread
   float* p = Tpart + (size_t)bh * nseg * per + e;
@@ -343,7 +345,7 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
   load_rows_g(qr, Qb, a.Q.sl, row_beg, row_end);
   store_query_rows(qr, sm, 0, wmax);
   __syncthreads();
-  int buf = 0;
+  int buf = 0, nzero = 0;          // nzero: rows this wave finished with a zero normaliser
   for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
     const bool more = row0 + TC < row_end;
     if (more) load_rows_g(qr, Qb, a.Q.sl, row0 + TC, row_end);
@@ -365,7 +367,9 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
       f32x4 fs[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
       finish_tiles(fs, sm, w, 0, lane);
       finish_tiles(fs, sm, w, 2, lane);
-      finish_norm(fs, sm, w, lane);
+      unsigned zt;
+      finish_norm(fs, sm, w, lane, &zt);
+      nzero += count_zero_tokens(zt, w, row_end - row0);
       const int token = row0 + 16 * w + c;
       if (token < row_end) {
         if (a.Y.dtype == 1) {
@@ -382,6 +386,7 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
     if (more) store_query_rows(qr, sm, buf ^ 1, wmax);
     __syncthreads();
   }
+  report_zero_rows(a.flushed, nzero, lane);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -478,6 +483,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   a.sub = f.sub; a.nslot = f.nseg * f.sub;
   a.timg = images ? 1 : 0;
   a.scale = f.scale;
+  a.flushed = f.flushed;
   const int BH = f.B * f.H;
   const int rowblocks = std::min(64, (f.Lk + 3) / 4), nprep = (M / 4) * 2 * f.pgroups;
   if (f.pre_mode == 0) {
@@ -498,7 +504,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
     FS_LAUNCH_CHECK();
   }
   hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
-                     a.nslot, nstate, f.causal ? (every_slot ? 1 : 2) : 0, every_slot ? 1 : f.sub);
+                     a.nslot, nstate, f.causal ? (every_slot ? 1 : 2) : 0, every_slot ? 1 : f.sub, f.flushed);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -513,7 +519,8 @@ int launch_fast_prepare(const float* theta, int groups, const float* Omega, int 
 
 // Sum of `nslot` segment states per (b,h) into slot 0 (the reduction kernel of the forward pass on another buffer).
 void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st) {
-  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, part, cpart, cstar, nslot, nslot, 0, 1);
+  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, part, cpart, cstar, nslot, nslot, 0, 1,
+                     (unsigned*)nullptr);
 }
 
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {

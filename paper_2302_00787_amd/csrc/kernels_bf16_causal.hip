@@ -199,6 +199,7 @@ __device__ __forceinline__ void key_tile_major(const W64& wk, const XOp& x, f32x
 
 __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const SegCtx& cx, int j) {
   const int tid = threadIdx.x, lane = tid & 63;
+  int nzero = 0;                   // rows this wave finished with a zero normaliser
   const float wmax1 = max256(a.wnorm + ((size_t)cx.pg * 2) * M), amax1 = max256(a.bias + ((size_t)cx.pg * 2) * M);
   const float wmax2 = max256(a.wnorm + ((size_t)cx.pg * 2 + 1) * M);
   // both projection slices stay in registers (they are the same numbers when B1 = B2; the producers have room)
@@ -304,7 +305,9 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
         if (tid_here < 2) { if (tid_here == 0) sm.kmax[buf ^ 1] = -INFINITY; else sm.qmax[buf ^ 1] = -INFINITY; }
         finish_tiles(fsum, sm, j, 0, lane_here);
         finish_tiles(fsum, sm, j, 2, lane_here);
-        finish_norm(fsum, sm, j, lane_here);
+        unsigned zt;
+        finish_norm(fsum, sm, j, lane_here, &zt);
+        nzero += row0 > cx.row_beg ? __builtin_popcount(zt) : 0;      // (the previous chunk is a whole one)
       }
       if (S == 3) {
         finish_store(fsum, a.Y, yprev, row0 > cx.row_beg ? TC : 0, j, lane_here);
@@ -322,9 +325,12 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
     f32x4 fsum[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     finish_tiles(fsum, sm, j, 0, lane);
     finish_tiles(fsum, sm, j, 2, lane);
-    finish_norm(fsum, sm, j, lane);
+    unsigned zt;
+    finish_norm(fsum, sm, j, lane, &zt);
+    nzero += count_zero_tokens(zt, j, cx.row_end - last0);
     finish_store(fsum, a.Y, yprev, cx.row_end - last0, j, lane);
   }
+  report_zero_rows(a.flushed, nzero, lane);
 }
 
 __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const SegCtx& cx, int seg, int j) {

@@ -51,6 +51,7 @@ struct WideArgs {
   int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;
   int fh;            // feature half of this launch of the walk
   float scale;
+  unsigned* flushed; // counter of output rows with a zero normaliser (nullptr: not counted)
 };
 
 __device__ __forceinline__ float max512(const float* p) {
@@ -287,8 +288,10 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
 // cstar[B*H + bh * nslot + s]; cstar[bh] = the sequence's largest).  Keys late in the sequence thus cannot push the
 // states that earlier rows need out of the fp32 range.  Four consecutive numbers per thread.
 // grid (ceil(256*144/1024), B*H*2).
-__global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot) {
+__global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot, unsigned* flushed) {
   const int bh2 = blockIdx.y, bh = bh2 >> 1;
+  // the walk of the call counts into this word: it starts every call at zero
+  if (flushed != nullptr && (blockIdx.x | blockIdx.y | threadIdx.x) == 0) *flushed = 0u;
   constexpr size_t per = (size_t)256 * TLD;
   const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
   const bool writer = e == 0 && (bh2 & 1) == 0;
@@ -439,6 +442,9 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
       for (int vt = 0; vt < 4; ++vt) fsum[vt] += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(ry, off + 64 * vt, 0, 0));
       den += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ry, doff, 0, 0));
       const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+      // a row is finished once per column half: the first half counts it
+      if (a.flushed != nullptr && cx.ch == 0 && __builtin_expect(!(den > 0.f) && g == 0 && 16 * j + c < nv, 0))
+        atomicAdd(a.flushed, 1u);
 #pragma unroll
       for (int vt = 0; vt < 4; ++vt) fsum[vt] *= inv;
       const int esz = a.Y.dtype == 1 ? 2 : 4;
@@ -670,6 +676,7 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   a.Ypart = f.Ypart;
   a.groups = f.groups; a.omega_groups = f.omega_groups; a.pgroups = f.pgroups; a.B = f.B; a.H = f.H; a.L = f.L;
   a.nslot = f.nslot; a.rows_per_slot = f.rows_per_slot; a.scale = f.scale;
+  a.flushed = f.flushed;
   const int BH = f.B * f.H;
   if (hipFuncSetAttribute((const void*)k_wide_state, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWState)) != hipSuccess ||
       hipFuncSetAttribute((const void*)k_wide_walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWWalk)) != hipSuccess) {
@@ -686,7 +693,8 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   }
   hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
   FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot);
+  hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
+                     f.flushed);
   FS_LAUNCH_CHECK();
   // the optional events are attached to the dispatches of the two walks: begin of the first, end of the second
   for (int fh = 0; fh < 2; ++fh) {

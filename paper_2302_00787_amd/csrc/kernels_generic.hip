@@ -373,9 +373,10 @@ __global__ void __launch_bounds__(256) k_gen_reduce(float* Tpart, int nseg, size
   }
 }
 
-// Normalise (attention) or rescale (operator) an accumulated 32 x ldt tile held in LDS and store it.
+// Normalise (attention) or rescale (operator) an accumulated 32 x ldt tile held in LDS and store it.  Attention
+// rows whose normaliser is not positive are written as zeros and, with a counter, counted (once per row).
 __device__ void store_result(const float* Os, int ldo, const TensorDev& Y, long long ybase, int row0, int nrows,
-                             int nv, int matvec, const float* row_log2scale) {
+                             int nv, int matvec, const float* row_log2scale, unsigned* flushed = nullptr) {
   for (int idx = threadIdx.x; idx < TR * nv; idx += NT) {
     const int r = idx / nv, c = idx - r * nv;
     if (row0 + r >= nrows) continue;
@@ -384,6 +385,7 @@ __device__ void store_result(const float* Os, int ldo, const TensorDev& Y, long 
     else {
       const float den = Os[r * ldo + nv];
       v = den > 0.f ? v / den : 0.f;
+      if (flushed != nullptr && c == 0 && !(den > 0.f)) atomicAdd(flushed, 1u);
     }
     store_elem(Y, ybase + (long long)(row0 + r) * Y.sl + c, v);
   }
@@ -395,7 +397,8 @@ __device__ void store_result(const float* Os, int ldo, const TensorDev& Y, long 
 // ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int M, int d, int nv, int ldt,
                                                   const float* T, size_t state_stride, const uint32_t* kmax_u,
-                                                  int matvec, TensorDev Y, float* den_out, float* shift_out) {
+                                                  int matvec, TensorDev Y, float* den_out, float* shift_out,
+                                                  unsigned* flushed) {
   extern __shared__ float smem[];
   const int dpad = (d + 3) & ~3, ld = dpad + 1, ldts = ldt + 1, lds = MB + 1;
   float* Xs = smem;
@@ -486,7 +489,7 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
     }
   }
   __syncthreads();
-  store_result(Os, ldts, Y, b * Y.sb + h * Y.sh, row0, Lq, nv, matvec, rscale);
+  store_result(Os, ldts, Y, b * Y.sb + h * Y.sh, row0, Lq, nv, matvec, rscale, flushed);
   // for the backward pass: the (shifted) denominators and the shifts themselves, so that it rebuilds the same features
   if (den_out != nullptr && threadIdx.x < TR && row0 + threadIdx.x < Lq) {
     den_out[(size_t)bh * Lq + row0 + threadIdx.x] = Os[threadIdx.x * ldts + nv];
@@ -503,7 +506,7 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
 __global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, TensorDev V, int L, int H, int M, int d,
                                                    int nv, int ldt, int rows_per_seg, int nseg,
                                                    const uint32_t* kmax_u, float* Tstate, TensorDev Y, float* den_out,
-                                                   float* shift_out) {
+                                                   float* shift_out, unsigned* flushed) {
   extern __shared__ float smem[];
   const int dpad = (d + 3) & ~3, ld = dpad + 1, ldv = ldt + 1, lds = MB + 1;
   float* Qs = smem;
@@ -631,7 +634,7 @@ __global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, Tenso
       }
     }
     __syncthreads();
-    store_result(Os, ldv, Y, b * Y.sb + h * Y.sh, row0, row_end, nv, 0, nullptr);
+    store_result(Os, ldv, Y, b * Y.sb + h * Y.sh, row0, row_end, nv, 0, nullptr, flushed);
     if (den_out != nullptr && threadIdx.x < TR && row0 + threadIdx.x < row_end) {   // for the backward pass
       den_out[(size_t)bh * L + row0 + threadIdx.x] = Os[threadIdx.x * ldv + nv];
       shift_out[(size_t)bh * L + row0 + threadIdx.x] = ordered_to_float(rowmax_u[threadIdx.x]);
@@ -1397,11 +1400,11 @@ int launch_gen_reduce(float* Tpart, int BH, int nseg, size_t per_state, int pref
 
 int launch_gen_apply(const GenSide& qs, int Lq, int BH, int H, int M, int d, int nv, int ldt, const float* T,
                      size_t state_stride, const uint32_t* kmax_u, int matvec, const TensorDev& Y, float* den_out,
-                     float* shift_out, hipStream_t st) {
+                     float* shift_out, hipStream_t st, unsigned* flushed) {
   const size_t lds = gen_lds_apply(d, ldt);
   if (int rc = set_lds((const void*)k_gen_apply, lds)) return rc;
   hipLaunchKernelGGL(k_gen_apply, dim3((Lq + TR - 1) / TR, BH), dim3(NT), lds, st, qs, Lq, H, M, d, nv, ldt, T,
-                     state_stride, kmax_u, matvec, Y, den_out, shift_out);
+                     state_stride, kmax_u, matvec, Y, den_out, shift_out, flushed);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -1454,11 +1457,11 @@ int launch_gen_bwd_causal(const GenSide& qs, const GenSide& ks, const TensorDev&
 
 int launch_gen_causal(const GenSide& qs, const GenSide& ks, const TensorDev& V, int L, int BH, int H, int M, int d,
                       int nv, int ldt, int rows_per_seg, int nseg, const uint32_t* kmax_u, float* Tstate,
-                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st) {
+                      const TensorDev& Y, float* den_out, float* shift_out, hipStream_t st, unsigned* flushed) {
   const size_t lds = gen_lds_causal(d, ldt);
   if (int rc = set_lds((const void*)k_gen_causal, lds)) return rc;
   hipLaunchKernelGGL(k_gen_causal, dim3(nseg, BH), dim3(NT), lds, st, qs, ks, V, L, H, M, d, nv, ldt, rows_per_seg,
-                     nseg, kmax_u, Tstate, Y, den_out, shift_out);
+                     nseg, kmax_u, Tstate, Y, den_out, shift_out, flushed);
   FS_LAUNCH_CHECK();
   return 0;
 }

@@ -594,6 +594,56 @@ def test_bf16_causal_late_key_with_a_huge_bound_leaves_earlier_rows_intact(fs, n
     assert fro <= 2e-2 and row <= 8e-2, (fro, row)
 
 
+@pytest.mark.parametrize("name,L,causal,dtype", [("c4", 1000, True, "bf16"), ("c3", 1000, False, "bf16"),
+                                                 ("c5", 1000, True, "bf16"), ("c1", 300, True, "f32"),
+                                                 ("c1", 300, False, "f32")])
+def test_rows_with_a_zero_normaliser_are_written_as_zeros_and_counted(fs, name, L, causal, dtype):
+    """Denominator guard (Section 2.2).  On the bf16 kernels the shift of a query row is a Cauchy-Schwarz bound over
+    all features: a query 40 times longer than the data's has every actual feature more than 2^126 below it, all of
+    them flush, and the row's normaliser is exactly 0.  Such rows (five per (b, h), one of them in the ragged last
+    chunk) must come out as zeros, the counter must report exactly their number, every other row must still agree
+    with the oracle, and a call without such rows on the same workspace must put the counter back to 0.  The
+    general-shape kernels shift a query row by its exact maximum, so no query can flush there: the count stays 0
+    and all rows agree with the oracle."""
+    import torch
+    w = synth.make(name, B=1, H=2, L=L, seed=23)
+    Q0, K, V, s, d, Om = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"], w["Omega"]
+    if dtype == "bf16":
+        Q0, K, V = synth.round_to_bf16(Q0), synth.round_to_bf16(K), synth.round_to_bf16(V)
+    Q = Q0.copy()
+    rows = [3, 64, 150, 257, L - 2]
+    Q[:, :, rows] *= 120.0 if name == "c5" else 40.0
+    if dtype == "bf16":
+        Q = synth.round_to_bf16(Q)
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    th = util.oracle_theta_from_vec(vec, d)
+    thd, Omd = torch.from_numpy(vec[None]).cuda(), torch.from_numpy(Om).cuda()
+    B, H = Q.shape[:2]
+    groups, og = 1, Om.shape[0]
+    nbytes = fs.attention_workspace_bytes(B, H, L, L, d, V.shape[-1], Om.shape[-2], causal, groups, og)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    Kd, Vd = util.to_device(K, dtype), util.to_device(V, dtype)
+    Y = fs.attention(thd, util.to_device(Q, dtype), Kd, Vd, s, Omd, causal=causal, out_dtype=torch.float32, workspace=ws)
+    count = fs.attention_flushed_rows(ws)
+    Yh = util.to_host(Y)
+    assert np.isfinite(Yh).all()
+    zero_rows = int((np.abs(Yh).max(axis=-1) == 0).sum())
+    assert count == zero_rows, (count, zero_rows)
+    on_fast_kernels = dtype == "bf16"
+    assert count == (B * H * len(rows) if on_fast_kernels else 0), count
+    keep = np.ones(L, bool)
+    keep[rows] = False             # (the long rows themselves are outside the tolerances' range of exponents)
+    if on_fast_kernels:
+        assert (Yh[:, :, rows] == 0).all()
+    tol = (2e-2, 8e-2) if dtype == "bf16" else (1e-4, 1e-3)
+    for h in range(H):
+        ref = orc.attention(th, Om[h % og], Q[0, h], K[0, h], V[0, h], s, causal)
+        fro, row = util.attention_errors(Yh[0, h][keep], ref[keep], V[0, h].astype(np.float64))
+        assert fro <= tol[0] and row <= tol[1], (h, fro, row)
+    fs.attention(thd, util.to_device(Q0, dtype), Kd, Vd, s, Omd, causal=causal, out_dtype=torch.float32, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 0
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_bf16_path_ragged_tail_with_uniformly_large_keys(fs, causal):
     """Every key rescaled to the norm 21 (in the scaled space), so that the key shift (dominated by -|y|^2/2) is
