@@ -252,10 +252,12 @@ int favorsharp_attention_noalloc(const float* theta, int groups, const fs_tensor
  * about 2^126 below the row's own shift, or that meets only key features flushed the same way, can still give a row
  * sum of exactly 0.  Every attention entry point above then writes that output row as zeros instead of dividing, and
  * counts it: the first 32-bit word of the call's workspace holds, once the call's kernels have finished, the number
- * of such rows of that call (all (b, h) together; every call starts it at 0).  A caller that wants no host
- * synchronisation reads that word from the workspace itself; this function does it for them:
- *   workspace:  the workspace of the attention call in question (device), or NULL for the scratch array of
- *               favorsharp_attention_noalloc on the current device;
+ * of such rows of that call (all (b, h) together; every call starts it at 0).  favorsharp_attention_backward
+ * recomputes the normalisers and counts the same rows in the first word of ITS workspace: such a row gets a zero
+ * dQ row and contributes nothing to dK and dV.  A caller that wants no host synchronisation reads that word from
+ * the workspace itself; this function does it for them:
+ *   workspace:  the workspace of the attention (or backward) call in question (device), or NULL for the scratch
+ *               array of favorsharp_attention_noalloc on the current device;
  *   host_count: (out, host) the counter.
  * SYNCHRONOUS with respect to `stream` (pass the attention call's stream).  FS_ERR_INVALID_ARG on a null
  * host_count, FS_ERR_DEVICE when the copy fails.

@@ -672,6 +672,7 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
     f.Wbf = (uint16_t*)(w8 + fp.f.off_Wbf); f.bias = (float*)(w8 + fp.f.off_bias); f.wnorm = (float*)(w8 + fp.f.off_wnorm);
     f.rk = (float*)(w8 + fp.f.off_rk); f.Tpart = (float*)(w8 + fp.f.off_state); f.cpart = (float*)(w8 + fp.f.off_cpart);
     f.cstar = (float*)(w8 + fp.f.off_cstar);
+    f.flushed = (unsigned*)w8;      // counted by the kernel that recomputes the normalisers
     return launch_fast_attention_backward(f, dev(dY), dev(dQ), dev(dK), dev(dV), (uint16_t*)(w8 + fp.off_gh),
                                           (float*)(w8 + fp.off_rpart), (float*)(w8 + fp.off_rcpart),
                                           (float*)(w8 + fp.off_rcstar), fp.rslots, fp.rows_per_rslot, (hipStream_t)stream);
@@ -701,7 +702,9 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   // forward quantities: segment states of S^T [V 1] (summed, or their exclusive prefix when causal), then Y, the
   // denominators and the query shifts
   if (int rc = launch_prep(theta, groups, Omega, omega_groups, pgroups, B, H, M, d, W, Wbf, bias, st)) return rc;
-  if (int rc = launch_fill_u32(kmax, 0u, BH, st)) return rc;
+  // the counter word and the key maxima behind it
+  unsigned* flushed = (unsigned*)ws;
+  if (int rc = launch_fill_u32((uint32_t*)ws, 0u, p.k.off_kmax / sizeof(uint32_t) + BH, st)) return rc;
   GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
   GenSide ks{dev(K), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
   if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
@@ -714,10 +717,11 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
     if (hipMemcpyAsync(state2, state, (size_t)BH * p.k.nseg * per_state * sizeof(float), hipMemcpyDeviceToDevice, st) != hipSuccess)
       return FS_ERR_DEVICE;
     if (int rc = launch_gen_causal(qs, ks, dev(V), Lk, BH, H, M, d, dv, ldt, p.k.rows_per_seg, p.k.nseg, kmax, state, gbuf, den,
-                                   shift, st))
+                                   shift, st, flushed))
       return rc;
   } else {
-    if (int rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, ldt, state, (size_t)p.k.nseg * per_state, kmax, 0, gbuf, den, shift, st))
+    if (int rc = launch_gen_apply(qs, Lq, BH, H, M, d, dv, ldt, state, (size_t)p.k.nseg * per_state, kmax, 0, gbuf, den, shift, st,
+                                  flushed))
       return rc;
   }
   // G1 in place of Y, then the segment sums of P^T G1 (the query-side twin of the state pass)

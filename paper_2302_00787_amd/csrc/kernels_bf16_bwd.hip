@@ -62,6 +62,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
       for (int e = 0; e < 8; ++e) t[e] = Sg[(size_t)(64 * w + 32 * mb + 16 * (e >> 2) + 4 * g + (e & 3)) * DVP + 16 * vt + c];
       tb[vt][mb] = __builtin_convertvector(t, bf16x8);
     }
+  int nzero = 0;                   // (MODE 1) rows this wave finished with a zero normaliser
   const int row_beg = blk * rows_per_blk, row_end = min(L, row_beg + rows_per_blk);
 
   // staged rows -> LDS with what is added to their exponents: - row_shift (queries), row term - key shift (keys)
@@ -112,7 +113,9 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
       const int token = row0 + 16 * w + c;
       const bool valid = token < row_end;
       if (MODE == 1) {
-        const float inv = finish_norm(fs, sm, w, lane);      // fs = Y rows now
+        unsigned zt;
+        const float inv = finish_norm(fs, sm, w, lane, &zt);      // fs = Y rows now
+        nzero += count_zero_tokens(zt, w, row_end - row0);
         const uint16_t* gy = (const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)token * ba.dY.sl + 4 * g;
         f32x4 gv[4];
         float dot = 0.f;
@@ -148,6 +151,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
     if (more) stage(xr, buf ^ 1, row0 + TC);
     __syncthreads();
   }
+  if (MODE == 1) report_zero_rows(a.flushed, nzero, lane);
 }
 
 // ---------------------------------------------------------------------------------------------------------------

@@ -590,6 +590,7 @@ __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, c
     for (int vt = 0; vt < 4; ++vt)
       gy[vt] = __builtin_amdgcn_raw_buffer_load_b64(rd, 2 * ((16 * j + c) * (int)ba.dY.sl + 16 * vt + 4 * g), 0, 0);
   };
+  int nzero = 0;                   // (forward walk) rows this wave finished with a zero normaliser
   auto finish = [&](int ci_done) {
     f32x4 fsum[4];
 #pragma unroll
@@ -602,7 +603,9 @@ __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, c
       const char* gp = (const char*)ba.dV.ptr + (b * ba.dV.sb + h * ba.dV.sh + (long long)r0 * ba.dV.sl) * esz;
       finish_store(fsum, ba.dV, gp, nv, j, lane);
     } else {
-      const float inv = finish_norm(fsum, sm, j, lane);        // fsum = Y rows now
+      unsigned zt;
+      const float inv = finish_norm(fsum, sm, j, lane, &zt);   // fsum = Y rows now
+      nzero += count_zero_tokens(zt, j, nv);
       f32x4 gv[4];
       float dot = 0.f;
 #pragma unroll
@@ -664,6 +667,7 @@ __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, c
   if (!MODE && cx.nchunk > 0) load_dy(cx.nchunk - 1);
   __syncthreads();                 // the consumers' last step
   if (cx.nchunk > 0) finish(cx.nchunk - 1);
+  if (!MODE) report_zero_rows(a.flushed, nzero, lane);
 }
 
 template <int MODE>

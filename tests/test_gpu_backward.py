@@ -346,6 +346,43 @@ def test_backward_gradient_tensors_with_huge_row_strides(fs, causal):
     assert float(wide[0][..., d:d + 64].abs().max()) == 0.0          # nothing written beside the rows
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_counts_rows_with_a_zero_normaliser_and_drops_their_terms(fs, causal):
+    """Denominator guard in the backward pass (bf16 gradient kernels): a query row whose features all flush (40
+    times the data's length: its Cauchy-Schwarz shift is more than 2^126 above every actual feature) has the
+    normaliser 0, so its G1 row is 0: it gets a zero dQ row and adds nothing to dK and dV, which is what the oracle
+    computes when that row of dY is zero.  The counter in the workspace's first word must report exactly these
+    rows, and 0 again after a call without them."""
+    import torch
+    L = 300
+    w = synth.make("c4", B=1, H=2, L=L, seed=29)
+    Q0, K, V, s, d, Om = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"], w["Omega"]
+    rows = [2, 64, 200, L - 1]
+    Q = Q0.copy()
+    Q[:, :, rows] *= 40.0
+    Q = synth.round_to_bf16(Q)
+    rng = np.random.default_rng(30)
+    dY = synth.round_to_bf16(rng.standard_normal(V.shape).astype(np.float32))
+    dY_seen = dY.copy()
+    dY_seen[:, :, rows] = 0.0
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    th = util.oracle_theta_from_vec(vec, d)
+    thd, Omd = torch.from_numpy(vec[None]).cuda(), torch.from_numpy(Om).cuda()
+    nbytes = fs.attention_backward_workspace_bytes(1, 2, L, L, d, d, Om.shape[1], causal, 1, Om.shape[0])
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    Kd, Vd, dYd = (util.to_device(t, "bf16") for t in (K, V, dY))
+    grads = fs.attention_backward(thd, util.to_device(Q, "bf16"), Kd, Vd, dYd, s, Omd, causal=causal, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 2 * len(rows)
+    gQ, gK, gV = (util.to_host(g) for g in grads)
+    assert np.isfinite(gQ).all() and np.isfinite(gK).all() and np.isfinite(gV).all()
+    assert (gQ[:, :, rows] == 0).all()
+    for h in range(2):
+        ref = orc.attention_backward(th, Om[h], Q[0, h], K[0, h], V[0, h], dY_seen[0, h], s, causal)
+        _assert_grads((gQ[0, h], gK[0, h], gV[0, h]), ref, 2e-2, h)
+    fs.attention_backward(thd, util.to_device(Q0, "bf16"), Kd, Vd, dYd, s, Omd, causal=causal, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 0
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
