@@ -42,6 +42,25 @@ def test_noalloc_attention_two_calls_in_a_row_second_smaller(fs):
     _case(fs, "c1", True)
 
 
+def test_noalloc_attention_counts_zero_normalisers_in_its_own_array(fs):
+    """The counter of rows with a zero normaliser is the first word of the scratch array for these calls: four query
+    rows 40 times longer than the data's flush on the bf16 kernels and are counted; the next, ordinary call puts the
+    counter back to 0.  Both calls must still agree bit for bit with the calls on a caller-owned workspace."""
+    import torch
+    w = synth.make("c4", B=1, H=2, L=500, seed=41)
+    Q0, K, V = (fs.to_device(w[k], "bf16") for k in ("Q", "K", "V"))
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    theta = fs.fit_params("sderf", Q0, K, w["qk_scale"], groups=2)
+    Q = Q0.clone()
+    Q[:, :, [5, 100, 333, 499]] *= 40.0
+    for q, expect in ((Q, 8), (Q0, 0)):
+        want = fs.attention(theta, q, K, V, w["qk_scale"], Om, causal=True, chunk=64)
+        got = torch.full_like(want, float("nan"))
+        fs.attention_noalloc(theta, q, K, V, w["qk_scale"], Om, got, causal=True, chunk=64)
+        assert fs.attention_flushed_rows(None) == expect
+        assert torch.equal(got, want)
+
+
 def test_noalloc_attention_rejects_what_does_not_fit(fs):
     import torch
     w = synth.make("c5", B=1, H=1, L=64)
