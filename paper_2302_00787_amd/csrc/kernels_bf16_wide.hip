@@ -330,7 +330,7 @@ struct SmemWWalk {
 struct WCtx {
   const uint16_t *Qb, *Kb, *Vb;
   int bh, pg, fh, ch, row_beg, row_end, nchunk;
-  bool isoC;
+  bool isoC, sameB;
   float cs;
 };
 __device__ __forceinline__ int wrow(const WCtx& cx, int ci) { return cx.row_beg + min(ci, cx.nchunk) * TC; }
@@ -479,8 +479,10 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
           *(bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]) = img;
         }
       }
-      if (S == 1) load_w(0);
-      if (S == 3) load_w(1);
+      if (!cx.sameB) {             // (with B1 = B2 the two slices are the same numbers and stay where they are)
+        if (S == 1) load_w(0);
+        if (S == 3) load_w(1);
+      }
 
       if (S == 0) {
         store_x(stg.xw, false, sm.xown, sm.add_own, nv);
@@ -508,6 +510,7 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW);
   WCtx cx;
   cx.isoC = ((int)th[2]) & 1;
+  cx.sameB = (((int)th[2]) & 2) != 0;
   cx.bh = bh;
   cx.fh = a.fh;
   cx.ch = blockIdx.z;
