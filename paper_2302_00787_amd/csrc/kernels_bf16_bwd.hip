@@ -93,6 +93,13 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
   for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
     const bool more = row0 + TC < row_end;
     if (more) load_rows_g(xr, Xb, X.sl, row0 + TC, row_end);
+    // (MODE 1) this wave's rows of dY are requested before the chunk's feature tiles and used after them
+    bf16x4 gpre[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    if (MODE == 1 && row0 + 16 * w + c < row_end) {
+      const uint16_t* gy = (const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)(row0 + 16 * w + c) * ba.dY.sl + 4 * g;
+#pragma unroll
+      for (int vt = 0; vt < 4; ++vt) gpre[vt] = *(const bf16x4*)(gy + 16 * vt);
+    }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
       bf16x8 p[2];
@@ -116,14 +123,11 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
         unsigned zt;
         const float inv = finish_norm(fs, sm, w, lane, &zt);      // fs = Y rows now
         nzero += count_zero_tokens(zt, w, row_end - row0);
-        const uint16_t* gy = (const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)token * ba.dY.sl + 4 * g;
         f32x4 gv[4];
         float dot = 0.f;
 #pragma unroll
         for (int vt = 0; vt < 4; ++vt) {
-          bf16x4 t = {0, 0, 0, 0};
-          if (valid) t = *(const bf16x4*)(gy + 16 * vt);
-          gv[vt] = __builtin_convertvector(t, f32x4);
+          gv[vt] = __builtin_convertvector(gpre[vt], f32x4);
 #pragma unroll
           for (int r = 0; r < 4; ++r) dot += gv[vt][r] * fs[vt][r];
         }
