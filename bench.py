@@ -46,7 +46,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3
 MEASURED_TRAFFIC_BYTES = {
     "c4": (294.1e6, 508e6, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
     "c3": (111.5e6, 270e6, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
-    "c5": (3.40e9, 4.07e9, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
+    "c5": (3.04e9, 3.71e9, "profiles/hbm_traffic_c2_c3_c4_c5.md"),
 }
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
