@@ -78,6 +78,9 @@ typedef struct {
  *   [0] log D   [1] fitted value of the shifted log-variance objective (Section 3.1; NaN if none)
  *   [2] flags (as a float; bit 0 set: C1 = C2 = -I/2 exactly, bit 1 set: B1 = B2)   [3] fs_variant   [4..7] reserved
  *   then diag(A)[d], B1[d*d], B2[d*d], C1[d*d], C2[d*d], all row-major.
+ * The flags are promises the kernels rely on (a set bit lets them skip the dense quadratic form, or use one
+ * projection matrix for both sides); the fits set them, and a caller who builds theta by hand sets a bit only when
+ * the arrays satisfy it exactly (0 is always safe).
  * A parameter buffer holds `groups` such sets back to back; the set used for
  * batch b, head h is 0 (groups = 1), h (groups = H) or b*H + h (groups = B*H).
  */
