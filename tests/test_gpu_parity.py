@@ -584,10 +584,14 @@ def test_bf16_causal_late_key_with_a_huge_bound_leaves_earlier_rows_intact(fs, n
     th = util.oracle_theta_from_vec(vec, d)
     shift_log2 = (longest * longest / 2.0) / np.log(2.0) - 120.0
     assert shift_log2 > 200.0, shift_log2
+    ws = torch.empty(fs.attention_workspace_bytes(1, 1, L, L, d, d, Om.shape[1], True, 1, 1), dtype=torch.uint8, device="cuda")
     Y = fs.attention(torch.from_numpy(vec[None]).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
-                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32)
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32,
+                     workspace=ws)
     Yh = util.to_host(Y)[0, 0]
     assert np.isfinite(Yh).all()
+    # whatever the rows behind the outlier lose is reported: the counter is the number of rows written as zeros
+    assert fs.attention_flushed_rows(ws) == int((np.abs(Yh).max(axis=1) == 0).sum())
     ref = orc.attention(th, Om[0], Q[0, 0], K[0, 0], V[0, 0], s, True)
     safe = (late // 64) * 64           # segments and slots are whole chunks of 64 rows
     fro, row = util.attention_errors(Yh[:safe], ref[:safe], V[0, 0, :safe].astype(np.float64))
