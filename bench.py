@@ -19,7 +19,8 @@ begin and end on the stream the library launches on).
 Prints ONE JSON line.  Headline fields: the metric workload.  `roofline`: the dominant kernel of the metric workload
 (`frac`) and the whole call (`call_frac`) against the tighter of the HBM / MFMA bounds on the algorithmic counts.
 `workloads`: the same measurements for the other four workloads and the two backward-pass workloads, taken in the
-same run (unless --only).  `parity`: measured errors of the library's results against the CPU oracle on the same
+same run (unless --only).  `families_ms` (headline, c3, c5): ms per call of the same workload with GERF, SADERF and
+ADERF parameters instead of SDERF (the last two have a dense key-side quadratic form and B1 != B2).  `parity`: measured errors of the library's results against the CPU oracle on the same
 inputs and the same float32 parameter block (computed in the CPU-baseline leg, which is the only part of this
 script that touches the oracle).  `cpu_baseline`: the oracle timed on a bounded sample of the metric workload.
 """
@@ -224,6 +225,30 @@ def run_attention(name: str, steps: int, warmup: int, fs, synth, torch, nsets: i
                main_kernel_ms=main_ms, roofline=roofline, counts=counts,
                Y0=outs[0], sets=sets, tokens_per_s=B * L / (ms_per_step * 1e-3))
     return out
+
+
+def run_families(r: dict, steps: int, warmup: int, fs, torch) -> dict:
+    """ms per call of the same workload (first input set, prepared constants where the library keeps them) with the
+    parameters of the other families: GERF (isotropic, B1 = B2 like SDERF), SADERF and ADERF (dense key-side
+    quadratic form, B1 != B2: the calls that also run the row-term kernel and reload projection slices)."""
+    cfg, st_ = r["cfg"], r["sets"][0]
+    B, H, L, d, M = cfg["B"], cfg["H"], cfg["L"], cfg["d"], cfg["M"]
+    causal, chunk, s = cfg["causal"], cfg.get("chunk", 0), r["w0"]["qk_scale"]
+    ws = torch.empty(fs.attention_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(st_["V"])
+    res = {}
+    for variant in ("gerf", "saderf", "aderf"):
+        theta = fs.fit_params(variant, st_["Q"], st_["K"], s, groups=H)
+        if r["prepared"]:
+            prep = fs.attention_prepare(theta, st_["Omega"], B, H, s)
+            step = lambda i: fs.attention_prepared(prep, theta, st_["Q"], st_["K"], st_["V"], s, st_["Omega"], causal=causal,
+                                                   chunk=chunk, out=out, workspace=ws)
+        else:
+            step = lambda i: fs.attention(theta, st_["Q"], st_["K"], st_["V"], s, st_["Omega"], causal=causal, chunk=chunk,
+                                          out=out, workspace=ws)
+        res[variant] = timed(step, steps, warmup, torch)
+        assert torch.isfinite(out.float()).all().item(), variant
+    return res
 
 
 def describe_attention(name: str, cfg: dict) -> str:
@@ -503,6 +528,9 @@ def main():
                 result["cpu_baseline"], parity[name] = oracle.attention_full(r, 20.0 if name == "c4" else 5.0)
             else:
                 parity[name] = oracle.attention_sampled(r, 2, 24)
+        if not args.only and name == "c4":
+            # (after the oracle leg the chip has been idle for seconds: the full warm-up, for the clocks)
+            result["families_ms"] = run_families(r, max(5, min(args.steps, 100)), args.warmup, fs, torch)
     free(r, torch)
 
     # ---- the other workloads, same run, fewer steps
@@ -515,6 +543,8 @@ def main():
             others[other]["workload"] = describe_attention(other, r["cfg"])
             if other == "c5":
                 others[other]["fit_ms"], others[other]["fit_device_ms"] = r["fit_ms"], r["fit_device_ms"]
+            if other != "c1":
+                others[other]["families_ms"] = run_families(r, steps, warmup if other == "c5" else args.warmup, fs, torch)
             if oracle:
                 # whole sequences, every row (c3: all 64 fit in the budget; c5: as many of its 16 as 10 s of the oracle
                 # allow), and for the long workloads also sampled rows straight from the definition of K_hat

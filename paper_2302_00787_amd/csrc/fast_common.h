@@ -437,6 +437,9 @@ int launch_fast_causal_kernel(const fast::FastArgs& a, int BH, hipStream_t st, h
 size_t fast_causal_lds_bytes();
 // Backward pass (kernels_bf16_bwd.hip) and the reduction it borrows from the forward pass (kernels_bf16.hip).
 void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int nslot, int BH, hipStream_t st);
+// Key-side row terms of parameter sets with a dense C2 for bf16 rows of d = 64 or 128 numbers (kernels_bf16.hip).
+int launch_key_row_terms(const float* theta, int groups, const TensorDev& K, int B, int H, int L, int d, float scale,
+                         float* rk, hipStream_t st);
 int launch_fast_backward(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
                          const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
                          float* rcstar, int rslots, int rows_per_rslot, hipStream_t st);

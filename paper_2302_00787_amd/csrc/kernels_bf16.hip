@@ -13,25 +13,17 @@ namespace fs {
 using namespace fast;
 
 // ---------------------------------------------------------------------------------------------------
-// Per-call constants, one launch.  grid 128 * pgroups + rowblocks * B*H workgroups of 256 threads:
-//
-// workgroups [0, 128 pgroups): projection constants (Section 4, evaluation recipe), one wave per feature, one lane
-// per column: Wbf[pg][side][m][:] = bf16(qk_scale log2e omega_m^T B), bias[pg][side][m] = log2e (omega_m^T A omega_m
-// + log D - 1/2 log M), wnorm[pg][side][m] = |Wbf_m|.
-//
-// the other workgroups: key-side row term log2e * y^T C2 y for parameter sets whose C2 is not -I/2 (ADERF, SADERF);
-// workgroups of sets with the -I/2 flag return at once (the kernels then use -|y|^2/2).  One wave per token
-// (grid-stride over the tokens of a sequence), lane a handles row a of C2.
-// ---------------------------------------------------------------------------------------------------
-// `first_block` is added to the block index (a launch of the row-term part alone starts at 128 pgroups);
+// Projection constants (Section 4, evaluation recipe), one launch of 128 * pgroups workgroups of 256 threads, one
+// wave per feature, one lane per column: Wbf[pg][side][m][:] = bf16(qk_scale log2e omega_m^T B), bias[pg][side][m] =
+// log2e (omega_m^T A omega_m + log D - 1/2 log M), wnorm[pg][side][m] = |Wbf_m|.
 // dense_flag (optional) is or-ed with 1 when a visited parameter set has a dense C2.
+// ---------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups, const float* Omega, int omega_groups,
                                                   int pgroups, int B, int H, float scale, uint16_t* Wbf, float* bias,
-                                                  float* wnorm, TensorDev K, int L, int rowblocks, float* rk,
-                                                  int first_block, int* dense_flag) {
+                                                  float* wnorm, int* dense_flag) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D;
-  const int nprep = (M / 4) * 2 * pgroups, block = blockIdx.x + first_block;
-  if (block < nprep) {
+  const int block = blockIdx.x;
+  {
     const int pg = block / ((M / 4) * 2), rem = block % ((M / 4) * 2), side = rem / (M / 4);
     const int m = (rem % (M / 4)) * 4 + (threadIdx.x >> 6), c = threadIdx.x & 63;
     int b = 0, h = 0;
@@ -56,24 +48,126 @@ __global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups
       bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)M));
       wnorm[o] = sqrtf(n2);
     }
-    return;
   }
-  const int rb = block - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
-  const float* th = theta + (size_t)group_of(groups, b, h, H) * tf;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Key-side row terms rk[bh][j] = log2e * y_j^T C2 y_j, y_j = qk_scale K_j (the quadratic form of the DERF exponent,
+// Section 4), for parameter sets whose C2 is not -I/2 (ADERF, SADERF; workgroups of sets with the -I/2 flag return at
+// once: the kernels then use -|y|^2/2), for bf16 rows of DD = 64 or 128 numbers.
+//
+// C2 y runs on the MFMA pipe.  The rows are bf16 as they come; C2 is split into two bf16 parts, C2 = hi + lo with
+// |C2 - hi - lo| <= 2^-17 |C2|, so the fp32 sums carry the accuracy of an fp32 product (the term is an exponent:
+// bf16 entries of C2 alone would shift it by tenths).  Both parts lie in LDS as operand images (rows a of C2 as
+// the A operand: lane (g, c) <-> row 16 mt + c, contraction index 32 ks + 8 g + e); a wave takes 64 tokens at a
+// time, its rows straight from memory as B operands (lane <-> token, the same contraction index), and for every
+// block of 16 rows of C2 gets (C2 y)[a] for a = 16 mt + 4 g + r of token c in its accumulators, multiplies by y[a]
+// (an 8-byte read of the row) and sums over the lane's numbers; two cross-lane steps finish the token.
+// grid (blocks per sequence, B*H), block 256 (DD = 64) or 512 (DD = 128: the images take 64 kB, so two workgroups
+// share a CU and eight waves each keep four waves per SIMD); the waves of a sequence stride over its groups of 64
+// tokens.
+// ---------------------------------------------------------------------------------------------------
+template <int DD>
+__global__ void __launch_bounds__(4 * DD, 2) k_key_row_terms(const float* theta, int groups, TensorDev K, int L, int H,
+                                                       float scale, float* rk) {
+  constexpr int NMT = DD / 16, NKS = DD / 32, NTH = 4 * DD, NWV = NTH / 64;
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  typedef uint16_t OpImage[NMT][NKS][64][8];
+  OpImage* c2op = reinterpret_cast<OpImage*>(smem_raw);        // [hi / lo]
+  const int bh = blockIdx.y, b = bh / H, h = bh % H;
+  const float* th = theta + (size_t)group_of(groups, b, h, H) * (FS_THETA_HEADER_ + (size_t)DD + 4 * (size_t)DD * DD);
   if (((int)th[2]) & 1) return;
-  const float* C2 = th + FS_THETA_HEADER_ + D + 3 * (size_t)D * D;
-  const int a = threadIdx.x & 63;
-  for (int j = blk * 4 + (threadIdx.x >> 6); j < L; j += 4 * rowblocks) {
-    const uint16_t* row = (const uint16_t*)K.ptr + b * K.sb + h * K.sh + (long long)j * K.sl;
-    const float ya = scale * bf16_bits_to_f32(row[a]);
-    float t = 0.f;
-#pragma unroll 8
-    for (int c = 0; c < D; ++c) t += C2[a * D + c] * __shfl(ya, c);
-    float acc = ya * t;
+  const float* C2 = th + FS_THETA_HEADER_ + DD + 3 * (size_t)DD * DD;
+  for (int idx = threadIdx.x; idx < NMT * NKS * 64; idx += NTH) {
+    const int l = idx & 63, ks = (idx >> 6) % NKS, mt = idx / (64 * NKS);
+    const float* src = C2 + (size_t)(16 * mt + (l & 15)) * DD + 32 * ks + 8 * (l >> 4);
+    u32x4 hi4 = {0u, 0u, 0u, 0u}, lo4 = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int s = 1; s < 64; s <<= 1) acc += __shfl_xor(acc, s);
-    if (a == 0) rk[(size_t)bh * L + j] = kLog2e * acc;
+    for (int e = 0; e < 8; ++e) {
+      const float v = src[e];
+      const uint16_t hi = f32_to_bf16_bits(v);
+      hi4[e >> 1] |= (uint32_t)hi << (16 * (e & 1));
+      lo4[e >> 1] |= (uint32_t)f32_to_bf16_bits(v - bf16_bits_to_f32(hi)) << (16 * (e & 1));
+    }
+    *(u32x4*)(&c2op[0][mt][ks][l][0]) = hi4;
+    *(u32x4*)(&c2op[1][mt][ks][l][0]) = lo4;
   }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const uint16_t* Kb = (const uint16_t*)K.ptr + b * K.sb + h * K.sh;
+  for (int t0 = (blockIdx.x * NWV + w) * 64; t0 < L; t0 += gridDim.x * NWV * 64) {
+    // the rows of the group as B operands (a buffer descriptor that ends with the last row: rows past it read as zero)
+    u32x4 yb[4][NKS];
+    const __amdgpu_buffer_rsrc_t rs = pc::chunk_rsrc(Kb + (long long)t0 * K.sl, 2 * (int)K.sl, min(64, L - t0), 2 * DD);
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile)
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+        yb[tile][ks] = __builtin_amdgcn_raw_buffer_load_b128(rs, 2 * ((16 * tile + c) * (int)K.sl + 32 * ks + 8 * g), 0, 0);
+    float part[4] = {0.f, 0.f, 0.f, 0.f};
+    // (an opaque copy of the lane number: the images do not depend on the group, and reading all of them once,
+    // ahead of the loop, would not fit in the registers)
+    int lane_here = lane;
+    asm volatile("" : "+v"(lane_here));
+#pragma unroll
+    for (int mt = 0; mt < NMT; ++mt) {
+      __builtin_amdgcn_sched_barrier(0);     // block by block: not every block's LDS reads at the top
+      f32x4 acc[4];
+#pragma unroll
+      for (int tile = 0; tile < 4; ++tile) acc[tile] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks) {
+        const bf16x8 hi = *(const bf16x8*)(&c2op[0][mt][ks][lane_here][0]), lo = *(const bf16x8*)(&c2op[1][mt][ks][lane_here][0]);
+#pragma unroll
+        for (int tile = 0; tile < 4; ++tile) {
+          acc[tile] = mfma(hi, __builtin_bit_cast(bf16x8, yb[tile][ks]), acc[tile]);
+          acc[tile] = mfma(lo, __builtin_bit_cast(bf16x8, yb[tile][ks]), acc[tile]);
+        }
+      }
+      // y[a] for a = 16 mt + 4 g + r of the lane's token: the numbers are in the operand registers of the lane with
+      // the same token and lane group 2 (mt % 2) + g / 2 (k-step mt / 2, its dwords 2 (g % 2) and 2 (g % 2) + 1)
+      const int src = 4 * (16 * (2 * (mt & 1) + (g >> 1)) + c);
+#pragma unroll
+      for (int tile = 0; tile < 4; ++tile) {
+        const u32x4 v = yb[tile][mt >> 1];
+        const uint32_t d0 = __builtin_amdgcn_ds_bpermute(src, v[0]), d1 = __builtin_amdgcn_ds_bpermute(src, v[1]);
+        const uint32_t d2 = __builtin_amdgcn_ds_bpermute(src, v[2]), d3 = __builtin_amdgcn_ds_bpermute(src, v[3]);
+        const u32x2 pr = {(g & 1) ? d2 : d0, (g & 1) ? d3 : d1};
+        const f32x4 yf = __builtin_convertvector(__builtin_bit_cast(bf16x4, pr), f32x4);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[tile] += acc[tile][r] * yf[r];
+      }
+    }
+#pragma unroll
+    for (int tile = 0; tile < 4; ++tile) {
+      float p = part[tile];
+      p += __shfl_xor(p, 16);
+      p += __shfl_xor(p, 32);
+      const int token = t0 + 16 * tile + c;
+      if (g == 0 && token < L) rk[(size_t)bh * L + token] = kLog2e * scale * scale * p;
+    }
+  }
+}
+
+int launch_key_row_terms(const float* theta, int groups, const TensorDev& K, int B, int H, int L, int d, float scale,
+                         float* rk, hipStream_t st) {
+  // every wave of a sequence gets about four groups of 64 tokens, so that the operand images are built rarely
+  const int BH = B * H, waves = d / 16, per_block = 4 * 64 * waves;
+  const int blocks = std::max(1, std::min((L + per_block - 1) / per_block, std::max(1, 2048 / BH)));
+  const size_t lds = (size_t)2 * d * d * sizeof(uint16_t);
+  if (d == 64) {
+    hipLaunchKernelGGL(k_key_row_terms<64>, dim3(blocks, BH), dim3(256), lds, st, theta, groups, K, L, H, scale, rk);
+  } else if (d == 128) {
+    if (hipFuncSetAttribute((const void*)k_key_row_terms<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+      (void)hipGetLastError();
+      return 2;
+    }
+    hipLaunchKernelGGL(k_key_row_terms<128>, dim3(blocks, BH), dim3(512), lds, st, theta, groups, K, L, H, scale, rk);
+  } else {
+    return 2;
+  }
+  if (hipGetLastError() != hipSuccess) return 5;
+  return 0;
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -150,12 +244,18 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
   };
   // Per-token constants of token tile w of a chunk (first row r0 of the slot) from the squared norms n2 of its rows
   // (valid in the lanes (g, c) = (c / 4, c)): row terms to kadd[cb], the largest bound into kmax[mb].
-  auto constants = [&](float n2, int cb, int mb, int r0) {
+  // (`rkv`: the token's row term from memory, for parameter sets with a dense C2: requested by the caller ahead of time)
+  auto row_term_of = [&](int r0) {
+    float v = 0.f;
+    if (!isoC && g == (c >> 2) && r0 + 16 * w + c < nrows) v = rkb[r0 + 16 * w + c];
+    return v;
+  };
+  auto constants = [&](float n2, float rkv, int cb, int mb, int r0) {
     if (g == (c >> 2)) {
       const int t = 16 * w + c;
       const bool valid = r0 + t < nrows;
       float rt = -0.5f * kLog2e * a.scale * a.scale * n2;
-      if (!isoC) rt = valid ? rkb[r0 + t] : 0.f;
+      if (!isoC) rt = valid ? rkv : 0.f;
       // rows past the end get -inf: their features are exactly zero whatever the key shift is
       sm.kadd[cb][t] = valid ? rt : -INFINITY;
       if (valid) lds_fmax(&sm.kmax[mb], row_shift(n2, wmax) + rt);
@@ -175,7 +275,7 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
     store_v(0);
   }
   __syncthreads();
-  constants(tile_row_norms(tile_op(0, w, 0), tile_op(0, w, 1), lane), 0, 0, 0);
+  constants(tile_row_norms(tile_op(0, w, 0), tile_op(0, w, 1), lane), row_term_of(0), 0, 0, 0);
   load_v(TC);
   load_k(2 * TC);
   __syncthreads();
@@ -194,6 +294,7 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
       kadd4[jt] = *(const f32x4*)(&sm.kadd[cb][16 * jt + 4 * g]);
     }
     const bf16x8 xn0 = tile_op(knext, w, 0), xn1 = tile_op(knext, w, 1);     // token tile w of the next chunk
+    const float rk_next = row_term_of(r0 + TC);      // (dense C2) requested here, used at the end of the iteration
     // ---- running key shift: the state is rebased when the chunk's largest bound exceeds the current shift
     if (dnew > dk) {
       const float f = fast_exp2(dk - dnew);
@@ -238,7 +339,7 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) T[mt][vt] = mfma(st[mt], vop[jp][vt], T[mt][vt]);
     }
-    constants(n2, cb ^ 1, knext, r0 + TC);
+    constants(n2, rk_next, cb ^ 1, knext, r0 + TC);
     store_v(cb ^ 1);
     store_k(kfree);
     load_v(r0 + 2 * TC);
@@ -485,18 +586,14 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   a.scale = f.scale;
   a.flushed = f.flushed;
   const int BH = f.B * f.H;
-  const int rowblocks = std::min(64, (f.Lk + 3) / 4), nprep = (M / 4) * 2 * f.pgroups;
   if (f.pre_mode == 0) {
-    hipLaunchKernelGGL(k_fast_pre, dim3(nprep + rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
-                       f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk, 0,
-                       (int*)nullptr);
-    FS_LAUNCH_CHECK();
-  } else if (f.pre_mode == 1) {      // the key row terms alone
-    hipLaunchKernelGGL(k_fast_pre, dim3(rowblocks * BH), dim3(256), 0, st, f.theta, f.groups, f.Omega,
-                       f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, f.K, f.Lk, rowblocks, f.rk,
-                       nprep, (int*)nullptr);
+    hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * f.pgroups), dim3(256), 0, st, f.theta, f.groups, f.Omega,
+                       f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, (int*)nullptr);
     FS_LAUNCH_CHECK();
   }
+  // the key row terms of parameter sets with a dense C2 (the host knows that there are none only in mode 2)
+  if (f.pre_mode != 2)
+    if (int rc = launch_key_row_terms(f.theta, f.groups, f.K, f.B, f.H, f.Lk, D, f.scale, f.rk, st)) return rc;
   // the last segment's states are never needed by the causal pass
   const int nstate = (f.causal && !every_slot ? f.nseg - 1 : f.nseg) * f.sub;
   if (nstate > 0) {
@@ -512,7 +609,7 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
 int launch_fast_prepare(const float* theta, int groups, const float* Omega, int omega_groups, int pgroups, int B, int H,
                         float scale, uint16_t* Wbf, float* bias, float* wnorm, int* dense_flag, hipStream_t st) {
   hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * pgroups), dim3(256), 0, st, theta, groups, Omega, omega_groups, pgroups,
-                     B, H, scale, Wbf, bias, wnorm, TensorDev{nullptr, 1, 0, 0, 0}, 0, 1, (float*)nullptr, 0, dense_flag);
+                     B, H, scale, Wbf, bias, wnorm, dense_flag);
   FS_LAUNCH_CHECK();
   return 0;
 }

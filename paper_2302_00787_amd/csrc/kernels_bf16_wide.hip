@@ -68,14 +68,14 @@ __device__ __forceinline__ float sum16(float v) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// grid 128 * 2 * pgroups + rowblocks * B*H workgroups of 256 threads; see k_fast_pre.  One wave per feature, lane c
-// handles columns c and c + 64; for the row terms one wave per token, lane a handles rows a and a + 64 of C2.
+// Projection constants: grid 128 * 2 * pgroups workgroups of 256 threads; see k_fast_pre.  One wave per feature, lane c
+// handles columns c and c + 64.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks, int first_block, int* dense_flag) {
+__global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int* dense_flag) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW;
-  const int nprep = (MW / 4) * 2 * a.pgroups, H = a.H, block = blockIdx.x + first_block;
+  const int H = a.H, block = blockIdx.x;
   const int c = threadIdx.x & 63;
-  if (block < nprep) {
+  {
     const int pg = block / ((MW / 4) * 2), rem = block % ((MW / 4) * 2), side = rem / (MW / 4);
     const int m = (rem % (MW / 4)) * 4 + (threadIdx.x >> 6);
     int b = 0, h = 0;
@@ -104,26 +104,6 @@ __global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int rowblocks, int
       a.bias[o] = kLog2e * (q + th[0] - 0.5f * logf((float)MW));
       a.wnorm[o] = sqrtf(n2);
     }
-    return;
-  }
-  const int rb = block - nprep, bh = rb / rowblocks, blk = rb % rowblocks, b = bh / H, h = bh % H;
-  const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
-  if (((int)th[2]) & 1) return;
-  const float* C2 = th + FS_THETA_HEADER_ + DW + 3 * (size_t)DW * DW;
-  for (int j = blk * 4 + (threadIdx.x >> 6); j < a.L; j += 4 * rowblocks) {
-    const uint16_t* row = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh + (long long)j * a.K.sl;
-    const float y0 = a.scale * bf16_bits_to_f32(row[c]), y1 = a.scale * bf16_bits_to_f32(row[c + 64]);
-    float t0 = 0.f, t1 = 0.f;
-#pragma unroll 8
-    for (int e = 0; e < 64; ++e) {
-      const float ye0 = __shfl(y0, e), ye1 = __shfl(y1, e);
-      t0 += C2[c * DW + e] * ye0 + C2[c * DW + e + 64] * ye1;
-      t1 += C2[(c + 64) * DW + e] * ye0 + C2[(c + 64) * DW + e + 64] * ye1;
-    }
-    float acc = y0 * t0 + y1 * t1;
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) acc += __shfl_xor(acc, s);
-    if (c == 0) a.rk[(size_t)bh * a.L + j] = kLog2e * acc;
   }
 }
 
@@ -666,7 +646,7 @@ int launch_wide_prepare(const float* theta, int groups, const float* Omega, int 
   WideArgs a = {};
   a.theta = theta; a.Omega = Omega; a.Wbf = Wbf; a.bias = bias; a.wnorm = wnorm;
   a.groups = groups; a.omega_groups = omega_groups; a.pgroups = pgroups; a.B = B; a.H = H; a.scale = scale;
-  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * pgroups), dim3(256), 0, st, a, 1, 0, dense_flag);
+  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * pgroups), dim3(256), 0, st, a, dense_flag);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -686,14 +666,13 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
     (void)hipGetLastError();
     return 2;
   }
-  const int rowblocks = std::min(64, (f.L + 3) / 4), nprep = (MW / 4) * 2 * f.pgroups;
   if (f.pre_mode == 0) {
-    hipLaunchKernelGGL(k_wide_pre, dim3(nprep + rowblocks * BH), dim3(256), 0, st, a, rowblocks, 0, (int*)nullptr);
-    FS_LAUNCH_CHECK();
-  } else if (f.pre_mode == 1) {      // the key row terms alone
-    hipLaunchKernelGGL(k_wide_pre, dim3(rowblocks * BH), dim3(256), 0, st, a, rowblocks, nprep, (int*)nullptr);
+    hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * f.pgroups), dim3(256), 0, st, a, (int*)nullptr);
     FS_LAUNCH_CHECK();
   }
+  // the key row terms of parameter sets with a dense C2 (the host knows that there are none only in mode 2)
+  if (f.pre_mode != 2)
+    if (int rc = launch_key_row_terms(f.theta, f.groups, f.K, f.B, f.H, f.L, DW, f.scale, f.rk, st)) return rc;
   hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
   FS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
