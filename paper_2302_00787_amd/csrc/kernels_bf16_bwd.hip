@@ -239,13 +239,15 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
 // state = R).  Per 16-token tile: F (feature tile), dF = state x (left rows)^T in the same accumulator layout
 // (rows = features, column = token), dE = F * dF, gradient tile = W~^T (A operand: rows = coordinates, k <->
 // features; a row of ones appended: row sum of dE) x dE.  The four waves' partial gradient tiles are summed through
-// LDS on the MFMA pipe.  grid (nblk, B*H); 66 kB of dynamic LDS: two workgroups per CU.
+// LDS on the MFMA pipe.  grid (nblk, B*H); 74 kB of dynamic LDS: two workgroups per CU.
 // ---------------------------------------------------------------------------------------------------------------
 struct SmemGrad {
   __attribute__((aligned(16))) uint16_t q[1][TC][LDR];            // rows of the chunk (one buffer)
   float qadd[TC];
   __attribute__((aligned(16))) uint16_t lam[TC][LDL];             // left rows: G1 (queries) or [V 1 0..] (keys)
   __attribute__((aligned(16))) uint16_t xch[NW][NW][16][LDXB];
+  // C2 + C2^T as A operands of the keys' row term when C2 is dense: [16-row tile][k-step][lane] (rows = gradient columns)
+  __attribute__((aligned(16))) uint16_t csym[4][KS][64][8];
 };
 
 template <int KEY>
@@ -309,6 +311,16 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
       wt[dt][bk] = __builtin_bit_cast(bf16x8, v);
     }
 
+  if (KEY && !isoC) {
+    for (int piece = threadIdx.x; piece < 4 * KS * 64; piece += NT) {
+      const int l = piece & 63, ks = (piece >> 6) % KS, dt = piece / (64 * KS);
+      const int dd = 16 * dt + (l & 15), e0 = 32 * ks + 8 * (l >> 4);
+      f32x8 cv;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) cv[e] = C2[dd * D + e0 + e] + C2[(e0 + e) * D + dd];
+      *(bf16x8*)(&sm.csym[dt][ks][l][0]) = __builtin_convertvector(cv, bf16x8);
+    }
+  }
   // zero padding of the left-rows tile (columns the staging never writes)
   for (int idx = threadIdx.x; idx < TC * (KL - (KEY ? D : DVP)); idx += NT) {
     const int n = KL - (KEY ? D : DVP);
@@ -429,25 +441,16 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
             for (int r = 0; r < 4; ++r)
               fs[dt][r] = kLn2 * fs[dt][r] - rs * bf16_bits_to_f32(sm.q[0][trow][16 * dt + 4 * g + r]);
         } else {
-          // dense C2 (ADERF): one row of (C2 + C2^T) per coordinate, rolled loops (rare path, kept small)
-#pragma unroll 1
+          // dense C2 (ADERF, SADERF): the matrix as A operand (rows = gradient columns), the key rows as B operand
+          bf16x8 kop[KS];
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) kop[ks] = *(const bf16x8*)(&sm.q[0][trow][32 * ks + 8 * g]);
+#pragma unroll
           for (int dt = 0; dt < 4; ++dt) {
             f32x4 u = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-            for (int e = 0; e < D; ++e) {
-              const float ke = bf16_bits_to_f32(sm.q[0][trow][e]);
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                const int dd = 16 * dt + 4 * g + r;
-                u[r] += (C2[dd * D + e] + C2[e * D + dd]) * ke;
-              }
-            }
-            f32x4 o = kLn2 * fs[dt] + rs * u;
-            // fs is indexed with a loop variable here: write through a switch-free select to keep it in registers
-            fs[0] = dt == 0 ? o : fs[0];
-            fs[1] = dt == 1 ? o : fs[1];
-            fs[2] = dt == 2 ? o : fs[2];
-            fs[3] = dt == 3 ? o : fs[3];
+            for (int ks = 0; ks < KS; ++ks) u = mfma(*(const bf16x8*)(&sm.csym[dt][ks][lane][0]), kop[ks], u);
+            fs[dt] = kLn2 * fs[dt] + rs * u;
           }
         }
       } else {
