@@ -328,10 +328,20 @@ def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
 
     ms = timed(step, steps, warmup, torch)
     assert all(torch.isfinite(g.float()).all().item() for g in last[0])
+    # the same call with ADERF parameters (dense C2: row-term kernel, dense derivative of the row term), first set
+    _, Q, K, V, dY, Om, s = sets[0]
+    theta_a = fs.fit_params("aderf", Q, K, s, groups=H)
+    grads_a = {}
+
+    def step_aderf(i):
+        grads_a[0] = fs.attention_backward(theta_a, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
+
+    ms_aderf = timed(step_aderf, steps, warmup, torch)
+    assert all(torch.isfinite(g.float()).all().item() for g in grads_a[0])
     chunk = cfg.get("chunk", 64)
     per_token = 8 * d * M + 12 * M * (d + 1) + (3 * (chunk + 1) // 2 * (2 * M + 2 * (d + 1)) if causal else 0)
     tf = B * H * L * per_token / (ms * 1e-3) / 1e12
-    return dict(cfg=cfg, w0=w0, dY0=dY0, theta0=sets[0][0], grads0=last[0], ms_per_step=ms,
+    return dict(cfg=cfg, w0=w0, dY0=dY0, theta0=sets[0][0], grads0=last[0], ms_per_step=ms, ms_per_step_aderf=ms_aderf,
                 tokens_per_s=B * L / (ms * 1e-3),
                 roofline={"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                           "frac": tf / MFMA_BF16_PEAK_TFLOPS, "step_frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
@@ -501,7 +511,7 @@ def main():
                   "config": {"workload": f"{name}: gradients of {'causal' if cfg['causal'] else 'non-causal'} attention "
                                          f"w.r.t. Q, K, V, bf16 in and out, B={cfg['B']} H={cfg['H']} L={cfg['L']} "
                                          f"d={cfg['d']} M={cfg['M']}, SDERF per head, theta and omega resident"},
-                  "roofline": r["roofline"]}
+                  "families_ms": {"aderf": r["ms_per_step_aderf"]}, "roofline": r["roofline"]}
         if oracle:
             parity[name] = oracle.backward(r)
     else:
@@ -563,6 +573,7 @@ def main():
             r = run_backward(short, steps, warmup, fs, synth, torch)
             others[f"{short}_backward"] = {"ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"],
                                            "main_kernel_ms": None, "roofline": r["roofline"],
+                                           "families_ms": {"aderf": r["ms_per_step_aderf"]},
                                            "workload": f"{short} shapes: gradients w.r.t. Q, K, V, bf16 in and out"}
             if oracle:
                 parity[f"{short}_backward"] = oracle.backward(r)
