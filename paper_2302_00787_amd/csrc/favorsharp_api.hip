@@ -38,7 +38,7 @@ bool groups_ok(int g, int B, int H) { return g == 1 || g == H || g == B * H; }
 
 struct AttnPlan {
   int pgroups, ldt, nseg, rows_per_seg;
-  size_t off_W, off_Wbf, off_bias, off_kmax, off_state, total;
+  size_t off_W, off_Wbf, off_bias, off_kmax, off_rk, off_state, total;
 };
 
 // Every attention workspace starts with one 32-bit word (in a block of kAlign bytes): the number of output rows of the
@@ -59,6 +59,7 @@ void plan_contraction(int BH, int pgroups, int Lk, int d, int M, int nv1, int ca
   p->off_W = off;    off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(float));
   p->off_Wbf = off;  off = align_up(off + (size_t)pgroups * 2 * M * d * sizeof(uint16_t));
   p->off_bias = off; off = align_up(off + (size_t)pgroups * 2 * M * sizeof(float));
+  p->off_rk = off;   off = align_up(off + (size_t)BH * Lk * sizeof(float));       // key row terms (general attention kernels)
   p->off_state = off; off = align_up(off + (size_t)BH * p->nseg * M * p->ldt * sizeof(float));
   p->total = off;
 }
@@ -321,7 +322,7 @@ size_t favorsharp_features_workspace_bytes(int n, int d, int M) {
   if (n < 0 || d < 1 || d > 128 || M < 1) return 0;
   AttnPlan p;
   plan_contraction(1, 1, 32, d, M, 1, 0, &p);
-  return p.off_state;      // everything in front of the states: the projection constants are the part used here
+  return p.off_rk;         // everything in front of the row terms: the projection constants are the part used here
 }
 
 int favorsharp_features(const float* theta, int side, const fs_tensor* X, int n, int d, float qk_scale, float alpha,
@@ -531,6 +532,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
   if (int rc = launch_fill_u32((uint32_t*)ws, 0u, p.off_kmax / sizeof(uint32_t) + BH, st)) return rc;
   GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
   GenSide ks{dev(K), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
+  ks.rk = (float*)(ws + p.off_rk);      // the key row terms are evaluated once (k_gen_kmax) and read by the kernels after it
   if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
   if (int rc = launch_gen_state(ks, dev(V), Lk, BH, H, M, d, dv, 1, p.ldt, p.rows_per_seg, p.nseg, kmax, nullptr, state, st))
     return rc;
@@ -707,6 +709,7 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   if (int rc = launch_fill_u32((uint32_t*)ws, 0u, p.k.off_kmax / sizeof(uint32_t) + BH, st)) return rc;
   GenSide qs{dev(Q), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 2 * dd)};
   GenSide ks{dev(K), qk_scale, 0.f, W, bias, theta, groups, pgroups, tf, (long long)(FS_THETA_HEADER + d + 3 * dd)};
+  ks.rk = (float*)(ws + p.k.off_rk);      // the key row terms are evaluated once (k_gen_kmax) and read by the kernels after it
   if (int rc = launch_gen_kmax(ks, Lk, BH, H, M, d, kmax, st)) return rc;
   if (int rc = launch_gen_state(ks, dev(V), Lk, BH, H, M, d, dv, 1, ldt, p.k.rows_per_seg, p.k.nseg, kmax, nullptr, state, st))
     return rc;

@@ -23,6 +23,8 @@ struct GenSide {
   int pgroups;          // number of projection-constant sets
   long long theta_stride;
   long long c_offset;   // offset of this side's C matrix inside a parameter set
+  float* rk = nullptr;  // [B*H][rows] row terms of this side's rows (written by k_gen_kmax, read by the kernels after
+                        // it instead of evaluating the quadratic form once per feature block); nullptr: none
 };
 
 size_t gen_lds_features(int d);

@@ -95,16 +95,36 @@ __device__ void row_terms(float* rterm, const float* Xs, int ld, int d, const fl
     for (int a = part; a < d; a += 8) acc += x[a] * x[a];
     acc *= (alpha - 0.5f);
   } else {
+    // (eight loads of the row of C in flight and four partial sums: the loop is a chain of cache latencies otherwise)
     for (int a = part; a < d; a += 8) {
-      float t = 0.f;
-      for (int b = 0; b < d; ++b) t += Cmat[a * d + b] * x[b];
-      acc += x[a] * (t + alpha * x[a]);
+      const float* crow = Cmat + (size_t)a * d;
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+      int b = 0;
+#pragma unroll 2
+      for (; b + 4 <= d; b += 4) {
+        t0 += crow[b] * x[b];
+        t1 += crow[b + 1] * x[b + 1];
+        t2 += crow[b + 2] * x[b + 2];
+        t3 += crow[b + 3] * x[b + 3];
+      }
+      for (; b < d; ++b) t0 += crow[b] * x[b];
+      acc += x[a] * ((t0 + t1) + (t2 + t3) + alpha * x[a]);
     }
   }
   acc += __shfl_xor(acc, 1);
   acc += __shfl_xor(acc, 2);
   acc += __shfl_xor(acc, 4);
   if (part == 0) rterm[r] = kLog2e * acc;
+}
+
+// Row terms of the 32-row tile at row0 of (b,h): from the side's table when the call keeps one, else computed.
+__device__ void row_terms_of(float* rterm, const GenSide& sd, int bh, int L, int row0, int row_end, const float* Xs,
+                             int ld, int d, const float* Cmat, float alpha) {
+  if (sd.rk != nullptr) {
+    if (threadIdx.x < TR) rterm[threadIdx.x] = row0 + (int)threadIdx.x < row_end ? sd.rk[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
+  } else {
+    row_terms(rterm, Xs, ld, d, Cmat, alpha);
+  }
 }
 
 // Wave w computes the 16x16 tile (row tile w>>1, feature tile w&1) of Xs * Ws^T.
@@ -259,6 +279,7 @@ __global__ void __launch_bounds__(NT) k_gen_kmax(GenSide ks, int Lk, int H, int 
                   ? ordered_to_float(rowmax_u[threadIdx.x]) + rterm[threadIdx.x] : -INFINITY;
     for (int s = 1; s < 64; s <<= 1) v = fmaxf(v, __shfl_xor(v, s));
     if (threadIdx.x == 0) atomicMax(&kmax_u[bh], float_to_ordered(v));
+    if (ks.rk != nullptr && threadIdx.x < TR && row0 + (int)threadIdx.x < Lk) ks.rk[(size_t)bh * Lk + row0 + threadIdx.x] = rterm[threadIdx.x];
   }
 }
 
@@ -300,7 +321,7 @@ __global__ void __launch_bounds__(NT) k_gen_state(GenSide ks, TensorDev V, int L
     load_rows(Xs, ld, ks.X, b * ks.X.sb + h * ks.X.sh, row0, row_end, d, dpad, ks.scale);
     load_values(Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, append_ones);
     __syncthreads();
-    if (row_shift == nullptr) row_terms(rterm, Xs, ld, d, Cmat, ks.alpha);
+    if (row_shift == nullptr) row_terms_of(rterm, ks, bh, Lk, row0, row_end, Xs, ld, d, Cmat, ks.alpha);
     else if (threadIdx.x < TR) rterm[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * Lk + row0 + threadIdx.x] : 0.f;
     __syncthreads();
     const f32x4 e = proj_tile(Xs, Ws, ld, dpad);
@@ -420,7 +441,9 @@ __global__ void __launch_bounds__(NT) k_gen_apply(GenSide qs, int Lq, int H, int
 
   load_rows(Xs, ld, qs.X, b * qs.X.sb + h * qs.X.sh, row0, Lq, d, dpad, qs.scale);
   __syncthreads();
-  row_terms(rterm, Xs, ld, d, Cmat, qs.alpha);
+  // (the query row terms matter in operator mode only: in attention they cancel in the normalisation)
+  if (matvec) row_terms(rterm, Xs, ld, d, Cmat, qs.alpha);
+  else if (threadIdx.x < TR) rterm[threadIdx.x] = 0.f;
   rowmax_pass(rowmax_u, Xs, Ws, bias_s, ld, W, bias, M, d, dpad);
   // operator mode multiplies the shifts back: exp2(rowmax + rterm + kmax)
   if (threadIdx.x < TR)
@@ -540,7 +563,7 @@ __global__ void __launch_bounds__(NT) k_gen_causal(GenSide qs, GenSide ks, Tenso
     load_rows(Ks, ld, ks.X, kbase, row0, row_end, d, dpad, ks.scale);
     load_values(Vs, ldv, V, b * V.sb + h * V.sh, row0, row_end, nv, ldt, 1);
     __syncthreads();
-    row_terms(rterm, Ks, ld, d, Cmat2, 0.f);
+    row_terms_of(rterm, ks, bh, L, row0, row_end, Ks, ld, d, Cmat2, 0.f);
     rowmax_pass(rowmax_u, Qs, Ws, bias_s, ld, W1, bias1, M, d, dpad);
 
     f32x4 acc[ACC_PER_WAVE];
@@ -789,7 +812,7 @@ __global__ void __launch_bounds__(NT) k_gen_bwd_side(GenSide sd, int side, Tenso
   load_values(As, ldts, A, b * A.sb + h * A.sh, row0, L, a_cols, ldt, append_ones);
   __syncthreads();
   if (side == 1) {
-    row_terms(rterm, Xs, ld, d, Cmat, sd.alpha);
+    row_terms_of(rterm, sd, bh, L, row0, L, Xs, ld, d, Cmat, sd.alpha);
     __syncthreads();
     if (threadIdx.x < TR) rterm[threadIdx.x] -= ordered_to_float(kmax_u[bh]);
   } else if (threadIdx.x < TR) {
@@ -1011,7 +1034,7 @@ __global__ void __launch_bounds__(NT) k_gen_bwd_causal_q(GenSide qs, GenSide ks,
     load_values(m.Gs, ldv, G, b * G.sb + h * G.sh, row0, row_end, ldt, ldt, 0);
     if (threadIdx.x < TR) m.qsh[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
     __syncthreads();
-    row_terms(m.rterm, m.Ks, ld, d, Cmat2, 0.f);
+    row_terms_of(m.rterm, ks, bh, L, row0, row_end, m.Ks, ld, d, Cmat2, 0.f);
     bwd_causal_amat(m.As, m.Gs, m.Vs, ldv, lds, ldt);
 
     f32x4 acc_g[4];
@@ -1155,7 +1178,7 @@ __global__ void __launch_bounds__(NT) k_gen_bwd_causal_k(GenSide qs, GenSide ks,
     load_values(m.Gs, ldv, G, b * G.sb + h * G.sh, row0, row_end, ldt, ldt, 0);
     if (threadIdx.x < TR) m.qsh[threadIdx.x] = row0 + threadIdx.x < row_end ? -row_shift[(size_t)bh * L + row0 + threadIdx.x] : 0.f;
     __syncthreads();
-    row_terms(m.rterm, m.Ks, ld, d, Cmat2, 0.f);
+    row_terms_of(m.rterm, ks, bh, L, row0, row_end, m.Ks, ld, d, Cmat2, 0.f);
     bwd_causal_amat(m.As, m.Gs, m.Vs, ldv, lds, ldt);
 
     f32x4 acc_o[ACC_PER_WAVE], acc_g[4];
