@@ -86,6 +86,24 @@ __device__ __forceinline__ void wblock_put(const WRegs& r, float* Ws, float* bia
   if (threadIdx.x < MB) bias_s[threadIdx.x] = r.b;
 }
 
+// ((C + C^T) x)[c] for a dense C (four partial sums and several loads in flight: a plain loop is a chain of cache
+// latencies).
+__device__ __forceinline__ float sym_row_dot(const float* Cmat, int d, int c, const float* x) {
+  const float* crow = Cmat + (size_t)c * d;
+  const float* ccol = Cmat + c;
+  float t0 = 0.f, t1 = 0.f, t2 = 0.f, t3 = 0.f;
+  int a = 0;
+#pragma unroll 2
+  for (; a + 4 <= d; a += 4) {
+    t0 += (crow[a] + ccol[(size_t)a * d]) * x[a];
+    t1 += (crow[a + 1] + ccol[(size_t)(a + 1) * d]) * x[a + 1];
+    t2 += (crow[a + 2] + ccol[(size_t)(a + 2) * d]) * x[a + 2];
+    t3 += (crow[a + 3] + ccol[(size_t)(a + 3) * d]) * x[a + 3];
+  }
+  for (; a < d; ++a) t0 += (crow[a] + ccol[(size_t)a * d]) * x[a];
+  return (t0 + t1) + (t2 + t3);
+}
+
 // rterm[r] = log2e * (x_r^T C x_r + alpha |x_r|^2); Cmat == nullptr means C = -I/2.
 __device__ void row_terms(float* rterm, const float* Xs, int ld, int d, const float* Cmat, float alpha) {
   const int r = threadIdx.x >> 3, part = threadIdx.x & 7;
@@ -924,8 +942,7 @@ __global__ void __launch_bounds__(NT) k_gen_bwd_side(GenSide sd, int side, Tenso
     float cx;
     if (Cmat == nullptr) cx = -Xs[r * ld + c];
     else {
-      cx = 0.f;
-      for (int a = 0; a < d; ++a) cx += (Cmat[c * d + a] + Cmat[a * d + c]) * Xs[r * ld + a];
+      cx = sym_row_dot(Cmat, d, c, Xs + r * ld);
     }
     const float v = sd.scale * (Gs[r * ld + c] * kLn2 + rsum[r] * (cx + 2.f * sd.alpha * Xs[r * ld + c]));
     store_elem(grad, b * grad.sb + h * grad.sh + (long long)(row0 + r) * grad.sl + c, v);
@@ -995,8 +1012,7 @@ __device__ __forceinline__ void bwd_store_grad(const TensorDev& grad, long long 
     float cx;
     if (Cmat == nullptr) cx = -Xs[r * ld + c];
     else {
-      cx = 0.f;
-      for (int a = 0; a < d; ++a) cx += (Cmat[c * d + a] + Cmat[a * d + c]) * Xs[r * ld + a];
+      cx = sym_row_dot(Cmat, d, c, Xs + r * ld);
     }
     const float v = scale * (Gsrc[r * ld + c] * kLn2 + rsum[r] * (cx + 2.f * alpha * Xs[r * ld + c]));
     store_elem(grad, base + (long long)(row0 + r) * grad.sl + c, v);
