@@ -376,20 +376,37 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
   const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);      // four consecutive numbers per thread
   float* p = Tpart + (size_t)bh * nseg * per + e;
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  // The slots are taken eight at a time: all of a batch's loads are requested before the first number is used (one
+  // memory latency per batch instead of one per slot: with few sequences and hundreds of slots the kernel is a chain
+  // of latencies), and a slot is overwritten only after its batch was read.
+  constexpr int NB = 8;
   if (prefix == 2) {
     float* cpre = cstar + gridDim.y + (size_t)bh * nseg;
     float cr = -INFINITY;
-    for (int s = 0; s < nseg; ++s) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (s < nseg_valid && e < per) v = *(const f32x4*)(p + (size_t)s * per);
-      if (s % sub == 0) {            // only the slots that open a segment are read back
-        if (e == 0) cpre[s] = cr;
-        if (e < per) *(f32x4*)(p + (size_t)s * per) = run;
+    for (int s0 = 0; s0 < nseg; s0 += NB) {
+      f32x4 v[NB];
+      float c[NB];
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int s = s0 + i;
+        v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        c[i] = -INFINITY;
+        if (s < nseg_valid) {
+          c[i] = cpart[(size_t)bh * nseg + s];
+          if (e < per) v[i] = *(const f32x4*)(p + (size_t)s * per);
+        }
       }
-      if (s < nseg_valid) {
-        const float c = cpart[(size_t)bh * nseg + s];
-        if (c > cr) { run *= fast_exp2(cr - c); cr = c; }
-        run += v * fast_exp2(c - cr);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int s = s0 + i;
+        if (s < nseg && s % sub == 0) {            // only the slots that open a segment are read back
+          if (e == 0) cpre[s] = cr;
+          if (e < per) *(f32x4*)(p + (size_t)s * per) = run;
+        }
+        if (s < nseg_valid) {
+          if (c[i] > cr) { run *= fast_exp2(cr - c[i]); cr = c[i]; }
+          run += v[i] * fast_exp2(c[i] - cr);
+        }
       }
     }
     if (e == 0) cstar[bh] = cr;
@@ -399,12 +416,20 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
   for (int s = 0; s < nseg_valid; ++s) cs = fmaxf(cs, cpart[(size_t)bh * nseg + s]);
   if (e == 0) cstar[bh] = cs;
   if (e >= per) return;
-#pragma unroll 4
-  for (int s = 0; s < nseg; ++s) {
-    f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (s < nseg_valid) v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nseg + s] - cs);
-    if (prefix && s % sub == 0) *(f32x4*)(p + (size_t)s * per) = run;    // only the slots that open a segment are read back
-    run += v;
+  for (int s0 = 0; s0 < nseg; s0 += NB) {
+    f32x4 v[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (s < nseg_valid) v[i] = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nseg + s] - cs);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      if (prefix && s < nseg && s % sub == 0) *(f32x4*)(p + (size_t)s * per) = run;    // only the slots that open a segment are read back
+      run += v[i];
+    }
   }
   if (!prefix) *(f32x4*)p = run;
 }
