@@ -129,7 +129,8 @@ __device__ __forceinline__ bf16x8 load_vop_l(const uint16_t (*vt)[LDJ], int jp, 
 // for producers that hand over token-major register images of both sides and values transposed in LDS: the walks of
 // the causal gradient kernels and of the d = dv = 128 shape.  (The forward kernel for d = dv = 64 has a consumer of
 // its own, built on row-major tiles and transposing reads, with a running key shift: kernels_bf16_causal.hip.)
-//   MODE 0: second-side token i sees first-side tokens j <= i;  MODE 1: j >= i.
+//   MODE 0: second-side token i sees first-side tokens j <= i;  MODE 1: j >= i;  MODE 2: no first side at all (the
+//   state is the whole sum and stays as it is: the query pass of a non-causal call; steps 0 and 1 are empty).
 // `sm` needs feat[2][4][4][64][8], uothT[DVP][LDJ] and xch[4][4][16][LDXB].  Executes 2 + 4 nchunk barriers.
 template <int MODE, class SM>
 __device__ __forceinline__ void walk_consume(SM& sm, f32x4 (&T)[4][NVT], int nchunk, int j) {
@@ -137,18 +138,28 @@ __device__ __forceinline__ void walk_consume(SM& sm, f32x4 (&T)[4][NVT], int nch
   __syncthreads();                 // barrier 0
   __syncthreads();                 // the producers' first step
 
-  for (int ci = 0; ci < nchunk; ++ci) {
-    // state before this chunk as A operand (rows = value columns, contraction index <-> feature)
-    bf16x8 tb[2][NVT];
+  // state as A operand (rows = value columns, contraction index <-> feature): before every chunk, or once
+  bf16x8 tb[2][NVT];
+  if (MODE == 2) {
 #pragma unroll
     for (int blk = 0; blk < 2; ++blk)
 #pragma unroll
       for (int vt = 0; vt < NVT; ++vt) tb[blk][vt] = pack8(T[2 * blk][vt], T[2 * blk + 1][vt]);
+  }
+  for (int ci = 0; ci < nchunk; ++ci) {
+    if (MODE != 2) {
+#pragma unroll
+      for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int vt = 0; vt < NVT; ++vt) tb[blk][vt] = pack8(T[2 * blk][vt], T[2 * blk + 1][vt]);
+    }
     bf16x8 sk[4][2];               // first-side feature tiles of the chunk
     bf16x8 vop[2][NVT];            // value operands of the chunk
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
-      if (S < 2) {
+      if (S < 2 && MODE == 2) {
+        // nothing: the barrier below keeps the step structure of the producers
+      } else if (S < 2) {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -188,7 +199,7 @@ __device__ __forceinline__ void walk_consume(SM& sm, f32x4 (&T)[4][NVT], int nch
           // scores^T tiles (rows = first-side tokens 16 jt + 4g + r, column = second-side token 16 it + c), masked
 #pragma unroll
           for (int jp = 0; jp < 2; ++jp) {
-            if (MODE ? 2 * jp + 1 >= it : 2 * jp <= it) {
+            if (MODE != 2 && (MODE ? 2 * jp + 1 >= it : 2 * jp <= it)) {
               f32x4 sc[2];
 #pragma unroll
               for (int jj = 0; jj < 2; ++jj) {

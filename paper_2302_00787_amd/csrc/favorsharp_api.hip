@@ -487,7 +487,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     }
     return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
   }
-  if (wide_supported(Q->dtype, d, dv, M, causal) && small_strides && (int)wide_lds_bytes() <= lds_limit) {
+  if (wide_supported(Q->dtype, d, dv, M, causal) && Lq == Lk && small_strides && (int)wide_lds_bytes() <= lds_limit) {
     WidePlan wp;
     plan_wide(BH, pgroups, Lk, &wp);
     char* w8 = (char*)workspace;
@@ -496,6 +496,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     f.theta = theta; f.Omega = Omega;
     f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
     f.B = B; f.H = H; f.L = Lk; f.nslot = wp.nslot; f.rows_per_slot = wp.rows_per_slot; f.scale = qk_scale;
+    f.causal = causal;
     f.Wbf = (uint16_t*)(w8 + wp.off_Wbf); f.bias = (float*)(w8 + wp.off_bias); f.wnorm = (float*)(w8 + wp.off_wnorm);
     f.rk = (float*)(w8 + wp.off_rk); f.Tpart = (float*)(w8 + wp.off_state); f.cpart = (float*)(w8 + wp.off_cpart);
     f.cstar = (float*)(w8 + wp.off_cstar); f.Ypart = (float*)(w8 + wp.off_ypart);

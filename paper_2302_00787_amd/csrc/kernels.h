@@ -113,6 +113,7 @@ struct WideLaunch {
   int groups, omega_groups, pgroups;
   int B, H, L;
   int nslot, rows_per_slot;
+  int causal = 1;
   float scale;
   uint16_t* Wbf;    // [pgroups][2][512][128]
   float* bias;      // [pgroups][2][512]

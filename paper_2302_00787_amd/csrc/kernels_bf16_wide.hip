@@ -1,4 +1,6 @@
-// bf16 path of causal FAVOR# attention for d = dv = 128, M = 512 (the long-context shape).
+// bf16 path of FAVOR# attention for d = dv = 128, M = 512 (the long-context shape): causal, and non-causal with as
+// many queries as keys (the same kernels: the reduction then leaves the sum of all slot states, and the walk has no
+// first side).
 //
 // The kernels for d = dv = 64, M = 256 keep 64 features x 80 state columns per wave in registers.  This shape is
 // four such problems: the sums over features that make up numerator and normaliser split into two halves of 256
@@ -268,7 +270,8 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
 // cstar[B*H + bh * nslot + s]; cstar[bh] = the sequence's largest).  Keys late in the sequence thus cannot push the
 // states that earlier rows need out of the fp32 range.  Four consecutive numbers per thread.
 // grid (ceil(256*144/1024), B*H*2).
-__global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot, unsigned* flushed) {
+// `total` (non-causal calls): no prefixes; the sum of all slots, on the largest shift, goes to slot 0.
+__global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, int nslot, int total, unsigned* flushed) {
   const int bh2 = blockIdx.y, bh = bh2 >> 1;
   // the walk of the call counts into this word: it starts every call at zero
   if (flushed != nullptr && (blockIdx.x | blockIdx.y | threadIdx.x) == 0) *flushed = 0u;
@@ -285,10 +288,11 @@ __global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, in
     if (writer) cpre[s] = cr;
     if (e < per) {
       const f32x4 v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(c - cr);
-      *(f32x4*)(p + (size_t)s * per) = run;
+      if (!total) *(f32x4*)(p + (size_t)s * per) = run;
       run += v;
     }
   }
+  if (total && e < per) *(f32x4*)p = run;
   if (writer) cstar[bh] = cr;
 }
 
@@ -319,6 +323,9 @@ __device__ __forceinline__ int wrows(const WCtx& cx, int ci) { return ci < cx.nc
 struct WStage { u32x4 xo[4], xw[4], v[2]; float rk[4]; };
 struct XOpW { bf16x8 b[KSW]; };
 
+// CAUSAL = false: the query pass of a non-causal call: no key rows, no values, no key feature tiles (steps 0 and 1
+// only stage and finish); the projection slice is the query side's throughout.
+template <bool CAUSAL>
 __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, const WCtx& cx, int j) {
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
   const int b = cx.bh / a.H, h = cx.bh % a.H;
@@ -336,7 +343,7 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
       for (int ks = 0; ks < KSW; ++ks)
         wx[mt][ks] = *(const bf16x8*)(a.Wbf + (((size_t)cx.pg * 2 + side) * MW + f0 + 16 * mt + c) * DW + 32 * ks + 8 * g);
   };
-  load_w(1);
+  load_w(CAUSAL ? 1 : 0);
   f32x4 qb[4];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -390,12 +397,14 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
 
 #pragma unroll
   for (int i = 0; i < 4; ++i) stg.rk[i] = 0.f;
-  load_x(stg.xo, cx.Kb, a.K.sl, 0, true);
-  load_v(0);
-  store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, 0));
-  store_v(wrows(cx, 0));
-  load_x(stg.xo, cx.Kb, a.K.sl, 1, true);
-  load_v(1);
+  if (CAUSAL) {
+    load_x(stg.xo, cx.Kb, a.K.sl, 0, true);
+    load_v(0);
+    store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, 0));
+    store_v(wrows(cx, 0));
+    load_x(stg.xo, cx.Kb, a.K.sl, 1, true);
+    load_v(1);
+  }
   load_x(stg.xw, cx.Qb, a.Q.sl, 0, false);
   __syncthreads();                 // barrier 0
 
@@ -437,6 +446,7 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
     const int nv = wrows(cx, ci);
 #pragma unroll
     for (int S = 0; S < 4; ++S) {
+      if (CAUSAL || S >= 2) {
       XOpW xs[2];                  // both tiles of the step are requested before the first is used
 #pragma unroll
       for (int u = 0; u < 2; ++u) load_xop(xs[u], S < 2 ? sm.xoth : sm.xown, 2 * (S & 1) + u);
@@ -459,7 +469,8 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
           *(bf16x8*)(&sm.feat[S & 1][2 * u + blk][j][lane][0]) = img;
         }
       }
-      if (!cx.sameB) {             // (with B1 = B2 the two slices are the same numbers and stay where they are)
+      }
+      if (CAUSAL && !cx.sameB) {   // (with B1 = B2 the two slices are the same numbers and stay where they are)
         if (S == 1) load_w(0);
         if (S == 3) load_w(1);
       }
@@ -470,9 +481,11 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
       } else if (S == 1) {
         if (ci > 0) finish(ci - 1);
       } else if (S == 2) {
-        store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, ci + 1));
-        load_x(stg.xo, cx.Kb, a.K.sl, ci + 2, true);
-      } else {
+        if (CAUSAL) {
+          store_x(stg.xo, true, sm.xoth, sm.add_oth, wrows(cx, ci + 1));
+          load_x(stg.xo, cx.Kb, a.K.sl, ci + 2, true);
+        }
+      } else if (CAUSAL) {
         store_v(wrows(cx, ci + 1));
         load_v(ci + 2);
       }
@@ -483,6 +496,7 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
   if (cx.nchunk > 0) finish(cx.nchunk - 1);
 }
 
+template <bool CAUSAL>
 __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   SmemWWalk& sm = *reinterpret_cast<SmemWWalk*>(smem_raw);
@@ -495,7 +509,7 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   cx.fh = a.fh;
   cx.ch = blockIdx.z;
   cx.pg = group_of(a.pgroups, b, h, a.H);
-  cx.cs = a.cstar[gridDim.y + (size_t)bh * a.nslot + slot];     // the slot's key shift (k_wide_reduce)
+  cx.cs = a.cstar[gridDim.y + (size_t)bh * a.nslot + slot];     // the slot's key shift (k_wide_reduce; causal calls)
   cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   cx.Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
   cx.Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
@@ -506,12 +520,13 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   __syncthreads();
   const int w = threadIdx.x >> 6;
   if (w < 4) {
-    wide_producer(a, sm, cx, w);
+    wide_producer<CAUSAL>(a, sm, cx, w);
   } else {
     const int j = w - 4, lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
     // state slice: 64 features of this half x the 64 columns of this column half and the normaliser column (tile 4)
     f32x4 T[4][NVT];
-    const float* Tg = a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + slot) * 256 * TLD;
+    // (non-causal: the sum over all slots, which the reduction left in slot 0)
+    const float* Tg = a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + (CAUSAL ? slot : 0)) * 256 * TLD;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -521,7 +536,7 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
           const int col = vt < 4 ? 64 * cx.ch + 16 * vt + c : DW + c;
           T[mt][vt][r] = Tg[(size_t)(64 * j + 16 * mt + 4 * g + r) * TLD + col];
         }
-    walk_consume<0>(sm, T, cx.nchunk, j);
+    walk_consume<CAUSAL ? 0 : 2>(sm, T, cx.nchunk, j);
   }
 }
 
@@ -628,7 +643,9 @@ int launch_stats_wide(const TensorDev& X, const TensorDev& Y, int BH, int H, int
   return 0;
 }
 
-bool wide_supported(int dtype, int d, int dv, int M_, int causal) { return dtype == 1 && d == DW && dv == DW && M_ == MW && causal == 1; }
+bool wide_supported(int dtype, int d, int dv, int M_, int causal) {
+  return dtype == 1 && d == DW && dv == DW && M_ == MW && (causal == 0 || causal == 1);
+}
 
 size_t wide_lds_bytes() { return std::max(sizeof(SmemWState), sizeof(SmemWWalk)); }
 
@@ -661,8 +678,9 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   a.nslot = f.nslot; a.rows_per_slot = f.rows_per_slot; a.scale = f.scale;
   a.flushed = f.flushed;
   const int BH = f.B * f.H;
+  const void* walk = f.causal ? (const void*)k_wide_walk<true> : (const void*)k_wide_walk<false>;
   if (hipFuncSetAttribute((const void*)k_wide_state, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWState)) != hipSuccess ||
-      hipFuncSetAttribute((const void*)k_wide_walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWWalk)) != hipSuccess) {
+      hipFuncSetAttribute(walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWWalk)) != hipSuccess) {
     (void)hipGetLastError();
     return 2;
   }
@@ -676,14 +694,19 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
   FS_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
-                     f.flushed);
+                     f.causal ? 0 : 1, f.flushed);
   FS_LAUNCH_CHECK();
   // the optional events are attached to the dispatches of the two walks: begin of the first, end of the second
   for (int fh = 0; fh < 2; ++fh) {
     a.fh = fh;
     hipEvent_t e0 = fh == 0 ? ev_begin : nullptr, e1 = fh == 1 ? ev_end : nullptr;
-    if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
-    else hipLaunchKernelGGL(k_wide_walk, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+    if (f.causal) {
+      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<true>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
+      else hipLaunchKernelGGL(k_wide_walk<true>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+    } else {
+      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<false>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
+      else hipLaunchKernelGGL(k_wide_walk<false>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+    }
     FS_LAUNCH_CHECK();
   }
   return 0;

@@ -472,6 +472,35 @@ def test_bf16_wide_path_lengths_and_variants(fs, L, variant):
     print(f"bf16 wide path L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
 
 
+@pytest.mark.parametrize("variant,L", [("posrf", 1), ("sderf", 64), ("sderf", 100), ("sderf", 1000), ("aderf", 200),
+                                       ("aderf", 1000), ("gerf", 333)])
+def test_bf16_wide_path_non_causal(fs, L, variant):
+    """The same shape without the mask (the query pass of the walk on the sum of all slot states, no key tiles in
+    it): single-token, chunk-exact, ragged and multi-slot lengths, isotropic and dense key-side quadratic forms."""
+    w = synth.make("c5", B=1, H=2, L=L, seed=277 + L)
+    worst = _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], False, variant, "bf16")
+    print(f"bf16 wide path, non-causal, L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
+def test_bf16_wide_path_non_causal_runs_on_the_wide_kernels_and_keeps_the_general_path_for_other_lengths(fs):
+    """Non-causal calls with as many queries as keys take the d = 128 kernels (a late key row 40 times longer than the
+    data's flushes on their bound-based shifts and is counted; the general-shape kernels, with exact maxima, never
+    flush a query); with fewer keys than queries the call must still be right (general-shape kernels)."""
+    import torch
+    w = synth.make("c5", B=1, H=2, L=300, seed=281)
+    Q, K, V, Om, s, d = w["Q"].copy(), w["K"], w["V"], w["Omega"], w["qk_scale"], w["d"]
+    Q[:, :, [7, 150]] *= 120.0
+    Q = synth.round_to_bf16(Q)
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    thd, Omd = torch.from_numpy(vec[None]).cuda(), torch.from_numpy(Om).cuda()
+    ws = torch.empty(fs.attention_workspace_bytes(1, 2, 300, 300, d, d, Om.shape[1], False, 1, Om.shape[0]),
+                     dtype=torch.uint8, device="cuda")
+    fs.attention(thd, util.to_device(Q, "bf16"), util.to_device(K, "bf16"), util.to_device(V, "bf16"), s, Omd,
+                 causal=False, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 4
+    _check_attention(fs, w["Q"], K[:, :, :200], V[:, :, :200], Om, s, False, "sderf", "bf16")
+
+
 def test_bf16_wide_path_f32_output_and_strided_inputs(fs):
     import torch
     w = synth.make("c5", B=2, H=2, L=320)
