@@ -657,9 +657,9 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   const int BH = B * H, pgroups = std::max(groups, omega_groups);
   if (workspace_bytes < favorsharp_attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, omega_groups))
     return FS_ERR_WORKSPACE_TOO_SMALL;
-  // bf16 kernels: d = dv = 64, M = 256, bf16 inputs and output gradient, rows addressable with 32 bits
+  // bf16 kernels: d = dv = 64, M = 256, bf16 inputs (dY and the gradients: bf16 or fp32), rows addressable with 32 bits
   const long long max_sl = 1ll << 23;
-  if (fast_supported(Q->dtype, d, dv, M) && dY->dtype == FS_BF16 && Q->stride_l < max_sl && K->stride_l < max_sl &&
+  if (fast_supported(Q->dtype, d, dv, M) && Q->stride_l < max_sl && K->stride_l < max_sl &&
       V->stride_l < max_sl && dY->stride_l < max_sl && dQ->stride_l < max_sl && dK->stride_l < max_sl &&
       dV->stride_l < max_sl &&
       (int)std::max({fast_lds_bytes(), fast_bwd_lds_bytes(), fast_bwd_causal_lds_bytes()}) <= device_lds_limit()) {

@@ -94,11 +94,16 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
     const bool more = row0 + TC < row_end;
     if (more) load_rows_g(xr, Xb, X.sl, row0 + TC, row_end);
     // (MODE 1) this wave's rows of dY are requested before the chunk's feature tiles and used after them
-    bf16x4 gpre[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+    f32x4 gpre[4] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
     if (MODE == 1 && row0 + 16 * w + c < row_end) {
-      const uint16_t* gy = (const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)(row0 + 16 * w + c) * ba.dY.sl + 4 * g;
+      const long long go = b * ba.dY.sb + h * ba.dY.sh + (long long)(row0 + 16 * w + c) * ba.dY.sl + 4 * g;
+      if (ba.dY.dtype == 1) {
 #pragma unroll
-      for (int vt = 0; vt < 4; ++vt) gpre[vt] = *(const bf16x4*)(gy + 16 * vt);
+        for (int vt = 0; vt < 4; ++vt) gpre[vt] = __builtin_convertvector(*(const bf16x4*)((const uint16_t*)ba.dY.ptr + go + 16 * vt), f32x4);
+      } else {
+#pragma unroll
+        for (int vt = 0; vt < 4; ++vt) gpre[vt] = *(const f32x4*)((const float*)ba.dY.ptr + go + 16 * vt);
+      }
     }
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
@@ -127,7 +132,7 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
         float dot = 0.f;
 #pragma unroll
         for (int vt = 0; vt < 4; ++vt) {
-          gv[vt] = __builtin_convertvector(gpre[vt], f32x4);
+          gv[vt] = gpre[vt];
 #pragma unroll
           for (int r = 0; r < 4; ++r) dot += gv[vt][r] * fs[vt][r];
         }

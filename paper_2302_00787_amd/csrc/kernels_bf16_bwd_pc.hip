@@ -43,6 +43,8 @@
 //   uothT (U_oth transposed)        written in step 3, read by the consumers' state update in intervals 4c+5, 4c+6
 //   ab (mask products)              written in step 2, read in intervals 4c+3 and 4c+4
 //   xch (partial tiles)             written in intervals 4c+3 and 4c+4, summed in step 1 of the next chunk (4c+5)
+#include <type_traits>
+
 #include "fast_bwd.h"
 #include "fast_pc.h"
 
@@ -543,7 +545,8 @@ struct SmemWalk {
   __attribute__((aligned(16))) uint16_t xch[4][4][16][LDXB];
 };
 
-template <int MODE>
+// DYF32: the rows of dY are fp32 (MODE 0 reads them; they stay fp32 until the G1 row is rounded)
+template <int MODE, bool DYF32>
 __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, const Ctx& cx, int j) {
   const FastArgs& a = ba.f;
   const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, c = lane & 15;
@@ -578,17 +581,23 @@ __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, c
   XOp xo[2][2];
   load_xop(xo[0][0], sm.xoth, 0, lane);
   load_xop(xo[0][1], sm.xoth, 1, lane);
-  u32x2 gy[4];                     // dY pieces of token tile j of the chunk that is finished next (MODE 0)
+  // dY pieces of token tile j of the chunk that is finished next (MODE 0): four bf16 or four fp32 numbers per tile
+  typedef typename std::conditional<DYF32, u32x4, u32x2>::type GyPiece;
+  GyPiece gy[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) gy[i] = u32x2{0u, 0u};
+  for (int i = 0; i < 4; ++i) gy[i] = GyPiece{};
 
   auto load_dy = [&](int ci_done) {
     const int r0 = chunk_row<MODE>(cx, ci_done);
-    const __amdgpu_buffer_rsrc_t rd = chunk_rsrc((const uint16_t*)ba.dY.ptr + b * ba.dY.sb + h * ba.dY.sh + (long long)r0 * ba.dY.sl,
-                                                 2 * (int)ba.dY.sl, chunk_rows<MODE>(cx, ci_done), 2 * D);
+    constexpr int esz = DYF32 ? 4 : 2;
+    const __amdgpu_buffer_rsrc_t rd = chunk_rsrc((const char*)ba.dY.ptr + (b * ba.dY.sb + h * ba.dY.sh + (long long)r0 * ba.dY.sl) * esz,
+                                                 esz * (int)ba.dY.sl, chunk_rows<MODE>(cx, ci_done), esz * D);
 #pragma unroll
-    for (int vt = 0; vt < 4; ++vt)
-      gy[vt] = __builtin_amdgcn_raw_buffer_load_b64(rd, 2 * ((16 * j + c) * (int)ba.dY.sl + 16 * vt + 4 * g), 0, 0);
+    for (int vt = 0; vt < 4; ++vt) {
+      const int off = esz * ((16 * j + c) * (int)ba.dY.sl + 16 * vt + 4 * g);
+      if constexpr (DYF32) gy[vt] = __builtin_amdgcn_raw_buffer_load_b128(rd, off, 0, 0);
+      else gy[vt] = __builtin_amdgcn_raw_buffer_load_b64(rd, off, 0, 0);
+    }
   };
   int nzero = 0;                   // (forward walk) rows this wave finished with a zero normaliser
   auto finish = [&](int ci_done) {
@@ -610,7 +619,8 @@ __device__ __forceinline__ void walk_producer(const BwdArgs& ba, SmemWalk& sm, c
       float dot = 0.f;
 #pragma unroll
       for (int vt = 0; vt < 4; ++vt) {
-        gv[vt] = __builtin_convertvector(__builtin_bit_cast(bf16x4, gy[vt]), f32x4);
+        if constexpr (DYF32) gv[vt] = __builtin_bit_cast(f32x4, gy[vt]);
+        else gv[vt] = __builtin_convertvector(__builtin_bit_cast(bf16x4, gy[vt]), f32x4);
 #pragma unroll
         for (int r = 0; r < 4; ++r) dot += gv[vt][r] * fsum[vt][r];
       }
@@ -688,7 +698,7 @@ __device__ __forceinline__ void walk_consumer(const BwdArgs& ba, SmemWalk& sm, c
 }
 
 // grid (nslot, B*H), block 512.
-template <int MODE>
+template <int MODE, bool DYF32>
 __global__ void __launch_bounds__(NT8) k_bwd_walk_pc(BwdArgs ba) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   SmemWalk& sm = *reinterpret_cast<SmemWalk*>(smem_raw);
@@ -711,7 +721,7 @@ __global__ void __launch_bounds__(NT8) k_bwd_walk_pc(BwdArgs ba) {
   for (int idx = threadIdx.x; idx < DVP * LDJ / 2; idx += NT8) ((uint32_t*)&sm.uothT[0][0])[idx] = 0u;
   __syncthreads();
   const int w = threadIdx.x >> 6;
-  if (w < 4) walk_producer<MODE>(ba, sm, cx, w);
+  if (w < 4) walk_producer<MODE, DYF32>(ba, sm, cx, w);
   else walk_consumer<MODE>(ba, sm, cx, slot, w - 4);
 }
 
@@ -752,13 +762,16 @@ int launch_bwd_cgrad_pc(const bwd::BwdArgs& ba, int nslot, int BH, hipStream_t s
 }
 
 int launch_bwd_walk_pc(const bwd::BwdArgs& ba, int mode, int nslot, int BH, hipStream_t st) {
-  const void* fn = mode ? (const void*)cg::k_bwd_walk_pc<1> : (const void*)cg::k_bwd_walk_pc<0>;
+  const bool f32dy = ba.dY.dtype == 0;
+  const void* fn = mode ? (const void*)cg::k_bwd_walk_pc<1, false>
+                        : (f32dy ? (const void*)cg::k_bwd_walk_pc<0, true> : (const void*)cg::k_bwd_walk_pc<0, false>);
   if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(cg::SmemWalk)) != hipSuccess) {
     (void)hipGetLastError();
     return 2;
   }
-  if (mode) hipLaunchKernelGGL(cg::k_bwd_walk_pc<1>, dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
-  else hipLaunchKernelGGL(cg::k_bwd_walk_pc<0>, dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
+  if (mode) hipLaunchKernelGGL((cg::k_bwd_walk_pc<1, false>), dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
+  else if (f32dy) hipLaunchKernelGGL((cg::k_bwd_walk_pc<0, true>), dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
+  else hipLaunchKernelGGL((cg::k_bwd_walk_pc<0, false>), dim3(nslot, BH), dim3(pc::NT8), sizeof(cg::SmemWalk), st, ba);
   if (hipGetLastError() != hipSuccess) return 5;
   return 0;
 }

@@ -383,6 +383,30 @@ def test_backward_counts_rows_with_a_zero_normaliser_and_drops_their_terms(fs, c
     assert fs.attention_flushed_rows(ws) == 0
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_bf16_kernels_take_an_fp32_output_gradient(fs, causal):
+    """dY in fp32 next to bf16 Q, K, V (a caller that asked for an fp32 Y): the bf16 gradient kernels read it as it is
+    (it stays fp32 until the G1 rows are rounded), so the result must agree with the oracle on the UNROUNDED dY to the
+    bf16 bar, and must not be the result for the bf16-rounded dY bit for bit."""
+    import torch
+    w = synth.make("c4", B=1, H=2, L=333, seed=97)
+    Q, K, V, s, d, Om = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"], w["Omega"]
+    rng = np.random.default_rng(98)
+    dY = rng.standard_normal(V.shape).astype(np.float32)
+    theta = _theta_block("sderf", Q, K, s)
+    thd, Omd = torch.from_numpy(theta).cuda(), torch.from_numpy(Om).cuda()
+    Qd, Kd, Vd = (util.to_device(t, "bf16") for t in (Q, K, V))
+    got = fs.attention_backward(thd, Qd, Kd, Vd, util.to_device(dY, "f32"), s, Omd, causal=causal, grad_dtype=torch.float32)
+    got = [util.to_host(g) for g in got]
+    rounded = fs.attention_backward(thd, Qd, Kd, Vd, util.to_device(synth.round_to_bf16(dY), "bf16"), s, Omd, causal=causal,
+                                    grad_dtype=torch.float32)
+    assert any(not np.array_equal(a, util.to_host(b)) for a, b in zip(got, rounded))
+    for h in range(2):
+        th = util.oracle_theta_from_vec(theta[h], d)
+        ref = orc.attention_backward(th, Om[h], Q[0, h], K[0, h], V[0, h], dY[0, h], s, causal)
+        _assert_grads(tuple(g[0, h] for g in got), ref, 2e-2, h)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
