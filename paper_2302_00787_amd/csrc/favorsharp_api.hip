@@ -84,7 +84,8 @@ void plan_fit(int B, int H, int Lx, int Ly, int d, int groups, FitPlan* p) {
 
 struct FastPlan {
   int pgroups, nseg, rows_per_seg, sub;
-  size_t off_Wbf, off_bias, off_wnorm, off_rk, off_state, off_cpart, off_cstar, total;
+  size_t off_Wbf, off_bias, off_wnorm, off_rk, off_state, off_cpart, off_cstar, off_rscr, off_cscr, total;
+  int Z;
 };
 
 void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
@@ -98,6 +99,11 @@ void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
   p->off_state = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * 256 * 80 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nseg * p->sub * sizeof(float));
   p->off_cstar = off;  off = align_up(off + (size_t)BH * (1 + (size_t)p->nseg * p->sub) * sizeof(float));
+  // (few sequences with many slots: the range totals of the slot reduction and their shifts)
+  int R;
+  fast_reduce_ranges(BH, p->nseg * p->sub, &p->Z, &R);
+  p->off_rscr = off;   off = align_up(off + (p->Z > 1 ? (size_t)BH * p->Z * 256 * 80 * sizeof(float) : 0));
+  p->off_cscr = off;   off = align_up(off + (p->Z > 1 ? (size_t)BH * (1 + 2 * (size_t)p->Z) * sizeof(float) : 0));
   p->total = off;
 }
 
@@ -478,6 +484,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     f.rk = (float*)(w8 + fp.off_rk); f.Tpart = (float*)(w8 + fp.off_state); f.cpart = (float*)(w8 + fp.off_cpart);
     f.cstar = (float*)(w8 + fp.off_cstar);
     f.flushed = (unsigned*)w8;
+    if (fp.Z > 1) { f.rscr = (float*)(w8 + fp.off_rscr); f.cscr = (float*)(w8 + fp.off_cscr); }
     if (prepared != nullptr) {
       PreparedPlan pp;
       plan_prepared(d, M, pgroups, &pp);

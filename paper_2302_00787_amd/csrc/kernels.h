@@ -99,6 +99,8 @@ struct FastLaunch {
   float* cpart;     // [B*H][nseg*sub]
   float* cstar;     // [B*H]
   unsigned* flushed = nullptr;   // counter of output rows whose normaliser came out as zero (nullptr: not counted)
+  float* rscr = nullptr;         // [B*H][Z][256][80] range totals of the slot reduction (nullptr: one-kernel reduction)
+  float* cscr = nullptr;         // [B*H][Z] their shifts, then [B*H] + [B*H][Z] the shifts of the scan over them
   // 0: compute the projection constants and the key row terms; 1: the constants are already in Wbf / bias / wnorm
   // (prepared by an earlier call), only the row terms of parameter sets with a dense C2 are computed; 2: the
   // constants are there and no parameter set has a dense C2: nothing to do
@@ -146,6 +148,8 @@ int launch_op_matvec(const float* theta, const TensorDev& X, const TensorDev& Y,
 size_t fast_lds_bytes();
 bool fast_supported(int dtype, int d, int dv, int M);
 void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub);
+// Ranges of the slot reduction: Z > 1 (ranges of R slots, reduced side by side) for few sequences with many slots.
+void fast_reduce_ranges(int BH, int nslot, int* Z, int* R);
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end);
 int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, const TensorDev& dQ, const TensorDev& dK,
                                    const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart, float* rcstar,

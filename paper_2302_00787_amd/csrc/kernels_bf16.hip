@@ -434,6 +434,86 @@ __global__ void k_fast_reduce(float* Tpart, const float* cpart, float* cstar, in
   if (!prefix) *(f32x4*)p = run;
 }
 
+// The same reduction for few sequences with many slots (one sequence of 262144 rows has 512 of them, and twenty
+// workgroups walking them one after the other take longer than the two kernels around them): the slots are cut into
+// ranges of R, one workgroup row per range.
+//   k_fast_reduce_totals  range z: sum of its slots on the range's own largest shift -> scr[bh][z], cscr[bh][z]
+//   k_fast_reduce         over the Z totals (sum, or exclusive prefixes on running shifts), in place in scr
+//   k_fast_reduce_walk    (causal) range z: the exclusive prefixes of its slots as k_fast_reduce (prefix = 2) writes
+//                         them, starting from the prefix and the shift of the range
+// Sums are taken in another order than by the one-kernel form: the results agree to rounding, not bit for bit.
+// grid (ceil(M*DVP/1024), B*H, Z).
+__global__ void k_fast_reduce_totals(const float* Tpart, const float* cpart, float* scr, float* cscr, int nseg,
+                                     int nseg_valid, int R) {
+  const int bh = blockIdx.y, z = blockIdx.z, Z = gridDim.z;
+  constexpr size_t per = (size_t)M * DVP;
+  const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
+  const int s_beg = z * R, s_end = min(nseg_valid, s_beg + R);
+  float m = -INFINITY;
+  for (int s = s_beg; s < s_end; ++s) m = fmaxf(m, cpart[(size_t)bh * nseg + s]);
+  if (e == 0) cscr[(size_t)bh * Z + z] = m;
+  if (e >= per) return;
+  const float* p = Tpart + (size_t)bh * nseg * per + e;
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  constexpr int NB = 8;
+  for (int s0 = s_beg; s0 < s_end; s0 += NB) {
+    f32x4 v[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (s < s_end) v[i] = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(cpart[(size_t)bh * nseg + s] - m);
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) run += v[i];
+  }
+  *(f32x4*)(scr + ((size_t)bh * Z + z) * per + e) = run;
+}
+
+// `base` = scr after the scan (exclusive prefix of range z), `cbase` = the scan's shifts (largest shift of the ranges
+// before z at cbase[B*H + bh * Z + z]).
+__global__ void k_fast_reduce_walk(float* Tpart, const float* cpart, float* cstar, const float* base, const float* cbase,
+                                   int nseg, int nseg_valid, int sub, int R, unsigned* flushed) {
+  const int bh = blockIdx.y, z = blockIdx.z, Z = gridDim.z;
+  if (flushed != nullptr && (blockIdx.x | blockIdx.y | blockIdx.z | threadIdx.x) == 0) *flushed = 0u;
+  constexpr size_t per = (size_t)M * DVP;
+  const size_t e = 4 * ((size_t)blockIdx.x * blockDim.x + threadIdx.x);
+  float* p = Tpart + (size_t)bh * nseg * per + e;
+  float* cpre = cstar + gridDim.y + (size_t)bh * nseg;
+  const int s_beg = z * R, s_end = min(nseg, s_beg + R);
+  f32x4 run = {0.f, 0.f, 0.f, 0.f};
+  if (e < per) run = *(const f32x4*)(base + ((size_t)bh * Z + z) * per + e);
+  float cr = cbase[gridDim.y + (size_t)bh * Z + z];
+  constexpr int NB = 8;
+  for (int s0 = s_beg; s0 < s_end; s0 += NB) {
+    f32x4 v[NB];
+    float c[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      c[i] = -INFINITY;
+      if (s < s_end && s < nseg_valid) {
+        c[i] = cpart[(size_t)bh * nseg + s];
+        if (e < per) v[i] = *(const f32x4*)(p + (size_t)s * per);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      if (s < s_end && s % sub == 0) {
+        if (e == 0) cpre[s] = cr;
+        if (e < per) *(f32x4*)(p + (size_t)s * per) = run;
+      }
+      if (s < s_end && s < nseg_valid) {
+        if (c[i] > cr) { run *= fast_exp2(cr - c[i]); cr = c[i]; }
+        run += v[i] * fast_exp2(c[i] - cr);
+      }
+    }
+  }
+  if (e == 0 && z == Z - 1) cstar[bh] = cr;
+}
+
 // ---------------------------------------------------------------------------------------------------
 // Query side of the non-causal contraction: Y = (P T) normalised by its last column (Sections 2.1, 2.2) for a block
 // of query rows; T = total state of the (b,h) (slot 0 of Tpart).  Four waves of 64 features; the partial output
@@ -524,6 +604,15 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
 size_t fast_lds_bytes() { return std::max({sizeof(SmemState), sizeof(SmemApply), fast_causal_lds_bytes()}); }
 
 bool fast_supported(int dtype, int d, int dv, int M_) { return dtype == 1 && d == D && dv == D && M_ == M; }
+
+void fast_reduce_ranges(int BH, int nslot, int* Z, int* R) {
+  *Z = 1;
+  *R = nslot;
+  if (BH <= 8 && nslot >= 64) {
+    *R = 16;
+    *Z = (nslot + 15) / 16;
+  }
+}
 
 void fast_plan(int BH, int L, int* nseg, int* rows_per_seg, int* sub) {
   int want = std::max(1, std::min((256 + BH - 1) / BH, (L + TC - 1) / TC));
@@ -625,8 +714,34 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
     hipLaunchKernelGGL(k_fast_state, dim3(nstate, BH), dim3(NT), sizeof(SmemState), st, a);
     FS_LAUNCH_CHECK();
   }
-  hipLaunchKernelGGL(k_fast_reduce, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar,
-                     a.nslot, nstate, f.causal ? (every_slot ? 1 : 2) : 0, every_slot ? 1 : f.sub, f.flushed);
+  const int prefix = f.causal ? (every_slot ? 1 : 2) : 0, nblk = (M * DVP / 4 + 255) / 256;
+  int Z = 1, R = a.nslot;
+  if (f.rscr != nullptr && prefix != 1) fast_reduce_ranges(BH, a.nslot, &Z, &R);
+  const int Zvalid = (nstate + R - 1) / R;
+  if (Z > 1 && Zvalid >= 1) {
+    // few sequences, many slots: range totals, the reduction over them, and (causal) the walk over every range
+    float* cscan = f.cscr + (size_t)BH * Z;
+    hipLaunchKernelGGL(k_fast_reduce_totals, dim3(nblk, BH, Z), dim3(256), 0, st, f.Tpart, f.cpart, f.rscr, f.cscr, a.nslot,
+                       nstate, R);
+    FS_LAUNCH_CHECK();
+    if (prefix == 0) {
+      // the sum of everything ends in range 0 of the scratch buffer: the query-side kernel reads it there
+      hipLaunchKernelGGL(k_fast_reduce, dim3(nblk, BH), dim3(256), 0, st, f.rscr, f.cscr, f.cstar, Z, Zvalid, 0, 1, f.flushed);
+      FS_LAUNCH_CHECK();
+      a.Tpart = f.rscr;
+      a.nslot = Z;
+    } else {
+      hipLaunchKernelGGL(k_fast_reduce, dim3(nblk, BH), dim3(256), 0, st, f.rscr, f.cscr, cscan, Z, Zvalid, 2, 1,
+                         (unsigned*)nullptr);
+      FS_LAUNCH_CHECK();
+      hipLaunchKernelGGL(k_fast_reduce_walk, dim3(nblk, BH, Z), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.rscr, cscan,
+                         a.nslot, nstate, every_slot ? 1 : f.sub, R, f.flushed);
+      FS_LAUNCH_CHECK();
+    }
+    return 0;
+  }
+  hipLaunchKernelGGL(k_fast_reduce, dim3(nblk, BH), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, a.nslot, nstate, prefix,
+                     every_slot ? 1 : f.sub, f.flushed);
   FS_LAUNCH_CHECK();
   return 0;
 }

@@ -460,6 +460,41 @@ def test_bf16_path_lengths_and_variants(fs, causal, L, variant):
     print(f"bf16 path causal={causal} L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("H,L", [(1, 4096), (1, 5000), (2, 8209)])
+def test_bf16_path_few_sequences_many_slots(fs, causal, H, L):
+    """One or two sequences cut into 64 and more slots: the slot reduction then runs range by range (totals per range,
+    a scan over them, and for causal calls a walk over every range), in another summation order than the one-kernel
+    form: whole sequences against the oracle, chunk-exact and ragged lengths, one and two slots per segment."""
+    w = synth.make("c4", B=1, H=H, L=L, seed=401 + L)
+    worst = _check_attention(fs, w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], causal, "sderf", "bf16", chunk=64)
+    print(f"bf16 path, ranges, causal={causal} H={H} L={L}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
+def test_bf16_path_few_sequences_many_slots_late_outlier(fs):
+    """The running shifts survive the range form: a key with a huge bound late in a single sequence of 64 slots leaves
+    the rows of all earlier segments within tolerance (as in the late-key test, which has too few slots for ranges)."""
+    import torch
+    L = 4096
+    w = synth.make("c4", B=1, H=1, L=L, seed=419)
+    Q, K, V, s, d = w["Q"], w["K"].copy(), w["V"], w["qk_scale"], w["d"]
+    Om = (2.2 * w["Omega"]).astype(np.float32)
+    longest = float(np.linalg.norm(Om[0], axis=1).max())
+    late = L - 300
+    K[0, 0, late] *= (longest / s) / np.linalg.norm(K[0, 0, late])
+    K = synth.round_to_bf16(K)
+    vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
+    th = util.oracle_theta_from_vec(vec, d)
+    Y = fs.attention(torch.from_numpy(vec[None]).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, out_dtype=torch.float32)
+    Yh = util.to_host(Y)[0, 0]
+    assert np.isfinite(Yh).all()
+    ref = orc.attention(th, Om[0], Q[0, 0], K[0, 0], V[0, 0], s, True)
+    safe = (late // 64) * 64
+    fro, row = util.attention_errors(Yh[:safe], ref[:safe], V[0, 0, :safe].astype(np.float64))
+    assert fro <= 2e-2 and row <= 8e-2, (fro, row)
+
+
 # ----------------------------------------------------------------------------- bf16 MFMA path (d = 128, M = 512)
 @pytest.mark.parametrize("variant,L", [("posrf", 1), ("sderf", 64), ("sderf", 100), ("sderf", 1000), ("aderf", 200),
                                        ("aderf", 1000)])
