@@ -282,14 +282,35 @@ __global__ void k_wide_reduce(float* Tpart, const float* cpart, float* cstar, in
   float* p = Tpart + (size_t)bh2 * nslot * per + e;
   f32x4 run = {0.f, 0.f, 0.f, 0.f};
   float cr = -INFINITY;
-  for (int s = 0; s < nslot; ++s) {
-    const float c = cpart[(size_t)bh * nslot + s];
-    if (c > cr) { run *= fast_exp2(cr - c); cr = c; }
-    if (writer) cpre[s] = cr;
-    if (e < per) {
-      const f32x4 v = *(const f32x4*)(p + (size_t)s * per) * fast_exp2(c - cr);
-      if (!total) *(f32x4*)(p + (size_t)s * per) = run;
-      run += v;
+  // eight slots at a time: a batch's loads are all requested before the first number is used (with one or two
+  // sequences the kernel is a chain of memory latencies otherwise), and a slot is overwritten only after its batch
+  // was read
+  constexpr int NB = 8;
+  for (int s0 = 0; s0 < nslot; s0 += NB) {
+    f32x4 v[NB];
+    float cb[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      cb[i] = -INFINITY;
+      if (s < nslot) {
+        cb[i] = cpart[(size_t)bh * nslot + s];
+        if (e < per) v[i] = *(const f32x4*)(p + (size_t)s * per);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int s = s0 + i;
+      if (s < nslot) {
+        const float c = cb[i];
+        if (c > cr) { run *= fast_exp2(cr - c); cr = c; }
+        if (writer) cpre[s] = cr;
+        if (e < per) {
+          if (!total) *(f32x4*)(p + (size_t)s * per) = run;
+          run += v[i] * fast_exp2(c - cr);
+        }
+      }
     }
   }
   if (total && e < per) *(f32x4*)p = run;
