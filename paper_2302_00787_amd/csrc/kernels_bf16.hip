@@ -35,13 +35,19 @@ __global__ void __launch_bounds__(256) k_fast_pre(const float* theta, int groups
     const float* Bm = th + FS_THETA_HEADER_ + D + (side ? (size_t)D * D : 0);
     const float* A = th + FS_THETA_HEADER_;
     const size_t o = ((size_t)pg * 2 + side) * M + m;
+    // omega_m^T B, column c: the lane's column of B is requested whole (64 loads in flight, one memory latency),
+    // omega_m sits one number per lane and is read across the wave
+    float bcol[D];
+#pragma unroll
+    for (int l = 0; l < D; ++l) bcol[l] = Bm[l * D + c];
+    const float om_c = om[c];
     float acc = 0.f;
-#pragma unroll 8
-    for (int l = 0; l < D; ++l) acc += om[l] * Bm[l * D + c];
+#pragma unroll
+    for (int l = 0; l < D; ++l) acc += __shfl(om_c, l) * bcol[l];
     const uint16_t bits = f32_to_bf16_bits(acc * kLog2e * scale);
     Wbf[o * D + c] = bits;
     const float r = bf16_bits_to_f32(bits);
-    float n2 = r * r, q = A[c] * om[c] * om[c];
+    float n2 = r * r, q = A[c] * om_c * om_c;
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) { n2 += __shfl_xor(n2, s); q += __shfl_xor(q, s); }
     if (c == 0) {
