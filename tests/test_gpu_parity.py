@@ -754,14 +754,18 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name):
     assert torch.isfinite(Y.float()).all().item()
 
 
-@pytest.mark.parametrize("name,over,prepared", [("c1", {}, False), ("c4", dict(B=1, H=2, L=1216), False),
-                                                ("c5", dict(B=1, H=2, L=832), False), ("c4", dict(B=1, H=2, L=1216), True),
-                                                ("c2", {}, False)])
-def test_attention_call_replays_from_a_hip_graph(fs, name, over, prepared):
+@pytest.mark.parametrize("name,over,prepared,variant", [
+    ("c1", {}, False, "sderf"), ("c4", dict(B=1, H=2, L=1216), False, "sderf"), ("c5", dict(B=1, H=2, L=832), False, "sderf"),
+    ("c4", dict(B=1, H=2, L=1216), True, "sderf"), ("c2", {}, False, "sderf"),
+    ("c4", dict(B=1, H=2, L=1216), True, "aderf"), ("c5", dict(B=1, H=2, L=832), False, "aderf"),
+    ("c4", dict(B=1, H=1, L=4100), False, "sderf"), ("c3", dict(B=1, H=1, L=4100), True, "sderf")])
+def test_attention_call_replays_from_a_hip_graph(fs, name, over, prepared, variant):
     """The entry point only enqueues kernels on the caller's stream (no synchronisation, no allocation, no memset
     nodes), so a caller may capture it: the graph is replayed three times, with eager work and synchronisations in
     between, and every replay must reproduce the eager result bit for bit (general path, both bf16 paths, the call
-    on prepared projection constants, and the kernel operator on its fp32 MFMA kernels)."""
+    on prepared projection constants, the kernel operator on its fp32 MFMA kernels, parameter sets with a dense
+    quadratic form, which add the row-term kernel, and a single sequence of 65 slots, whose slot reduction is the
+    three-kernel form)."""
     import torch
     if name == "c2":
         _operator_graph_replay(fs)
@@ -770,7 +774,7 @@ def test_attention_call_replays_from_a_hip_graph(fs, name, over, prepared):
     dt = w.get("dtype", "f32")
     Q, K, V = (util.to_device(w[k], dt) for k in "QKV")
     Om, s, causal = torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"], bool(w["causal"])
-    theta = fs.fit_params("sderf", Q, K, s, groups=w["H"])
+    theta = fs.fit_params(variant, Q, K, s, groups=w["H"])
     B, H, L, d = Q.shape
     ws = torch.empty(fs.attention_workspace_bytes(B, H, L, L, d, V.shape[-1], Om.shape[-2], causal, H, H), dtype=torch.uint8,
                      device="cuda")
