@@ -107,7 +107,7 @@ struct FastLaunch {
   int pre_mode = 0;
 };
 
-// bf16 path for causal calls with d = dv = 128, M = 512 (kernels_bf16_wide.hip).
+// bf16 path for d = dv = 128, M = 512: causal, and non-causal with Lq = Lk (kernels_bf16_wide.hip).
 struct WideLaunch {
   TensorDev Q, K, V, Y;
   const float* theta;

@@ -12,7 +12,8 @@
 // of the two partial normalisers and stores Y.  All combinations share every shift (the per-row query shift and the
 // per-slot key shift are bounds over all 512 features), so their partial rows are on one scale.
 //
-//   k_wide_pre     projection constants for both sides (Section 4, evaluation recipe), key row terms for dense C2
+//   k_wide_pre     projection constants for both sides (Section 4, evaluation recipe)
+//   (k_key_row_terms of the d = 64 file: the key row terms of parameter sets with a dense C2)
 //   k_wide_state   per (slot, feature half): S^T [V 1] over the slot (eight waves of 32 features, all 129 columns)
 //   k_wide_reduce  exclusive prefix over the slots, each on the running maximum of the slots' shifts
 //   k_wide_walk    per (slot, column half), once per feature half: the causal walk; the second launch finishes Y
