@@ -108,12 +108,14 @@ void plan_fast(int BH, int pgroups, int Lk, FastPlan* p) {
 }
 
 struct WidePlan {
-  int nslot, rows_per_slot;
+  int nslot, rows_per_slot;         // slots of the keys
+  int nslot_q, rows_per_slot_q;     // slots of the queries (the walk)
   size_t off_Wbf, off_bias, off_wnorm, off_rk, off_state, off_cpart, off_cstar, off_ypart, total;
 };
 
-void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
+void plan_wide(int BH, int pgroups, int Lq, int L, WidePlan* p) {
   wide_plan(BH, L, &p->nslot, &p->rows_per_slot);
+  wide_plan(BH, Lq, &p->nslot_q, &p->rows_per_slot_q);
   size_t off = kAlign;       // the counter word
   p->off_Wbf = off;    off = align_up(off + (size_t)pgroups * 2 * 512 * 128 * sizeof(uint16_t));
   p->off_bias = off;   off = align_up(off + (size_t)pgroups * 2 * 512 * sizeof(float));
@@ -122,7 +124,7 @@ void plan_wide(int BH, int pgroups, int L, WidePlan* p) {
   p->off_state = off;  off = align_up(off + (size_t)BH * 2 * p->nslot * 256 * 144 * sizeof(float));
   p->off_cpart = off;  off = align_up(off + (size_t)BH * p->nslot * sizeof(float));
   p->off_cstar = off;  off = align_up(off + (size_t)BH * (1 + (size_t)p->nslot) * sizeof(float));
-  p->off_ypart = off;  off = align_up(off + (size_t)BH * L * 132 * sizeof(float));
+  p->off_ypart = off;  off = align_up(off + (size_t)BH * Lq * 132 * sizeof(float));
   p->total = off;
 }
 
@@ -368,9 +370,9 @@ size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d,
     plan_fast(B * H, std::max(groups, omega_groups), Lk, &fp);
     total = std::max(total, fp.total);
   }
-  if (wide_supported(FS_BF16, d, dv, M, causal) && Lq == Lk) {
+  if (wide_supported(FS_BF16, d, dv, M, causal) && (Lq == Lk || !causal)) {
     WidePlan wp;
-    plan_wide(B * H, std::max(groups, omega_groups), Lk, &wp);
+    plan_wide(B * H, std::max(groups, omega_groups), Lq, Lk, &wp);
     total = std::max(total, wp.total);
   }
   return total;
@@ -494,9 +496,10 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     }
     return launch_fast_attention(f, (hipStream_t)stream, (hipEvent_t)event_main_begin, (hipEvent_t)event_main_end);
   }
-  if (wide_supported(Q->dtype, d, dv, M, causal) && Lq == Lk && small_strides && (int)wide_lds_bytes() <= lds_limit) {
+  if (wide_supported(Q->dtype, d, dv, M, causal) && (Lq == Lk || !causal) && small_strides &&
+      (int)wide_lds_bytes() <= lds_limit) {
     WidePlan wp;
-    plan_wide(BH, pgroups, Lk, &wp);
+    plan_wide(BH, pgroups, Lq, Lk, &wp);
     char* w8 = (char*)workspace;
     WideLaunch f;
     f.Q = dev(Q); f.K = dev(K); f.V = dev(V); f.Y = dev(Y);
@@ -504,6 +507,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
     f.groups = groups; f.omega_groups = omega_groups; f.pgroups = pgroups;
     f.B = B; f.H = H; f.L = Lk; f.nslot = wp.nslot; f.rows_per_slot = wp.rows_per_slot; f.scale = qk_scale;
     f.causal = causal;
+    f.Lq = Lq; f.nslot_q = wp.nslot_q; f.rows_per_slot_q = wp.rows_per_slot_q;
     f.Wbf = (uint16_t*)(w8 + wp.off_Wbf); f.bias = (float*)(w8 + wp.off_bias); f.wnorm = (float*)(w8 + wp.off_wnorm);
     f.rk = (float*)(w8 + wp.off_rk); f.Tpart = (float*)(w8 + wp.off_state); f.cpart = (float*)(w8 + wp.off_cpart);
     f.cstar = (float*)(w8 + wp.off_cstar); f.Ypart = (float*)(w8 + wp.off_ypart);

@@ -107,15 +107,16 @@ struct FastLaunch {
   int pre_mode = 0;
 };
 
-// bf16 path for d = dv = 128, M = 512: causal, and non-causal with Lq = Lk (kernels_bf16_wide.hip).
+// bf16 path for d = dv = 128, M = 512, causal and non-causal (kernels_bf16_wide.hip).
 struct WideLaunch {
   TensorDev Q, K, V, Y;
   const float* theta;
   const float* Omega;
   int groups, omega_groups, pgroups;
-  int B, H, L;
-  int nslot, rows_per_slot;
+  int B, H, L;                       // L keys (causal calls: and as many queries)
+  int nslot, rows_per_slot;          // wide_plan of the keys
   int causal = 1;
+  int Lq = 0, nslot_q = 0, rows_per_slot_q = 0;   // non-causal calls: the queries and their wide_plan
   float scale;
   uint16_t* Wbf;    // [pgroups][2][512][128]
   float* bias;      // [pgroups][2][512]
@@ -124,7 +125,7 @@ struct WideLaunch {
   float* Tpart;     // [B*H][2][nslot][256][144]
   float* cpart;     // [B*H][nslot]
   float* cstar;     // [B*H]
-  float* Ypart;     // [B*H][L][132]
+  float* Ypart;     // [B*H][queries][132]
   unsigned* flushed = nullptr;   // as in FastLaunch
   int pre_mode = 0; // as in FastLaunch
 };

@@ -1,6 +1,6 @@
-// bf16 path of FAVOR# attention for d = dv = 128, M = 512 (the long-context shape): causal, and non-causal with as
-// many queries as keys (the same kernels: the reduction then leaves the sum of all slot states, and the walk has no
-// first side).
+// bf16 path of FAVOR# attention for d = dv = 128, M = 512 (the long-context shape): causal and non-causal (the same
+// kernels: the reduction then leaves the sum of all slot states, and the walk has no first side and its own
+// division of the queries into slots).
 //
 // The kernels for d = dv = 64, M = 256 keep 64 features x 80 state columns per wave in registers.  This shape is
 // four such problems: the sums over features that make up numerator and normaliser split into two halves of 256
@@ -50,8 +50,9 @@ struct WideArgs {
   float* Tpart;      // [BH][2][nslot][256][144]
   float* cpart;      // [BH][nslot]
   float* cstar;      // [BH] largest shift of each sequence, then [BH][nslot] the key shift of each slot
-  float* Ypart;      // [BH][L][132]: partial rows of feature half 0
-  int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;
+  float* Ypart;      // [BH][Lq][132]: partial rows of feature half 0
+  int groups, omega_groups, pgroups, B, H, L, nslot, rows_per_slot;   // L keys in nslot slots (state kernel, reduction)
+  int Lq, rows_per_slot_q;   // the walk's rows and its slots (causal calls: the same numbers as the key side's)
   int fh;            // feature half of this launch of the walk
   float scale;
   unsigned* flushed; // counter of output rows with a zero normaliser (nullptr: not counted)
@@ -441,7 +442,7 @@ __device__ __forceinline__ void wide_producer(const WideArgs& a, SmemWWalk& sm, 
     finish_tiles(fsum, sm, j, 2, lane);
     float den = finish_col64(sm, j, lane);
     const int r0 = wrow(cx, ci_done), nv = wrows(cx, ci_done);
-    float* yp = a.Ypart + ((size_t)cx.bh * a.L + r0) * YLD;
+    float* yp = a.Ypart + ((size_t)cx.bh * a.Lq + r0) * YLD;
     const __amdgpu_buffer_rsrc_t ry = chunk_rsrc(yp, 4 * YLD, nv, 4 * YLD);
     const int off = 4 * ((16 * j + c) * YLD + 64 * cx.ch + 4 * g), doff = 4 * ((16 * j + c) * YLD + DW + cx.ch);
     if (cx.fh == 0) {
@@ -531,12 +532,12 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
   cx.fh = a.fh;
   cx.ch = blockIdx.z;
   cx.pg = group_of(a.pgroups, b, h, a.H);
-  cx.cs = a.cstar[gridDim.y + (size_t)bh * a.nslot + slot];     // the slot's key shift (k_wide_reduce; causal calls)
+  cx.cs = CAUSAL ? a.cstar[gridDim.y + (size_t)bh * a.nslot + slot] : 0.f;     // the slot's key shift (k_wide_reduce)
   cx.Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   cx.Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh;
   cx.Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh;
-  cx.row_beg = min(a.L, slot * a.rows_per_slot);
-  cx.row_end = min(a.L, cx.row_beg + a.rows_per_slot);
+  cx.row_beg = min(a.Lq, slot * a.rows_per_slot_q);
+  cx.row_end = min(a.Lq, cx.row_beg + a.rows_per_slot_q);
   cx.nchunk = (cx.row_end - cx.row_beg + TC - 1) / TC;
   for (int idx = threadIdx.x; idx < DVP * LDJ / 2; idx += NT8) ((uint32_t*)&sm.uothT[0][0])[idx] = 0u;
   __syncthreads();
@@ -698,6 +699,9 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   a.Ypart = f.Ypart;
   a.groups = f.groups; a.omega_groups = f.omega_groups; a.pgroups = f.pgroups; a.B = f.B; a.H = f.H; a.L = f.L;
   a.nslot = f.nslot; a.rows_per_slot = f.rows_per_slot; a.scale = f.scale;
+  a.Lq = f.causal ? f.L : f.Lq;
+  a.rows_per_slot_q = f.causal ? f.rows_per_slot : f.rows_per_slot_q;
+  const int nslot_q = f.causal ? f.nslot : f.nslot_q;
   a.flushed = f.flushed;
   const int BH = f.B * f.H;
   const void* walk = f.causal ? (const void*)k_wide_walk<true> : (const void*)k_wide_walk<false>;
@@ -723,11 +727,11 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
     a.fh = fh;
     hipEvent_t e0 = fh == 0 ? ev_begin : nullptr, e1 = fh == 1 ? ev_end : nullptr;
     if (f.causal) {
-      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<true>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
-      else hipLaunchKernelGGL(k_wide_walk<true>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<true>, dim3(nslot_q, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
+      else hipLaunchKernelGGL(k_wide_walk<true>, dim3(nslot_q, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
     } else {
-      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<false>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
-      else hipLaunchKernelGGL(k_wide_walk<false>, dim3(f.nslot, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
+      if (e0 || e1) hipExtLaunchKernelGGL(k_wide_walk<false>, dim3(nslot_q, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, e0, e1, 0, a);
+      else hipLaunchKernelGGL(k_wide_walk<false>, dim3(nslot_q, BH, 2), dim3(NT8), sizeof(SmemWWalk), st, a);
     }
     FS_LAUNCH_CHECK();
   }

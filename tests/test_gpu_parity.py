@@ -517,23 +517,43 @@ def test_bf16_wide_path_non_causal(fs, L, variant):
     print(f"bf16 wide path, non-causal, L={L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
 
 
-def test_bf16_wide_path_non_causal_runs_on_the_wide_kernels_and_keeps_the_general_path_for_other_lengths(fs):
-    """Non-causal calls with as many queries as keys take the d = 128 kernels (a late key row 40 times longer than the
-    data's flushes on their bound-based shifts and is counted; the general-shape kernels, with exact maxima, never
-    flush a query); with fewer keys than queries the call must still be right (general-shape kernels)."""
+@pytest.mark.parametrize("variant,Lq,Lk", [("sderf", 300, 200), ("sderf", 64, 1000), ("aderf", 1000, 200),
+                                           ("gerf", 1, 500), ("posrf", 700, 1), ("saderf", 130, 131)])
+def test_bf16_wide_path_non_causal_other_numbers_of_queries_than_keys(fs, variant, Lq, Lk):
+    """Without the mask the queries and the keys are cut into slots separately (state kernel and reduction over the
+    keys' slots, the query pass over the queries'): more queries than keys, fewer, a single query, a single key."""
+    w = synth.make("c5", B=1, H=2, L=max(Lq, Lk), seed=291 + Lq + Lk)
+    worst = _check_attention(fs, w["Q"][:, :, :Lq], w["K"][:, :, :Lk], w["V"][:, :, :Lk], w["Omega"], w["qk_scale"],
+                             False, variant, "bf16")
+    print(f"bf16 wide path, non-causal, Lq={Lq} Lk={Lk} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
+@pytest.mark.parametrize("Lk", [300, 200])
+def test_bf16_wide_path_non_causal_runs_on_the_wide_kernels(fs, Lk):
+    """Non-causal calls take the d = 128 kernels, with as many queries as keys and with other numbers: query rows 120
+    times longer than the data's flush on their bound-based shifts and are counted (the general-shape kernels, with
+    exact maxima, never flush a query)."""
     import torch
     w = synth.make("c5", B=1, H=2, L=300, seed=281)
-    Q, K, V, Om, s, d = w["Q"].copy(), w["K"], w["V"], w["Omega"], w["qk_scale"], w["d"]
+    Q, K, V, Om, s, d = w["Q"].copy(), w["K"][:, :, :Lk], w["V"][:, :, :Lk], w["Omega"], w["qk_scale"], w["d"]
     Q[:, :, [7, 150]] *= 120.0
     Q = synth.round_to_bf16(Q)
     vec = util.theta_vec_from_oracle(orc.fit_posrf(d))
     thd, Omd = torch.from_numpy(vec[None]).cuda(), torch.from_numpy(Om).cuda()
-    ws = torch.empty(fs.attention_workspace_bytes(1, 2, 300, 300, d, d, Om.shape[1], False, 1, Om.shape[0]),
+    ws = torch.empty(fs.attention_workspace_bytes(1, 2, 300, Lk, d, d, Om.shape[1], False, 1, Om.shape[0]),
                      dtype=torch.uint8, device="cuda")
-    fs.attention(thd, util.to_device(Q, "bf16"), util.to_device(K, "bf16"), util.to_device(V, "bf16"), s, Omd,
-                 causal=False, workspace=ws)
+    Y = fs.attention(thd, util.to_device(Q, "bf16"), util.to_device(K, "bf16"), util.to_device(V, "bf16"), s, Omd,
+                     causal=False, workspace=ws, out_dtype=torch.float32)
     assert fs.attention_flushed_rows(ws) == 4
-    _check_attention(fs, w["Q"], K[:, :, :200], V[:, :, :200], Om, s, False, "sderf", "bf16")
+    Yh = util.to_host(Y)
+    assert np.isfinite(Yh).all()
+    assert (Yh[:, :, [7, 150]] == 0).all()
+    th = util.oracle_theta_from_vec(vec, d)
+    keep = np.setdiff1d(np.arange(300), [7, 150])
+    for h in range(2):
+        ref = orc.attention(th, Om[h], Q[0, h], K[0, h], V[0, h], s, False)
+        fro, row = util.attention_errors(Yh[0, h][keep], ref[keep], V[0, h].astype(np.float64))
+        assert fro <= 2e-2 and row <= 8e-2, (h, fro, row)
 
 
 def test_bf16_wide_path_f32_output_and_strided_inputs(fs):
