@@ -199,17 +199,16 @@ struct SmemState {
   float kmax[4];                                            // largest row_shift + row term of a chunk, at chunk index % 3
 };
 
-__global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  SmemState& sm = *reinterpret_cast<SmemState*>(smem_raw);
-  const int slot = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+// The state of the key rows [row_beg, row_end) of one (b,h), left in the registers of the workgroup's four waves
+// (wave w: features 64w .. 64w+63 x 80 columns) on the shift dk.  Ends behind a barrier: the caller may reuse the LDS.
+__device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int bh, int row_beg, int row_end,
+                                           f32x4 (&T)[4][NVT], float& dk) {
+  const int b = bh / a.H, h = bh % a.H;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
   const bool isoC = ((int)th[2]) & 1;
   const float wmax = max256(a.wnorm + ((size_t)pg * 2 + 1) * M);
-  const int rows_per_slot = a.rows_per_seg / a.sub;
-  const int row_beg = slot * rows_per_slot, row_end = min(a.L, row_beg + rows_per_slot);
   const uint16_t* Kb = (const uint16_t*)a.K.ptr + b * a.K.sb + h * a.K.sh + (long long)row_beg * a.K.sl;
   const uint16_t* Vb = (const uint16_t*)a.V.ptr + b * a.V.sb + h * a.V.sh + (long long)row_beg * a.V.sl;
   const float* rkb = a.rk + (size_t)bh * a.L + row_beg;
@@ -219,12 +218,11 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
   load_wslice(wk, a.Wbf + ((size_t)pg * 2 + 1) * M * D);
   init_value_pad(sm.v[0], 2 * TC, NT);
   if (tid < 3) sm.kmax[tid] = -INFINITY;
-  f32x4 T[4][NVT];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
     for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float dk = -INFINITY;
+  dk = -INFINITY;
 
   // staging: thread -> rows tid/8 and tid/8 + 32 of a chunk, bytes 16 (tid%8); rows past the end read as zero
   // (a fresh descriptor per chunk: uniform base = the chunk's first row, 32-bit offsets inside the chunk)
@@ -353,6 +351,17 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
     __syncthreads();
     const int t = kcur; kcur = knext; knext = kfree; kfree = t;
   }
+}
+
+__global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int slot = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int rows_per_slot = a.rows_per_seg / a.sub;
+  const int row_beg = slot * rows_per_slot;
+  f32x4 T[4][NVT];
+  float dk;
+  state_rows(a, *reinterpret_cast<SmemState*>(smem_raw), bh, row_beg, min(a.L, row_beg + rows_per_slot), T, dk);
   float* out = a.Tpart + ((size_t)bh * a.nslot + slot) * M * DVP;
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -527,37 +536,26 @@ __global__ void k_fast_reduce_walk(float* Tpart, const float* cpart, float* csta
 // key-side kernels and at most 256 registers, so two workgroups share a CU (two waves per SIMD: one's exp2 and
 // convert work beside the other's MFMAs and memory waits).  grid (nblk, B*H), block 256.
 // ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int rows_per_blk) {
-  __shared__ SmemApply sm;
-  const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+// Rows [row_beg, row_end) of the queries of one (b,h) against the state image tb (T^T as A operand: row v = 16 vt + c,
+// k <-> features 64w + 32 mb + 16 (e/4) + 4g + e%4).  Returns the number of rows this wave finished with a zero
+// normaliser.
+__device__ __forceinline__ int apply_rows(const FastArgs& a, SmemApply& sm, int bh, const bf16x8 (&tb)[NVT][2], int row_beg,
+                                          int row_end) {
+  const int b = bh / a.H, h = bh % a.H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
   const float wmax = max256(a.wnorm + ((size_t)pg * 2) * M), amax = max256(a.bias + ((size_t)pg * 2) * M);
   const uint16_t* Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
   const long long ybase = b * a.Y.sb + h * a.Y.sh;
-
   WSlice wq;
   load_wslice(wq, a.Wbf + ((size_t)pg * 2) * M * D);
   QBias qb;
   load_qbias(qb, a.bias + ((size_t)pg * 2) * M, amax);
-  // T^T as A operand: row v = 16 vt + c, k <-> features 64w + 32 mb + 16 (e/4) + 4g + e%4
-  bf16x8 tb[NVT][2];
-  const float* Tg = a.Tpart + (size_t)bh * a.nslot * M * DVP;
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt)
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      // accumulator images of tiles (2 mb, vt) and (2 mb + 1, vt) of wave w (the forward state pass writes images)
-      const f32x4 lo = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb) * NVT + vt) * 256 + 4 * lane);
-      const f32x4 hi = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb + 1) * NVT + vt) * 256 + 4 * lane);
-      tb[vt][mb] = pack8(lo, hi);
-    }
-  const int row_beg = blk * rows_per_blk, row_end = min(Lq, row_beg + rows_per_blk);
   RowRegs qr;
   load_rows_g(qr, Qb, a.Q.sl, row_beg, row_end);
   store_query_rows(qr, sm, 0, wmax);
   __syncthreads();
-  int buf = 0, nzero = 0;          // nzero: rows this wave finished with a zero normaliser
+  int buf = 0, nzero = 0;
   for (int row0 = row_beg; row0 < row_end; row0 += TC, buf ^= 1) {
     const bool more = row0 + TC < row_end;
     if (more) load_rows_g(qr, Qb, a.Q.sl, row0 + TC, row_end);
@@ -598,6 +596,54 @@ __global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int ro
     if (more) store_query_rows(qr, sm, buf ^ 1, wmax);
     __syncthreads();
   }
+  return nzero;
+}
+
+__global__ void __launch_bounds__(NT, 2) k_fast_apply(FastArgs a, int Lq, int rows_per_blk) {
+  __shared__ SmemApply sm;
+  const int blk = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  bf16x8 tb[NVT][2];
+  const float* Tg = a.Tpart + (size_t)bh * a.nslot * M * DVP;
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      // accumulator images of tiles (2 mb, vt) and (2 mb + 1, vt) of wave w (the forward state pass writes images)
+      const f32x4 lo = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb) * NVT + vt) * 256 + 4 * lane);
+      const f32x4 hi = *(const f32x4*)(Tg + (size_t)((w * 4 + 2 * mb + 1) * NVT + vt) * 256 + 4 * lane);
+      tb[vt][mb] = pack8(lo, hi);
+    }
+  const int row_beg = blk * rows_per_blk;
+  const int nzero = apply_rows(a, sm, bh, tb, row_beg, min(Lq, row_beg + rows_per_blk));
+  report_zero_rows(a.flushed, nzero, lane);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Non-causal call, one workgroup per (b,h): the state of all keys, then all query rows against it, the state never
+// leaving the registers (with many short sequences the states' way through memory, 80 kB each written and read
+// again, outweighs the rows themselves: a sequence of 128 tokens is 64 kB of Q, K, V, Y).  The shift of the state
+// cancels in the normalised rows.  grid (B*H), block 256, two workgroups per CU.
+// ---------------------------------------------------------------------------------------------------
+union SmemWhole {
+  SmemState s;
+  SmemApply q;
+};
+
+__global__ void __launch_bounds__(NT, 2) k_fast_whole(FastArgs a, int Lq) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int bh = blockIdx.x, lane = threadIdx.x & 63;
+  bf16x8 tb[NVT][2];
+  {
+    f32x4 T[4][NVT];
+    float dk;
+    state_rows(a, *reinterpret_cast<SmemState*>(smem_raw), bh, 0, a.L, T, dk);
+#pragma unroll
+    for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) tb[vt][mb] = pack8(T[2 * mb][vt], T[2 * mb + 1][vt]);
+  }
+  const int nzero = apply_rows(a, *reinterpret_cast<SmemApply*>(smem_raw), bh, tb, 0, Lq);
   report_zero_rows(a.flushed, nzero, lane);
 }
 
@@ -694,9 +740,8 @@ int launch_stats_bf16(const TensorDev& X, const TensorDev& Y, int BH, int H, int
   return 0;
 }
 
-// Projection constants, key-side segment states and their reduction (sum, or exclusive prefix when causal).
-// `every_slot`: states of all slots (the last segment's too) and, when causal, the exclusive prefix of every slot.
-static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st, bool every_slot = false, bool images = false) {
+// Kernel arguments of a call, its projection constants and, for parameter sets with a dense C2, the key row terms.
+static int launch_fast_constants(const FastLaunch& f, FastArgs& a, hipStream_t st, bool images) {
   a.Q = f.Q; a.K = f.K; a.V = f.V; a.Y = f.Y;
   a.Wbf = f.Wbf; a.bias = f.bias; a.wnorm = f.wnorm; a.theta = f.theta; a.rk = f.rk;
   a.Tpart = f.Tpart; a.cpart = f.cpart; a.cstar = f.cstar;
@@ -705,7 +750,6 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   a.timg = images ? 1 : 0;
   a.scale = f.scale;
   a.flushed = f.flushed;
-  const int BH = f.B * f.H;
   if (f.pre_mode == 0) {
     hipLaunchKernelGGL(k_fast_pre, dim3((M / 4) * 2 * f.pgroups), dim3(256), 0, st, f.theta, f.groups, f.Omega,
                        f.omega_groups, f.pgroups, f.B, f.H, f.scale, f.Wbf, f.bias, f.wnorm, (int*)nullptr);
@@ -714,6 +758,14 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
   // the key row terms of parameter sets with a dense C2 (the host knows that there are none only in mode 2)
   if (f.pre_mode != 2)
     if (int rc = launch_key_row_terms(f.theta, f.groups, f.K, f.B, f.H, f.Lk, D, f.scale, f.rk, st)) return rc;
+  return 0;
+}
+
+// Constants, key-side segment states and their reduction (sum, or exclusive prefix when causal).
+// `every_slot`: states of all slots (the last segment's too) and, when causal, the exclusive prefix of every slot.
+static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t st, bool every_slot = false, bool images = false) {
+  if (int rc = launch_fast_constants(f, a, st, images)) return rc;
+  const int BH = f.B * f.H;
   // the last segment's states are never needed by the causal pass
   const int nstate = (f.causal && !every_slot ? f.nseg - 1 : f.nseg) * f.sub;
   if (nstate > 0) {
@@ -721,6 +773,12 @@ static int launch_fast_state_pass(const FastLaunch& f, FastArgs& a, hipStream_t 
     FS_LAUNCH_CHECK();
   }
   const int prefix = f.causal ? (every_slot ? 1 : 2) : 0, nblk = (M * DVP / 4 + 255) / 256;
+  if (prefix == 2 && nstate == 0) {
+    // one segment per sequence: the causal kernel starts it from nothing and reads no prefix; only the counter of
+    // the call has to start at zero
+    if (f.flushed != nullptr) return launch_fill_u32((uint32_t*)f.flushed, 0u, 1, st);
+    return 0;
+  }
   int Z = 1, R = a.nslot;
   if (f.rscr != nullptr && prefix != 1) fast_reduce_ranges(BH, a.nslot, &Z, &R);
   const int Zvalid = (nstate + R - 1) / R;
@@ -766,10 +824,29 @@ void launch_fast_reduce_sum(float* part, const float* cpart, float* cstar, int n
                      (unsigned*)nullptr);
 }
 
+// Non-causal calls that run one workgroup per sequence (k_fast_whole): enough sequences to fill most of the chip's
+// 512 workgroup places, or sequences so short that their chunks in a row cost less than the two further launches
+// and the states' way through memory (measured: the three-kernel form wins from about B*H / 8 chunks of keys and
+// queries together; with 384 sequences or more it never does).
+static bool fast_whole_sequences(int BH, int Lq, int Lk) {
+  const int chunks = (Lq + TC - 1) / TC + (Lk + TC - 1) / TC;
+  return BH >= 384 || chunks <= std::min(32, std::max(4, BH / 8));
+}
+
 int launch_fast_attention(const FastLaunch& f, hipStream_t st, hipEvent_t ev_begin, hipEvent_t ev_end) {
   FastArgs a;
-  if (int rc = launch_fast_state_pass(f, a, st, false, true)) return rc;
   const int BH = f.B * f.H;
+  if (!f.causal && fast_whole_sequences(BH, f.Lq, f.Lk)) {
+    static_assert(sizeof(SmemWhole) <= 65536, "k_fast_whole: two workgroups per CU");
+    if (int rc = launch_fast_constants(f, a, st, false)) return rc;
+    if (f.flushed != nullptr)
+      if (int rc = launch_fill_u32((uint32_t*)f.flushed, 0u, 1, st)) return rc;
+    if (ev_begin || ev_end) hipExtLaunchKernelGGL(k_fast_whole, dim3(BH), dim3(NT), sizeof(SmemWhole), st, ev_begin, ev_end, 0, a, f.Lq);
+    else hipLaunchKernelGGL(k_fast_whole, dim3(BH), dim3(NT), sizeof(SmemWhole), st, a, f.Lq);
+    FS_LAUNCH_CHECK();
+    return 0;
+  }
+  if (int rc = launch_fast_state_pass(f, a, st, false, true)) return rc;
   // the optional events are attached to the main kernel's dispatch: they carry its own begin and end times
   if (f.causal) {
     if (int rc = launch_fast_causal_kernel(a, BH, st, ev_begin, ev_end)) return rc;

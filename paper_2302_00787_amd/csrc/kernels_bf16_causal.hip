@@ -214,7 +214,8 @@ __device__ __forceinline__ void producer(const FastArgs& a, SmemPC& sm, const Se
 #pragma unroll
       for (int r = 0; r < 4; ++r) qb.b[mt][r] = 2.f * (a.bias[((size_t)cx.pg * 2) * M + 64 * j + 16 * mt + 4 * g + r] - amax1);
   }
-  float dk = a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)blockIdx.x * a.sub];   // shift of the prefix state (-inf for the first segment)
+  // shift of the prefix state (the first segment has none: a zero state on the shift -inf, nothing read)
+  float dk = blockIdx.x > 0 ? a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)blockIdx.x * a.sub] : -INFINITY;
 
   // first chunk to LDS, second chunk into the staging registers
   Stage stg;
@@ -338,13 +339,18 @@ __device__ __forceinline__ void consumer(const FastArgs& a, SmemPC& sm, const Se
   f32x4 T[4][NVT];
   {
     // the prefix state as the state pass left it: accumulator images, 16 bytes per lane and tile
+    // (the first segment starts from nothing: with many short sequences every segment is a first one, and a state is
+    // more bytes than 128 rows of Q, K, V and Y)
     const float* Tg = a.Tpart + ((size_t)cx.bh * a.nslot + (size_t)seg * a.sub) * M * DVP;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-      for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = *(const f32x4*)(Tg + (size_t)((j * 4 + mt) * NVT + vt) * 256 + 4 * lane);
+      for (int vt = 0; vt < NVT; ++vt) {
+        T[mt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (seg > 0) T[mt][vt] = *(const f32x4*)(Tg + (size_t)((j * 4 + mt) * NVT + vt) * 256 + 4 * lane);
+      }
   }
-  float dk = a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)seg * a.sub];   // shift of the prefix state
+  float dk = seg > 0 ? a.cstar[gridDim.y + (size_t)cx.bh * a.nslot + (size_t)seg * a.sub] : -INFINITY;   // shift of the prefix state
   FS_STEP_BARRIER();               // barrier 0
   bf16x8 vop[2][NVT];              // value operands of the chunk; the first pair's are requested one step early
 #pragma unroll

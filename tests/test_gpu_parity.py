@@ -495,6 +495,20 @@ def test_bf16_path_few_sequences_many_slots_late_outlier(fs):
     assert fro <= 2e-2 and row <= 8e-2, (fro, row)
 
 
+@pytest.mark.parametrize("variant,B,H,Lq,Lk", [("sderf", 64, 8, 300, 300), ("gerf", 64, 8, 70, 333), ("aderf", 1, 2, 128, 128),
+                                               ("saderf", 2, 2, 200, 64), ("posrf", 1, 1, 1, 1), ("sderf", 1, 3, 64, 256),
+                                               ("aderf", 1, 2, 256, 190)])
+def test_bf16_path_non_causal_whole_sequences_per_workgroup(fs, variant, B, H, Lq, Lk):
+    """Non-causal calls with many sequences (B*H >= 512) or short ones (at most four chunks) run one workgroup per
+    sequence, the state staying in registers between the key rows and the query rows: equal and different numbers
+    of queries and keys, ragged tails, a single token, isotropic and dense key-side quadratic forms."""
+    w = synth.make("c3", B=B, H=H, L=max(Lq, Lk), seed=431 + Lq + Lk)
+    worst = _check_attention(fs, w["Q"][:, :, :Lq], w["K"][:, :, :Lk], w["V"][:, :, :Lk], w["Omega"], w["qk_scale"],
+                             False, variant, "bf16")
+    print(f"bf16 path, whole sequences, B={B} H={H} Lq={Lq} Lk={Lk} {variant}: worst frobenius {worst[0]:.2e}, "
+          f"worst row {worst[1]:.2e}")
+
+
 # ----------------------------------------------------------------------------- bf16 MFMA path (d = 128, M = 512)
 @pytest.mark.parametrize("variant,L", [("posrf", 1), ("sderf", 64), ("sderf", 100), ("sderf", 1000), ("aderf", 200),
                                        ("aderf", 1000)])
@@ -683,13 +697,13 @@ def test_bf16_causal_late_key_with_a_huge_bound_leaves_earlier_rows_intact(fs, n
 
 
 @pytest.mark.parametrize("name,L,causal,dtype", [("c4", 1000, True, "bf16"), ("c3", 1000, False, "bf16"),
-                                                 ("c5", 1000, True, "bf16"), ("c1", 300, True, "f32"),
-                                                 ("c1", 300, False, "f32")])
+                                                 ("c3", 200, False, "bf16"), ("c5", 1000, True, "bf16"),
+                                                 ("c1", 300, True, "f32"), ("c1", 300, False, "f32")])
 def test_rows_with_a_zero_normaliser_are_written_as_zeros_and_counted(fs, name, L, causal, dtype):
     """Denominator guard (Section 2.2).  On the bf16 kernels the shift of a query row is a Cauchy-Schwarz bound over
     all features: a query 40 times longer than the data's has every actual feature more than 2^126 below it, all of
-    them flush, and the row's normaliser is exactly 0.  Such rows (five per (b, h), one of them in the ragged last
-    chunk) must come out as zeros, the counter must report exactly their number, every other row must still agree
+    them flush, and the row's normaliser is exactly 0.  Such rows (four or five per (b, h), one of them in the ragged
+    last chunk; the sequence of 200 rows runs in the kernel that takes a whole sequence per workgroup) must come out as zeros, the counter must report exactly their number, every other row must still agree
     with the oracle, and a call without such rows on the same workspace must put the counter back to 0.  The
     general-shape kernels shift a query row by its exact maximum, so no query can flush there: the count stays 0
     and all rows agree with the oracle."""
@@ -699,7 +713,7 @@ def test_rows_with_a_zero_normaliser_are_written_as_zeros_and_counted(fs, name, 
     if dtype == "bf16":
         Q0, K, V = synth.round_to_bf16(Q0), synth.round_to_bf16(K), synth.round_to_bf16(V)
     Q = Q0.copy()
-    rows = [3, 64, 150, 257, L - 2]
+    rows = [r for r in (3, 64, 150, 257) if r < L - 2] + [L - 2]
     Q[:, :, rows] *= 120.0 if name == "c5" else 40.0
     if dtype == "bf16":
         Q = synth.round_to_bf16(Q)
@@ -780,14 +794,15 @@ def test_bf16_workloads_full_size_sampled_rows(fs, name, variant):
     ("c1", {}, False, "sderf"), ("c4", dict(B=1, H=2, L=1216), False, "sderf"), ("c5", dict(B=1, H=2, L=832), False, "sderf"),
     ("c4", dict(B=1, H=2, L=1216), True, "sderf"), ("c2", {}, False, "sderf"),
     ("c4", dict(B=1, H=2, L=1216), True, "aderf"), ("c5", dict(B=1, H=2, L=832), False, "aderf"),
-    ("c4", dict(B=1, H=1, L=4100), False, "sderf"), ("c3", dict(B=1, H=1, L=4100), True, "sderf")])
+    ("c4", dict(B=1, H=1, L=4100), False, "sderf"), ("c3", dict(B=1, H=1, L=4100), True, "sderf"),
+    ("c3", dict(B=1, H=2, L=200), False, "aderf")])
 def test_attention_call_replays_from_a_hip_graph(fs, name, over, prepared, variant):
     """The entry point only enqueues kernels on the caller's stream (no synchronisation, no allocation, no memset
     nodes), so a caller may capture it: the graph is replayed three times, with eager work and synchronisations in
     between, and every replay must reproduce the eager result bit for bit (general path, both bf16 paths, the call
     on prepared projection constants, the kernel operator on its fp32 MFMA kernels, parameter sets with a dense
-    quadratic form, which add the row-term kernel, and a single sequence of 65 slots, whose slot reduction is the
-    three-kernel form)."""
+    quadratic form, which add the row-term kernel, a single sequence of 65 slots, whose slot reduction is the
+    three-kernel form, and short sequences that take a workgroup each)."""
     import torch
     if name == "c2":
         _operator_graph_replay(fs)
