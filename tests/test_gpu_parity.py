@@ -509,6 +509,32 @@ def test_bf16_path_non_causal_whole_sequences_per_workgroup(fs, variant, B, H, L
           f"worst row {worst[1]:.2e}")
 
 
+@pytest.mark.parametrize("variant,L", [("sderf", 128), ("aderf", 100), ("gerf", 333)])
+def test_bf16_path_causal_many_short_sequences(fs, variant, L):
+    """Causal calls with 256 sequences or more are one segment per sequence: no state pass and no reduction run, the
+    causal kernel starts every sequence from nothing (and must not read a prefix state that nobody wrote: the
+    workspace is filled with NaN bit patterns first)."""
+    import torch
+    w = synth.make("c4", B=32, H=8, L=L, seed=443 + L)
+    Q, K, V, Om, s, d = w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], w["d"]
+    theta = _fit_theta_block(variant, Q, K, s, None)
+    ws = torch.full((fs.attention_workspace_bytes(32, 8, L, L, d, d, Om.shape[1], True, 8, Om.shape[0]),), 0xFF,
+                    dtype=torch.uint8, device="cuda")
+    Y = fs.attention(torch.from_numpy(theta).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, chunk=64, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 0
+    Yh = util.to_host(Y)
+    assert np.isfinite(Yh).all()
+    worst = (0.0, 0.0)
+    for b in range(0, 32, 5):
+        for h in range(8):
+            ref = orc.attention(util.oracle_theta_from_vec(theta[h], d), Om[h], Q[b, h], K[b, h], V[b, h], s, True)
+            fro, row = util.attention_errors(Yh[b, h], ref, V[b, h].astype(np.float64))
+            worst = (max(worst[0], fro), max(worst[1], row))
+            assert fro <= 2e-2 and row <= 8e-2, (b, h, fro, row)
+    print(f"bf16 path, causal, 256 sequences of {L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
 # ----------------------------------------------------------------------------- bf16 MFMA path (d = 128, M = 512)
 @pytest.mark.parametrize("variant,L", [("posrf", 1), ("sderf", 64), ("sderf", 100), ("sderf", 1000), ("aderf", 200),
                                        ("aderf", 1000)])
@@ -880,7 +906,8 @@ def _replay_and_compare(call, Y, name):
 
 
 @pytest.mark.parametrize("name,over", [("c1", {}), ("c3", dict(B=2, H=2, L=704)), ("c4", dict(B=1, H=2, L=1216)),
-                                       ("c5", dict(B=1, H=2, L=832))])
+                                       ("c5", dict(B=1, H=2, L=832)), ("c3", dict(B=2, H=2, L=128)),
+                                       ("c4", dict(B=32, H=8, L=128))])
 def test_attention_timed_gives_the_same_result_and_a_kernel_time(fs, name, over):
     """favorsharp_attention_timed: the two events bracket the main kernel (attached to its dispatch on the bf16 paths,
     recorded around it on the general path); the result is that of favorsharp_attention bit for bit, and the time
@@ -918,7 +945,8 @@ def test_attention_timed_gives_the_same_result_and_a_kernel_time(fs, name, over)
 
 @pytest.mark.parametrize("name,over,variant", [("c4", dict(B=2, H=2, L=1216), "sderf"), ("c4", dict(B=1, H=2, L=333), "aderf"),
                                                ("c3", dict(B=2, H=2, L=712), "sderf"), ("c5", dict(B=1, H=2, L=832), "sderf"),
-                                               ("c5", dict(B=1, H=2, L=200), "aderf")])
+                                               ("c5", dict(B=1, H=2, L=200), "aderf"), ("c3", dict(B=2, H=2, L=200), "aderf"),
+                                               ("c4", dict(B=32, H=8, L=100), "sderf")])
 def test_prepared_constants_give_the_same_bits(fs, name, over, variant):
     """favorsharp_attention_prepare + favorsharp_attention_prepared against favorsharp_attention: the projection
     constants are the same numbers, so the outputs agree bit for bit; a second prepared call on other data of the
