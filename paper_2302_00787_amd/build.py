@@ -19,7 +19,7 @@ SOURCES = {
     "kernels_generic.hip": [],
     "kernels_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
     "kernels_bf16_causal.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
-    "kernels_bf16_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "kernels_bf16_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-mllvm", "-amdgpu-atomic-optimizer-strategy=None"],
     "kernels_bf16_bwd_pc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_bf16_wide.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "kernels_op.hip": [],

@@ -443,6 +443,8 @@ int launch_key_row_terms(const float* theta, int groups, const TensorDev& K, int
 int launch_fast_backward(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
                          const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,
                          float* rcstar, int rslots, int rows_per_rslot, hipStream_t st);
+int launch_fast_backward_whole(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
+                               const TensorDev& dK, const TensorDev& dV, uint16_t* gh, hipStream_t st);
 size_t fast_bwd_lds_bytes();
 int launch_fast_backward_causal(const FastLaunch& f, const fast::FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
                                 const TensorDev& dK, const TensorDev& dV, uint16_t* gh, float* Rpart, float* rcpart,

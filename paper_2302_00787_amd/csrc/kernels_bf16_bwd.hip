@@ -20,6 +20,7 @@
 //   k_bwd_grad<0/1>  queries / keys: dF = (state) (left rows)^T, dE = F * dF, gradient rows
 // All of them keep a wave's 64 features of every operand in registers, as the forward kernels do.
 #include "fast_bwd.h"
+#include "fast_state.h"
 
 namespace fs {
 
@@ -30,40 +31,28 @@ namespace bwd {
 // ---------------------------------------------------------------------------------------------------------------
 // MODE 1 (queries): rows of G1.  MODE 2 (keys): dV = S R.  Structure of k_fast_apply.  grid (nblk, B*H).
 // ---------------------------------------------------------------------------------------------------------------
+// Rows [row_beg, row_end) of one (b,h) against the state image tb (state^T as A operand: row v = 16 vt + c, k <->
+// features 64w + 32 mb + 16 (e/4) + 4g + e%4); cs: the key shift of the sequence (MODE 2).  Returns the number of
+// rows this wave finished with a zero normaliser (MODE 1).
 template <int MODE>
-__global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_blk) {
-  __shared__ SmemApply sm;
+__device__ __forceinline__ int apply_rows_b(const BwdArgs& ba, SmemApply& sm, int bh, const bf16x8 (&tb)[NVT][2], float cs,
+                                            int row_beg, int row_end) {
   const FastArgs& a = ba.f;
-  const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int b = bh / a.H, h = bh % a.H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
   constexpr int side = MODE == 1 ? 0 : 1;
-  const int L = MODE == 1 ? ba.Lq : ba.Lk;
   const TensorDev& X = MODE == 1 ? a.Q : a.K;
   const float wmax = max256(a.wnorm + ((size_t)pg * 2 + side) * M), amax = max256(a.bias + ((size_t)pg * 2) * M);
   const uint16_t* Xb = (const uint16_t*)X.ptr + b * X.sb + h * X.sh;
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
   const bool isoC = ((int)th[2]) & 1;
-  const float cs = a.cstar[bh];
 
   WSlice wx;
   load_wslice(wx, a.Wbf + ((size_t)pg * 2 + side) * M * D);
   QBias qb;
   load_qbias(qb, a.bias + ((size_t)pg * 2) * M, amax);
-  // state^T as A operand: row v = 16 vt + c, k <-> features 64w + 32 mb + 16 (e/4) + 4g + e%4
-  bf16x8 tb[NVT][2];
-  const float* Sg = MODE == 1 ? a.Tpart + (size_t)bh * a.nslot * M * DVP : ba.Rpart + (size_t)bh * ba.rslots * M * DVP;
-#pragma unroll
-  for (int vt = 0; vt < NVT; ++vt)
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      f32x8 t;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = Sg[(size_t)(64 * w + 32 * mb + 16 * (e >> 2) + 4 * g + (e & 3)) * DVP + 16 * vt + c];
-      tb[vt][mb] = __builtin_convertvector(t, bf16x8);
-    }
   int nzero = 0;                   // (MODE 1) rows this wave finished with a zero normaliser
-  const int row_beg = blk * rows_per_blk, row_end = min(L, row_beg + rows_per_blk);
 
   // staged rows -> LDS with what is added to their exponents: - row_shift (queries), row term - key shift (keys)
   auto stage = [&](const RowRegs& r, int buf, int row0) {
@@ -160,6 +149,29 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
     if (more) stage(xr, buf ^ 1, row0 + TC);
     __syncthreads();
   }
+  return nzero;
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_blk) {
+  __shared__ SmemApply sm;
+  const FastArgs& a = ba.f;
+  const int blk = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int L = MODE == 1 ? ba.Lq : ba.Lk;
+  bf16x8 tb[NVT][2];
+  const float* Sg = MODE == 1 ? a.Tpart + (size_t)bh * a.nslot * M * DVP : ba.Rpart + (size_t)bh * ba.rslots * M * DVP;
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      f32x8 t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = Sg[(size_t)(64 * w + 32 * mb + 16 * (e >> 2) + 4 * g + (e & 3)) * DVP + 16 * vt + c];
+      tb[vt][mb] = __builtin_convertvector(t, bf16x8);
+    }
+  const int row_beg = blk * rows_per_blk;
+  const int nzero = apply_rows_b<MODE>(ba, sm, bh, tb, a.cstar[bh], row_beg, min(L, row_beg + rows_per_blk));
   if (MODE == 1) report_zero_rows(a.flushed, nzero, lane);
 }
 
@@ -167,12 +179,10 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_apply(BwdArgs ba, int rows_per_bl
 // Segment sums of P^T G1 (structure of k_fast_state: query features with their per-row shifts, "values" = rows of
 // G1, all 80 columns).  grid (rslots, B*H); LDS: Smem (rows, transposed values, shifts).
 // ---------------------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  Smem& sm = *reinterpret_cast<Smem*>(smem_raw);
+__device__ __forceinline__ void rstate_rows(const BwdArgs& ba, Smem& sm, int bh, int row_beg, int row_end, f32x4 (&R)[4][NVT]) {
   const FastArgs& a = ba.f;
-  const int slot = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int b = bh / a.H, h = bh % a.H;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
   const float wmax = max256(a.wnorm + ((size_t)pg * 2) * M), amax = max256(a.bias + ((size_t)pg * 2) * M);
   const uint16_t* Qb = (const uint16_t*)a.Q.ptr + b * a.Q.sb + h * a.Q.sh;
@@ -183,7 +193,6 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
   float bcol[4];         // 2 (bias - largest bias) of feature 64w + 16 mt + c
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt) bcol[mt] = 2.f * (a.bias[((size_t)pg * 2) * M + 64 * w + 16 * mt + c] - amax);
-  f32x4 R[4][NVT];
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -200,7 +209,6 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
     store_g80_s(gr, sm.vt[buf]);
   };
 
-  const int row_beg = slot * ba.rows_per_rslot, row_end = min(ba.Lq, row_beg + ba.rows_per_rslot);
   RowRegs qr;
   RowRegs3 gr;
   load_rows_g(qr, Qb, a.Q.sl, row_beg, row_end);
@@ -229,6 +237,15 @@ __global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
     if (more) stage(qr, gr, buf ^ 1);
     __syncthreads();
   }
+}
+
+__global__ void __launch_bounds__(NT) k_bwd_rstate(BwdArgs ba) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int slot = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int row_beg = slot * ba.rows_per_rslot;
+  f32x4 R[4][NVT];
+  rstate_rows(ba, *reinterpret_cast<Smem*>(smem_raw), bh, row_beg, min(ba.Lq, row_beg + ba.rows_per_rslot), R);
   float* out = ba.Rpart + ((size_t)bh * ba.rslots + slot) * M * DVP;
 #pragma unroll
   for (int mt = 0; mt < 4; ++mt)
@@ -255,15 +272,15 @@ struct SmemGrad {
   __attribute__((aligned(16))) uint16_t csym[4][KS][64][8];
 };
 
+// Rows [row_beg, row_end) of one (b,h); sa: the state as A operand of dF (row f = 64w + 16mt + c, k = 32kk + 8g + e
+// <-> column v, zero from 80 on); cs: the key shift of the sequence (KEY).
 template <int KEY>
-__global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  SmemGrad& sm = *reinterpret_cast<SmemGrad*>(smem_raw);
+__device__ __forceinline__ void grad_rows(const BwdArgs& ba, SmemGrad& sm, int bh, const bf16x8 (&sa)[4][3], float cs,
+                                          int row_beg, int row_end) {
   const FastArgs& a = ba.f;
-  const int blk = blockIdx.x, bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int b = bh / a.H, h = bh % a.H;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
   const int pg = group_of(a.pgroups, b, h, a.H);
-  const int L = KEY ? ba.Lk : ba.Lq;
   const TensorDev& X = KEY ? a.K : a.Q;
   const TensorDev& G = KEY ? ba.dK : ba.dQ;
   const float wmax = max256(a.wnorm + ((size_t)pg * 2 + KEY) * M), amax = max256(a.bias + ((size_t)pg * 2) * M);
@@ -273,30 +290,12 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
   const float* th = a.theta + (size_t)group_of(a.groups, b, h, a.H) * (FS_THETA_HEADER_ + (size_t)D + 4 * (size_t)D * D);
   const bool isoC = ((int)th[2]) & 1;
   const float* C2 = th + FS_THETA_HEADER_ + D + 3 * (size_t)D * D;
-  const float cs = a.cstar[bh];
   const uint16_t* Wg = a.Wbf + ((size_t)pg * 2 + KEY) * M * D;
 
   WSlice wx;
   load_wslice(wx, Wg);
   QBias qb;
   load_qbias(qb, a.bias + ((size_t)pg * 2) * M, amax);
-  // state as A operand of dF: row f = 64w + 16mt + c, k = 32kk + 8g + e <-> column v (zero from 80 on)
-  bf16x8 sa[4][3];
-  {
-    const float* Sg = KEY ? ba.Rpart + (size_t)bh * ba.rslots * M * DVP : a.Tpart + (size_t)bh * a.nslot * M * DVP;
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-      for (int kk = 0; kk < 3; ++kk) {
-        f32x8 t;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const int v = 32 * kk + 8 * g + e;
-          t[e] = v < DVP ? Sg[(size_t)(64 * w + 16 * mt + c) * DVP + v] : 0.f;
-        }
-        sa[mt][kk] = __builtin_convertvector(t, bf16x8);
-      }
-  }
   // W~^T as A operand of the gradient tile: row = coordinate 16dt + c, k <-> feature 64w + 32blk + 16(e/4) + 4g + e%4;
   // tile dt = 4 has ones in its row 0 (coordinate "64" = the row sum of dE) and zeros elsewhere
   bf16x8 wt[NVT][2];
@@ -331,8 +330,6 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
     const int n = KL - (KEY ? D : DVP);
     sm.lam[idx / n][(KEY ? D : DVP) + idx % n] = 0;
   }
-
-  const int row_beg = blk * rows_per_blk, row_end = min(L, row_beg + rows_per_blk);
 
   auto load_left = [&](RowRegs3& r, int row0) {
     if (KEY) {
@@ -480,6 +477,119 @@ __global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk
   }
 }
 
+template <int KEY>
+__global__ void __launch_bounds__(NT, 2) k_bwd_grad(BwdArgs ba, int rows_per_blk) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const FastArgs& a = ba.f;
+  const int blk = blockIdx.x, bh = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, c = lane & 15;
+  const int L = KEY ? ba.Lk : ba.Lq;
+  bf16x8 sa[4][3];
+  {
+    const float* Sg = KEY ? ba.Rpart + (size_t)bh * ba.rslots * M * DVP : a.Tpart + (size_t)bh * a.nslot * M * DVP;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int kk = 0; kk < 3; ++kk) {
+        f32x8 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int v = 32 * kk + 8 * g + e;
+          t[e] = v < DVP ? Sg[(size_t)(64 * w + 16 * mt + c) * DVP + v] : 0.f;
+        }
+        sa[mt][kk] = __builtin_convertvector(t, bf16x8);
+      }
+  }
+  const int row_beg = blk * rows_per_blk;
+  grad_rows<KEY>(ba, *reinterpret_cast<SmemGrad*>(smem_raw), bh, sa, a.cstar[bh], row_beg, min(L, row_beg + rows_per_blk));
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The whole backward pass of one (b,h) in one workgroup (non-causal calls with many or short sequences): the states T
+// and R never leave the workgroup.  In the kernels above each of them goes to memory once per slot, through a
+// reduction, and back twice, 80 kB a time, while a sequence of 128 tokens is 150 kB of rows altogether.  Phases, each
+// the loop of one of the kernels above over all rows of the sequence:
+//   keys:    T = S^T [V 1]                (state_rows)
+//   queries: G1 rows -> gh                (apply_rows_b<1>, T as operand image)
+//   queries: dQ                           (grad_rows<0>; T's image turned into the row operand through LDS)
+//   queries: R = P^T G1                   (rstate_rows; gh read back: written by this workgroup, behind a barrier)
+//   keys:    dV = S R                     (apply_rows_b<2>)
+//   keys:    dK                           (grad_rows<1>)
+// T is dead before R is built, so no phase holds more than its kernel does.  grid (B*H), block 256, two per CU.
+// ---------------------------------------------------------------------------------------------------------------
+union SmemBwdWhole {
+  SmemState s;
+  SmemApply q;
+  Smem r;
+  SmemGrad g;
+  uint16_t tr[NW][64][LDL];        // a wave's state slice as rows of 96 columns (transposition of the operand image)
+};
+
+// Operand image of a state slice (apply kernels: tb[vt][mb] element e <-> feature 32 mb + 16 (e/4) + 4g + e%4, column
+// 16 vt + c) -> rows operand of the gradient kernels (sa[mt][kk] element e <-> feature 16 mt + c, column 32 kk + 8g + e;
+// columns 80 .. 95 zero), through the wave's own LDS rows.  Barriers on both sides: the region overlays the buffers
+// of the phases before and after.
+__device__ __forceinline__ void image_to_rows(const bf16x8 (&tb)[NVT][2], uint16_t (*tr)[LDL], bf16x8 (&sa)[4][3]) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+  __syncthreads();
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      const u32x4 bits = __builtin_bit_cast(u32x4, tb[vt][mb]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        tr[32 * mb + 16 * (e >> 2) + 4 * g + (e & 3)][16 * vt + c] = (uint16_t)(bits[e >> 1] >> (16 * (e & 1)));
+    }
+  *(u32x4*)(&tr[lane][DVP]) = u32x4{0u, 0u, 0u, 0u};
+  *(u32x4*)(&tr[lane][DVP + 8]) = u32x4{0u, 0u, 0u, 0u};
+  __syncthreads();
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+    for (int kk = 0; kk < 3; ++kk) sa[mt][kk] = *(const bf16x8*)(&tr[16 * mt + c][32 * kk + 8 * g]);
+  __syncthreads();
+}
+
+__device__ __forceinline__ void pack_state(const f32x4 (&T)[4][NVT], bf16x8 (&tb)[NVT][2]) {
+#pragma unroll
+  for (int vt = 0; vt < NVT; ++vt)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) tb[vt][mb] = pack8(T[2 * mb][vt], T[2 * mb + 1][vt]);
+}
+
+__global__ void __launch_bounds__(NT, 2) k_bwd_whole(BwdArgs ba) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  SmemBwdWhole& sm = *reinterpret_cast<SmemBwdWhole*>(smem_raw);
+  const FastArgs& a = ba.f;
+  const int bh = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  bf16x8 tb[NVT][2];
+  float cs;
+  {
+    f32x4 T[4][NVT];
+    state_rows(a, sm.s, bh, 0, ba.Lk, T, cs);
+    pack_state(T, tb);
+  }
+  const int nzero = apply_rows_b<1>(ba, sm.q, bh, tb, cs, 0, ba.Lq);
+  report_zero_rows(a.flushed, nzero, lane);
+  {
+    bf16x8 sa[4][3];
+    image_to_rows(tb, sm.tr[w], sa);
+    grad_rows<0>(ba, sm.g, bh, sa, cs, 0, ba.Lq);
+  }
+  {
+    f32x4 R[4][NVT];
+    rstate_rows(ba, sm.r, bh, 0, ba.Lq, R);
+    pack_state(R, tb);
+  }
+  apply_rows_b<2>(ba, sm.q, bh, tb, cs, 0, ba.Lk);
+  {
+    bf16x8 sa[4][3];
+    image_to_rows(tb, sm.tr[w], sa);
+    grad_rows<1>(ba, sm.g, bh, sa, cs, 0, ba.Lk);
+  }
+}
+
 #define FS_LAUNCH_CHECK_() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
 int launch_bwd_rstate(const BwdArgs& ba, int BH, hipStream_t st) {
   hipLaunchKernelGGL(k_bwd_rstate, dim3(ba.rslots, BH), dim3(NT), sizeof(Smem), st, ba);
@@ -493,7 +603,25 @@ using namespace bwd;
 
 #define FS_LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return 5; } while (0)
 
-size_t fast_bwd_lds_bytes() { return sizeof(SmemGrad); }
+size_t fast_bwd_lds_bytes() { return sizeof(SmemBwdWhole); }
+
+// One non-causal backward call with a workgroup per sequence (after the constants; no state pass before it).
+int launch_fast_backward_whole(const FastLaunch& f, const FastArgs& a, const TensorDev& dY, const TensorDev& dQ,
+                               const TensorDev& dK, const TensorDev& dV, uint16_t* gh, hipStream_t st) {
+  static_assert(sizeof(SmemBwdWhole) <= 80 * 1024, "k_bwd_whole: two workgroups per CU");
+  BwdArgs ba;
+  ba.f = a;
+  ba.dY = dY; ba.dQ = dQ; ba.dK = dK; ba.dV = dV;
+  ba.gh = gh; ba.Rpart = nullptr; ba.rcpart = nullptr;
+  ba.Lq = f.Lq; ba.Lk = f.Lk; ba.rslots = 0; ba.rows_per_rslot = 0;
+  if (hipFuncSetAttribute((const void*)k_bwd_whole, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemBwdWhole)) != hipSuccess) {
+    (void)hipGetLastError();
+    return 2;
+  }
+  hipLaunchKernelGGL(k_bwd_whole, dim3(f.B * f.H), dim3(NT), sizeof(SmemBwdWhole), st, ba);
+  FS_LAUNCH_CHECK();
+  return 0;
+}
 
 // One non-causal backward call after the forward state pass (f.Tpart slot 0 = total state, f.cstar = key shifts).
 int launch_fast_backward(const FastLaunch& f, const FastArgs& a, const TensorDev& dY, const TensorDev& dQ,

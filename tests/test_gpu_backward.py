@@ -121,6 +121,69 @@ def test_backward_bf16_path_other_families_and_lengths(fs, variant):
     _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, variant, "bf16", 2e-2, grad_dtype=torch.float32)
 
 
+@pytest.mark.parametrize("variant,B,H,Lq,Lk,f32", [("sderf", 1, 2, 128, 128, True), ("aderf", 1, 2, 100, 120, True),
+                                                   ("saderf", 2, 2, 64, 190, False), ("gerf", 48, 8, 300, 200, False),
+                                                   ("aderf", 64, 8, 70, 333, True), ("posrf", 1, 3, 1, 190, True)])
+def test_backward_bf16_path_whole_sequences_per_workgroup(fs, variant, B, H, Lq, Lk, f32):
+    """Non-causal calls with many sequences (B*H >= 384) or short ones (at most four chunks of queries and keys
+    together) run the whole backward pass of a sequence in one workgroup, both states staying on chip: equal and
+    different numbers of queries and keys, ragged tails, isotropic and dense key-side quadratic forms, fp32 output
+    gradients into fp32 gradients and bf16 into bf16 (every seventh batch entry against the oracle)."""
+    import torch
+    rng = np.random.default_rng(67 + Lq + Lk)
+    d, M = 64, 256
+    sc = np.linspace(0.6, 1.1, d)
+    Q = synth.round_to_bf16((rng.standard_normal((B, H, Lq, d)) * sc + 0.05).astype(np.float32))
+    K = synth.round_to_bf16((rng.standard_normal((B, H, Lk, d)) * sc[::-1] - 0.05).astype(np.float32))
+    V = synth.round_to_bf16(rng.standard_normal((B, H, Lk, d)).astype(np.float32))
+    dY = rng.standard_normal((B, H, Lq, d)).astype(np.float32)
+    if not f32:
+        dY = synth.round_to_bf16(dY)
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    scale = d ** -0.25
+    theta = _theta_block(variant, Q[::7], K[::7], scale)
+    gQ, gK, gV = fs.attention_backward(torch.from_numpy(theta).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                                       util.to_device(V, "bf16"), util.to_device(dY, "f32" if f32 else "bf16"), scale,
+                                       torch.from_numpy(Om).cuda(), causal=False,
+                                       grad_dtype=torch.float32 if f32 else torch.bfloat16)
+    torch.cuda.synchronize()
+    gQ, gK, gV = util.to_host(gQ), util.to_host(gK), util.to_host(gV)
+    assert np.isfinite(gQ).all() and np.isfinite(gK).all() and np.isfinite(gV).all()
+    worst = (0.0, 0.0)
+    for b in range(0, B, 7):
+        for h in range(H):
+            th = util.oracle_theta_from_vec(theta[h], d)
+            ref = orc.attention_backward(th, Om[h], Q[b, h], K[b, h], V[b, h], dY[b, h], scale, False)
+            floor = 1e-2 * float(np.linalg.norm(dY[b, h]))
+            e = _assert_grads((gQ[b, h], gK[b, h], gV[b, h]), ref, 2e-2, (b, h), floor)
+            worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    print(f"backward, whole sequences, B={B} H={H} Lq={Lq} Lk={Lk} {variant}: worst frobenius {worst[0]:.2e}, "
+          f"worst row {worst[1]:.2e}")
+
+
+def test_backward_whole_sequences_per_workgroup_is_bitwise_reproducible(fs):
+    """The one-workgroup backward pass reuses one LDS region for six loops and a transposition, ordered by workgroup
+    barriers only, and reads back rows of G1 that the same workgroup wrote to memory: a missing barrier would show up
+    as run-to-run differences (512 sequences of 200 rows, five repetitions, other work in between), and the forward
+    call of the same shape must be reproducible too."""
+    import torch
+    torch.manual_seed(5)
+    B, H, L, d, M = 64, 8, 200, 64, 256
+    Q, K, V, dY = (torch.randn(B, H, L, d, device="cuda").to(torch.bfloat16) for _ in range(4))
+    Om = torch.randn(H, M, d, device="cuda")
+    s = d ** -0.25
+    theta = fs.fit_params("aderf", Q, K, s, groups=H)
+    first = [g.clone() for g in fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=False)]
+    y0 = fs.attention(theta, Q, K, V, s, Om, causal=False).clone()
+    assert all(torch.isfinite(g.float()).all().item() for g in first)
+    for rep in range(5):
+        scratch = torch.randn(1 << 22, device="cuda").sum().item()
+        again = fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=False)
+        for a, b in zip(first, again):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (rep, scratch)
+        assert torch.equal(y0.view(torch.int16), fs.attention(theta, Q, K, V, s, Om, causal=False).view(torch.int16))
+
+
 def test_backward_value_gradients_sum_to_output_gradients_at_full_c3_size(fs):
     """At the full size of the non-causal workload the oracle cannot run; what holds at any size: the attention
     weights of a row sum to one, so sum_j dV_j = sum_i dY_i per (b, h); and sampled rows of dV against the oracle's
@@ -346,18 +409,17 @@ def test_backward_gradient_tensors_with_huge_row_strides(fs, causal):
     assert float(wide[0][..., d:d + 64].abs().max()) == 0.0          # nothing written beside the rows
 
 
-@pytest.mark.parametrize("causal", [False, True])
-def test_backward_counts_rows_with_a_zero_normaliser_and_drops_their_terms(fs, causal):
+@pytest.mark.parametrize("causal,L", [(False, 300), (True, 300), (False, 120)])
+def test_backward_counts_rows_with_a_zero_normaliser_and_drops_their_terms(fs, causal, L):
     """Denominator guard in the backward pass (bf16 gradient kernels): a query row whose features all flush (40
     times the data's length: its Cauchy-Schwarz shift is more than 2^126 above every actual feature) has the
     normaliser 0, so its G1 row is 0: it gets a zero dQ row and adds nothing to dK and dV, which is what the oracle
     computes when that row of dY is zero.  The counter in the workspace's first word must report exactly these
-    rows, and 0 again after a call without them."""
+    rows, and 0 again after a call without them (120 rows: the kernel that takes a whole sequence per workgroup)."""
     import torch
-    L = 300
     w = synth.make("c4", B=1, H=2, L=L, seed=29)
     Q0, K, V, s, d, Om = w["Q"], w["K"], w["V"], w["qk_scale"], w["d"], w["Omega"]
-    rows = [2, 64, 200, L - 1]
+    rows = [2, 64, min(200, L - 20), L - 1]
     Q = Q0.copy()
     Q[:, :, rows] *= 40.0
     Q = synth.round_to_bf16(Q)
