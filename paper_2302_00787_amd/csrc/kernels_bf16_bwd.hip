@@ -18,6 +18,7 @@
 //   k_bwd_rstate     queries: segment sums of P^T G1                                 -> Rpart (k_fast_reduce sums them)
 //   k_bwd_apply<2>   keys:    dV = S R
 //   k_bwd_grad<0/1>  queries / keys: dF = (state) (left rows)^T, dE = F * dF, gradient rows
+//   k_bwd_whole      many or short sequences: all of the above (and the forward state) for one (b,h) per workgroup
 // All of them keep a wave's 64 features of every operand in registers, as the forward kernels do.
 #include "fast_bwd.h"
 #include "fast_state.h"
