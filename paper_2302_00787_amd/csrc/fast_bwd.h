@@ -15,6 +15,7 @@ struct BwdArgs {
   float* Rpart;              // [BH][rslots][256][80]
   float* rcpart;             // [BH][rslots] zeros (shifts of the R segments: none)
   int Lq, Lk, rslots, rows_per_rslot;
+  const float* zero_state = nullptr;   // causal kernels, one slot per sequence: a state of zeros in place of prefix and suffix
 };
 
 // Three 16-byte pieces per thread for tiles of up to 768 pieces.

@@ -32,6 +32,9 @@ struct SmemState {
 
 // The state of the key rows [row_beg, row_end) of one (b,h), left in the registers of the workgroup's four waves
 // (wave w: features 64w .. 64w+63 x 80 columns) on the shift dk.  Ends behind a barrier: the caller may reuse the LDS.
+// BOUND_ONLY: nothing but dk, the largest bound of the rows (the shift such a state would have): no projections, no
+// values, T untouched.
+template <bool BOUND_ONLY = false>
 __device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int bh, int row_beg, int row_end,
                                            f32x4 (&T)[4][NVT], float& dk) {
   const int b = bh / a.H, h = bh % a.H;
@@ -46,13 +49,15 @@ __device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int
   const int nrows = row_end - row_beg;
 
   WSlice wk;
-  load_wslice(wk, a.Wbf + ((size_t)pg * 2 + 1) * M * D);
-  init_value_pad(sm.v[0], 2 * TC, NT);
+  if (!BOUND_ONLY) {
+    load_wslice(wk, a.Wbf + ((size_t)pg * 2 + 1) * M * D);
+    init_value_pad(sm.v[0], 2 * TC, NT);
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+      for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   if (tid < 3) sm.kmax[tid] = -INFINITY;
-#pragma unroll
-  for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-    for (int vt = 0; vt < NVT; ++vt) T[mt][vt] = f32x4{0.f, 0.f, 0.f, 0.f};
   dk = -INFINITY;
 
   // staging: thread -> rows tid/8 and tid/8 + 32 of a chunk, bytes 16 (tid%8); rows past the end read as zero
@@ -65,6 +70,7 @@ __device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int
     for (int i = 0; i < 2; ++i) kr[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, 2 * ((srow + 32 * i) * (int)a.K.sl + spc * 8), 0, 0);
   };
   auto load_v = [&](int r0) {
+    if (BOUND_ONLY) return;
     const __amdgpu_buffer_rsrc_t rv_ = pc::chunk_rsrc(Vb + (long long)r0 * a.V.sl, 2 * (int)a.V.sl, nrows - r0, 2 * D);
 #pragma unroll
     for (int i = 0; i < 2; ++i) vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, 2 * ((srow + 32 * i) * (int)a.V.sl + spc * 8), 0, 0);
@@ -74,6 +80,7 @@ __device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int
     for (int i = 0; i < 2; ++i) *(u32x4*)(&sm.k[kb][srow + 32 * i][spc * 8]) = kr[i];
   };
   auto store_v = [&](int vb) {
+    if (BOUND_ONLY) return;
 #pragma unroll
     for (int i = 0; i < 2; ++i) *(u32x4*)(&sm.v[vb][srow + 32 * i][spc * 8]) = vr[i];
   };
@@ -118,6 +125,21 @@ __device__ __forceinline__ void state_rows(const FastArgs& a, SmemState& sm, int
   int kcur = 0, knext = 1, kfree = 2;
   for (int r0 = 0, ci = 0; r0 < nrows; r0 += TC, ++ci) {
     const int cb = ci & 1;
+    if constexpr (BOUND_ONLY) {
+      // the constants of the next chunk and the running maximum only
+      const float dnew = sm.kmax[kcur];
+      const bf16x8 xn0 = tile_op(knext, w, 0), xn1 = tile_op(knext, w, 1);
+      const float rk_next = row_term_of(r0 + TC);
+      dk = fmaxf(dk, dnew);
+      const float n2 = tile_row_norms(xn0, xn1, lane);
+      if (tid == 0) sm.kmax[kfree] = -INFINITY;
+      constants(n2, rk_next, cb ^ 1, knext, r0 + TC);
+      store_k(kfree);
+      load_k(r0 + 3 * TC);
+      __syncthreads();
+      const int t = kcur; kcur = knext; knext = kfree; kfree = t;
+      continue;
+    }
     // ---- every LDS read of the chunk, up front
     const float dnew = sm.kmax[kcur];
     bf16x8 x[4][KS];

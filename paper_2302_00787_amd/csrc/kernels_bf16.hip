@@ -203,6 +203,21 @@ __global__ void __launch_bounds__(NT, 2) k_fast_state(FastArgs a) {
   if (threadIdx.x == 0) a.cpart[(size_t)bh * a.nslot + slot] = dk;
 }
 
+// The key shift of every sequence without the states (causal backward pass with one slot per sequence: its kernels
+// start from nothing and need the shift only): cstar[bh] = the largest bound of the sequence's keys, as the state
+// kernel would have left it.  Also puts the call's counter of flushed rows back to zero.  grid (B*H), block 256.
+__global__ void __launch_bounds__(NT, 2) k_fast_bound(FastArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  const int bh = blockIdx.x;
+  f32x4 T[4][NVT];
+  float dk;
+  state_rows<true>(a, *reinterpret_cast<SmemState*>(smem_raw), bh, 0, a.L, T, dk);
+  if (threadIdx.x == 0) {
+    a.cstar[bh] = dk;
+    if (bh == 0 && a.flushed != nullptr) *a.flushed = 0u;
+  }
+}
+
 // Brings the segment states of one (b,h) to the common shift c* = max_seg cpart and sums them (prefix = 0: total
 // in slot 0) or replaces them by their exclusive prefix sums (prefix = 1).  prefix = 2: exclusive prefix sums on
 // running shifts: the prefix of slot s is scaled by the largest shift of the slots before it (written behind the
@@ -701,6 +716,16 @@ int launch_fast_attention_backward(const FastLaunch& f, const TensorDev& dY, con
                                    int rslots, int rows_per_rslot, hipStream_t st) {
   FastArgs a;
   if (f.causal) {
+    if (f.nseg == 1) {
+      // one slot per sequence (256 sequences or more, or a single chunk): the walks start from nothing, so there are
+      // no states to compute, to scan or to read; only the sequence's key shift
+      FastLaunch f1 = f;
+      f1.sub = 1;
+      if (int rc = launch_fast_constants(f1, a, st, false)) return rc;
+      hipLaunchKernelGGL(k_fast_bound, dim3(f.B * f.H), dim3(NT), sizeof(SmemState), st, a);
+      FS_LAUNCH_CHECK();
+      return launch_fast_backward_causal(f1, a, dY, dQ, dK, dV, gh, Rpart, rcpart, st);
+    }
     if (int rc = launch_fast_state_pass(f, a, st, true)) return rc;
     return launch_fast_backward_causal(f, a, dY, dQ, dK, dV, gh, Rpart, rcpart, st);
   }

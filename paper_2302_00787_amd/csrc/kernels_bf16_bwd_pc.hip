@@ -378,7 +378,9 @@ __device__ __forceinline__ void consumer(const BwdArgs& ba, SmemCG& sm, const Ct
   // state, transposed: Zt[vt][mt] has rows = U columns 16 vt + 4g + r, lane <-> feature 64j + 16 mt + c
   f32x4 Zt[NVT][4];
   {
-    const float* Zg = (KEY ? ba.Rpart : a.Tpart) + ((size_t)cx.bh * a.nslot + slot) * M * DVP;
+    // (single slot per sequence: neither a prefix nor a suffix was computed; every workgroup reads one block of zeros)
+    const float* Zg = ba.zero_state != nullptr ? ba.zero_state
+                                               : (KEY ? ba.Rpart : a.Tpart) + ((size_t)cx.bh * a.nslot + slot) * M * DVP;
 #pragma unroll
     for (int vt = 0; vt < NVT; ++vt)
 #pragma unroll
@@ -686,7 +688,9 @@ __device__ __forceinline__ void walk_consumer(const BwdArgs& ba, SmemWalk& sm, c
   const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
   f32x4 T[4][NVT];
   {
-    const float* Tg = (MODE ? ba.Rpart : a.Tpart) + ((size_t)cx.bh * a.nslot + slot) * M * DVP;
+    // (single slot per sequence: neither a prefix nor a suffix was computed; every workgroup reads one block of zeros)
+    const float* Tg = ba.zero_state != nullptr ? ba.zero_state
+                                               : (MODE ? ba.Rpart : a.Tpart) + ((size_t)cx.bh * a.nslot + slot) * M * DVP;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -789,10 +793,18 @@ int launch_fast_backward_causal(const FastLaunch& f, const FastArgs& a, const Te
   ba.gh = gh; ba.Rpart = Rpart; ba.rcpart = rcpart;
   ba.Lq = f.Lq; ba.Lk = f.Lk; ba.rslots = a.nslot; ba.rows_per_rslot = a.rows_per_seg / a.sub;
   const int BH = f.B * f.H;
+  if (a.nslot == 1) {
+    // a single slot per sequence: no prefix and no suffix states; the first state of the (unused) suffix buffer is
+    // the block of zeros that every workgroup starts from
+    if (int rc = launch_fill_u32((uint32_t*)Rpart, 0u, (size_t)M * DVP, st)) return rc;
+    ba.zero_state = Rpart;
+  }
   if (int rc = launch_bwd_walk_pc(ba, 0, a.nslot, BH, st)) return rc;
-  if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
-  hipLaunchKernelGGL(bwd::k_bwd_suffix, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
-  FS_LAUNCH_CHECK();
+  if (a.nslot > 1) {
+    if (int rc = launch_bwd_rstate(ba, BH, st)) return rc;
+    hipLaunchKernelGGL(bwd::k_bwd_suffix, dim3((M * DVP / 4 + 255) / 256, BH), dim3(256), 0, st, Rpart, a.nslot);
+    FS_LAUNCH_CHECK();
+  }
   if (int rc = launch_bwd_walk_pc(ba, 1, a.nslot, BH, st)) return rc;
   return launch_bwd_cgrad_pc(ba, a.nslot, BH, st);
 }

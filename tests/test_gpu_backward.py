@@ -259,6 +259,41 @@ def test_backward_causal_bf16_path_other_families_and_lengths(fs, variant, L):
     _check_backward(fs, Q, K, V, dY, Om, d ** -0.25, variant, "bf16", 2e-2, grad_dtype=torch.float32, causal=True)
 
 
+@pytest.mark.parametrize("variant,L", [("sderf", 200), ("aderf", 128), ("gerf", 333)])
+def test_backward_causal_one_slot_per_sequence(fs, variant, L):
+    """Causal calls with 256 sequences or more give every sequence one slot: no prefix and no suffix states exist, the
+    walks start from a block of zeros and only the key shift of each sequence is computed beforehand (the workspace
+    is filled with NaN bit patterns first: nothing that was not written may be read; every fifth batch entry against
+    the oracle)."""
+    import torch
+    rng = np.random.default_rng(79 + L)
+    B, H, d, M = 32, 8, 64, 256
+    sc = np.linspace(0.6, 1.1, d)
+    Q = synth.round_to_bf16((rng.standard_normal((B, H, L, d)) * sc + 0.05).astype(np.float32))
+    K = synth.round_to_bf16((rng.standard_normal((B, H, L, d)) * sc[::-1] - 0.05).astype(np.float32))
+    V = synth.round_to_bf16(rng.standard_normal((B, H, L, d)).astype(np.float32))
+    dY = synth.round_to_bf16(rng.standard_normal((B, H, L, d)).astype(np.float32))
+    Om = rng.standard_normal((H, M, d)).astype(np.float32)
+    scale = d ** -0.25
+    theta = _theta_block(variant, Q[::5], K[::5], scale)
+    ws = torch.full((fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, True, H, H),), 0xFF, dtype=torch.uint8,
+                    device="cuda")
+    grads = fs.attention_backward(torch.from_numpy(theta).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
+                                  util.to_device(V, "bf16"), util.to_device(dY, "bf16"), scale, torch.from_numpy(Om).cuda(),
+                                  causal=True, grad_dtype=torch.float32, workspace=ws)
+    assert fs.attention_flushed_rows(ws) == 0
+    gQ, gK, gV = (util.to_host(g) for g in grads)
+    assert np.isfinite(gQ).all() and np.isfinite(gK).all() and np.isfinite(gV).all()
+    worst = (0.0, 0.0)
+    for b in range(0, B, 5):
+        for h in range(H):
+            th = util.oracle_theta_from_vec(theta[h], d)
+            ref = orc.attention_backward(th, Om[h], Q[b, h], K[b, h], V[b, h], dY[b, h], scale, True)
+            e = _assert_grads((gQ[b, h], gK[b, h], gV[b, h]), ref, 2e-2, (b, h))
+            worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    print(f"backward, causal, 256 sequences of {L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+
+
 @pytest.mark.parametrize("causal", [False, True])
 def test_backward_bf16_path_single_token(fs, causal):
     """One query and one key: Y = V_0 whatever Q and K are, so dQ = dK = 0 and dV = dY.  On the bf16 kernels the zero
