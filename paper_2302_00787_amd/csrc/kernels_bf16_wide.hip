@@ -56,6 +56,7 @@ struct WideArgs {
   int fh;            // feature half of this launch of the walk
   float scale;
   unsigned* flushed; // counter of output rows with a zero normaliser (nullptr: not counted)
+  const float* zero_state;   // causal call with one slot per sequence: a state of zeros, the start of every walk
 };
 
 __device__ __forceinline__ float max512(const float* p) {
@@ -134,6 +135,10 @@ struct SmemWState {
   __attribute__((aligned(16))) float kbnd[2][TC];
 };
 
+// BOUND_ONLY (causal calls with one slot per sequence: the walk starts from nothing and needs the key shift only):
+// no projections, no values, no state; the shift goes where the reduction would have put it and the call's counter of
+// flushed rows back to zero.  grid (1, B*H, 1).
+template <bool BOUND_ONLY>
 __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   SmemWState& sm = *reinterpret_cast<SmemWState*>(smem_raw);
@@ -149,7 +154,7 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
 
   // projection slice as B operand: column = feature 256 fh + 32 w + 16 mt + c, k = 32 ks + 8g + e
   bf16x8 wk[2][KSW];
-  {
+  if (!BOUND_ONLY) {
     const uint16_t* Wg = a.Wbf + ((size_t)pg * 2 + 1) * MW * DW;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -157,7 +162,7 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
       for (int ks = 0; ks < KSW; ++ks)
         wk[mt][ks] = *(const bf16x8*)(Wg + (size_t)(256 * fh + 32 * w + 16 * mt + c) * DW + 32 * ks + 8 * g);
   }
-  for (int idx = tid; idx < 2 * (TLD - DW - 1) * LDJ; idx += 512) {
+  for (int idx = tid; !BOUND_ONLY && idx < 2 * (TLD - DW - 1) * LDJ; idx += 512) {
     const int bb = idx / ((TLD - DW - 1) * LDJ), rem = idx - bb * (TLD - DW - 1) * LDJ;
     sm.vt[bb][DW + 1 + rem / LDJ][rem % LDJ] = 0;
   }
@@ -182,7 +187,7 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
       const int row = (tid >> 4) + 32 * i;
       kr[i] = __builtin_amdgcn_raw_buffer_load_b128(rk_, 2 * (row * (int)a.K.sl + (tid & 15) * 8), 0, 0);
       rkr[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr_, 4 * row, 0, 0));
-      vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, 2 * ((tid & 63) * (int)a.V.sl + ((tid >> 6) + 8 * i) * 8), 0, 0);
+      if (!BOUND_ONLY) vr[i] = __builtin_amdgcn_raw_buffer_load_b128(rv_, 2 * ((tid & 63) * (int)a.V.sl + ((tid >> 6) + 8 * i) * 8), 0, 0);
     }
   };
   auto store = [&](int buf, int row0) {
@@ -195,9 +200,9 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
       // rows past the end get -inf: their features are exactly zero whatever the key shift is
       sm.kadd[buf][row] = row < nv ? rt : -INFINITY;
       sm.kbnd[buf][row] = row < nv ? row_shift(n2, wmax) + rt : -INFINITY;
-      store_val_piece(vr[i], sm.vt[buf], tid & 63, (tid >> 6) + 8 * i);
+      if (!BOUND_ONLY) store_val_piece(vr[i], sm.vt[buf], tid & 63, (tid >> 6) + 8 * i);
     }
-    if (tid < 32) {
+    if (!BOUND_ONLY && tid < 32) {
       const int t0 = 2 * tid;
       *(uint32_t*)(&sm.vt[buf][DW][t0]) = (t0 < nv ? 0x3f80u : 0u) | (t0 + 1 < nv ? 0x3f80u << 16 : 0u);
     }
@@ -213,7 +218,8 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
     {
       const f32x4 b4 = *(const f32x4*)(&sm.kbnd[buf][4 * c]);
       const float dnew = max16(fmaxf(fmaxf(b4[0], b4[1]), fmaxf(b4[2], b4[3])));
-      if (dnew > dk) {
+      if (BOUND_ONLY) dk = fmaxf(dk, dnew);
+      else if (dnew > dk) {
         const float f = fast_exp2(dk - dnew);
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
@@ -223,7 +229,7 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
       }
     }
 #pragma unroll
-    for (int jp = 0; jp < 2; ++jp) {
+    for (int jp = 0; !BOUND_ONLY && jp < 2; ++jp) {
       bf16x8 st[2];
       {
         bf16x8 x[2][KSW];
@@ -256,6 +262,14 @@ __global__ void __launch_bounds__(512) k_wide_state(WideArgs a) {
     }
     if (more) store(buf ^ 1, row0 + TC);
     __syncthreads();
+  }
+  if (BOUND_ONLY) {
+    if (tid == 0) {
+      a.cstar[bh] = dk;
+      a.cstar[gridDim.y + bh] = dk;        // the key shift of the sequence's only slot
+      if (bh == 0 && a.flushed != nullptr) *a.flushed = 0u;
+    }
+    return;
   }
   float* out = a.Tpart + (((size_t)bh * 2 + fh) * a.nslot + slot) * 256 * TLD;
 #pragma unroll
@@ -549,7 +563,8 @@ __global__ void __launch_bounds__(NT8) k_wide_walk(WideArgs a) {
     // state slice: 64 features of this half x the 64 columns of this column half and the normaliser column (tile 4)
     f32x4 T[4][NVT];
     // (non-causal: the sum over all slots, which the reduction left in slot 0)
-    const float* Tg = a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + (CAUSAL ? slot : 0)) * 256 * TLD;
+    const float* Tg = a.zero_state != nullptr ? a.zero_state
+                                              : a.Tpart + (((size_t)bh * 2 + cx.fh) * a.nslot + (CAUSAL ? slot : 0)) * 256 * TLD;
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -703,9 +718,12 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   a.rows_per_slot_q = f.causal ? f.rows_per_slot : f.rows_per_slot_q;
   const int nslot_q = f.causal ? f.nslot : f.nslot_q;
   a.flushed = f.flushed;
+  a.zero_state = nullptr;
   const int BH = f.B * f.H;
   const void* walk = f.causal ? (const void*)k_wide_walk<true> : (const void*)k_wide_walk<false>;
-  if (hipFuncSetAttribute((const void*)k_wide_state, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWState)) != hipSuccess ||
+  const bool one_slot = f.causal && f.nslot == 1;
+  const void* state = one_slot ? (const void*)k_wide_state<true> : (const void*)k_wide_state<false>;
+  if (hipFuncSetAttribute(state, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWState)) != hipSuccess ||
       hipFuncSetAttribute(walk, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SmemWWalk)) != hipSuccess) {
     (void)hipGetLastError();
     return 2;
@@ -717,11 +735,20 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   // the key row terms of parameter sets with a dense C2 (the host knows that there are none only in mode 2)
   if (f.pre_mode != 2)
     if (int rc = launch_key_row_terms(f.theta, f.groups, f.K, f.B, f.H, f.L, DW, f.scale, f.rk, st)) return rc;
-  hipLaunchKernelGGL(k_wide_state, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
-  FS_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
-                     f.causal ? 0 : 1, f.flushed);
-  FS_LAUNCH_CHECK();
+  if (one_slot) {
+    // one slot per sequence (128 sequences or more): the walks start from nothing, so no state is computed or
+    // scanned; the first state of the (unused) buffer becomes the block of zeros that every workgroup reads
+    if (int rc = launch_fill_u32((uint32_t*)f.Tpart, 0u, (size_t)256 * TLD, st)) return rc;
+    a.zero_state = f.Tpart;
+    hipLaunchKernelGGL(k_wide_state<true>, dim3(1, BH, 1), dim3(512), sizeof(SmemWState), st, a);
+    FS_LAUNCH_CHECK();
+  } else {
+    hipLaunchKernelGGL(k_wide_state<false>, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
+    FS_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
+                       f.causal ? 0 : 1, f.flushed);
+    FS_LAUNCH_CHECK();
+  }
   // the optional events are attached to the dispatches of the two walks: begin of the first, end of the second
   for (int fh = 0; fh < 2; ++fh) {
     a.fh = fh;
