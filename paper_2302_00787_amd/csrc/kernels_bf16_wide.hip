@@ -745,9 +745,15 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
   } else {
     hipLaunchKernelGGL(k_wide_state<false>, dim3(f.nslot, BH, 2), dim3(512), sizeof(SmemWState), st, a);
     FS_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
-                       f.causal ? 0 : 1, f.flushed);
-    FS_LAUNCH_CHECK();
+    if (!f.causal && f.nslot == 1) {
+      // the sum over one slot is that slot (its shift cancels in the normalised rows): only the counter is reset
+      if (f.flushed != nullptr)
+        if (int rc = launch_fill_u32((uint32_t*)f.flushed, 0u, 1, st)) return rc;
+    } else {
+      hipLaunchKernelGGL(k_wide_reduce, dim3((256 * TLD / 4 + 255) / 256, BH * 2), dim3(256), 0, st, f.Tpart, f.cpart, f.cstar, f.nslot,
+                         f.causal ? 0 : 1, f.flushed);
+      FS_LAUNCH_CHECK();
+    }
   }
   // the optional events are attached to the dispatches of the two walks: begin of the first, end of the second
   for (int fh = 0; fh < 2; ++fh) {

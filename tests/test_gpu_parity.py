@@ -596,30 +596,33 @@ def test_bf16_wide_path_non_causal_runs_on_the_wide_kernels(fs, Lk):
         assert fro <= 2e-2 and row <= 8e-2, (h, fro, row)
 
 
-@pytest.mark.parametrize("variant,L", [("sderf", 200), ("aderf", 320)])
-def test_bf16_wide_path_causal_one_slot_per_sequence(fs, variant, L):
-    """Causal calls of the d = 128 shape with 128 sequences or more have one slot per sequence: no state is computed
-    or scanned, the walks start from a block of zeros and only the key shift of each sequence is computed beforehand
-    (NaN bit patterns in the workspace: nothing unwritten may be read; every third batch entry against the oracle)."""
+@pytest.mark.parametrize("variant,L,causal", [("sderf", 200, True), ("aderf", 320, True), ("saderf", 200, False)])
+def test_bf16_wide_path_one_slot_per_sequence(fs, variant, L, causal):
+    """Calls of the d = 128 shape with 128 sequences or more have one slot per sequence.  Causal: no state is computed
+    or scanned, the walks start from a block of zeros and only the key shift of each sequence is computed beforehand.
+    Non-causal: the state of the only slot is the total, no reduction runs.  (NaN bit patterns in the workspace:
+    nothing unwritten may be read; every third batch entry against the oracle.)"""
     import torch
     w = synth.make("c5", B=16, H=8, L=L, seed=457 + L)
     Q, K, V, Om, s, d = w["Q"], w["K"], w["V"], w["Omega"], w["qk_scale"], w["d"]
     theta = _fit_theta_block(variant, Q, K, s, None)
-    ws = torch.full((fs.attention_workspace_bytes(16, 8, L, L, d, d, Om.shape[1], True, 8, Om.shape[0]),), 0xFF,
+    ws = torch.full((fs.attention_workspace_bytes(16, 8, L, L, d, d, Om.shape[1], causal, 8, Om.shape[0]),), 0xFF,
                     dtype=torch.uint8, device="cuda")
     Y = fs.attention(torch.from_numpy(theta).cuda(), util.to_device(Q, "bf16"), util.to_device(K, "bf16"),
-                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=True, chunk=64, workspace=ws)
+                     util.to_device(V, "bf16"), s, torch.from_numpy(Om).cuda(), causal=causal, chunk=64 if causal else 0,
+                     workspace=ws)
     assert fs.attention_flushed_rows(ws) == 0
     Yh = util.to_host(Y)
     assert np.isfinite(Yh).all()
     worst = (0.0, 0.0)
     for b in range(0, 16, 3):
         for h in range(8):
-            ref = orc.attention(util.oracle_theta_from_vec(theta[h], d), Om[h], Q[b, h], K[b, h], V[b, h], s, True)
+            ref = orc.attention(util.oracle_theta_from_vec(theta[h], d), Om[h], Q[b, h], K[b, h], V[b, h], s, causal)
             fro, row = util.attention_errors(Yh[b, h], ref, V[b, h].astype(np.float64))
             worst = (max(worst[0], fro), max(worst[1], row))
             assert fro <= 2e-2 and row <= 8e-2, (b, h, fro, row)
-    print(f"bf16 wide path, causal, 128 sequences of {L} {variant}: worst frobenius {worst[0]:.2e}, worst row {worst[1]:.2e}")
+    print(f"bf16 wide path, causal={causal}, 128 sequences of {L} {variant}: worst frobenius {worst[0]:.2e}, "
+          f"worst row {worst[1]:.2e}")
 
 
 def test_bf16_wide_path_f32_output_and_strided_inputs(fs):
