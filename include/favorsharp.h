@@ -46,7 +46,8 @@ extern "C" {
 typedef enum {
   FS_OK = 0,
   FS_ERR_INVALID_ARG = 1,        /* null pointer, bad shape / stride / dtype / enum */
-  FS_ERR_UNSUPPORTED = 2,        /* valid but outside what the kernels cover (d > 128, causal with Lq != Lk, ...) */
+  FS_ERR_UNSUPPORTED = 2,        /* valid but outside what the kernels cover (d > 128, causal with Lq != Lk,
+                                    B * H > 65535: the sequences are a grid dimension, ...) */
   FS_ERR_NOT_PD = 3,             /* fit: statistics are singular where the theorem needs them nonsingular */
   FS_ERR_WORKSPACE_TOO_SMALL = 4,
   FS_ERR_DEVICE = 5,             /* a HIP call failed */

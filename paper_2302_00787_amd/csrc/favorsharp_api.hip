@@ -34,6 +34,10 @@ bool tensor_ok(const fs_tensor* t, int d, bool need_ptr = true) {
 
 TensorDev dev(const fs_tensor* t) { return TensorDev{t->ptr, t->dtype, t->stride_b, t->stride_h, t->stride_l}; }
 
+// B*H is a grid dimension of most kernels (at most 65535 workgroups there)
+constexpr long long kMaxSequences = 65535;
+bool sequences_ok(int B, int H) { return (long long)B * H <= kMaxSequences; }
+
 bool groups_ok(int g, int B, int H) { return g == 1 || g == H || g == B * H; }
 
 struct AttnPlan {
@@ -236,7 +240,7 @@ int favorsharp_orthogonal_omega(const float* host_gauss_dir, const float* host_g
 
 // ------------------------------------------------------------------------------------------ fit
 size_t favorsharp_fit_workspace_bytes(int B, int H, int Lx, int Ly, int d, int groups) {
-  if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || d > 128 || !groups_ok(groups, B, H)) return 0;
+  if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || d > 128 || !sequences_ok(B, H) || !groups_ok(groups, B, H)) return 0;
   FitPlan p;
   plan_fit(B, H, Lx, Ly, d, groups, &p);
   return p.total;
@@ -247,7 +251,7 @@ int favorsharp_fit_params(int variant, const fs_tensor* X, const fs_tensor* Y, i
                           size_t workspace_bytes, void* stream) {
   if (variant < FS_POSRF || variant > FS_SDERF) return FS_ERR_INVALID_ARG;
   if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || !groups_ok(groups, B, H)) return FS_ERR_INVALID_ARG;
-  if (d > 128) return FS_ERR_UNSUPPORTED;
+  if (d > 128 || !sequences_ok(B, H)) return FS_ERR_UNSUPPORTED;
   if (!tensor_ok(X, d) || !tensor_ok(Y, d) || X->dtype != Y->dtype) return FS_ERR_INVALID_ARG;
   if (theta == nullptr || workspace == nullptr || !(eig_ridge >= 0.f) || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
   FitPlan p;
@@ -305,7 +309,7 @@ int favorsharp_fit_params_device(int variant, const fs_tensor* X, const fs_tenso
                                  void* workspace, size_t workspace_bytes, void* stream) {
   if (variant < FS_POSRF || variant > FS_SDERF) return FS_ERR_INVALID_ARG;
   if (B < 1 || H < 1 || Lx < 1 || Ly < 1 || d < 1 || !groups_ok(groups, B, H)) return FS_ERR_INVALID_ARG;
-  if (d > 128) return FS_ERR_UNSUPPORTED;
+  if (d > 128 || !sequences_ok(B, H)) return FS_ERR_UNSUPPORTED;
   if (!tensor_ok(X, d) || !tensor_ok(Y, d) || X->dtype != Y->dtype) return FS_ERR_INVALID_ARG;
   if (theta == nullptr || status == nullptr || workspace == nullptr || !(eig_ridge >= 0.f) || !(qk_scale > 0.f))
     return FS_ERR_INVALID_ARG;
@@ -360,7 +364,7 @@ int favorsharp_features(const float* theta, int side, const fs_tensor* X, int n,
 // ------------------------------------------------------------------------------------------ attention
 size_t favorsharp_attention_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M, int causal,
                                             int groups, int omega_groups) {
-  if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1) return 0;
+  if (B < 1 || H < 1 || Lq < 0 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1 || !sequences_ok(B, H)) return 0;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
   AttnPlan p;
   plan_contraction(B * H, std::max(groups, omega_groups), Lk, d, M, dv + 1, causal, &p);
@@ -458,7 +462,7 @@ int attention_impl(const float* theta, int groups, const fs_tensor* Q, const fs_
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
   if (chunk != 0 && chunk != 32 && chunk != 64) return chunk < 0 ? FS_ERR_INVALID_ARG : FS_ERR_UNSUPPORTED;
-  if (d > 128 || dv > 128) return FS_ERR_UNSUPPORTED;
+  if (d > 128 || dv > 128 || !sequences_ok(B, H)) return FS_ERR_UNSUPPORTED;
   if (causal && Lq != Lk) return FS_ERR_UNSUPPORTED;
   if (theta == nullptr || Omega == nullptr || workspace == nullptr || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
   if (!tensor_ok(Q, d, Lq > 0) || !tensor_ok(K, d) || !tensor_ok(V, dv) || !tensor_ok(Y, dv, Lq > 0))
@@ -638,7 +642,7 @@ void plan_fast_backward(int BH, int pgroups, int Lq, int Lk, FastBwdPlan* p) {
 
 size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int Lk, int d, int dv, int M, int causal,
                                                      int groups, int omega_groups) {
-  if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1) return 0;
+  if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || d > 128 || dv < 1 || dv > 128 || M < 1 || !sequences_ok(B, H)) return 0;
   if ((causal != 0 && causal != 1) || (causal && Lq != Lk)) return 0;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return 0;
   BwdPlan p;
@@ -660,7 +664,7 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
   if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
-  if (d > 128 || dv > 128 || (causal && Lq != Lk)) return FS_ERR_UNSUPPORTED;
+  if (d > 128 || dv > 128 || (causal && Lq != Lk) || !sequences_ok(B, H)) return FS_ERR_UNSUPPORTED;
   if (theta == nullptr || Omega == nullptr || workspace == nullptr || !(qk_scale > 0.f)) return FS_ERR_INVALID_ARG;
   if (!tensor_ok(Q, d) || !tensor_ok(K, d) || !tensor_ok(V, dv) || !tensor_ok(dY, dv)) return FS_ERR_INVALID_ARG;
   if (!tensor_ok(dQ, d) || !tensor_ok(dK, d) || !tensor_ok(dV, dv)) return FS_ERR_INVALID_ARG;

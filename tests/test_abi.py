@@ -42,6 +42,11 @@ def test_host_only_queries(lib):
     assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 64, 64, 256, 1, 8, 8) > 0
     assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 129, 64, 256, 1, 8, 8) == 0     # d > 128
     assert lib.favorsharp_attention_workspace_bytes(4, 8, 16384, 16384, 64, 64, 256, 1, 3, 8) == 0      # bad groups
+    # the sequences are a grid dimension of the kernels: at most 65535 of them
+    assert lib.favorsharp_attention_workspace_bytes(65535, 1, 64, 64, 64, 64, 256, 0, 1, 1) > 0
+    assert lib.favorsharp_attention_workspace_bytes(8192, 8, 64, 64, 64, 64, 256, 0, 1, 1) == 0
+    assert lib.favorsharp_attention_backward_workspace_bytes(8192, 8, 64, 64, 64, 64, 256, 0, 1, 1) == 0
+    assert lib.favorsharp_fit_workspace_bytes(8192, 8, 64, 64, 64, 1) == 0
     assert lib.favorsharp_kernel_matvec_workspace_bytes(16384, 16384, 32, 512, 8) > 0
     # room for both sides' projection matrices (fp32 and bf16 copies) and biases
     assert lib.favorsharp_features_workspace_bytes(100, 16, 64) >= 2 * 64 * 16 * (4 + 2) + 2 * 64 * 4
@@ -60,6 +65,10 @@ def test_argument_errors_are_reported_before_any_device_work(lib):
                                     None, 0, None) == 2
     assert lib.favorsharp_attention(None, 1, P(t), P(t), P(t), 1, 1, 64, 64, 256, 64, 1.0, None, 1, 64, 0, 0, P(t),
                                     None, 0, None) == 2
+    # more than 65535 sequences -> unsupported
+    assert lib.favorsharp_attention(None, 1, P(t), P(t), P(t), 8192, 8, 64, 64, 64, 64, 1.0, None, 1, 64, 0, 0, P(t),
+                                    None, 0, None) == 2
+    assert lib.favorsharp_fit_params(1, P(t), P(t), 8192, 8, 8, 8, 8, 1.0, 1, 0.0, None, None, 0, None) == 2
     assert lib.favorsharp_fit_params(9, P(t), P(t), 1, 1, 8, 8, 8, 1.0, 1, 0.0, None, None, 0, None) == 1
     assert lib.favorsharp_attention_flushed_rows(None, None, None) == 1
     assert lib.favorsharp_features(None, 3, P(t), 8, 8, 1.0, 0.0, None, 8, None, None, None, 0, None) == 1
