@@ -19,7 +19,8 @@ begin and end on the stream the library launches on).
 Prints ONE JSON line.  Headline fields: the metric workload.  `roofline`: the dominant kernel of the metric workload
 (`frac`) and the whole call (`call_frac`) against the tighter of the HBM / MFMA bounds on the algorithmic counts.
 `workloads`: the same measurements for the other four workloads and the two backward-pass workloads, taken in the
-same run (unless --only).  `families_ms` (headline, c3, c5): ms per call of the same workload with GERF, SADERF and
+same run (unless --only), plus `many_short_sequences` (4096 sequences of 128 tokens on the d = 64 kernels, forward
+and backward, outside the five configurations).  `families_ms` (headline, c3, c5): ms per call of the same workload with GERF, SADERF and
 ADERF parameters instead of SDERF (the last two have a dense key-side quadratic form and B1 != B2).  `parity`: measured errors of the library's results against the CPU oracle on the same
 inputs and the same float32 parameter block (computed in the CPU-baseline leg, which is the only part of this
 script that touches the oracle).  `cpu_baseline`: the oracle timed on a bounded sample of the metric workload.
@@ -347,6 +348,55 @@ def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
                           "frac": tf / MFMA_BF16_PEAK_TFLOPS, "step_frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
 
 
+def run_many_sequences(steps: int, warmup: int, fs, synth, torch, oracle) -> tuple:
+    """Outside the five configurations: the d = 64 / M = 256 kernels on MANY SHORT sequences (512 x 8 sequences of 128
+    tokens with the c3 recipe, the shape of an encoder's training batch), where a state is more bytes than a
+    sequence's rows: forward and backward, without and with the mask, ms per call, theta and omega resident.  The
+    non-causal calls run one workgroup per sequence (k_fast_whole, k_bwd_whole); the causal ones have one slot per
+    sequence (no state pass, no scan).  Parity: three whole sequences of every call against the CPU oracle."""
+    B, H, L = 512, 8, 128
+    w = synth.make("c3", B=B, H=H, L=L)
+    d, M, s = w["d"], w["M"], w["qk_scale"]
+    rng = np.random.default_rng(977)
+    dY = synth.round_to_bf16(rng.standard_normal(w["V"].shape).astype(np.float32))
+    Q, K, V, dYd = (fs.to_device(a, "bf16") for a in (w["Q"], w["K"], w["V"], dY))
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    theta = fs.fit_params("sderf", Q, K, s, groups=H)
+    prepared = fs.attention_prepare(theta, Om, B, H, s)
+    out = {"workload": f"many short sequences: B={B} H={H} L={L} d={d} M={M}, bf16, SDERF per head, theta and omega "
+                       "resident (not one of the five configurations)", "attention_ms": {}, "backward_ms": {}}
+    worst = [0.0, 0.0]
+    th_host = fs.to_host(theta).astype(np.float32)
+    for causal in (False, True):
+        key = "causal" if causal else "non_causal"
+        ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8,
+                         device="cuda")
+        wf = torch.empty(fs.attention_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8, device="cuda")
+        Y = torch.empty_like(Q)
+        grads = tuple(torch.empty_like(Q) for _ in range(3))
+        out["attention_ms"][key] = timed(lambda i: fs.attention_prepared(prepared, theta, Q, K, V, s, Om, causal=causal,
+                                                                         chunk=64 if causal else 0, out=Y, workspace=wf),
+                                         steps, warmup, torch)
+        out["backward_ms"][key] = timed(lambda i: fs.attention_backward(theta, Q, K, V, dYd, s, Om, causal=causal,
+                                                                        workspace=ws, grads=grads), steps, warmup, torch)
+        if oracle:
+            for b, h in ((0, 0), (17, 3), (B - 1, H - 1)):
+                th = oracle.theta(th_host[h], d)
+                args = (th, w["Omega"][h], w["Q"][b, h], w["K"][b, h], w["V"][b, h])
+                fro, row = oracle.errors(fs.to_host(Y[b, h]), oracle.orc.attention(*args, s, causal), w["V"][b, h].astype(np.float64))
+                worst = [max(worst[0], fro), max(worst[1], row)]
+                for g, rf in zip(grads, oracle.orc.attention_backward(*args, dY[b, h], s, causal)):
+                    fro, row = oracle.errors(fs.to_host(g[b, h]), rf, rf)
+                    worst = [max(worst[0], fro), max(worst[1], row)]
+        del ws, wf, Y, grads
+    parity = {"reference": "CPU oracle (fp64), same inputs, omega and float32 parameter block",
+              "rows": "every row of Y, dQ, dK, dV of three (b,h) sequences, without and with the mask",
+              "worst_frobenius": worst[0], "worst_row": worst[1], "tol_frobenius": 2e-2, "tol_row": 8e-2,
+              "ok": bool(worst[0] <= 2e-2 and worst[1] <= 8e-2)} if oracle else None
+    torch.cuda.empty_cache()
+    return out, parity
+
+
 # ---------------------------------------------------------------------------------------------- CPU oracle leg
 class OracleLeg:
     """Everything that touches the CPU oracle: the timed baseline and the parity figures.  Both sides see the same
@@ -578,6 +628,9 @@ def main():
             if oracle:
                 parity[f"{short}_backward"] = oracle.backward(r)
             free(r, torch)
+        others["many_short_sequences"], p = run_many_sequences(steps, warmup, fs, synth, torch, oracle)
+        if oracle:
+            parity["many_short_sequences"] = p
         result["workloads"] = others
         result["workloads_steps"], result["workloads_warmup"] = steps, warmup
     if oracle:
