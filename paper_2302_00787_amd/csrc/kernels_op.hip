@@ -68,7 +68,18 @@ __global__ void __launch_bounds__(256) k_op_pre(const float* theta, const float*
   const float* A = theta + FS_THETA_HEADER_;
   float acc = 0.f, q = 0.f;
   if (c < d) {
-    for (int l = 0; l < d; ++l) acc += om[l] * Bm[l * d + c];
+    // eight rows of B requested at a time (d is a multiple of 4): the loop is a chain of memory latencies otherwise
+    for (int l0 = 0; l0 < d; l0 += 8) {
+      float o[8], bv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int l = min(l0 + i, d - 1);
+        o[i] = l0 + i < d ? om[l] : 0.f;
+        bv[i] = Bm[l * d + c];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc += o[i] * bv[i];
+    }
     acc *= kLog2e;
     W[((size_t)side * M + m) * d + c] = acc;
     q = A[c] * om[c] * om[c];
