@@ -302,8 +302,9 @@ def run_matvec(steps: int, warmup: int, fs, synth, torch) -> dict:
 # ---------------------------------------------------------------------------------------------- backward pass
 def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
     """Backward pass of attention on the c3 (non-causal) or c4 (causal) shapes, bf16 inputs and gradients: one step =
-    one favorsharp_attention_backward call with theta and omega resident (bf16 MFMA kernels; bound: the bf16 MFMA
-    peak).  Algorithmic flops per head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six
+    one favorsharp_attention_backward_prepared call with theta, omega and the projection constants derived from
+    them resident (`ms_per_step_unprepared`: favorsharp_attention_backward, which rebuilds the constants); bf16 MFMA
+    kernels; bound: the bf16 MFMA peak.  Algorithmic flops per head-token: the two projections twice (features are rebuilt, and dE W) 8 d M, six
     M x (dv + 1) contractions (T, P T, G1 T^T, P^T G1, S R, [V 1] R^T) 12 M (dv + 1), and when causal the
     intra-chunk triangles of 64 rows (three times the forward pass's extra term)."""
     cfg = dict(synth.WORKLOADS[name])
@@ -318,24 +319,33 @@ def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
             w0, dY0 = w, dY
         Q, K, V = (fs.to_device(w[k], "bf16") for k in "QKV")
         theta = fs.fit_params("sderf", Q, K, w["qk_scale"], groups=H)
-        sets.append((theta, Q, K, V, fs.to_device(dY, "bf16"), torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"]))
+        Om = torch.from_numpy(w["Omega"]).cuda()
+        sets.append((theta, Q, K, V, fs.to_device(dY, "bf16"), Om, w["qk_scale"],
+                     fs.attention_prepare(theta, Om, B, H, w["qk_scale"])))
     ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, d, M, causal, H, H), dtype=torch.uint8,
                      device="cuda")
     last = {}
 
-    def step(i):
-        theta, Q, K, V, dY, Om, s = sets[i % nsets]
+    def step_unprepared(i):
+        theta, Q, K, V, dY, Om, s, _ = sets[i % nsets]
         last[i % nsets] = fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
 
+    # the step: projection constants prepared once per parameter set, as in the forward workloads
+    def step(i):
+        theta, Q, K, V, dY, Om, s, prep = sets[i % nsets]
+        last[i % nsets] = fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws, prepared=prep)
+
+    ms_unprepared = timed(step_unprepared, steps, warmup, torch)
     ms = timed(step, steps, warmup, torch)
     assert all(torch.isfinite(g.float()).all().item() for g in last[0])
     # the same call with ADERF parameters (dense C2: row-term kernel, dense derivative of the row term), first set
-    _, Q, K, V, dY, Om, s = sets[0]
+    _, Q, K, V, dY, Om, s, _ = sets[0]
     theta_a = fs.fit_params("aderf", Q, K, s, groups=H)
+    prep_a = fs.attention_prepare(theta_a, Om, B, H, s)
     grads_a = {}
 
     def step_aderf(i):
-        grads_a[0] = fs.attention_backward(theta_a, Q, K, V, dY, s, Om, causal=causal, workspace=ws)
+        grads_a[0] = fs.attention_backward(theta_a, Q, K, V, dY, s, Om, causal=causal, workspace=ws, prepared=prep_a)
 
     ms_aderf = timed(step_aderf, steps, warmup, torch)
     assert all(torch.isfinite(g.float()).all().item() for g in grads_a[0])
@@ -343,6 +353,7 @@ def run_backward(name: str, steps: int, warmup: int, fs, synth, torch) -> dict:
     per_token = 8 * d * M + 12 * M * (d + 1) + (3 * (chunk + 1) // 2 * (2 * M + 2 * (d + 1)) if causal else 0)
     tf = B * H * L * per_token / (ms * 1e-3) / 1e12
     return dict(cfg=cfg, w0=w0, dY0=dY0, theta0=sets[0][0], grads0=last[0], ms_per_step=ms, ms_per_step_aderf=ms_aderf,
+                ms_per_step_unprepared=ms_unprepared,
                 tokens_per_s=B * L / (ms * 1e-3),
                 roofline={"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                           "frac": tf / MFMA_BF16_PEAK_TFLOPS, "step_frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None})
@@ -378,7 +389,8 @@ def run_many_sequences(steps: int, warmup: int, fs, synth, torch, oracle) -> tup
                                                                          chunk=64 if causal else 0, out=Y, workspace=wf),
                                          steps, warmup, torch)
         out["backward_ms"][key] = timed(lambda i: fs.attention_backward(theta, Q, K, V, dYd, s, Om, causal=causal,
-                                                                        workspace=ws, grads=grads), steps, warmup, torch)
+                                                                        workspace=ws, grads=grads, prepared=prepared),
+                                        steps, warmup, torch)
         if oracle:
             for b, h in ((0, 0), (17, 3), (B - 1, H - 1)):
                 th = oracle.theta(th_host[h], d)
@@ -561,6 +573,7 @@ def main():
                   "config": {"workload": f"{name}: gradients of {'causal' if cfg['causal'] else 'non-causal'} attention "
                                          f"w.r.t. Q, K, V, bf16 in and out, B={cfg['B']} H={cfg['H']} L={cfg['L']} "
                                          f"d={cfg['d']} M={cfg['M']}, SDERF per head, theta and omega resident"},
+                  "ms_per_step_unprepared": r["ms_per_step_unprepared"],
                   "families_ms": {"aderf": r["ms_per_step_aderf"]}, "roofline": r["roofline"]}
         if oracle:
             parity[name] = oracle.backward(r)
@@ -621,7 +634,9 @@ def main():
         free(r, torch)
         for short in ("c3", "c4"):
             r = run_backward(short, steps, warmup, fs, synth, torch)
-            others[f"{short}_backward"] = {"ms_per_step": r["ms_per_step"], "tokens_per_s": r["tokens_per_s"],
+            others[f"{short}_backward"] = {"ms_per_step": r["ms_per_step"],
+                                           "ms_per_step_unprepared": r["ms_per_step_unprepared"],
+                                           "tokens_per_s": r["tokens_per_s"],
                                            "main_kernel_ms": None, "roofline": r["roofline"],
                                            "families_ms": {"aderf": r["ms_per_step_aderf"]},
                                            "workload": f"{short} shapes: gradients w.r.t. Q, K, V, bf16 in and out"}

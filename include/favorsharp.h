@@ -231,6 +231,20 @@ int favorsharp_attention_prepared(const void* prepared, size_t prepared_bytes, i
                                   float qk_scale, const float* Omega, int omega_groups, int M,
                                   int causal, int chunk, const fs_tensor* Y,
                                   void* workspace, size_t workspace_bytes, void* stream);
+/*
+ * favorsharp_attention_backward on the same kept constants (Section 4, evaluation recipe: B^T omega is computed once per
+ * parameter set, here for the forward and the backward call of a training step alike): `prepared`, `dense_c2` as for
+ * favorsharp_attention_prepared, every other argument, the workspace and the statuses as
+ * favorsharp_attention_backward.  Gradients are bit-identical to favorsharp_attention_backward's.  Shapes whose
+ * gradient kernels keep no constants (everything but bf16 rows with d = dv = 64, M = 256) recompute them.
+ * Asynchronous.
+ */
+int favorsharp_attention_backward_prepared(const void* prepared, size_t prepared_bytes, int dense_c2,
+                                           const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                           const fs_tensor* V, const fs_tensor* dY, int B, int H, int Lq, int Lk,
+                                           int d, int dv, float qk_scale, const float* Omega, int omega_groups, int M,
+                                           int causal, const fs_tensor* dQ, const fs_tensor* dK, const fs_tensor* dV,
+                                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * favorsharp_attention for callers that cannot allocate or pass device memory of their own: code under HIP graph

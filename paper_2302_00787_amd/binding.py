@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.favorsharp_attention_backward.argtypes = [c_void_p, c_int, P, P, P, P, c_int, c_int, c_int, c_int, c_int, c_int,
                                                     c_float, c_void_p, c_int, c_int, c_int, P, P, P, c_void_p, c_size_t,
                                                     c_void_p]
+        L.favorsharp_attention_backward_prepared.restype = c_int
+        L.favorsharp_attention_backward_prepared.argtypes = [c_void_p, c_size_t, c_int] + L.favorsharp_attention_backward.argtypes
         L.favorsharp_kernel_matvec_workspace_bytes.restype = c_size_t
         L.favorsharp_kernel_matvec_workspace_bytes.argtypes = [c_int] * 5
         L.favorsharp_kernel_matvec.restype = c_int
@@ -358,9 +360,10 @@ def attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, o
 
 def attention_backward(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, dY: torch.Tensor,
                        qk_scale: float, Omega: torch.Tensor, causal: bool = False, grad_dtype=None,
-                       workspace: torch.Tensor | None = None, grads=None):
+                       workspace: torch.Tensor | None = None, grads=None, prepared=None):
     """favorsharp_attention_backward: gradients of sum(Y * dY) -> (dQ, dK, dV), shaped like Q, K, V
-    (`grads`: three preallocated tensors to write into, any row strides)."""
+    (`grads`: three preallocated tensors to write into, any row strides; `prepared`: what attention_prepare returned
+    for the same theta, Omega, qk_scale: favorsharp_attention_backward_prepared)."""
     B, H, Lq, d = Q.shape
     Lk, dv = K.shape[2], V.shape[3]
     groups = theta.shape[0] if theta.dim() == 2 else 1
@@ -375,12 +378,15 @@ def attention_backward(theta: torch.Tensor, Q: torch.Tensor, K: torch.Tensor, V:
     nbytes = attention_backward_workspace_bytes(B, H, Lq, Lk, d, dv, M, causal, groups, og)
     ws = _workspace(nbytes, Q.device, workspace)
     descs = [_desc4(t) for t in (Q, K, V, dY, gQ, gK, gV)]
-    st = lib().favorsharp_attention_backward(theta.data_ptr(), groups, ctypes.byref(descs[0]), ctypes.byref(descs[1]),
-                                             ctypes.byref(descs[2]), ctypes.byref(descs[3]), B, H, Lq, Lk, d, dv,
-                                             qk_scale, Omega.data_ptr(), og, M, int(causal), ctypes.byref(descs[4]),
-                                             ctypes.byref(descs[5]), ctypes.byref(descs[6]), ws.data_ptr(), ws.numel(),
-                                             _stream())
-    _check(st, "favorsharp_attention_backward")
+    args = (theta.data_ptr(), groups, ctypes.byref(descs[0]), ctypes.byref(descs[1]), ctypes.byref(descs[2]),
+            ctypes.byref(descs[3]), B, H, Lq, Lk, d, dv, qk_scale, Omega.data_ptr(), og, M, int(causal),
+            ctypes.byref(descs[4]), ctypes.byref(descs[5]), ctypes.byref(descs[6]), ws.data_ptr(), ws.numel(), _stream())
+    if prepared is None:
+        _check(lib().favorsharp_attention_backward(*args), "favorsharp_attention_backward")
+    else:
+        buf, dense = prepared
+        _check(lib().favorsharp_attention_backward_prepared(buf.data_ptr(), buf.numel(), dense, *args),
+               "favorsharp_attention_backward_prepared")
     return gQ, gK, gV
 
 

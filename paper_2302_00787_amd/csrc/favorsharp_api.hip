@@ -656,11 +656,14 @@ size_t favorsharp_attention_backward_workspace_bytes(int B, int H, int Lq, int L
   return total;
 }
 
-int favorsharp_attention_backward(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
-                                  const fs_tensor* V, const fs_tensor* dY, int B, int H, int Lq, int Lk, int d, int dv,
-                                  float qk_scale, const float* Omega, int omega_groups, int M, int causal,
-                                  const fs_tensor* dQ, const fs_tensor* dK, const fs_tensor* dV, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+int attention_backward_impl(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V,
+                            const fs_tensor* dY, int B, int H, int Lq, int Lk, int d, int dv, float qk_scale,
+                            const float* Omega, int omega_groups, int M, int causal, const fs_tensor* dQ,
+                            const fs_tensor* dK, const fs_tensor* dV, void* workspace, size_t workspace_bytes, void* stream,
+                            const void* prepared, int dense_c2) {
   if (B < 1 || H < 1 || Lq < 1 || Lk < 1 || d < 1 || dv < 1 || M < 1) return FS_ERR_INVALID_ARG;
   if (!groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H)) return FS_ERR_INVALID_ARG;
   if (causal != 0 && causal != 1) return FS_ERR_INVALID_ARG;
@@ -691,6 +694,13 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
     f.rk = (float*)(w8 + fp.f.off_rk); f.Tpart = (float*)(w8 + fp.f.off_state); f.cpart = (float*)(w8 + fp.f.off_cpart);
     f.cstar = (float*)(w8 + fp.f.off_cstar);
     f.flushed = (unsigned*)w8;      // counted by the kernel that recomputes the normalisers
+    if (prepared != nullptr) {
+      PreparedPlan pp;
+      plan_prepared(d, M, pgroups, &pp);
+      char* p8 = (char*)const_cast<void*>(prepared);
+      f.Wbf = (uint16_t*)(p8 + pp.off_Wbf); f.bias = (float*)(p8 + pp.off_bias); f.wnorm = (float*)(p8 + pp.off_wnorm);
+      f.pre_mode = dense_c2 ? 1 : 2;
+    }
     return launch_fast_attention_backward(f, dev(dY), dev(dQ), dev(dK), dev(dV), (uint16_t*)(w8 + fp.off_gh),
                                           (float*)(w8 + fp.off_rpart), (float*)(w8 + fp.off_rcpart),
                                           (float*)(w8 + fp.off_rcstar), fp.rslots, fp.rows_per_rslot, (hipStream_t)stream);
@@ -757,6 +767,35 @@ int favorsharp_attention_backward(const float* theta, int groups, const fs_tenso
     return rc;
   return launch_gen_bwd_side(ks, 1, dev(V), dv, 1, Lk, BH, H, M, d, dv, ldt, rstate, (size_t)p.q.nseg * per_state, kmax,
                              nullptr, dev(dV), 1, dev(dK), st);
+}
+}  // namespace
+
+extern "C" {
+
+int favorsharp_attention_backward(const float* theta, int groups, const fs_tensor* Q, const fs_tensor* K,
+                                  const fs_tensor* V, const fs_tensor* dY, int B, int H, int Lq, int Lk, int d, int dv,
+                                  float qk_scale, const float* Omega, int omega_groups, int M, int causal,
+                                  const fs_tensor* dQ, const fs_tensor* dK, const fs_tensor* dV, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  return attention_backward_impl(theta, groups, Q, K, V, dY, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M, causal,
+                                 dQ, dK, dV, workspace, workspace_bytes, stream, nullptr, 0);
+}
+
+int favorsharp_attention_backward_prepared(const void* prepared, size_t prepared_bytes, int dense_c2, const float* theta,
+                                           int groups, const fs_tensor* Q, const fs_tensor* K, const fs_tensor* V,
+                                           const fs_tensor* dY, int B, int H, int Lq, int Lk, int d, int dv,
+                                           float qk_scale, const float* Omega, int omega_groups, int M, int causal,
+                                           const fs_tensor* dQ, const fs_tensor* dK, const fs_tensor* dV, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  if (prepared == nullptr || (dense_c2 != 0 && dense_c2 != 1)) return FS_ERR_INVALID_ARG;
+  if (B < 1 || H < 1 || d < 1 || M < 1 || !groups_ok(groups, B, H) || !groups_ok(omega_groups, B, H))
+    return FS_ERR_INVALID_ARG;
+  PreparedPlan pp;
+  plan_prepared(d, M, std::max(groups, omega_groups), &pp);
+  if (pp.total == 0 || dv != d) return FS_ERR_UNSUPPORTED;
+  if (prepared_bytes < pp.total) return FS_ERR_WORKSPACE_TOO_SMALL;
+  return attention_backward_impl(theta, groups, Q, K, V, dY, B, H, Lq, Lk, d, dv, qk_scale, Omega, omega_groups, M, causal,
+                                 dQ, dK, dV, workspace, workspace_bytes, stream, prepared, dense_c2);
 }
 
 // ------------------------------------------------------------------------------------------ operator

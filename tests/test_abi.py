@@ -104,6 +104,19 @@ def test_prepared_entry_points_validate_before_any_device_work(lib):
     assert dense.value == 7
 
 
+def test_backward_prepared_entry_point_validates_before_any_device_work(lib):
+    from paper_2302_00787_amd.binding import FsTensor
+    t = FsTensor(None, 0, 0, 0, 64)
+    P = ctypes.byref
+    tail = (None, 1, P(t), P(t), P(t), P(t), 1, 1, 64, 64, 64, 64, 1.0, None, 1, 256, 0, P(t), P(t), P(t), None, 0, None)
+    assert lib.favorsharp_attention_backward_prepared(None, 0, 0, *tail) == 1                    # no buffer
+    buf = ctypes.create_string_buffer(16)
+    assert lib.favorsharp_attention_backward_prepared(buf, 16, 2, *tail) == 1                    # dense_c2 not 0 / 1
+    assert lib.favorsharp_attention_backward_prepared(buf, 16, 0, *tail) == 4                    # buffer too small
+    other = (None, 1, P(t), P(t), P(t), P(t), 1, 1, 64, 64, 32, 32, 1.0, None, 1, 64, 0, P(t), P(t), P(t), None, 0, None)
+    assert lib.favorsharp_attention_backward_prepared(buf, 16, 0, *other) == 2                   # no constants for d = 32
+
+
 def test_pack_and_unpack_theta_roundtrip():
     import numpy as np
     from paper_2302_00787_amd import binding

@@ -504,6 +504,30 @@ def test_backward_bf16_kernels_take_an_fp32_output_gradient(fs, causal):
         _assert_grads(tuple(g[0, h] for g in got), ref, 2e-2, h)
 
 
+@pytest.mark.parametrize("name,over,variant", [("c3", dict(B=2, H=2, L=712), "sderf"), ("c4", dict(B=1, H=2, L=1216), "aderf"),
+                                               ("c3", dict(B=2, H=2, L=128), "aderf"), ("c4", dict(B=32, H=8, L=100), "sderf"),
+                                               ("c5", dict(B=1, H=2, L=96), "sderf")])
+def test_backward_on_prepared_constants_gives_the_same_bits(fs, name, over, variant):
+    """favorsharp_attention_backward_prepared against favorsharp_attention_backward: the projection constants are the
+    same numbers, so the gradients agree bit for bit (separate kernels, the one-workgroup form, the causal form with
+    and without slots; parameter sets with a dense C2 still compute their key row terms per call; the d = 128 shape
+    runs on kernels that keep no constants and must simply ignore the buffer)."""
+    import torch
+    w = synth.make(name, **over)
+    s, causal = w["qk_scale"], bool(w["causal"])
+    Qd, Kd, Vd = (util.to_device(w[k], "bf16") for k in ("Q", "K", "V"))
+    dY = torch.randn(Vd.shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3)).to(torch.bfloat16)
+    Om = torch.from_numpy(w["Omega"]).cuda()
+    theta = fs.fit_params(variant, Qd, Kd, s, groups=w["H"])
+    prepared = fs.attention_prepare(theta, Om, w["B"], w["H"], s)
+    want = fs.attention_backward(theta, Qd, Kd, Vd, dY, s, Om, causal=causal)
+    got = fs.attention_backward(theta, Qd, Kd, Vd, dY, s, Om, causal=causal, prepared=prepared)
+    torch.cuda.synchronize()
+    for a, b in zip(want, got):
+        assert torch.isfinite(a.float()).all().item()
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (name, variant)
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
