@@ -8,8 +8,8 @@ namespace fs {
 using namespace fast;
 
 // ---------------------------------------------------------------------------------------------------
-// Key-side state of one segment: Tpart[bh][seg] = sum_{j in seg} S'_j [V_j 1]^T / 2^cpart[bh][seg], S' = features
-// without the bias (Section 2.1, S^T C with C = [V 1]).  grid (nseg, B*H), block 256, two workgroups per CU.
+// Key-side state of a range of rows: T = sum_j S'_j [V_j 1]^T / 2^dk, S' = features without the bias (Section 2.1,
+// S^T C with C = [V 1]), for a workgroup of 256 threads (two per CU).
 //
 // Four waves of 64 features; per 64-token chunk every wave builds its feature tiles feature-major (A = token rows,
 // B = W~; the per-token part of the exponent is the accumulator's initial value, read from LDS as a 16-byte vector)

@@ -1,5 +1,6 @@
-// bf16 path of FAVOR# attention (d = dv = 64, M = 256): projection constants, key-side segment states, their
-// reduction / prefix, the non-causal query-side kernel, and the host-side launcher of the whole call.
+// bf16 path of FAVOR# attention (d = dv = 64, M = 256): projection constants, key row terms, key-side segment
+// states (the loop itself: fast_state.h), their reduction / prefix, the non-causal query-side kernel, the kernel that
+// takes a whole non-causal sequence per workgroup, and the host-side launchers of the forward and backward calls.
 // The design is described in fast_common.h; the causal segment kernel lives in kernels_bf16_causal.hip.
 #include <hip/hip_ext.h>
 
