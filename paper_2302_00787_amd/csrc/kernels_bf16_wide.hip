@@ -73,36 +73,48 @@ __device__ __forceinline__ float sum16(float v) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Projection constants: grid 128 * 2 * pgroups workgroups of 256 threads; see k_fast_pre.  One wave per feature, lane c
+// Projection constants: grid 32 * 2 * pgroups workgroups of 256 threads; see k_fast_pre.  A wave computes four
+// features at a time (every number of B it requests serves all four: the kernel is bound by those requests), lane c
 // handles columns c and c + 64.
 // ---------------------------------------------------------------------------------------------------
+constexpr int PREF = 4;            // features per wave
 __global__ void __launch_bounds__(256) k_wide_pre(WideArgs a, int* dense_flag) {
   const size_t tf = FS_THETA_HEADER_ + (size_t)DW + 4 * (size_t)DW * DW;
   const int H = a.H, block = blockIdx.x;
   const int c = threadIdx.x & 63;
-  {
-    const int pg = block / ((MW / 4) * 2), rem = block % ((MW / 4) * 2), side = rem / (MW / 4);
-    const int m = (rem % (MW / 4)) * 4 + (threadIdx.x >> 6);
-    int b = 0, h = 0;
-    if (a.pgroups == H && a.pgroups != 1) h = pg;
-    else if (a.pgroups != 1) { b = pg / H; h = pg % H; }
-    const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
-    if (dense_flag != nullptr && rem == 0 && threadIdx.x == 0 && !(((int)th[2]) & 1)) atomicOr(dense_flag, 1);
-    const float* om = a.Omega + ((size_t)group_of(a.omega_groups, b, h, H) * MW + m) * DW;
-    const float* Bm = th + FS_THETA_HEADER_ + DW + (side ? (size_t)DW * DW : 0);
-    const float* A = th + FS_THETA_HEADER_;
-    const size_t o = ((size_t)pg * 2 + side) * MW + m;
-    float acc0 = 0.f, acc1 = 0.f;
-#pragma unroll 8
-    for (int l = 0; l < DW; ++l) {
-      acc0 += om[l] * Bm[l * DW + c];
-      acc1 += om[l] * Bm[l * DW + c + 64];
+  constexpr int per_side = MW / (4 * PREF);
+  const int pg = block / (per_side * 2), rem = block % (per_side * 2), side = rem / per_side;
+  const int m0 = (rem % per_side) * 4 * PREF + (threadIdx.x >> 6) * PREF;
+  int b = 0, h = 0;
+  if (a.pgroups == H && a.pgroups != 1) h = pg;
+  else if (a.pgroups != 1) { b = pg / H; h = pg % H; }
+  const float* th = a.theta + (size_t)group_of(a.groups, b, h, H) * tf;
+  if (dense_flag != nullptr && rem == 0 && threadIdx.x == 0 && !(((int)th[2]) & 1)) atomicOr(dense_flag, 1);
+  const float* om = a.Omega + ((size_t)group_of(a.omega_groups, b, h, H) * MW + m0) * DW;
+  const float* Bm = th + FS_THETA_HEADER_ + DW + (side ? (size_t)DW * DW : 0);
+  const float* A = th + FS_THETA_HEADER_;
+  float acc0[PREF], acc1[PREF];
+#pragma unroll
+  for (int f = 0; f < PREF; ++f) acc0[f] = acc1[f] = 0.f;
+#pragma unroll 4
+  for (int l = 0; l < DW; ++l) {
+    const float v0 = Bm[l * DW + c], v1 = Bm[l * DW + c + 64];
+#pragma unroll
+    for (int f = 0; f < PREF; ++f) {
+      const float o = om[f * DW + l];
+      acc0[f] += o * v0;
+      acc1[f] += o * v1;
     }
-    const uint16_t b0 = f32_to_bf16_bits(acc0 * kLog2e * a.scale), b1 = f32_to_bf16_bits(acc1 * kLog2e * a.scale);
+  }
+#pragma unroll
+  for (int f = 0; f < PREF; ++f) {
+    const size_t o = ((size_t)pg * 2 + side) * MW + m0 + f;
+    const uint16_t b0 = f32_to_bf16_bits(acc0[f] * kLog2e * a.scale), b1 = f32_to_bf16_bits(acc1[f] * kLog2e * a.scale);
     a.Wbf[o * DW + c] = b0;
     a.Wbf[o * DW + c + 64] = b1;
     const float r0 = bf16_bits_to_f32(b0), r1 = bf16_bits_to_f32(b1);
-    float n2 = r0 * r0 + r1 * r1, q = A[c] * om[c] * om[c] + A[c + 64] * om[c + 64] * om[c + 64];
+    const float* of = om + f * DW;
+    float n2 = r0 * r0 + r1 * r1, q = A[c] * of[c] * of[c] + A[c + 64] * of[c + 64] * of[c + 64];
 #pragma unroll
     for (int s = 1; s < 64; s <<= 1) { n2 += __shfl_xor(n2, s); q += __shfl_xor(q, s); }
     if (c == 0) {
@@ -701,7 +713,7 @@ int launch_wide_prepare(const float* theta, int groups, const float* Omega, int 
   WideArgs a = {};
   a.theta = theta; a.Omega = Omega; a.Wbf = Wbf; a.bias = bias; a.wnorm = wnorm;
   a.groups = groups; a.omega_groups = omega_groups; a.pgroups = pgroups; a.B = B; a.H = H; a.scale = scale;
-  hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * pgroups), dim3(256), 0, st, a, dense_flag);
+  hipLaunchKernelGGL(k_wide_pre, dim3((MW / (4 * PREF)) * 2 * pgroups), dim3(256), 0, st, a, dense_flag);
   FS_LAUNCH_CHECK();
   return 0;
 }
@@ -729,7 +741,7 @@ int launch_wide_attention(const WideLaunch& f, hipStream_t st, hipEvent_t ev_beg
     return 2;
   }
   if (f.pre_mode == 0) {
-    hipLaunchKernelGGL(k_wide_pre, dim3((MW / 4) * 2 * f.pgroups), dim3(256), 0, st, a, (int*)nullptr);
+    hipLaunchKernelGGL(k_wide_pre, dim3((MW / (4 * PREF)) * 2 * f.pgroups), dim3(256), 0, st, a, (int*)nullptr);
     FS_LAUNCH_CHECK();
   }
   // the key row terms of parameter sets with a dense C2 (the host knows that there are none only in mode 2)
