@@ -528,6 +528,54 @@ def test_backward_on_prepared_constants_gives_the_same_bits(fs, name, over, vari
         assert torch.equal(a.view(torch.int16), b.view(torch.int16)), (name, variant)
 
 
+@pytest.mark.parametrize("name,over,prepared", [("c3", dict(B=2, H=2, L=712), False), ("c4", dict(B=1, H=2, L=1216), True),
+                                                ("c3", dict(B=2, H=2, L=128), True), ("c4", dict(B=32, H=8, L=100), False),
+                                                ("c1", {}, False)])
+def test_backward_call_replays_from_a_hip_graph(fs, name, over, prepared):
+    """The backward entry points only enqueue kernels on the caller's stream (no synchronisation, no allocation, no
+    memset nodes): captured in a HIP graph and replayed three times, with eager work and synchronisations in between,
+    every replay reproduces the eager gradients bit for bit (separate non-causal kernels, the causal kernels with
+    slots, the one-workgroup form, the causal form with one slot per sequence, the general-shape kernels)."""
+    import torch
+    w = synth.make(name, **over)
+    dt = w.get("dtype", "f32")
+    Q, K, V = (util.to_device(w[k], dt) for k in "QKV")
+    dY = torch.randn(V.shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(7)).to(V.dtype)
+    Om, s, causal = torch.from_numpy(w["Omega"]).cuda(), w["qk_scale"], bool(w["causal"])
+    theta = fs.fit_params("aderf" if name == "c3" else "sderf", Q, K, s, groups=w["H"])
+    B, H, L, d = Q.shape
+    ws = torch.empty(fs.attention_backward_workspace_bytes(B, H, L, L, d, V.shape[-1], Om.shape[-2], causal, H, H),
+                     dtype=torch.uint8, device="cuda")
+    grads = tuple(torch.empty_like(t) for t in (Q, K, V))
+    prep = fs.attention_prepare(theta, Om, B, H, s) if prepared else None
+
+    def call():
+        fs.attention_backward(theta, Q, K, V, dY, s, Om, causal=causal, workspace=ws, grads=grads, prepared=prep)
+
+    call()
+    torch.cuda.synchronize()
+    ref = [g.clone() for g in grads]
+    assert all(torch.isfinite(g.float()).all().item() for g in ref)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):           # warm-up on a side stream, as graph capture asks for
+        call()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(3):
+        for g in grads:
+            g.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for g, r in zip(grads, ref):
+            assert torch.equal(g, r), (name, rep)
+        _ = torch.randn(1 << 20, device="cuda").sum().item()
+
+
 def test_backward_error_paths(fs):
     import torch
     Q = torch.zeros((1, 1, 8, 8), device="cuda")
